@@ -1,0 +1,157 @@
+/*
+ * dp.h -- C ABI of the per-layer training-compute library for MI355X (gfx950).
+ *
+ * The operations are the per-layer forward and backward computations whose
+ * time, at per-GPU batch B/g, is the planner input comp(i,g) of burst-parallel
+ * training (paper, section 4.1 "Computation cost"), for the "Conv, Dense"
+ * layer kinds of the evaluated models (paper, Table 1).  The paper treats the
+ * layers as black boxes; their arithmetic is the standard deep-learning
+ * definition (cross-correlation, zero padding, floor output size).
+ *
+ * Conventions that hold for every call unless stated otherwise:
+ *  - All tensor pointers are DEVICE pointers owned by the caller; the library
+ *    never allocates, frees or keeps them (dp_profile_layer is the exception,
+ *    see there).  Descriptors and row arrays are HOST pointers.
+ *  - Layouts are dense: activations NHWC, conv weights KRSC (K = c_out),
+ *    dense-layer weights [out_features, in_features].
+ *  - io_dtype DP_BF16: x, w, y, dy, dx are bfloat16 (raw 16-bit), products are
+ *    accumulated in fp32 on the matrix cores, y / dx are rounded to bf16
+ *    (nearest-even).  io_dtype DP_F32: everything fp32, plain fp32 FMA.
+ *    bias, dw, dW, dbias are always fp32.
+ *  - Outputs are fully overwritten (no accumulation into dw).
+ *  - Calls enqueue work on `hip_stream` (a hipStream_t; NULL = default stream)
+ *    and return without synchronising.  Arguments are validated before any
+ *    launch, so every error path can be reached on a host without a GPU.
+ *  - Tensor pointers must be 16-byte aligned; every tensor must hold fewer than
+ *    2^31 elements.
+ *  - Results are deterministic: split reductions are summed in a fixed order,
+ *    no floating-point atomics are used.
+ *  - Return value: DP_OK or an error code; dp_last_error() gives a message for
+ *    the calling thread's most recent failure.
+ */
+#ifndef DP_H
+#define DP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DP_OK = 0,
+    DP_ERR_NULL = 1,        /* a required pointer is NULL */
+    DP_ERR_BAD_DESC = 2,    /* non-positive size, empty output, misaligned pointer, too many elements */
+    DP_ERR_UNSUPPORTED = 3, /* unknown dtype / flag / pass */
+    DP_ERR_WORKSPACE = 4,   /* workspace missing or smaller than dp_*_workspace_bytes() */
+    DP_ERR_HIP = 5          /* a HIP runtime call failed (no device, launch error, ...) */
+} dp_status;
+
+typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
+
+enum {
+    DP_BIAS = 1u,          /* forward adds bias[c_out] */
+    DP_RELU = 2u,          /* forward applies max(.,0) after the bias */
+    DP_DETERMINISTIC = 4u, /* accepted; results are always deterministic */
+    DP_DX_F32 = 8u         /* bf16 path only: dx is written as fp32 instead of bf16 */
+};
+
+enum { DP_PASS_FWD = 0, DP_PASS_DGRAD = 1, DP_PASS_WGRAD = 2 };
+
+/* One conv2d layer at per-GPU batch n.  dilation 1, groups 1.
+ * Output size: ho = (h + 2*pad_h - r) / stride_h + 1 (floor), same for wo. */
+typedef struct {
+    int32_t n, h, w, c_in, c_out, r, s, stride_h, stride_w, pad_h, pad_w;
+    int32_t io_dtype; /* dp_dtype */
+    uint32_t flags;
+} dp_conv_desc;
+
+/* One dense layer at per-GPU batch n. */
+typedef struct {
+    int32_t n, in_features, out_features;
+    int32_t io_dtype; /* dp_dtype */
+    uint32_t flags;   /* DP_BIAS, DP_RELU, DP_DX_F32 */
+} dp_linear_desc;
+
+/* Bytes of device scratch the given pass (DP_PASS_*) of this layer needs.
+ * 0 is a valid answer.  Returns 0 for an invalid descriptor. */
+size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass);
+size_t dp_linear_workspace_bytes(const dp_linear_desc *desc);
+
+/* Forward: y[n,p,q,k] = bias[k] + sum_{r,s,c} x[n, p*sh-ph+r, q*sw-pw+s, c] * w[k,r,s,c],
+ * then ReLU if DP_RELU.  (Layer forward pass of comp(i,g), paper section 4.1.)
+ * x [n,h,w,c_in], w [c_out,r,s,c_in], bias [c_out] fp32 (required iff DP_BIAS),
+ * y [n,ho,wo,c_out].  ws: device scratch of >= dp_conv2d_workspace_bytes(desc, DP_PASS_FWD). */
+dp_status dp_conv2d_fwd(const dp_conv_desc *desc, const void *x, const void *w, const float *bias,
+                        void *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backward data: dx[n,h,w,c] = sum_{k,r,s} g[n,p,q,k] * w[k,r,s,c] over the (p,q) with
+ * p*sh-ph+r == h and q*sw-pw+s == w, where g = dy * [y_saved > 0] if y_saved is given
+ * (the layer's stored post-ReLU output), else g = dy.  (Backward pass of comp(i,g),
+ * paper section 4.1; "gradients during backward passes", section 4.1 "Communication cost".)
+ * dy, y_saved [n,ho,wo,c_out]; dx [n,h,w,c_in] in io_dtype (fp32 if DP_DX_F32). */
+dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const void *y_saved_or_null,
+                             const void *w, void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Backward filter: dw[k,r,s,c] = sum_{n,p,q} g[n,p,q,k] * x[n, p*sh-ph+r, q*sw-pw+s, c];
+ * dbias[k] = sum_{n,p,q} g[n,p,q,k] if dbias is given.  g as in dp_conv2d_bwd_data.
+ * dw [c_out,r,s,c_in] fp32, dbias [c_out] fp32.  These are the per-layer gradients that
+ * data-parallel training sums across GPUs (paper section 4.1, sync(i,g)). */
+dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const void *dy,
+                               const void *y_saved_or_null, float *dw, float *dbias_or_null,
+                               void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Dense layer, forward and/or backward in one call (paper Table 1 "Dense"; section 4.1):
+ *   y = x W^T + bias (ReLU if DP_RELU)                       if y != NULL   (needs x, W)
+ *   g = dy * [y_saved > 0] (or dy);  dx = g W; dW = g^T x; dbias = sum_n g
+ *                                                            each if its pointer != NULL
+ * x [n,in], W [out,in], dy / y / y_saved [n,out], dx [n,in], dW [out,in] fp32, dbias [out] fp32.
+ * Backward outputs need dy; dW needs x.  At least one output must be requested. */
+dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const void *W,
+                            const float *bias, const void *dy, const void *y_saved_or_null,
+                            void *y, void *dx, float *dW, float *dbias,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/* ReLU gradient and bias gradient of a [rows, k] activation matrix
+ * (the pointwise part of a layer's backward pass, paper section 4.1):
+ *   g = dy * [y_saved > 0];  g_out = g (if g_out != NULL, in io_dtype);
+ *   dbias[j] = sum_rows g[., j] (if dbias != NULL, fp32).
+ * ws: device scratch of >= dp_relu_bias_grad_workspace_bytes(rows, k) when dbias is requested. */
+size_t dp_relu_bias_grad_workspace_bytes(int64_t rows, int32_t k);
+dp_status dp_relu_bias_grad(int64_t rows, int32_t k, int32_t io_dtype, const void *dy,
+                            const void *y_saved, void *g_out_or_null, float *dbias_or_null,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/* One row of the time-versus-batch table comp(i,g) the planner consumes
+ * (paper section 4.1: each layer is profiled at every per-GPU batch size and the
+ * forward and backward times are summed). */
+typedef struct {
+    int32_t batch;
+    float fwd_us, dgrad_us, wgrad_us; /* average time of one launch, microseconds */
+    double flops_per_pass;            /* 2*n*ho*wo*c_out*r*s*c_in (2*n*in*out for dense) */
+    double min_bytes_fwd, min_bytes_dgrad, min_bytes_wgrad; /* algorithmic HBM bytes */
+} dp_profile_row;
+
+/* Time forward, backward-data and backward-filter of one layer at each batch in `batches`.
+ * Exactly one of conv / linear is non-NULL; its n field is ignored.  For each batch the
+ * call allocates device buffers itself (hipMalloc/hipFree), fills them with a fixed
+ * pattern, runs `warmup` untimed and `iters` timed back-to-back launches of each pass
+ * between HIP events on `hip_stream`, and synchronises: the only blocking call here.
+ * For a dense layer fwd_us is the y pass, dgrad_us the dx pass, wgrad_us the dW+dbias pass.
+ * rows_out: host array of n_batches rows. */
+dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linear,
+                           const int32_t *batches, int32_t n_batches, int32_t warmup,
+                           int32_t iters, dp_profile_row *rows_out, void *hip_stream);
+
+/* Tuning hook: force the tile variant (>= 0) and/or the number of reduction splits (> 0)
+ * used by the given pass; -1 / 0 restore the built-in choice.  Process-wide. */
+dp_status dp_set_override(int pass, int tile_variant, int splits);
+
+const char *dp_last_error(void); /* thread-local, static storage */
+const char *dp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DP_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of libdp_mi355x.so: same names as the C ABI (include/dp.h), argument
+marshalling only.  PyTorch supplies device memory and streams; every computation runs in
+the library's HIP kernels.  Importing this module fails loudly if the library is missing.
+"""
+import ctypes as C
+import os
+
+from . import build as _build
+
+DP_OK, DP_ERR_NULL, DP_ERR_BAD_DESC, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = range(6)
+DP_F32, DP_BF16 = 0, 1
+DP_BIAS, DP_RELU, DP_DETERMINISTIC, DP_DX_F32 = 1, 2, 4, 8
+DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
+
+EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data",
+           "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
+           "dp_profile_layer", "dp_set_override", "dp_last_error", "dp_version"]
+
+
+class dp_conv_desc(C.Structure):
+    _fields_ = [(f, C.c_int32) for f in ("n", "h", "w", "c_in", "c_out", "r", "s", "stride_h", "stride_w",
+                                         "pad_h", "pad_w", "io_dtype")] + [("flags", C.c_uint32)]
+
+
+class dp_linear_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("in_features", C.c_int32), ("out_features", C.c_int32),
+                ("io_dtype", C.c_int32), ("flags", C.c_uint32)]
+
+
+class dp_profile_row(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("fwd_us", C.c_float), ("dgrad_us", C.c_float), ("wgrad_us", C.c_float),
+                ("flops_per_pass", C.c_double), ("min_bytes_fwd", C.c_double), ("min_bytes_dgrad", C.c_double),
+                ("min_bytes_wgrad", C.c_double)]
+
+
+class DpError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__(f"dp status {status}: {msg}")
+        self.status = status
+
+
+def _load():
+    path = _build.LIB
+    if not os.path.exists(path):
+        path = _build.build(force=True)   # nothing built yet: compile once
+    lib = C.CDLL(path)
+    vp, sz, i32, i64, u32 = C.c_void_p, C.c_size_t, C.c_int32, C.c_int64, C.c_uint32
+    P = C.POINTER
+    lib.dp_conv2d_workspace_bytes.restype = sz
+    lib.dp_conv2d_workspace_bytes.argtypes = [P(dp_conv_desc), C.c_int]
+    lib.dp_linear_workspace_bytes.restype = sz
+    lib.dp_linear_workspace_bytes.argtypes = [P(dp_linear_desc)]
+    lib.dp_conv2d_fwd.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_conv2d_bwd_data.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_conv2d_bwd_filter.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_linear_fwd_bwd.argtypes = [P(dp_linear_desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_relu_bias_grad_workspace_bytes.restype = sz
+    lib.dp_relu_bias_grad_workspace_bytes.argtypes = [i64, i32]
+    lib.dp_relu_bias_grad.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_profile_layer.argtypes = [P(dp_conv_desc), P(dp_linear_desc), P(i32), i32, i32, i32, P(dp_profile_row), vp]
+    lib.dp_set_override.argtypes = [C.c_int, C.c_int, C.c_int]
+    for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
+                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override"):
+        getattr(lib, name).restype = C.c_int
+    lib.dp_last_error.restype = C.c_char_p
+    lib.dp_version.restype = C.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def _check(st):
+    if st != DP_OK:
+        raise DpError(st, lib.dp_last_error().decode())
+
+
+def _ptr(t):
+    """Device (or raw integer) address of a torch tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def _ws(ws):
+    if ws is None:
+        return None, 0
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def conv_desc(n, h, w, c_in, c_out, r, s, stride=(1, 1), pad=(0, 0), io_dtype=DP_BF16, flags=0):
+    return dp_conv_desc(n, h, w, c_in, c_out, r, s, stride[0], stride[1], pad[0], pad[1], io_dtype, flags)
+
+
+def linear_desc(n, in_features, out_features, io_dtype=DP_BF16, flags=0):
+    return dp_linear_desc(n, in_features, out_features, io_dtype, flags)
+
+
+def dp_version():
+    return lib.dp_version().decode()
+
+
+def dp_last_error():
+    return lib.dp_last_error().decode()
+
+
+def dp_set_override(pass_, tile_variant=-1, splits=0):
+    _check(lib.dp_set_override(pass_, tile_variant, splits))
+
+
+def dp_conv2d_workspace_bytes(desc, pass_):
+    return int(lib.dp_conv2d_workspace_bytes(C.byref(desc), pass_))
+
+
+def dp_linear_workspace_bytes(desc):
+    return int(lib.dp_linear_workspace_bytes(C.byref(desc)))
+
+
+def dp_relu_bias_grad_workspace_bytes(rows, k):
+    return int(lib.dp_relu_bias_grad_workspace_bytes(rows, k))
+
+
+def dp_conv2d_fwd(desc, x, w, bias, y, ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_conv2d_fwd(C.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), p, b, _stream(stream)))
+
+
+def dp_conv2d_bwd_data(desc, dy, y_saved, w, dx, ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_conv2d_bwd_data(C.byref(desc), _ptr(dy), _ptr(y_saved), _ptr(w), _ptr(dx), p, b, _stream(stream)))
+
+
+def dp_conv2d_bwd_filter(desc, x, dy, y_saved, dw, dbias=None, ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_conv2d_bwd_filter(C.byref(desc), _ptr(x), _ptr(dy), _ptr(y_saved), _ptr(dw), _ptr(dbias), p, b,
+                                    _stream(stream)))
+
+
+def dp_linear_fwd_bwd(desc, x=None, W=None, bias=None, dy=None, y_saved=None, y=None, dx=None, dW=None, dbias=None,
+                      ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_linear_fwd_bwd(C.byref(desc), _ptr(x), _ptr(W), _ptr(bias), _ptr(dy), _ptr(y_saved), _ptr(y),
+                                 _ptr(dx), _ptr(dW), _ptr(dbias), p, b, _stream(stream)))
+
+
+def dp_relu_bias_grad(rows, k, io_dtype, dy, y_saved, g_out=None, dbias=None, ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_relu_bias_grad(rows, k, io_dtype, _ptr(dy), _ptr(y_saved), _ptr(g_out), _ptr(dbias), p, b,
+                                 _stream(stream)))
+
+
+def dp_profile_layer(conv=None, linear=None, batches=(1,), warmup=3, iters=10, stream=None):
+    n = len(batches)
+    arr = (C.c_int32 * n)(*batches)
+    rows = (dp_profile_row * n)()
+    _check(lib.dp_profile_layer(C.byref(conv) if conv is not None else None,
+                                C.byref(linear) if linear is not None else None, arr, n, warmup, iters, rows,
+                                _stream(stream)))
+    return [dict((f, getattr(r, f)) for f, _ in dp_profile_row._fields_) for r in rows]

@@ -1,0 +1,414 @@
+// C-ABI layer: argument validation, kernel choice, workspace layout, layer profiler.
+// Every check runs before the first HIP call so error paths work on a host without a GPU.
+#include "../../include/dp.h"
+#include "dp_kernels.h"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+namespace {
+
+thread_local char g_err[512] = "";
+std::atomic<int> g_force_variant[3] = {{-1}, {-1}, {-1}};
+std::atomic<int> g_force_splits[3] = {{0}, {0}, {0}};
+std::once_flag g_init_once;
+hipError_t g_init_err = hipSuccess;
+
+dp_status fail(dp_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+dp_status hip_fail(hipError_t e, const char *what)
+{
+    return fail(DP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+constexpr long long kMaxElems = (1ll << 31) - 1;
+constexpr unsigned kKnownFlags = DP_BIAS | DP_RELU | DP_DETERMINISTIC | DP_DX_F32;
+
+dp_status check_conv(const dp_conv_desc *d, ConvGeom *g)
+{
+    if (d == nullptr) return fail(DP_ERR_NULL, "descriptor is NULL");
+    if (d->io_dtype != DP_F32 && d->io_dtype != DP_BF16) return fail(DP_ERR_UNSUPPORTED, "unknown io_dtype %d", d->io_dtype);
+    if (d->flags & ~kKnownFlags) return fail(DP_ERR_UNSUPPORTED, "unknown flag bits 0x%x", d->flags & ~kKnownFlags);
+    if ((d->flags & DP_DX_F32) && d->io_dtype != DP_BF16) return fail(DP_ERR_UNSUPPORTED, "DP_DX_F32 needs DP_BF16");
+    if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c_in <= 0 || d->c_out <= 0 || d->r <= 0 || d->s <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return fail(DP_ERR_BAD_DESC, "sizes must be positive and pads non-negative");
+    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return fail(DP_ERR_BAD_DESC, "filter larger than padded input: empty output");
+    g->N = d->n; g->H = d->h; g->W = d->w; g->C = d->c_in; g->K = d->c_out; g->R = d->r; g->S = d->s;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->Ho = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    g->Wo = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    long long xe = (long long)g->N * g->H * g->W * g->C, ye = (long long)g->N * g->Ho * g->Wo * g->K;
+    long long we = (long long)g->K * g->R * g->S * g->C;
+    if (xe > kMaxElems || ye > kMaxElems || we > kMaxElems) return fail(DP_ERR_BAD_DESC, "a tensor has 2^31 or more elements");
+    return DP_OK;
+}
+
+dp_status check_linear(const dp_linear_desc *d, ConvGeom *g)
+{
+    if (d == nullptr) return fail(DP_ERR_NULL, "descriptor is NULL");
+    if (d->io_dtype != DP_F32 && d->io_dtype != DP_BF16) return fail(DP_ERR_UNSUPPORTED, "unknown io_dtype %d", d->io_dtype);
+    if (d->flags & ~kKnownFlags) return fail(DP_ERR_UNSUPPORTED, "unknown flag bits 0x%x", d->flags & ~kKnownFlags);
+    if ((d->flags & DP_DX_F32) && d->io_dtype != DP_BF16) return fail(DP_ERR_UNSUPPORTED, "DP_DX_F32 needs DP_BF16");
+    if (d->n <= 0 || d->in_features <= 0 || d->out_features <= 0) return fail(DP_ERR_BAD_DESC, "sizes must be positive");
+    if ((long long)d->in_features * d->out_features > kMaxElems || (long long)d->n * d->in_features > kMaxElems ||
+        (long long)d->n * d->out_features > kMaxElems)
+        return fail(DP_ERR_BAD_DESC, "a tensor has 2^31 or more elements");
+    // a dense layer is a 1x1 convolution on a 1x1 image
+    *g = ConvGeom{d->n, 1, 1, d->in_features, d->out_features, 1, 1, 1, 1, 0, 0, 1, 1};
+    return DP_OK;
+}
+
+dp_status check_ptr(const void *p, const char *name)
+{
+    if (p == nullptr) return fail(DP_ERR_NULL, "%s is NULL", name);
+    if (!aligned16(p)) return fail(DP_ERR_BAD_DESC, "%s is not 16-byte aligned", name);
+    return DP_OK;
+}
+dp_status check_opt(const void *p, const char *name)
+{
+    if (p != nullptr && !aligned16(p)) return fail(DP_ERR_BAD_DESC, "%s is not 16-byte aligned", name);
+    return DP_OK;
+}
+
+void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
+{
+    mfma_plan(g, pass, g_force_variant[pass].load(), g_force_splits[pass].load(), pl);
+}
+
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+dp_status ensure_init()
+{
+    std::call_once(g_init_once, [] { g_init_err = mfma_init(); });
+    if (g_init_err != hipSuccess) return hip_fail(g_init_err, "library initialisation (is a gfx950 device present?)");
+    return DP_OK;
+}
+
+unsigned kflags(unsigned f, bool fwd)
+{
+    unsigned k = 0;
+    if (fwd && (f & DP_BIAS)) k |= KF_BIAS;
+    if (fwd && (f & DP_RELU)) k |= KF_RELU;
+    return k;
+}
+
+// ---- the three passes on a validated geometry --------------------------------------
+dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, const void *w, const float *bias, void *y,
+                  void *ws, size_t ws_bytes, hipStream_t st)
+{
+    if (dtype == DP_F32) {
+        hipError_t e = f32_conv_fwd(g, kflags(flags, true), (const float *)x, (const float *)w, bias, (float *)y, st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
+    }
+    ConvArgs a{};
+    a.g = g; a.pass = PASS_FWD; a.flags = kflags(flags, true);
+    plan_for(g, PASS_FWD, &a.plan);
+    size_t need = mfma_partial_bytes(g, PASS_FWD, a.plan);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
+    a.x = (const bf16_t *)x; a.w = (const bf16_t *)w; a.bias = bias; a.out = y; a.partial = (float *)ws;
+    hipError_t e = mfma_launch(a, st);
+    return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
+}
+
+dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy, const void *ym, const void *w, void *dx,
+                    void *ws, size_t ws_bytes, hipStream_t st)
+{
+    if (dtype == DP_F32) {
+        hipError_t e = f32_conv_dgrad(g, (const float *)dy, (const float *)ym, (const float *)w, (float *)dx, st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 backward-data launch");
+    }
+    ConvArgs a{};
+    a.g = g; a.pass = PASS_DGRAD; a.flags = (flags & DP_DX_F32) ? KF_OUT_F32 : 0u;
+    plan_for(g, PASS_DGRAD, &a.plan);
+    size_t need = mfma_partial_bytes(g, PASS_DGRAD, a.plan);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
+    a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
+    hipError_t e = mfma_launch(a, st);
+    return e == hipSuccess ? DP_OK : hip_fail(e, "backward-data launch");
+}
+
+size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
+{
+    size_t need = 0;
+    if (dtype == DP_BF16) {
+        GemmPlan pl;
+        plan_for(g, PASS_WGRAD, &pl);
+        need = round256(mfma_partial_bytes(g, PASS_WGRAD, pl));
+    }
+    if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
+    return need;
+}
+
+dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy, const void *ym, float *dw, float *db,
+                    void *ws, size_t ws_bytes, hipStream_t st)
+{
+    size_t need = wgrad_ws_bytes(g, dtype, db != nullptr);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-filter needs %zu workspace bytes, got %zu", need, ws_bytes);
+    size_t part = 0;
+    if (dw != nullptr) {
+        if (dtype == DP_F32) {
+            hipError_t e = f32_conv_wgrad(g, (const float *)x, (const float *)dy, (const float *)ym, dw, st);
+            if (e != hipSuccess) return hip_fail(e, "fp32 backward-filter launch");
+        } else {
+            ConvArgs a{};
+            a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
+            plan_for(g, PASS_WGRAD, &a.plan);
+            part = round256(mfma_partial_bytes(g, PASS_WGRAD, a.plan));
+            a.x = (const bf16_t *)x; a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.out = dw; a.partial = (float *)ws;
+            hipError_t e = mfma_launch(a, st);
+            if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
+        }
+    } else if (dtype == DP_BF16) {
+        GemmPlan pl;
+        plan_for(g, PASS_WGRAD, &pl);
+        part = round256(mfma_partial_bytes(g, PASS_WGRAD, pl));
+    }
+    if (db != nullptr) {
+        hipError_t e = rbg_launch((long long)g.N * g.Ho * g.Wo, g.K, dtype == DP_BF16, dy, ym, nullptr, db,
+                                  (float *)((char *)ws + part), st);
+        if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
+    }
+    return DP_OK;
+}
+
+size_t esize(int dtype) { return dtype == DP_BF16 ? 2 : 4; }
+
+}  // namespace
+
+extern "C" {
+
+const char *dp_last_error(void) { return g_err; }
+const char *dp_version(void) { return "dp-mi355x 0.1 (gfx950)"; }
+
+dp_status dp_set_override(int pass, int tile_variant, int splits)
+{
+    if (pass < 0 || pass > 2) return fail(DP_ERR_UNSUPPORTED, "pass must be 0, 1 or 2");
+    g_force_variant[pass].store(tile_variant);
+    g_force_splits[pass].store(splits);
+    return DP_OK;
+}
+
+size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
+{
+    ConvGeom g;
+    if (check_conv(desc, &g) != DP_OK || pass < 0 || pass > 2) return 0;
+    if (pass == DP_PASS_WGRAD) return wgrad_ws_bytes(g, desc->io_dtype, true);
+    if (desc->io_dtype == DP_F32) return 0;
+    GemmPlan pl;
+    plan_for(g, pass, &pl);
+    return mfma_partial_bytes(g, pass, pl);
+}
+
+size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
+{
+    ConvGeom g;
+    if (check_linear(desc, &g) != DP_OK) return 0;
+    size_t need = wgrad_ws_bytes(g, desc->io_dtype, true);
+    if (desc->io_dtype == DP_BF16) {
+        for (int pass = 0; pass < 2; ++pass) {
+            GemmPlan pl;
+            plan_for(g, pass, &pl);
+            size_t b = mfma_partial_bytes(g, pass, pl);
+            if (b > need) need = b;
+        }
+    }
+    return need;
+}
+
+dp_status dp_conv2d_fwd(const dp_conv_desc *desc, const void *x, const void *w, const float *bias, void *y, void *ws,
+                        size_t ws_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_conv(desc, &g)) != DP_OK) return s;
+    if ((s = check_ptr(x, "x")) != DP_OK || (s = check_ptr(w, "w")) != DP_OK || (s = check_ptr(y, "y")) != DP_OK) return s;
+    if (desc->flags & DP_BIAS) { if ((s = check_ptr(bias, "bias")) != DP_OK) return s; }
+    if ((s = check_opt(ws, "ws")) != DP_OK) return s;
+    if (desc->io_dtype == DP_BF16) {
+        GemmPlan pl;
+        plan_for(g, PASS_FWD, &pl);
+        size_t need = mfma_partial_bytes(g, PASS_FWD, pl);
+        if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
+    }
+    if ((s = ensure_init()) != DP_OK) return s;
+    return run_fwd(g, desc->io_dtype, desc->flags, x, w, bias, y, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const void *y_saved, const void *w, void *dx, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_conv(desc, &g)) != DP_OK) return s;
+    if ((s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(w, "w")) != DP_OK || (s = check_ptr(dx, "dx")) != DP_OK) return s;
+    if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK) return s;
+    if (desc->io_dtype == DP_BF16) {
+        GemmPlan pl;
+        plan_for(g, PASS_DGRAD, &pl);
+        size_t need = mfma_partial_bytes(g, PASS_DGRAD, pl);
+        if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
+    }
+    if ((s = ensure_init()) != DP_OK) return s;
+    return run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, w, dx, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const void *dy, const void *y_saved, float *dw,
+                               float *dbias, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_conv(desc, &g)) != DP_OK) return s;
+    if ((s = check_ptr(x, "x")) != DP_OK || (s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(dw, "dw")) != DP_OK) return s;
+    if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(dbias, "dbias")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK) return s;
+    size_t need = wgrad_ws_bytes(g, desc->io_dtype, dbias != nullptr);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-filter needs %zu workspace bytes, got %zu", need, ws_bytes);
+    if ((s = ensure_init()) != DP_OK) return s;
+    return run_wgrad(g, desc->io_dtype, x, dy, y_saved, dw, dbias, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const void *W, const float *bias, const void *dy,
+                            const void *y_saved, void *y, void *dx, float *dW, float *dbias, void *ws, size_t ws_bytes,
+                            void *hip_stream)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_linear(desc, &g)) != DP_OK) return s;
+    if (y == nullptr && dx == nullptr && dW == nullptr && dbias == nullptr) return fail(DP_ERR_NULL, "no output requested");
+    const bool bwd = dx != nullptr || dW != nullptr || dbias != nullptr;
+    if (y != nullptr || dW != nullptr) { if ((s = check_ptr(x, "x")) != DP_OK) return s; }
+    if (y != nullptr || dx != nullptr) { if ((s = check_ptr(W, "W")) != DP_OK) return s; }
+    if (y != nullptr && (desc->flags & DP_BIAS)) { if ((s = check_ptr(bias, "bias")) != DP_OK) return s; }
+    if (bwd) { if ((s = check_ptr(dy, "dy")) != DP_OK) return s; }
+    if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(y, "y")) != DP_OK || (s = check_opt(dx, "dx")) != DP_OK ||
+        (s = check_opt(dW, "dW")) != DP_OK || (s = check_opt(dbias, "dbias")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK)
+        return s;
+    size_t need = dp_linear_workspace_bytes(desc);
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "dense layer needs %zu workspace bytes, got %zu", need, ws_bytes);
+    if ((s = ensure_init()) != DP_OK) return s;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the passes run back to back on one stream and reuse the same workspace
+    if (y != nullptr && (s = run_fwd(g, desc->io_dtype, desc->flags, x, W, bias, y, ws, ws_bytes, st)) != DP_OK) return s;
+    if (dx != nullptr && (s = run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, W, dx, ws, ws_bytes, st)) != DP_OK) return s;
+    if ((dW != nullptr || dbias != nullptr) && (s = run_wgrad(g, desc->io_dtype, x, dy, y_saved, dW, dbias, ws, ws_bytes, st)) != DP_OK) return s;
+    return DP_OK;
+}
+
+size_t dp_relu_bias_grad_workspace_bytes(int64_t rows, int32_t k)
+{
+    if (rows <= 0 || k <= 0) return 0;
+    return rbg_workspace_bytes(rows, k);
+}
+
+dp_status dp_relu_bias_grad(int64_t rows, int32_t k, int32_t io_dtype, const void *dy, const void *y_saved, void *g_out,
+                            float *dbias, void *ws, size_t ws_bytes, void *hip_stream)
+{
+    dp_status s;
+    if (io_dtype != DP_F32 && io_dtype != DP_BF16) return fail(DP_ERR_UNSUPPORTED, "unknown io_dtype %d", io_dtype);
+    if (rows <= 0 || k <= 0 || rows * (long long)k > kMaxElems) return fail(DP_ERR_BAD_DESC, "rows and k must be positive, rows*k < 2^31");
+    if ((s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(y_saved, "y_saved")) != DP_OK) return s;
+    if (g_out == nullptr && dbias == nullptr) return fail(DP_ERR_NULL, "no output requested");
+    if ((s = check_opt(g_out, "g_out")) != DP_OK || (s = check_opt(dbias, "dbias")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK) return s;
+    if (dbias != nullptr) {
+        size_t need = rbg_workspace_bytes(rows, k);
+        if (ws == nullptr || ws_bytes < need) return fail(DP_ERR_WORKSPACE, "bias gradient needs %zu workspace bytes, got %zu", need, ws_bytes);
+    }
+    hipError_t e = rbg_launch(rows, k, io_dtype == DP_BF16, dy, y_saved, g_out, dbias, (float *)ws, (hipStream_t)hip_stream);
+    return e == hipSuccess ? DP_OK : hip_fail(e, "ReLU/bias-gradient launch");
+}
+
+dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linear, const int32_t *batches, int32_t n_batches,
+                           int32_t warmup, int32_t iters, dp_profile_row *rows_out, void *hip_stream)
+{
+    if ((conv == nullptr) == (linear == nullptr)) return fail(DP_ERR_NULL, "exactly one of conv / linear must be given");
+    if (batches == nullptr || rows_out == nullptr) return fail(DP_ERR_NULL, "batches / rows_out is NULL");
+    if (n_batches <= 0 || warmup < 0 || iters <= 0) return fail(DP_ERR_BAD_DESC, "n_batches and iters must be positive, warmup non-negative");
+    for (int i = 0; i < n_batches; ++i)
+        if (batches[i] <= 0) return fail(DP_ERR_BAD_DESC, "batch %d is not positive", batches[i]);
+    // validate every batch before touching the device
+    for (int i = 0; i < n_batches; ++i) {
+        ConvGeom g;
+        dp_status s;
+        if (conv) { dp_conv_desc d = *conv; d.n = batches[i]; s = check_conv(&d, &g); }
+        else { dp_linear_desc d = *linear; d.n = batches[i]; s = check_linear(&d, &g); }
+        if (s != DP_OK) return s;
+    }
+    dp_status s = ensure_init();
+    if (s != DP_OK) return s;
+    hipStream_t st = (hipStream_t)hip_stream;
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    hipError_t e;
+    if ((e = hipEventCreate(&ev0)) != hipSuccess) return hip_fail(e, "hipEventCreate");
+    if ((e = hipEventCreate(&ev1)) != hipSuccess) { hipEventDestroy(ev0); return hip_fail(e, "hipEventCreate"); }
+
+    dp_status result = DP_OK;
+    for (int bi = 0; bi < n_batches && result == DP_OK; ++bi) {
+        ConvGeom g;
+        int dtype; unsigned flags;
+        if (conv) { dp_conv_desc d = *conv; d.n = batches[bi]; check_conv(&d, &g); dtype = d.io_dtype; flags = d.flags; }
+        else { dp_linear_desc d = *linear; d.n = batches[bi]; check_linear(&d, &g); dtype = d.io_dtype; flags = d.flags; }
+        const size_t es = esize(dtype);
+        const size_t xe = (size_t)g.N * g.H * g.W * g.C, ye = (size_t)g.N * g.Ho * g.Wo * g.K, we = (size_t)g.K * g.R * g.S * g.C;
+        size_t wsb = wgrad_ws_bytes(g, dtype, true);
+        if (dtype == DP_BF16)
+            for (int pass = 0; pass < 2; ++pass) {
+                GemmPlan pl;
+                plan_for(g, pass, &pl);
+                size_t b = mfma_partial_bytes(g, pass, pl);
+                if (b > wsb) wsb = b;
+            }
+        const size_t dxes = (flags & DP_DX_F32) ? 4 : es;
+        void *x = nullptr, *w = nullptr, *y = nullptr, *dy = nullptr, *dx = nullptr, *dw = nullptr, *bias = nullptr, *db = nullptr, *ws = nullptr;
+        struct { void **p; size_t bytes; int fill; } bufs[] = {
+            {&x, xe * es, 1}, {&w, we * es, 1}, {&y, ye * es, 1}, {&dy, ye * es, 1}, {&dx, xe * dxes, 0},
+            {&dw, we * 4, 0}, {&bias, (size_t)g.K * 4, 1}, {&db, (size_t)g.K * 4, 0}, {&ws, wsb > 0 ? wsb : 256, 0}};
+        for (auto &b : bufs) {
+            if ((e = hipMalloc(b.p, b.bytes)) != hipSuccess) { result = hip_fail(e, "hipMalloc in dp_profile_layer"); break; }
+            // 0x3c3c is a small positive bf16 and 0x3c3c3c3c a small positive fp32: finite inputs, no mask holes
+            if (b.fill && (e = hipMemsetAsync(*b.p, 0x3c, b.bytes, st)) != hipSuccess) { result = hip_fail(e, "hipMemsetAsync"); break; }
+        }
+        const void *ym = (flags & DP_RELU) ? y : nullptr;
+        float us[3] = {0, 0, 0};
+        for (int pass = 0; pass < 3 && result == DP_OK; ++pass) {
+            for (int it = 0; it < warmup + iters && result == DP_OK; ++it) {
+                if (it == warmup && (e = hipEventRecord(ev0, st)) != hipSuccess) { result = hip_fail(e, "hipEventRecord"); break; }
+                if (pass == 0) result = run_fwd(g, dtype, flags, x, w, (const float *)bias, y, ws, wsb, st);
+                else if (pass == 1) result = run_dgrad(g, dtype, flags, dy, ym, w, dx, ws, wsb, st);
+                else result = run_wgrad(g, dtype, x, dy, ym, (float *)dw, (float *)db, ws, wsb, st);
+            }
+            if (result != DP_OK) break;
+            if ((e = hipEventRecord(ev1, st)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess) { result = hip_fail(e, "hipEventSynchronize"); break; }
+            float ms = 0.f;
+            if ((e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) { result = hip_fail(e, "hipEventElapsedTime"); break; }
+            us[pass] = ms * 1000.f / (float)iters;
+        }
+        hipStreamSynchronize(st);
+        for (auto &b : bufs) if (*b.p) hipFree(*b.p);
+        if (result != DP_OK) break;
+        dp_profile_row &r = rows_out[bi];
+        r.batch = batches[bi];
+        r.fwd_us = us[0]; r.dgrad_us = us[1]; r.wgrad_us = us[2];
+        r.flops_per_pass = 2.0 * g.N * g.Ho * g.Wo * (double)g.K * g.R * g.S * g.C;
+        const double maskb = ym ? (double)ye * es : 0.0;
+        r.min_bytes_fwd = (double)xe * es + (double)we * es + (double)ye * es + ((flags & DP_BIAS) ? g.K * 4.0 : 0.0);
+        r.min_bytes_dgrad = (double)ye * es + maskb + (double)we * es + (double)xe * dxes;
+        r.min_bytes_wgrad = (double)xe * es + (double)ye * es + maskb + (double)we * 4 + g.K * 4.0;
+    }
+    hipEventDestroy(ev0);
+    hipEventDestroy(ev1);
+    return result;
+}
+
+}  // extern "C"

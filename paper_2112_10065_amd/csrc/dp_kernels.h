@@ -1,0 +1,67 @@
+// Internal interface between the C-ABI layer (dp_api.hip) and the kernel files.
+// Host-side launch functions take plain structs; no validation happens here.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+enum : unsigned {
+    KF_BIAS = 1u,     // add bias in the epilogue
+    KF_RELU = 2u,     // max(.,0) in the epilogue
+    KF_OUT_F32 = 4u,  // final output stored as fp32 instead of bf16
+};
+
+enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
+
+// Geometry of one conv layer plus its implicit-GEMM view for one pass.
+//   fwd   : A rows = c_out,  B rows = output pixels (n,p,q), reduction = (r,s,c)
+//   dgrad : A rows = c_in,   B rows = input pixels  (n,h,w), reduction = (r,s,k)
+//   wgrad : A rows = c_out,  B rows = filter taps   (r,s,c), reduction = output pixels
+// "A" / "B" are the matrix-core operands; D[i][j] has i over A rows, j over B rows.
+struct ConvGeom {
+    int N, H, W, C, K, R, S, sh, sw, ph, pw, Ho, Wo;
+};
+
+struct GemmPlan {
+    int variant;          // tile variant index (see tile table in conv_mfma.hip)
+    int TA, TB, BK;       // tile extents
+    int tilesA, tilesB;   // tile counts
+    int steps_total;      // reduction steps of BK
+    int steps_per_split;  // steps handled by one split
+    int splits;           // grid.y
+    bool vecA, vecB;      // 16-byte loads allowed for operand A / B
+};
+
+struct ConvArgs {
+    ConvGeom g;
+    GemmPlan plan;
+    int pass;
+    unsigned flags;
+    const bf16_t *x;      // fwd: x       dgrad: -        wgrad: x
+    const bf16_t *w;      // fwd: w       dgrad: w        wgrad: -
+    const bf16_t *dy;     // fwd: -       dgrad: dy       wgrad: dy
+    const bf16_t *ymask;  // saved post-ReLU output or nullptr (dgrad, wgrad)
+    const float *bias;    // fwd
+    void *out;            // fwd: y, dgrad: dx (bf16 or fp32), wgrad: dw (fp32)
+    float *partial;       // [splits][rowsB][rowsA] (fwd/dgrad) or [splits][rowsA][rowsB] (wgrad)
+};
+
+// conv_mfma.hip
+hipError_t mfma_init();                                      // raises dynamic LDS limits
+void mfma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
+size_t mfma_partial_bytes(const ConvGeom &g, int pass, const GemmPlan &plan);
+hipError_t mfma_launch(const ConvArgs &a, hipStream_t st);
+
+// conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
+hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,
+                        const float *bias, float *y, hipStream_t st);
+hipError_t f32_conv_dgrad(const ConvGeom &g, const float *dy, const float *ymask, const float *w,
+                          float *dx, hipStream_t st);
+hipError_t f32_conv_wgrad(const ConvGeom &g, const float *x, const float *dy, const float *ymask,
+                          float *dw, hipStream_t st);
+
+// pointwise.hip : ReLU-gradient / bias-gradient
+size_t rbg_workspace_bytes(long long rows, int k);
+hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask,
+                      void *g_out, float *dbias, float *ws, hipStream_t st);

@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI: the library loads, exports every declared symbol, and every
+argument error is reported before any launch (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dp():
+    from paper_2112_10065_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(dp):
+    hdr = open(os.path.join(ROOT, "include", "dp.h")).read()
+    declared = set(re.findall(r"\b(dp_[a-z0-9_]+)\s*\(", hdr))
+    assert {"dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
+            "dp_profile_layer"} <= declared
+    for name in declared:
+        assert hasattr(dp.lib, name), name
+    assert declared == set(dp.EXPORTS)
+    assert "gfx950" in dp.dp_version()
+
+
+def test_struct_sizes_match_header(dp):
+    assert C.sizeof(dp.dp_conv_desc) == 13 * 4
+    assert C.sizeof(dp.dp_linear_desc) == 5 * 4
+    assert C.sizeof(dp.dp_profile_row) == 48
+
+
+A = 0x1000  # fake, 16-byte aligned, never dereferenced: validation fails first
+
+
+def test_conv_argument_errors(dp):
+    lib = dp.lib
+    good = dp.conv_desc(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1), dp.DP_BF16, dp.DP_BIAS)
+    assert lib.dp_conv2d_fwd(None, A, A, A, A, None, 0, None) == dp.DP_ERR_NULL
+    assert lib.dp_conv2d_fwd(C.byref(good), None, A, A, A, None, 0, None) == dp.DP_ERR_NULL
+    assert b"x is NULL" in lib.dp_last_error()
+    assert lib.dp_conv2d_fwd(C.byref(good), A, A, None, A, None, 0, None) == dp.DP_ERR_NULL  # DP_BIAS without bias
+    assert lib.dp_conv2d_fwd(C.byref(good), A + 2, A, A, A, None, 0, None) == dp.DP_ERR_BAD_DESC  # misaligned
+    bad = dp.conv_desc(0, 16, 16, 16, 16, 3, 3)
+    assert lib.dp_conv2d_fwd(C.byref(bad), A, A, A, A, None, 0, None) == dp.DP_ERR_BAD_DESC
+    bad = dp.conv_desc(1, 2, 2, 4, 4, 3, 3)  # filter larger than the unpadded image
+    assert lib.dp_conv2d_bwd_data(C.byref(bad), A, None, A, A, None, 0, None) == dp.DP_ERR_BAD_DESC
+    bad = dp.conv_desc(1, 8, 8, 4, 4, 3, 3, io_dtype=7)
+    assert lib.dp_conv2d_bwd_filter(C.byref(bad), A, A, None, A, None, None, 0, None) == dp.DP_ERR_UNSUPPORTED
+    bad = dp.conv_desc(1, 8, 8, 4, 4, 3, 3, flags=1 << 20)
+    assert lib.dp_conv2d_fwd(C.byref(bad), A, A, A, A, None, 0, None) == dp.DP_ERR_UNSUPPORTED
+    bad = dp.conv_desc(1, 8, 8, 4, 4, 3, 3, io_dtype=dp.DP_F32, flags=dp.DP_DX_F32)
+    assert lib.dp_conv2d_fwd(C.byref(bad), A, A, A, A, None, 0, None) == dp.DP_ERR_UNSUPPORTED
+    huge = dp.conv_desc(1 << 12, 1 << 10, 1 << 10, 8, 8, 1, 1)
+    assert lib.dp_conv2d_fwd(C.byref(huge), A, A, A, A, None, 0, None) == dp.DP_ERR_BAD_DESC
+    assert dp.dp_conv2d_workspace_bytes(bad, 0) == 0
+    assert dp.dp_conv2d_workspace_bytes(good, 9) == 0
+
+
+def test_workspace_errors(dp):
+    lib = dp.lib
+    # backward-filter always splits its long reduction here -> needs scratch
+    d = dp.conv_desc(2, 56, 56, 64, 64, 3, 3, (1, 1), (1, 1), dp.DP_BF16, 0)
+    need = dp.dp_conv2d_workspace_bytes(d, dp.DP_PASS_WGRAD)
+    assert need > 0
+    assert lib.dp_conv2d_bwd_filter(C.byref(d), A, A, None, A, A, None, 0, None) == dp.DP_ERR_WORKSPACE
+    assert lib.dp_conv2d_bwd_filter(C.byref(d), A, A, None, A, A, A, 16, None) == dp.DP_ERR_WORKSPACE
+    ld = dp.linear_desc(4, 4096, 4096, dp.DP_BF16, 0)
+    assert dp.dp_linear_workspace_bytes(ld) > 0
+    assert lib.dp_linear_fwd_bwd(C.byref(ld), A, A, None, None, None, A, None, None, None, None, 0, None) == dp.DP_ERR_WORKSPACE
+    assert lib.dp_relu_bias_grad(100, 64, dp.DP_BF16, A, A, None, A, None, 0, None) == dp.DP_ERR_WORKSPACE
+    assert dp.dp_relu_bias_grad_workspace_bytes(100, 64) > 0
+
+
+def test_linear_and_pointwise_argument_errors(dp):
+    lib = dp.lib
+    ld = dp.linear_desc(4, 64, 32, dp.DP_BF16, dp.DP_BIAS)
+    N = None
+    assert lib.dp_linear_fwd_bwd(C.byref(ld), A, A, A, N, N, N, N, N, N, N, 0, N) == dp.DP_ERR_NULL  # nothing requested
+    assert lib.dp_linear_fwd_bwd(C.byref(ld), N, A, A, N, N, A, N, N, N, N, 0, N) == dp.DP_ERR_NULL  # y needs x
+    assert lib.dp_linear_fwd_bwd(C.byref(ld), A, A, A, N, N, N, A, N, N, N, 0, N) == dp.DP_ERR_NULL  # dx needs dy
+    assert lib.dp_linear_fwd_bwd(C.byref(dp.linear_desc(0, 64, 32)), A, A, A, N, N, A, N, N, N, N, 0, N) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_relu_bias_grad(0, 64, dp.DP_BF16, A, A, A, N, N, 0, N) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_relu_bias_grad(10, 64, dp.DP_BF16, A, A, N, N, N, 0, N) == dp.DP_ERR_NULL
+    assert lib.dp_relu_bias_grad(10, 64, 5, A, A, A, N, N, 0, N) == dp.DP_ERR_UNSUPPORTED
+
+
+def test_profile_and_override_argument_errors(dp):
+    lib = dp.lib
+    cd = dp.conv_desc(1, 8, 8, 8, 8, 3, 3, (1, 1), (1, 1))
+    ld = dp.linear_desc(1, 8, 8)
+    rows = (dp.dp_profile_row * 1)()
+    b = (C.c_int32 * 1)(1)
+    assert lib.dp_profile_layer(None, None, b, 1, 1, 1, rows, None) == dp.DP_ERR_NULL
+    assert lib.dp_profile_layer(C.byref(cd), C.byref(ld), b, 1, 1, 1, rows, None) == dp.DP_ERR_NULL
+    assert lib.dp_profile_layer(C.byref(cd), None, None, 1, 1, 1, rows, None) == dp.DP_ERR_NULL
+    assert lib.dp_profile_layer(C.byref(cd), None, b, 1, 1, 0, rows, None) == dp.DP_ERR_BAD_DESC
+    bneg = (C.c_int32 * 1)(-3)
+    assert lib.dp_profile_layer(C.byref(cd), None, bneg, 1, 1, 1, rows, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_set_override(5, 0, 0) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_set_override(0, -1, 0) == dp.DP_OK
+
+
+def test_no_gpu_fails_loudly(dp):
+    """On a host without a GPU a valid call must return DP_ERR_HIP, never succeed or fall back."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    d = dp.conv_desc(1, 8, 8, 8, 8, 3, 3, (1, 1), (1, 1), dp.DP_BF16, 0)
+    assert dp.lib.dp_conv2d_fwd(C.byref(d), A, A, None, A, None, 0, None) == dp.DP_ERR_HIP
+    assert dp.lib.dp_last_error() != b""

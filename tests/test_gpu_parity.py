@@ -1,0 +1,246 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances are the spec ones: fp32 path rel-L2 <= 1e-5; bf16-input path (fp32
+accumulation) rel-L2 <= 2e-2 and max-abs <= 5e-2.  Backward passes take the GPU forward's
+stored output as the saved activation on both sides, so a ReLU mask never differs.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(orc):
+    from paper_2112_10065_amd import binding as dp
+    import gpu_util as U
+    assert torch.cuda.is_available()
+    yield dp, U, orc
+    for p in range(3):
+        dp.dp_set_override(p, -1, 0)
+
+
+def check_case(dp, U, orc, case, what):
+    n, h, w, c, k, r, s = case.shape
+    st, pd = case.stride, case.pad
+    y = case.run_fwd()
+    dx = case.run_dgrad(y if case.relu else None)
+    dw, db = case.run_wgrad(y if case.relu else None)
+    torch.cuda.synchronize()
+    y_np = U.to_np(y)
+    ys = y_np if case.relu else None
+    ref_y = orc.conv2d_fwd(case.x, case.w, case.b, relu=case.relu, stride=st, pad=pd)
+    ref_dx = orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=ys, stride=st, pad=pd)
+    ref_dw, ref_db = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=ys, stride=st, pad=pd, want_db=True)
+    chk = U.assert_bf16_close if case.bf16 else U.assert_f32_close
+    chk(y_np, ref_y, f"{what} y")
+    chk(U.to_np(dx), ref_dx, f"{what} dx")
+    chk(U.to_np(dw), ref_dw, f"{what} dw")
+    chk(U.to_np(db), ref_db, f"{what} db")
+
+
+# ---- configuration 1: single 3x3 layer in fp32 ------------------------------------------
+@pytest.mark.parametrize("bias", [False, True])
+def test_config1_fp32(env, bias):
+    dp, U, orc = env
+    case = U.ConvCase("cfg1", 2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1), bf16=False, dist="he_uniform", bias=bias, relu=True)
+    check_case(dp, U, orc, case, f"config1 bias={bias}")
+
+
+def test_fp32_strided_asymmetric(env):
+    dp, U, orc = env
+    case = U.ConvCase("f32s", 3, 13, 11, 5, 7, 3, 5, (2, 1), (1, 2), bf16=False, dist="he_uniform", bias=True, relu=True)
+    check_case(dp, U, orc, case, "fp32 strided")
+
+
+# ---- bf16 matrix-core path: shapes that span several tiles with ragged tails ---------------
+BF16_CASES = [
+    # tag, n, h, w, c, k, r, s, stride, pad, bias, relu, dx_f32
+    ("vgg_like_64", 2, 28, 28, 64, 64, 3, 3, (1, 1), (1, 1), True, True, False),
+    ("vgg_like_128_256", 3, 14, 14, 128, 256, 3, 3, (1, 1), (1, 1), True, True, False),
+    ("rgb_3x3", 2, 20, 22, 3, 64, 3, 3, (1, 1), (1, 1), True, True, True),
+    ("stem_7x7_s2", 2, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3), False, False, True),
+    ("res_1x1", 2, 14, 14, 256, 64, 1, 1, (1, 1), (0, 0), False, False, False),
+    ("res_1x1_s2", 2, 14, 14, 128, 256, 1, 1, (2, 2), (0, 0), False, False, False),
+    ("res_3x3_s2", 2, 15, 15, 64, 64, 3, 3, (2, 2), (1, 1), False, True, False),
+    ("inc_1x7", 2, 17, 17, 128, 160, 1, 7, (1, 1), (0, 3), False, True, False),
+    ("inc_7x1", 2, 17, 17, 160, 128, 7, 1, (1, 1), (3, 0), False, False, False),
+    ("inc_c80", 1, 19, 19, 80, 192, 3, 3, (1, 1), (0, 0), False, True, False),
+    ("inc_3x3_s2_p0", 2, 17, 17, 32, 96, 3, 3, (2, 2), (0, 0), False, False, False),
+    ("odd_channels", 2, 9, 10, 24, 40, 3, 3, (1, 1), (1, 1), True, True, False),
+    ("k_not_mult8", 1, 8, 8, 16, 12, 3, 3, (1, 1), (1, 1), True, True, False),
+    ("tiny", 1, 1, 1, 1, 1, 1, 1, (1, 1), (0, 0), True, True, True),
+]
+
+
+@pytest.mark.parametrize("spec", BF16_CASES, ids=[c[0] for c in BF16_CASES])
+def test_bf16_conv_parity(env, spec):
+    dp, U, orc = env
+    tag, n, h, w, c, k, r, s, st, pd, bias, relu, dxf = spec
+    case = U.ConvCase(tag, n, h, w, c, k, r, s, st, pd, bf16=True, bias=bias, relu=relu, dx_f32=dxf)
+    check_case(dp, U, orc, case, tag)
+
+
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_every_tile_variant_and_split(env, variant, splits):
+    dp, U, orc = env
+    for p in range(3):
+        dp.dp_set_override(p, variant, splits)
+    try:
+        case = U.ConvCase("variants", 2, 13, 12, 72, 136, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+        check_case(dp, U, orc, case, f"variant {variant} splits {splits}")
+        case = U.ConvCase("variants_rgb", 1, 12, 12, 3, 40, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=True)
+        check_case(dp, U, orc, case, f"variant {variant} splits {splits} rgb")
+    finally:
+        for p in range(3):
+            dp.dp_set_override(p, -1, 0)
+
+
+def test_bitwise_deterministic(env):
+    dp, U, orc = env
+    case = U.ConvCase("det", 2, 28, 28, 64, 128, 3, 3, (1, 1), (1, 1), bf16=True)
+    y1 = case.run_fwd(); dw1, db1 = case.run_wgrad(y1); dx1 = case.run_dgrad(y1)
+    y2 = case.run_fwd(); dw2, db2 = case.run_wgrad(y2); dx2 = case.run_dgrad(y2)
+    torch.cuda.synchronize()
+    assert torch.equal(y1.view(torch.int16), y2.view(torch.int16))
+    assert torch.equal(dx1.view(torch.int16), dx2.view(torch.int16))
+    assert torch.equal(dw1, dw2) and torch.equal(db1, db2)
+
+
+# ---- dense layers ----------------------------------------------------------------------------
+@pytest.mark.parametrize("n,i,o,bf16", [(5, 200, 136, True), (32, 1024, 512, True), (1, 4096, 1000, True),
+                                        (3, 50, 20, False)])
+def test_linear_parity(env, n, i, o, bf16):
+    dp, U, orc = env
+    from paper_2112_10065_amd import synth
+    x, W, b = synth.linear_tensors(f"lin{n}_{i}_{o}", n, i, o)
+    dy = synth.upstream_grad(f"lin{n}_{i}_{o}", (n, o))
+    if bf16:
+        xb, Wb, dyb = (synth.f32_to_bf16_bits(a) for a in (x, W, dy))
+        x, W, dy = (synth.bf16_bits_to_f32(a) for a in (xb, Wb, dyb))
+        xd, Wd, dyd = U.bf16_dev(xb), U.bf16_dev(Wb), U.bf16_dev(dyb)
+        tdt = torch.bfloat16
+    else:
+        xd, Wd, dyd = (torch.from_numpy(a).to(U.DEV) for a in (x, W, dy))
+        tdt = torch.float32
+    bd = torch.from_numpy(b).to(U.DEV)
+    desc = dp.linear_desc(n, i, o, dp.DP_BF16 if bf16 else dp.DP_F32, dp.DP_BIAS | dp.DP_RELU)
+    ws = U.workspace(dp.dp_linear_workspace_bytes(desc))
+    y = torch.empty((n, o), dtype=tdt, device=U.DEV)
+    dx = torch.empty((n, i), dtype=tdt, device=U.DEV)
+    dW = torch.empty((o, i), dtype=torch.float32, device=U.DEV)
+    db = torch.empty((o,), dtype=torch.float32, device=U.DEV)
+    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, bias=bd, y=y, ws=ws)                      # forward half
+    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, dy=dyd, y_saved=y, dx=dx, dW=dW, dbias=db, ws=ws)  # backward half
+    torch.cuda.synchronize()
+    y_np = U.to_np(y)
+    chk = U.assert_bf16_close if bf16 else U.assert_f32_close
+    chk(y_np, orc.linear_fwd(x, W, b, relu=True), "linear y")
+    rdx, rdW, rdb = orc.linear_bwd(x, W, dy, y_np)
+    chk(U.to_np(dx), rdx, "linear dx")
+    chk(U.to_np(dW), rdW, "linear dW")
+    chk(U.to_np(db), rdb, "linear db")
+
+
+# ---- ReLU / bias gradient -----------------------------------------------------------------
+@pytest.mark.parametrize("rows,k,bf16", [(1000, 64, True), (777, 512, True), (50, 4096, True), (33, 1000, True),
+                                         (300, 24, True), (65, 12, True), (130, 16, False)])
+def test_relu_bias_grad(env, rows, k, bf16):
+    dp, U, orc = env
+    from paper_2112_10065_amd import synth
+    dy = synth.normal(f"rbg{rows}_{k}/dy", (rows, k))
+    y = np.maximum(synth.normal(f"rbg{rows}_{k}/y", (rows, k)), 0).astype(np.float32)
+    if bf16:
+        dyb, yb = synth.f32_to_bf16_bits(dy), synth.f32_to_bf16_bits(y)
+        dy, y = synth.bf16_bits_to_f32(dyb), synth.bf16_bits_to_f32(yb)
+        dyd, yd = U.bf16_dev(dyb), U.bf16_dev(yb)
+    else:
+        dyd, yd = torch.from_numpy(dy).to(U.DEV), torch.from_numpy(y).to(U.DEV)
+    g = torch.empty_like(dyd)
+    db = torch.empty((k,), dtype=torch.float32, device=U.DEV)
+    ws = U.workspace(dp.dp_relu_bias_grad_workspace_bytes(rows, k))
+    dp.dp_relu_bias_grad(rows, k, dp.DP_BF16 if bf16 else dp.DP_F32, dyd, yd, g, db, ws)
+    torch.cuda.synchronize()
+    rg, rdb = orc.relu_bias_grad(dy, y)
+    np.testing.assert_array_equal(U.to_np(g), rg.astype(np.float32))  # masking is exact
+    rel, mx = U.errs(U.to_np(db), rdb)
+    assert rel <= 1e-5, (rel, mx)
+
+
+# ---- full-size layers of the benchmark workload, spot-checked --------------------------------
+FULL = [("conv1_1", 224, 3, 64, 8, True), ("conv1_2", 224, 64, 64, 4, False), ("conv3_2", 56, 256, 256, 32, False),
+        ("conv5_1", 14, 512, 512, 2, False), ("conv5_1", 14, 512, 512, 32, False)]
+
+
+@pytest.mark.parametrize("name,hw,c,k,n,dxf", FULL, ids=[f"{f[0]}_n{f[4]}" for f in FULL])
+def test_vgg_layer_full_size_sampled(env, name, hw, c, k, n, dxf):
+    dp, U, orc = env
+    case = U.ConvCase(f"vgg/{name}", n, hw, hw, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=dxf)
+    y = case.run_fwd()
+    dx = case.run_dgrad(y)
+    dw, db = case.run_wgrad(y)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(7)
+    y_np = U.to_np(y)
+    # border pixels are always part of the sample
+    idx = rng.integers(0, y_np.size, 3000)
+    idx[:64] = np.arange(64)
+    idx[64:128] = y_np.size - 1 - np.arange(64)
+    U.assert_bf16_close(y_np.ravel()[idx], orc.conv2d_fwd_at(case.x, case.w, case.b, True, (1, 1), (1, 1), idx), f"{name} y")
+    dx_np = U.to_np(dx)
+    idx = rng.integers(0, dx_np.size, 3000)
+    idx[:32] = np.arange(32)
+    idx[32:64] = dx_np.size - 1 - np.arange(32)
+    U.assert_bf16_close(dx_np.ravel()[idx], orc.conv2d_bwd_data_at(case.dy, case.w, case.x.shape, y_np, (1, 1), (1, 1), idx), f"{name} dx")
+    dw_np = U.to_np(dw)
+    idx = rng.integers(0, dw_np.size, 600)
+    U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, y_np, (1, 1), (1, 1), idx), f"{name} dw")
+
+
+def test_fc6_full_size_sampled(env):
+    dp, U, orc = env
+    from paper_2112_10065_amd import synth
+    n, i, o = 32, 25088, 4096
+    x, W, b = synth.linear_tensors("vgg/fc6", n, i, o)
+    dy = synth.upstream_grad("vgg/fc6", (n, o))
+    xb, Wb, dyb = (synth.f32_to_bf16_bits(a) for a in (x, W, dy))
+    x, W, dy = (synth.bf16_bits_to_f32(a) for a in (xb, Wb, dyb))
+    xd, Wd, dyd = U.bf16_dev(xb), U.bf16_dev(Wb), U.bf16_dev(dyb)
+    bd = torch.from_numpy(b).to(U.DEV)
+    desc = dp.linear_desc(n, i, o, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
+    ws = U.workspace(dp.dp_linear_workspace_bytes(desc))
+    y = torch.empty((n, o), dtype=torch.bfloat16, device=U.DEV)
+    dx = torch.empty((n, i), dtype=torch.bfloat16, device=U.DEV)
+    dW = torch.empty((o, i), dtype=torch.float32, device=U.DEV)
+    db = torch.empty((o,), dtype=torch.float32, device=U.DEV)
+    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, bias=bd, y=y, ws=ws)
+    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, dy=dyd, y_saved=y, dx=dx, dW=dW, dbias=db, ws=ws)
+    torch.cuda.synchronize()
+    y_np = U.to_np(y)
+    rng = np.random.default_rng(11)
+    idx = rng.integers(0, n * o, 4000)
+    U.assert_bf16_close(y_np.ravel()[idx], orc.linear_fwd_at(x, W, b, True, idx), "fc6 y")
+    idx = rng.integers(0, n * i, 4000)
+    U.assert_bf16_close(U.to_np(dx).ravel()[idx], orc.linear_dx_at(W, dy, y_np, idx), "fc6 dx")
+    idx = rng.integers(0, o * i, 20000)
+    U.assert_bf16_close(U.to_np(dW).ravel()[idx], orc.linear_dw_at(x, dy, y_np, idx), "fc6 dW")
+    _, rdb = orc.relu_bias_grad(dy, y_np)
+    rel, _ = U.errs(U.to_np(db), rdb)
+    assert rel <= 1e-5
+
+
+# ---- the planner's table --------------------------------------------------------------------
+def test_profile_layer_rows(env):
+    dp, U, orc = env
+    d = dp.conv_desc(1, 28, 28, 256, 512, 3, 3, (1, 1), (1, 1), dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
+    rows = dp.dp_profile_layer(conv=d, batches=(1, 2, 4), warmup=2, iters=5)
+    assert [r["batch"] for r in rows] == [1, 2, 4]
+    for r in rows:
+        assert r["fwd_us"] > 0 and r["dgrad_us"] > 0 and r["wgrad_us"] > 0
+        assert r["flops_per_pass"] == 2.0 * r["batch"] * 28 * 28 * 512 * 9 * 256
+        assert r["min_bytes_fwd"] > 0
+    ld = dp.linear_desc(1, 4096, 1000, dp.DP_BF16, dp.DP_BIAS)
+    rows = dp.dp_profile_layer(linear=ld, batches=(1, 32), warmup=1, iters=3)
+    assert rows[1]["flops_per_pass"] == 2.0 * 32 * 4096 * 1000 and rows[0]["wgrad_us"] > 0
