@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Benchmark: VGG-16 per-layer training compute (conv + FC, forward and backward) at the
+strong-scaling per-GPU batches 1..32 on one MI355X.
+
+A step = one pass of the whole hot path: for every per-GPU batch N in {1,2,4,8,16,32} and
+every one of the 16 compute layers: forward (bias+ReLU fused), backward-data (ReLU mask
+fused), backward-filter + bias gradient.  Inputs are seeded synthetic tensors already
+resident in HBM.  value = nominal flops of the step / time (TFLOP/s); nominal flops per
+pass = 2*N*Ho*Wo*K*R*S*C (padding taps counted), three passes per layer.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batches", type=str, default="1,2,4,8,16,32")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--table", type=str, default="", help="also write the per-layer time-vs-batch table (JSON) here")
+    return ap.parse_args()
+
+
+class Layer:
+    """Device tensors of one layer at the largest batch; smaller batches use the leading samples."""
+
+    def __init__(self, torch, dp, spec, nmax, gen, dev, is_conv):
+        self.spec, self.is_conv, self.name = spec, is_conv, spec.name
+        bf = torch.bfloat16
+        if is_conv:
+            l = spec
+            self.ho = (l.h + 2 * l.ph - l.r) // l.sh + 1
+            self.wo = (l.w + 2 * l.pw - l.s) // l.sw + 1
+            fan_in = l.r * l.s * l.c
+            self.x = torch.randn((nmax, l.h, l.w, l.c), generator=gen, device=dev, dtype=torch.float32).to(bf)
+            self.w = (torch.randn((l.k, l.r, l.s, l.c), generator=gen, device=dev) * (2.0 / fan_in) ** 0.5).to(bf)
+            self.dy = torch.randn((nmax, self.ho, self.wo, l.k), generator=gen, device=dev, dtype=torch.float32).to(bf)
+            self.y = torch.empty((nmax, self.ho, self.wo, l.k), device=dev, dtype=bf)
+            self.dx_f32 = l.c < 8   # first layer: input gradient kept in fp32
+            self.dx = torch.empty((nmax, l.h, l.w, l.c), device=dev, dtype=torch.float32 if self.dx_f32 else bf)
+            self.dw = torch.empty((l.k, l.r, l.s, l.c), device=dev, dtype=torch.float32)
+            self.k = l.k
+        else:
+            l = spec
+            self.x = torch.randn((nmax, l.in_f), generator=gen, device=dev, dtype=torch.float32).to(bf)
+            self.w = (torch.randn((l.out_f, l.in_f), generator=gen, device=dev) * (2.0 / l.in_f) ** 0.5).to(bf)
+            self.dy = torch.randn((nmax, l.out_f), generator=gen, device=dev, dtype=torch.float32).to(bf)
+            self.y = torch.empty((nmax, l.out_f), device=dev, dtype=bf)
+            self.dx = torch.empty((nmax, l.in_f), device=dev, dtype=bf)
+            self.dw = torch.empty((l.out_f, l.in_f), device=dev, dtype=torch.float32)
+            self.k = l.out_f
+        self.bias = (torch.rand((self.k,), generator=gen, device=dev) * 0.2 - 0.1).float()
+        self.db = torch.empty((self.k,), device=dev, dtype=torch.float32)
+
+    def desc(self, dp, n):
+        l = self.spec
+        if self.is_conv:
+            flags = dp.DP_BIAS | dp.DP_RELU | (dp.DP_DX_F32 if self.dx_f32 else 0)
+            return dp.conv_desc(n, l.h, l.w, l.c, l.k, l.r, l.s, (l.sh, l.sw), (l.ph, l.pw), dp.DP_BF16, flags)
+        return dp.linear_desc(n, l.in_f, l.out_f, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
+
+    def flops(self, n):
+        l = self.spec
+        if self.is_conv:
+            return 2.0 * n * self.ho * self.wo * l.k * l.r * l.s * l.c
+        return 2.0 * n * l.in_f * l.out_f
+
+    def ws_bytes(self, dp, n):
+        d = self.desc(dp, n)
+        if self.is_conv:
+            return max(dp.dp_conv2d_workspace_bytes(d, p) for p in range(3))
+        return dp.dp_linear_workspace_bytes(d)
+
+    # the three passes; each is one library call
+    def fwd(self, dp, d, ws):
+        if self.is_conv:
+            dp.dp_conv2d_fwd(d, self.x, self.w, self.bias, self.y, ws)
+        else:
+            dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws)
+
+    def dgrad(self, dp, d, ws):
+        if self.is_conv:
+            dp.dp_conv2d_bwd_data(d, self.dy, self.y, self.w, self.dx, ws)
+        else:
+            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.dy, y_saved=self.y, dx=self.dx, ws=ws)
+
+    def wgrad(self, dp, d, ws):
+        if self.is_conv:
+            dp.dp_conv2d_bwd_filter(d, self.x, self.dy, self.y, self.dw, self.db, ws)
+        else:
+            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.dy, y_saved=self.y, dW=self.dw, dbias=self.db, ws=ws)
+
+
+def cpu_baseline():
+    """Time the fp64 oracle (as it stands) on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2112_10065_amd import synth
+    sample = [("conv3_2", 56, 256, 256, 1), ("conv4_2", 28, 512, 512, 1), ("conv5_1", 14, 512, 512, 2)]
+    flops, secs = 0.0, 0.0
+    for name, hw, c, k, n in sample:
+        x, w, b = synth.conv_tensors(f"vgg/{name}", n, hw, hw, c, k, 3, 3)
+        x, w = synth.round_bf16(x), synth.round_bf16(w)
+        dy = synth.round_bf16(synth.upstream_grad(f"vgg/{name}", (n, hw, hw, k)))
+        t0 = time.perf_counter()
+        y = oracle.conv2d_fwd(x, w, b, relu=True, pad=(1, 1))
+        oracle.conv2d_bwd_data(dy, w, x.shape, y_saved=y, pad=(1, 1))
+        oracle.conv2d_bwd_filter(x, dy, w.shape, y_saved=y, pad=(1, 1), want_db=True)
+        secs += time.perf_counter() - t0
+        flops += 3 * 2.0 * n * hw * hw * k * 9 * c
+    return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "fp64 nested-loop oracle, fwd+dgrad+wgrad of VGG-16 conv3_2 (N=1), conv4_2 (N=1), conv5_1 (N=2); "
+                      f"{flops / 1e9:.1f} GFLOP nominal in {secs:.1f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2112_10065_amd import binding as dp, workloads as W
+
+    if not torch.cuda.is_available():
+        print("no GPU visible: the HIP library cannot run", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20211210)
+    batches = [int(b) for b in args.batches.split(",")]
+    nmax = max(batches)
+
+    layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in W.vgg16_convs()]
+    layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in W.vgg16_linears()]
+    ws_bytes = max(l.ws_bytes(dp, n) for l in layers for n in batches)
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
+    descs = {(l.name, n): l.desc(dp, n) for l in layers for n in batches}
+
+    def step():
+        for n in batches:
+            for l in layers:
+                d = descs[(l.name, n)]
+                l.fwd(dp, d, ws)
+                l.dgrad(dp, d, ws)
+                l.wgrad(dp, d, ws)
+
+    flops_step = sum(3 * l.flops(n) for l in layers for n in batches)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = flops_step / (elapsed / args.steps) / 1e12
+
+    # ---- instrumented steps: HIP events (on the launch stream) around every library call ----
+    stream = torch.cuda.current_stream()
+    calls = []
+    for _ in range(args.steps):
+        for n in batches:
+            for l in layers:
+                d = descs[(l.name, n)]
+                for pname, fn in (("fwd", l.fwd), ("dgrad", l.dgrad), ("wgrad", l.wgrad)):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    fn(dp, d, ws)
+                    e1.record(stream)
+                    calls.append((l, n, pname, e0, e1))
+    torch.cuda.synchronize()
+    per = {}
+    for l, n, pname, e0, e1 in calls:
+        per.setdefault((l.name, n, pname), []).append(e0.elapsed_time(e1) * 1e3)  # microseconds
+    table = {}
+    for (lname, n, pname), v in per.items():
+        table.setdefault(lname, {}).setdefault(str(n), {})[pname + "_us"] = sum(v) / len(v)
+
+    # per-batch throughput (fraction of the bf16 dense MFMA peak) over all 16 layers
+    per_batch = {}
+    for n in batches:
+        us = sum(sum(per[(l.name, n, p)]) / len(per[(l.name, n, p)]) for l in layers for p in ("fwd", "dgrad", "wgrad"))
+        fl = sum(3 * l.flops(n) for l in layers)
+        per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us}
+
+    # dominant kernel: the conv kernel instantiation with the largest total time among calls
+    # that are a single launch (no split reduction, no separate bias-gradient kernel)
+    groups = {}
+    for l in layers:
+        if not l.is_conv:
+            continue
+        for n in batches:
+            for pi, pname in enumerate(("fwd", "dgrad")):
+                kname, splits = dp.dp_conv2d_kernel_info(descs[(l.name, n)], pi)
+                if splits != 1:
+                    continue
+                v = per[(l.name, n, pname)]
+                g = groups.setdefault(kname, {"us": 0.0, "launches": 0, "flops": 0.0})
+                g["us"] += sum(v)
+                g["launches"] += len(v)
+                g["flops"] += l.flops(n) * len(v)
+    roofline = None
+    if groups:
+        kname, g = max(groups.items(), key=lambda kv: kv[1]["us"])
+        achieved = g["flops"] / g["us"] / 1e6
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": kname,
+                    "avg_launch_us": g["us"] / g["launches"], "launches": g["launches"],
+                    "flops_per_launch_avg": g["flops"] / g["launches"]}
+
+    out = {
+        "metric": "conv+FC fwd/bwd TFLOP/s and % bf16 MFMA peak vs per-GPU batch 1-32 (VGG-16)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "strong", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
+        "config": {"workload": "VGG-16 13 conv + 3 FC layers, 224x224x3 input, fwd + dgrad + wgrad(+dbias) per layer, "
+                               "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
+                   "batches": batches, "flops_per_step": flops_step},
+        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,
+        "per_batch": per_batch,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    if args.table:
+        with open(args.table, "w") as f:
+            json.dump(table, f, indent=1)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

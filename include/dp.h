@@ -144,6 +144,13 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
                            const int32_t *batches, int32_t n_batches, int32_t warmup,
                            int32_t iters, dp_profile_row *rows_out, void *hip_stream);
 
+/* Names the main kernel this pass of the layer would launch, as the profiler prints it
+ * (e.g. "k_conv_gemm<0, 128, 128, 32, 2, 2, true, true>"), and its number of reduction
+ * splits (> 1 means a second, small reduction kernel follows).  Host-only, no launch.
+ * name: host buffer of name_bytes; either output pointer may be NULL. */
+dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, size_t name_bytes,
+                                int32_t *splits);
+
 /* Tuning hook: force the tile variant (>= 0) and/or the number of reduction splits (> 0)
  * used by the given pass; -1 / 0 restore the built-in choice.  Process-wide. */
 dp_status dp_set_override(int pass, int tile_variant, int splits);

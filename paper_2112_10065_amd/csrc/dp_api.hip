@@ -83,16 +83,24 @@ dp_status check_opt(const void *p, const char *name)
     return DP_OK;
 }
 
+// tile_variant override: -1 built-in choice (fast path when the shape allows), 0..99 generic
+// kernel variant, 100.. fast-path variant (falls back to the generic kernel if not eligible)
 void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
 {
-    mfma_plan(g, pass, g_force_variant[pass].load(), g_force_splits[pass].load(), pl);
+    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
+    if ((fv < 0 || fv >= 100) && fast_plan(g, pass, fv, fs, pl)) return;
+    mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
 }
+
+hipError_t launch_plan(const ConvArgs &a, hipStream_t st) { return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st); }
+
+size_t ybytes(const ConvGeom &g) { return (size_t)g.N * g.Ho * g.Wo * g.K * 2; }
 
 size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 dp_status ensure_init()
 {
-    std::call_once(g_init_once, [] { g_init_err = mfma_init(); });
+    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); });
     if (g_init_err != hipSuccess) return hip_fail(g_init_err, "library initialisation (is a gfx950 device present?)");
     return DP_OK;
 }
@@ -119,8 +127,15 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     size_t need = mfma_partial_bytes(g, PASS_FWD, a.plan);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.x = (const bf16_t *)x; a.w = (const bf16_t *)w; a.bias = bias; a.out = y; a.partial = (float *)ws;
-    hipError_t e = mfma_launch(a, st);
+    hipError_t e = launch_plan(a, st);
     return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
+}
+
+size_t dgrad_ws_bytes(const ConvGeom &g, const GemmPlan &pl)
+{
+    size_t need = round256(mfma_partial_bytes(g, PASS_DGRAD, pl));
+    if (pl.fast) need += round256(ybytes(g));   // room for the masked gradient
+    return need;
 }
 
 dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy, const void *ym, const void *w, void *dx,
@@ -133,10 +148,17 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
     ConvArgs a{};
     a.g = g; a.pass = PASS_DGRAD; a.flags = (flags & DP_DX_F32) ? KF_OUT_F32 : 0u;
     plan_for(g, PASS_DGRAD, &a.plan);
-    size_t need = mfma_partial_bytes(g, PASS_DGRAD, a.plan);
+    size_t need = dgrad_ws_bytes(g, a.plan);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
-    hipError_t e = mfma_launch(a, st);
+    if (a.plan.fast && ym != nullptr) {
+        // the fast kernel takes a pre-masked gradient: materialise g = dy * [y_saved > 0] once
+        void *gbuf = (char *)ws + round256(mfma_partial_bytes(g, PASS_DGRAD, a.plan));
+        hipError_t e = rbg_launch((long long)g.N * g.Ho * g.Wo, g.K, true, dy, ym, gbuf, nullptr, nullptr, st);
+        if (e != hipSuccess) return hip_fail(e, "ReLU-gradient launch");
+        a.dy = (const bf16_t *)gbuf; a.ymask = nullptr;
+    }
+    hipError_t e = launch_plan(a, st);
     return e == hipSuccess ? DP_OK : hip_fail(e, "backward-data launch");
 }
 
@@ -147,38 +169,52 @@ size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
         GemmPlan pl;
         plan_for(g, PASS_WGRAD, &pl);
         need = round256(mfma_partial_bytes(g, PASS_WGRAD, pl));
+        if (pl.fast) need += round256(ybytes(g));
     }
     if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
     return need;
 }
 
+// workspace layout: [split partials | masked gradient (fast path) | bias-gradient scratch]
 dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy, const void *ym, float *dw, float *db,
                     void *ws, size_t ws_bytes, hipStream_t st)
 {
     size_t need = wgrad_ws_bytes(g, dtype, db != nullptr);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-filter needs %zu workspace bytes, got %zu", need, ws_bytes);
-    size_t part = 0;
-    if (dw != nullptr) {
-        if (dtype == DP_F32) {
+    const long long rows = (long long)g.N * g.Ho * g.Wo;
+    if (dtype == DP_F32) {
+        if (dw != nullptr) {
             hipError_t e = f32_conv_wgrad(g, (const float *)x, (const float *)dy, (const float *)ym, dw, st);
             if (e != hipSuccess) return hip_fail(e, "fp32 backward-filter launch");
-        } else {
-            ConvArgs a{};
-            a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
-            plan_for(g, PASS_WGRAD, &a.plan);
-            part = round256(mfma_partial_bytes(g, PASS_WGRAD, a.plan));
-            a.x = (const bf16_t *)x; a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.out = dw; a.partial = (float *)ws;
-            hipError_t e = mfma_launch(a, st);
-            if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
         }
-    } else if (dtype == DP_BF16) {
-        GemmPlan pl;
-        plan_for(g, PASS_WGRAD, &pl);
-        part = round256(mfma_partial_bytes(g, PASS_WGRAD, pl));
+        if (db != nullptr) {
+            hipError_t e = rbg_launch(rows, g.K, false, dy, ym, nullptr, db, (float *)ws, st);
+            if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
+        }
+        return DP_OK;
     }
-    if (db != nullptr) {
-        hipError_t e = rbg_launch((long long)g.N * g.Ho * g.Wo, g.K, dtype == DP_BF16, dy, ym, nullptr, db,
-                                  (float *)((char *)ws + part), st);
+    ConvArgs a{};
+    a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
+    plan_for(g, PASS_WGRAD, &a.plan);
+    const size_t part = round256(mfma_partial_bytes(g, PASS_WGRAD, a.plan));
+    const size_t gb = a.plan.fast ? round256(ybytes(g)) : 0;
+    void *gbuf = (char *)ws + part;
+    float *rws = (float *)((char *)ws + part + gb);
+    a.x = (const bf16_t *)x; a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.out = dw; a.partial = (float *)ws;
+    bool db_done = false;
+    if (a.plan.fast && ym != nullptr && dw != nullptr) {
+        // one pointwise pass yields both the masked gradient for the fast kernel and the bias gradient
+        hipError_t e = rbg_launch(rows, g.K, true, dy, ym, gbuf, db, rws, st);
+        if (e != hipSuccess) return hip_fail(e, "ReLU/bias-gradient launch");
+        a.dy = (const bf16_t *)gbuf; a.ymask = nullptr;
+        db_done = true;
+    }
+    if (dw != nullptr) {
+        hipError_t e = launch_plan(a, st);
+        if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
+    }
+    if (db != nullptr && !db_done) {
+        hipError_t e = rbg_launch(rows, g.K, true, dy, ym, nullptr, db, rws, st);
         if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
     }
     return DP_OK;
@@ -201,6 +237,25 @@ dp_status dp_set_override(int pass, int tile_variant, int splits)
     return DP_OK;
 }
 
+dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, size_t name_bytes, int32_t *splits)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_conv(desc, &g)) != DP_OK) return s;
+    if (pass < 0 || pass > 2) return fail(DP_ERR_UNSUPPORTED, "pass must be 0, 1 or 2");
+    if (desc->io_dtype == DP_F32) {
+        static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
+        if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    GemmPlan pl;
+    plan_for(g, pass, &pl);
+    if (name != nullptr && name_bytes > 0) { if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
+    if (splits != nullptr) *splits = pl.splits;
+    return DP_OK;
+}
+
 size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
 {
     ConvGeom g;
@@ -209,7 +264,7 @@ size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
     if (desc->io_dtype == DP_F32) return 0;
     GemmPlan pl;
     plan_for(g, pass, &pl);
-    return mfma_partial_bytes(g, pass, pl);
+    return pass == DP_PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
 }
 
 size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
@@ -221,7 +276,7 @@ size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
         for (int pass = 0; pass < 2; ++pass) {
             GemmPlan pl;
             plan_for(g, pass, &pl);
-            size_t b = mfma_partial_bytes(g, pass, pl);
+            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
             if (b > need) need = b;
         }
     }
@@ -258,7 +313,7 @@ dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const voi
     if (desc->io_dtype == DP_BF16) {
         GemmPlan pl;
         plan_for(g, PASS_DGRAD, &pl);
-        size_t need = mfma_partial_bytes(g, PASS_DGRAD, pl);
+        size_t need = dgrad_ws_bytes(g, pl);
         if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     }
     if ((s = ensure_init()) != DP_OK) return s;
@@ -366,7 +421,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
             for (int pass = 0; pass < 2; ++pass) {
                 GemmPlan pl;
                 plan_for(g, pass, &pl);
-                size_t b = mfma_partial_bytes(g, pass, pl);
+                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
                 if (b > wsb) wsb = b;
             }
         const size_t dxes = (flags & DP_DX_F32) ? 4 : es;

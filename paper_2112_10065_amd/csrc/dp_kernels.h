@@ -31,6 +31,7 @@ struct GemmPlan {
     int steps_per_split;  // steps handled by one split
     int splits;           // grid.y
     bool vecA, vecB;      // 16-byte loads allowed for operand A / B
+    bool fast;            // fast-path kernel (conv_fast.hip) instead of the generic one
 };
 
 struct ConvArgs {
@@ -52,6 +53,14 @@ hipError_t mfma_init();                                      // raises dynamic L
 void mfma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
 size_t mfma_partial_bytes(const ConvGeom &g, int pass, const GemmPlan &plan);
 hipError_t mfma_launch(const ConvArgs &a, hipStream_t st);
+void mfma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
+hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStream_t st);  // sums a.partial into a.out
+
+// conv_fast.hip : fast path for channel counts that are multiples of the reduction step
+hipError_t fast_init();
+bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
+hipError_t fast_launch(const ConvArgs &a, hipStream_t st);
+void fast_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
 
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
 hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,

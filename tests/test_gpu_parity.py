@@ -98,6 +98,53 @@ def test_every_tile_variant_and_split(env, variant, splits):
             dp.dp_set_override(p, -1, 0)
 
 
+@pytest.mark.parametrize("variant", [100, 101, 102, 103])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_every_fast_variant_and_split(env, variant, splits):
+    """Fast-path kernels (buffer loads, LDS transpose reads), every tile shape, split and unsplit."""
+    dp, U, orc = env
+    for p in range(3):
+        dp.dp_set_override(p, variant, splits)
+    try:
+        # c_in % 64 == 0 and c_out % 32 == 0 (reduction step 64 forward, 32 backward-data), ragged tiles
+        case = U.ConvCase("fastv", 2, 13, 12, 64, 96, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+        names = [dp.dp_conv2d_kernel_info(case.desc, p)[0] for p in range(3)]
+        assert all("fast" in n for n in names), names
+        check_case(dp, U, orc, case, f"fast variant {variant} splits {splits}")
+        # c_in % 32 == 0 only, 1x7 filter, backward-filter with stride 2 falls on the fast path too
+        case = U.ConvCase("fastv2", 2, 11, 17, 96, 64, 1, 7, (1, 1), (0, 3), bf16=True, bias=False, relu=False)
+        check_case(dp, U, orc, case, f"fast variant {variant} splits {splits} 1x7")
+        case = U.ConvCase("fastv3", 3, 15, 14, 32, 40, 3, 3, (2, 2), (1, 1), bf16=True, bias=True, relu=True)
+        check_case(dp, U, orc, case, f"fast variant {variant} splits {splits} stride 2")
+    finally:
+        for p in range(3):
+            dp.dp_set_override(p, -1, 0)
+
+
+def test_unfused_relu_gradient_flow(env):
+    """dp_relu_bias_grad materialises the masked gradient once; both backward passes then take it
+    with y_saved = NULL and must agree with the oracle's masked definitions."""
+    dp, U, orc = env
+    case = U.ConvCase("unfused", 2, 28, 28, 64, 128, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+    n, h, w, c, k, r, s = case.shape
+    y = case.run_fwd()
+    g = torch.empty_like(case.dyd)
+    db = torch.empty((k,), dtype=torch.float32, device=U.DEV)
+    rows = n * case.ho * case.wo
+    ws = U.workspace(max(dp.dp_relu_bias_grad_workspace_bytes(rows, k), *(dp.dp_conv2d_workspace_bytes(case.desc, p) for p in range(3))))
+    dp.dp_relu_bias_grad(rows, k, dp.DP_BF16, case.dyd, y, g, db, ws)
+    dx = torch.empty((n, h, w, c), dtype=torch.bfloat16, device=U.DEV)
+    dw = torch.empty((k, r, s, c), dtype=torch.float32, device=U.DEV)
+    dp.dp_conv2d_bwd_data(case.desc, g, None, case.wd, dx, ws)
+    dp.dp_conv2d_bwd_filter(case.desc, case.xd, g, None, dw, None, ws)
+    torch.cuda.synchronize()
+    y_np = U.to_np(y)
+    U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=y_np, pad=(1, 1)), "unfused dx")
+    rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=y_np, pad=(1, 1), want_db=True)
+    U.assert_bf16_close(U.to_np(dw), rdw, "unfused dw")
+    U.assert_bf16_close(U.to_np(db), rdb, "unfused db")
+
+
 def test_bitwise_deterministic(env):
     dp, U, orc = env
     case = U.ConvCase("det", 2, 28, 28, 64, 128, 3, 3, (1, 1), (1, 1), bf16=True)
