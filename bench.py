@@ -3,8 +3,10 @@
 strong-scaling per-GPU batches 1..32 on one MI355X.
 
 A step = one pass of the whole hot path: for every per-GPU batch N in {1,2,4,8,16,32} and
-every one of the 16 compute layers: forward (bias+ReLU fused), backward-data (ReLU mask
-fused), backward-filter + bias gradient.  Inputs are seeded synthetic tensors already
+every one of the 16 compute layers: forward (bias+ReLU fused), ReLU-gradient + bias-gradient
+(one pointwise pass that yields the masked upstream gradient), backward-data, backward-filter.
+The first layer's backward-data is not part of the step (a training step never needs the
+gradient of the input image); it is timed separately for the per-layer table.  Inputs are seeded synthetic tensors already
 resident in HBM.  value = nominal flops of the step / time (TFLOP/s); nominal flops per
 pass = 2*N*Ho*Wo*K*R*S*C (padding taps counted), three passes per layer.
 
@@ -65,6 +67,8 @@ class Layer:
             self.k = l.out_f
         self.bias = (torch.rand((self.k,), generator=gen, device=dev) * 0.2 - 0.1).float()
         self.db = torch.empty((self.k,), device=dev, dtype=torch.float32)
+        self.g = torch.empty_like(self.dy)          # masked upstream gradient dy * [y > 0]
+        self.needs_dx = not (is_conv and spec.c < 8)  # the network input needs no gradient
 
     def desc(self, dp, n):
         l = self.spec
@@ -81,9 +85,13 @@ class Layer:
 
     def ws_bytes(self, dp, n):
         d = self.desc(dp, n)
+        rb = dp.dp_relu_bias_grad_workspace_bytes(self.rows(n), self.k)
         if self.is_conv:
-            return max(dp.dp_conv2d_workspace_bytes(d, p) for p in range(3))
-        return dp.dp_linear_workspace_bytes(d)
+            return max(rb, *(dp.dp_conv2d_workspace_bytes(d, p) for p in range(3)))
+        return max(rb, dp.dp_linear_workspace_bytes(d))
+
+    def rows(self, n):
+        return n * self.ho * self.wo if self.is_conv else n
 
     # the three passes; each is one library call
     def fwd(self, dp, d, ws):
@@ -92,17 +100,32 @@ class Layer:
         else:
             dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws)
 
+    def rgrad(self, dp, d, ws):
+        """g = dy * [y > 0] and db = column sums of g, in one pointwise pass."""
+        dp.dp_relu_bias_grad(self.rows(d.n), self.k, dp.DP_BF16, self.dy, self.y, self.g, self.db, ws)
+
     def dgrad(self, dp, d, ws):
         if self.is_conv:
-            dp.dp_conv2d_bwd_data(d, self.dy, self.y, self.w, self.dx, ws)
+            dp.dp_conv2d_bwd_data(d, self.g, None, self.w, self.dx, ws)
         else:
-            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.dy, y_saved=self.y, dx=self.dx, ws=ws)
+            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.g, dx=self.dx, ws=ws)
 
     def wgrad(self, dp, d, ws):
         if self.is_conv:
-            dp.dp_conv2d_bwd_filter(d, self.x, self.dy, self.y, self.dw, self.db, ws)
+            dp.dp_conv2d_bwd_filter(d, self.x, self.g, None, self.dw, None, ws)
         else:
-            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.dy, y_saved=self.y, dW=self.dw, dbias=self.db, ws=ws)
+            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws)
+
+    def passes(self):
+        """(name, method, counts nominal flops) of the calls that make up this layer's share of a step."""
+        out = [("fwd", self.fwd, True), ("rgrad", self.rgrad, False)]
+        if self.needs_dx:
+            out.append(("dgrad", self.dgrad, True))
+        out.append(("wgrad", self.wgrad, True))
+        return out
+
+    def step_flops(self, n):
+        return self.flops(n) * sum(1 for _, _, c in self.passes() if c)
 
 
 def cpu_baseline():
@@ -155,11 +178,10 @@ def main():
         for n in batches:
             for l in layers:
                 d = descs[(l.name, n)]
-                l.fwd(dp, d, ws)
-                l.dgrad(dp, d, ws)
-                l.wgrad(dp, d, ws)
+                for _, fn, _ in l.passes():
+                    fn(dp, d, ws)
 
-    flops_step = sum(3 * l.flops(n) for l in layers for n in batches)
+    flops_step = sum(l.step_flops(n) for l in layers for n in batches)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -178,7 +200,7 @@ def main():
         for n in batches:
             for l in layers:
                 d = descs[(l.name, n)]
-                for pname, fn in (("fwd", l.fwd), ("dgrad", l.dgrad), ("wgrad", l.wgrad)):
+                for pname, fn, _ in l.passes():
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record(stream)
                     fn(dp, d, ws)
@@ -195,8 +217,8 @@ def main():
     # per-batch throughput (fraction of the bf16 dense MFMA peak) over all 16 layers
     per_batch = {}
     for n in batches:
-        us = sum(sum(per[(l.name, n, p)]) / len(per[(l.name, n, p)]) for l in layers for p in ("fwd", "dgrad", "wgrad"))
-        fl = sum(3 * l.flops(n) for l in layers)
+        us = sum(sum(per[(l.name, n, p)]) / len(per[(l.name, n, p)]) for l in layers for p, _, _ in l.passes())
+        fl = sum(l.step_flops(n) for l in layers)
         per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us}
 
     # dominant kernel: the conv kernel instantiation with the largest total time among calls
@@ -208,7 +230,7 @@ def main():
         for n in batches:
             for pi, pname in enumerate(("fwd", "dgrad")):
                 kname, splits = dp.dp_conv2d_kernel_info(descs[(l.name, n)], pi)
-                if splits != 1:
+                if splits != 1 or (l.name, n, pname) not in per:
                     continue
                 v = per[(l.name, n, pname)]
                 g = groups.setdefault(kname, {"us": 0.0, "launches": 0, "flops": 0.0})
@@ -229,7 +251,8 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "strong", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
-        "config": {"workload": "VGG-16 13 conv + 3 FC layers, 224x224x3 input, fwd + dgrad + wgrad(+dbias) per layer, "
+        "config": {"workload": "VGG-16 13 conv + 3 FC layers, 224x224x3 input, per layer fwd + ReLU/bias-grad + dgrad + wgrad "
+                               "(no dgrad for the first layer), "
                                "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
         "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS,

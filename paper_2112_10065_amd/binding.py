@@ -5,6 +5,8 @@ the library's HIP kernels.  Importing this module fails loudly if the library is
 import ctypes as C
 import os
 
+import torch  # noqa: F401  (first: the library must bind to the HIP runtime that PyTorch loads)
+
 from . import build as _build
 
 DP_OK, DP_ERR_NULL, DP_ERR_BAD_DESC, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = range(6)

@@ -23,6 +23,7 @@
 //    small LDS table {row_base, tap mask} for the pixels of the next steps.
 #include "tile_common.h"
 #include <cstdio>
+#include <cstdlib>
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
@@ -81,6 +82,55 @@ constexpr int tile_elems() { return TR ? BK * (T + 32) : T * (BK + 8); }
 // ---------------------------------------------------------------------------------------
 // forward and backward-data (stride 1): B rows are pixels with a per-row tap mask
 // ---------------------------------------------------------------------------------------
+
+// Valid-tap mask of a pixel row: bit r*S+s is set iff lo_h <= hb + sg*r < H' and the same for w.
+DEVFN unsigned tap_mask(int hb, int wb, int sg, int R, int S, int Hlim, int Wlim)
+{
+    unsigned smask = 0;
+    for (int s = 0; s < S; ++s) smask |= ((unsigned)(wb + sg * s) < (unsigned)Wlim) ? 1u << s : 0u;
+    unsigned mask = 0;
+    for (int r = 0; r < R; ++r) mask |= ((unsigned)(hb + sg * r) < (unsigned)Hlim) ? smask << (r * S) : 0u;
+    return mask;
+}
+
+// Epilogue of the pixel-major passes through LDS: bias / ReLU / bf16 rounding in registers, the
+// tile is staged as [pixel][channel] and leaves with 16-byte stores, 16 lanes per pixel row.
+// Needs rowsA % 8 == 0 and no split; the caller has passed the last barrier of the main loop.
+template <int FA, int FB, int TA, int TB, int NT>
+DEVFN void store_pixel_major_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *stage, const float *bias_lds,
+                                    int a0, int b0, int arow, int brow, int tid)
+{
+    constexpr int LSO = TA + 8;
+    const int lane = tid & 63;
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int ch = arow + i * 32 + 8 * gq + 4 * (lane >> 5);
+            f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+            if (p.flags & KF_BIAS) bv = *reinterpret_cast<const f32x4 *>(bias_lds + ch);
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y;
+                float v2 = acc[i][j][4 * gq + 2] + bv.z, v3 = acc[i][j][4 * gq + 3] + bv.w;
+                if (p.flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                const int pix = brow + j * 32 + (lane & 31);
+                *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) =
+                    u32x2{f32_to_bf16(v0) | (f32_to_bf16(v1) << 16), f32_to_bf16(v2) | (f32_to_bf16(v3) << 16)};
+            }
+        }
+    __syncthreads();
+    constexpr int CPR = TA / 8;
+    bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+#pragma unroll
+    for (int id = tid; id < TB * CPR; id += NT) {
+        const int pix = id / CPR, cc = id % CPR;
+        const int gp = b0 + pix, gc = a0 + cc * 8;
+        if (gp < p.rowsB && gc < p.rowsA)
+            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+    }
+}
+
 template <int PASS, int TA, int TB, int BK, int WA, int WB>
 __global__ __launch_bounds__(64 * WA * WB) void k_conv_fast(const KArgs p)
 {
@@ -90,9 +140,13 @@ __global__ __launch_bounds__(64 * WA * WB) void k_conv_fast(const KArgs p)
     constexpr bool TRA = PASS == PASS_DGRAD;
     constexpr int NA = TA * CH / NT, NB = TB * CH / NT;
     static_assert(NA * NT == TA * CH && NB * NT == TB * CH, "tile must divide evenly over the threads");
+    static_assert(TB <= NT, "one thread per pixel row fills the row table");
     constexpr int A_ELEMS = tile_elems<TA, BK, TRA>(), B_ELEMS = tile_elems<TB, BK, false>();
+    static_assert(2 * (A_ELEMS + B_ELEMS) >= TB * (TA + 8), "staged epilogue must fit in the tile buffers");
     extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
     bf16_t *As = lds, *Bs = lds + 2 * A_ELEMS;
+    unsigned *rowtab = reinterpret_cast<unsigned *>(lds + 2 * (A_ELEMS + B_ELEMS));  // [TB][2] = {row base bytes, tap mask}
+    float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);                     // [TA]
 
     const ConvGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -101,14 +155,37 @@ __global__ __launch_bounds__(64 * WA * WB) void k_conv_fast(const KArgs p)
     const int split = blockIdx.y;
     const int kbeg = split * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
 
-    // chan = channels of the pixel tensor (reduction inner extent); rsc = weight row length
+    // chan = channels of the pixel tensor (inner extent of the reduction)
     const int chan = PASS == PASS_FWD ? g.C : g.K;
     const int RSC = g.R * g.S * g.C;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
     __amdgpu_buffer_rsrc_t rp = PASS == PASS_FWD ? make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2)
                                                  : make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
 
+    // --- row table: one thread per pixel row of the tile --------------------------------------
+    if (tid < TB) {
+        const int m = b0 + tid;
+        unsigned base, mask = 0;
+        if constexpr (PASS == PASS_FWD) {
+            const int n = m / (g.Ho * g.Wo), rem = m - n * (g.Ho * g.Wo), pp = rem / g.Wo, qq = rem - pp * g.Wo;
+            const int hb = pp * g.sh - g.ph, wb = qq * g.sw - g.pw;
+            if (m < p.rowsB) mask = tap_mask(hb, wb, 1, g.R, g.S, g.H, g.W);
+            base = (unsigned)(((n * g.H + hb) * g.W + wb) * g.C) * 2u;
+        } else {
+            const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
+            const int hb = hh + g.ph, wb = ww + g.pw;   // the output pixel of tap (r,s) is (hb - r, wb - s)
+            if (m < p.rowsB) mask = tap_mask(hb, wb, -1, g.R, g.S, g.Ho, g.Wo);
+            base = (unsigned)(((n * g.Ho + hb) * g.Wo + wb) * g.K) * 2u;
+        }
+        rowtab[2 * tid] = base;
+        rowtab[2 * tid + 1] = mask;
+    }
+    if (PASS == PASS_FWD && (p.flags & KF_BIAS))
+        for (int i = tid; i < TA; i += NT) bias_lds[i] = a0 + i < p.rowsA ? p.bias[a0 + i] : 0.f;
+
     // --- per-thread constants -------------------------------------------------------------
+    // A rows beyond the tensor (tail of the last tile) may load anything the buffer returns:
+    // they only feed accumulator rows that the epilogue never stores.
     unsigned voffA[NA], ldsA[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
@@ -123,37 +200,15 @@ __global__ __launch_bounds__(64 * WA * WB) void k_conv_fast(const KArgs p)
             ldsA[i] = t * (TA + 32) + cch * 8;
         }
     }
-    // A rows beyond the tensor (c_out / c_in tail of the last tile) may load anything that the
-    // buffer returns: they only feed accumulator rows that the epilogue never stores.
-
+    __syncthreads();
     unsigned voffB[NB], maskB[NB], ldsB[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         const int id = tid + i * NT, row = id / CH, ch = id % CH;
-        const int m = b0 + row;
         ldsB[i] = row * (BK + 8) + ch * 8;
-        unsigned mask = 0;
-        int hb, wb, n;
-        if constexpr (PASS == PASS_FWD) {
-            n = m / (g.Ho * g.Wo);
-            const int rem = m - n * (g.Ho * g.Wo), pp = rem / g.Wo, qq = rem - pp * g.Wo;
-            hb = pp * g.sh - g.ph; wb = qq * g.sw - g.pw;
-            if (m < p.rowsB)
-                for (int r = 0; r < g.R; ++r)
-                    for (int s = 0; s < g.S; ++s)
-                        if ((unsigned)(hb + r) < (unsigned)g.H && (unsigned)(wb + s) < (unsigned)g.W) mask |= 1u << (r * g.S + s);
-            voffB[i] = (unsigned)(((n * g.H + hb) * g.W + wb) * g.C + ch * 8) * 2u;
-        } else {
-            n = m / (g.H * g.W);
-            const int rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
-            hb = hh + g.ph; wb = ww + g.pw;   // output pixel of tap (r,s) is (hb - r, wb - s)
-            if (m < p.rowsB)
-                for (int r = 0; r < g.R; ++r)
-                    for (int s = 0; s < g.S; ++s)
-                        if ((unsigned)(hb - r) < (unsigned)g.Ho && (unsigned)(wb - s) < (unsigned)g.Wo) mask |= 1u << (r * g.S + s);
-            voffB[i] = (unsigned)(((n * g.Ho + hb) * g.Wo + wb) * g.K + ch * 8) * 2u;
-        }
-        maskB[i] = mask;
+        const u32x2 e = *reinterpret_cast<const u32x2 *>(rowtab + 2 * row);
+        voffB[i] = e.x + ch * 16;
+        maskB[i] = e.y;
     }
 
     // --- wave-uniform reduction position --------------------------------------------------
@@ -208,7 +263,10 @@ __global__ __launch_bounds__(64 * WA * WB) void k_conv_fast(const KArgs p)
             __syncthreads();
         }
     }
-    store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, split);
+    if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
+        store_pixel_major_staged<FA, FB, TA, TB, NT>(p, acc, lds, bias_lds, a0, b0, arow, brow, tid);
+    else
+        store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, split);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -368,8 +426,8 @@ KernelFn pick_fast(int pass, int v, int bk)
 size_t fast_lds_bytes(int pass, int TA, int TB, int BK)
 {
     size_t a, b, extra = 0;
-    if (pass == PASS_FWD) { a = (size_t)TA * (BK + 8); b = (size_t)TB * (BK + 8); }
-    else if (pass == PASS_DGRAD) { a = (size_t)BK * (TA + 32); b = (size_t)TB * (BK + 8); }
+    if (pass == PASS_FWD) { a = (size_t)TA * (BK + 8); b = (size_t)TB * (BK + 8); extra = (size_t)TB * 8 + (size_t)TA * 4; }
+    else if (pass == PASS_DGRAD) { a = (size_t)BK * (TA + 32); b = (size_t)TB * (BK + 8); extra = (size_t)TB * 8 + (size_t)TA * 4; }
     else { a = (size_t)BK * (TA + 32); b = (size_t)BK * (TB + 32); extra = (size_t)2 * BK * 2 * sizeof(int); }
     return 2 * (a + b) * sizeof(bf16_t) + extra;
 }
@@ -410,6 +468,7 @@ bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         if (g.K % 8 || g.C % 8) return false;
         bk = 32;
     }
+    if (const char *e = getenv("DP_FAST_BK")) { if (atoi(e) == 32 && pass != PASS_WGRAD) bk = 32; if (atoi(e) == 64 && pass == PASS_WGRAD) bk = 64; }
     int rowsA, rowsB, red;
     extents(g, pass, &rowsA, &rowsB, &red);
     int v;

@@ -95,13 +95,32 @@ __global__ __launch_bounds__(64) void k_rbg_cols(long long rows, int k, const T 
     if (ws != nullptr) ws[(size_t)blockIdx.y * k + col] = acc;
 }
 
+// dbias[col] = sum over row blocks of ws[b][col], in a fixed order: 8 threads per column each sum
+// every 8th row block (independent loads, 4 in flight), then the 8 part sums are added in order
 __global__ __launch_bounds__(256) void k_rbg_final(int k, int row_blocks, const float *ws, float *dbias)
 {
-    const int col = blockIdx.x * 256 + threadIdx.x;
-    if (col >= k) return;
-    float s = 0.f;
-    for (int b = 0; b < row_blocks; ++b) s += ws[(size_t)b * k + col];
-    dbias[col] = s;
+    __shared__ float sm[8][32];
+    const int cl = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int col = blockIdx.x * 32 + cl;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (col < k) {
+        int b = part;
+        for (; b + 24 < row_blocks; b += 32) {
+            s0 += ws[(size_t)b * k + col];
+            s1 += ws[(size_t)(b + 8) * k + col];
+            s2 += ws[(size_t)(b + 16) * k + col];
+            s3 += ws[(size_t)(b + 24) * k + col];
+        }
+        for (; b < row_blocks; b += 8) s0 += ws[(size_t)b * k + col];
+    }
+    sm[part][cl] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (part == 0 && col < k) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += sm[i][cl];
+        dbias[col] = s;
+    }
 }
 
 int row_blocks_for(long long rows, int rows_per_iter, int col_blocks)
@@ -147,6 +166,6 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || dbias == nullptr) return e;
-    hipLaunchKernelGGL(k_rbg_final, dim3((k + 255) / 256), dim3(256), 0, st, k, rb, ws, dbias);
+    hipLaunchKernelGGL(k_rbg_final, dim3((k + 31) / 32), dim3(256), 0, st, k, rb, ws, dbias);
     return hipGetLastError();
 }
