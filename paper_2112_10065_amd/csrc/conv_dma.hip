@@ -1,0 +1,570 @@
+// Forward / backward-data kernels with a multi-stage global->LDS pipeline (gfx950 direct-to-LDS
+// buffer loads): the tiles of the next NS-1 reduction steps are in flight while the matrix
+// cores work on the current one, no registers or ds_write instructions are spent on staging.
+//
+// A direct-to-LDS load writes the 64 lanes' 16-byte pieces to 1 KiB of consecutive LDS, so the
+// tiles are unpadded; bank conflicts are avoided by choosing WHICH global chunk each lane
+// fetches: the 16-byte chunk c of tile row `row` lives at chunk position c ^ ((row >> 1) & 7)
+// of that row (rows are 128 bytes: BK = 64 bf16), which makes the fragment reads of 16
+// consecutive rows hit 16 distinct 16-byte bank groups.
+//
+// The compiler waits for every outstanding LDS-DMA before any LDS read it can see, which would
+// serialise the pipeline; the fragment reads are therefore inline assembly with explicit
+// s_waitcnt, and the per-step "stage has landed" wait is an explicit vmcnt.
+//
+// Step i:  wait(loads of step i) ; barrier ; issue loads of step i+NS-1 into the stage that
+//          step i-1 used ; matrix cores on stage i % NS.
+#include "tile_common.h"
+#include <cstdio>
+#include <cstdlib>
+
+namespace {
+
+constexpr unsigned OOR = 0xFFFFFFFFu;
+typedef __attribute__((address_space(3))) void *lds_void;
+
+DEVFN __amdgpu_buffer_rsrc_t make_rsrc(const void *p, size_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)(unsigned)bytes, 0x00020000);
+}
+// 16 bytes per lane from the buffer straight into LDS at lds_base + lane*16 (lds_base wave-uniform)
+DEVFN void dma16(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, 0, 0, 0);
+}
+DEVFN unsigned lds_offset(const void *p) { return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p; }
+
+template <int N> DEVFN void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int OFF> DEVFN u32x4 lds_read16(unsigned addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+
+// issue the fragment reads of one 16-wide reduction slice (blocks of 32 rows are BS bytes apart)
+template <int FA, int FB, int BS>
+DEVFN void read_frags(u32x4 (&a)[FA], u32x4 (&b)[FB], unsigned pa, unsigned pb)
+{
+    if constexpr (FA >= 1) a[0] = lds_read16<0>(pa);
+    if constexpr (FA >= 2) a[1] = lds_read16<BS>(pa);
+    if constexpr (FA >= 3) a[2] = lds_read16<2 * BS>(pa);
+    if constexpr (FA >= 4) a[3] = lds_read16<3 * BS>(pa);
+    if constexpr (FB >= 1) b[0] = lds_read16<0>(pb);
+    if constexpr (FB >= 2) b[1] = lds_read16<BS>(pb);
+    if constexpr (FB >= 3) b[2] = lds_read16<2 * BS>(pb);
+    if constexpr (FB >= 4) b[3] = lds_read16<3 * BS>(pb);
+}
+// The reads are invisible to the compiler: wait until at most N newer LDS reads are outstanding,
+// with the fragments as operands so that no matrix instruction using them is scheduled earlier.
+template <int N, int FA, int FB>
+DEVFN void wait_frags(u32x4 (&a)[FA], u32x4 (&b)[FB])
+{
+    static_assert(N >= 0 && N < 16, "lgkmcnt is a 4-bit counter");
+    asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N));
+    // volatile statements keep their order; the empty ones make the fragments depend on the wait
+#pragma unroll
+    for (int i = 0; i < FA; ++i) asm volatile("" : "+v"(a[i]));
+#pragma unroll
+    for (int j = 0; j < FB; ++j) asm volatile("" : "+v"(b[j]));
+}
+
+// Valid-tap mask of a pixel row: bit r*S+s is set iff 0 <= hb + sg*r < Hlim and 0 <= wb + sg*s < Wlim.
+DEVFN unsigned tap_mask(int hb, int wb, int sg, int R, int S, int Hlim, int Wlim)
+{
+    unsigned smask = 0;
+    for (int s = 0; s < S; ++s) smask |= ((unsigned)(wb + sg * s) < (unsigned)Wlim) ? 1u << s : 0u;
+    unsigned mask = 0;
+    for (int r = 0; r < R; ++r) mask |= ((unsigned)(hb + sg * r) < (unsigned)Hlim) ? smask << (r * S) : 0u;
+    return mask;
+}
+
+template <int FA, int FB, int TA, int TB, int NT>
+DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *stage, const float *bias_lds, int a0, int b0,
+                        int arow, int brow, int tid)
+{
+    constexpr int LSO = TA + 8;
+    const int lane = tid & 63;
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int ch = arow + i * 32 + 8 * gq + 4 * (lane >> 5);
+            f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+            if (p.flags & KF_BIAS) bv = *reinterpret_cast<const f32x4 *>(bias_lds + ch);
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y;
+                float v2 = acc[i][j][4 * gq + 2] + bv.z, v3 = acc[i][j][4 * gq + 3] + bv.w;
+                if (p.flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                const int pix = brow + j * 32 + (lane & 31);
+                *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) =
+                    u32x2{f32_to_bf16(v0) | (f32_to_bf16(v1) << 16), f32_to_bf16(v2) | (f32_to_bf16(v3) << 16)};
+            }
+        }
+    __syncthreads();
+    constexpr int CPR = TA / 8;
+    bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+#pragma unroll
+    for (int id = tid; id < TB * CPR; id += NT) {
+        const int pix = id / CPR, cc = id % CPR;
+        const int gp = b0 + pix, gc = a0 + cc * 8;
+        if (gp < p.rowsB && gc < p.rowsA)
+            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+    }
+}
+
+// Tiles: A [TA][BK] (weights rows), B [TB][BK] (pixel rows), unpadded, chunk-swizzled:
+// CH = BK/8 chunks per row; chunk c of row `row` sits at position c ^ ((row / RPS) % CH), RPS = rows
+// per 256 bytes.  One direct-to-LDS instruction fills RPI = 64/CH consecutive rows.
+template <int TA, int TB, int BK, int WA, int WB, int NS>
+__global__ __launch_bounds__(64 * WA * WB) void k_fwd_dma(const KArgs p)
+{
+    constexpr int NT = 64 * WA * WB, NW = WA * WB;
+    constexpr int CH = BK / 8, RPI = 64 / CH, RPS = 128 / BK, ROWB = BK * 2, KS = BK / 16;
+    constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
+    constexpr int A_BYTES = TA * ROWB, B_BYTES = TB * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int IA = TA / RPI / NW, IB = TB / RPI / NW;   // direct-to-LDS instructions per wave and step
+    static_assert(IA * NW * RPI == TA && IB * NW * RPI == TB, "tile rows must divide over the waves");
+    static_assert(TB <= NT, "one thread per pixel row fills the row table");
+    constexpr int TILE_BYTES = NS * STAGE > TB * (TA + 8) * 2 ? NS * STAGE : TB * (TA + 8) * 2;  // stages / staged epilogue
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    unsigned *rowtab = reinterpret_cast<unsigned *>(smem + TILE_BYTES);   // [TB][2]
+    float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // [TA]
+
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = logical_block(blockIdx.x, gridDim.x);
+    const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
+    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
+    const int nsteps = kend - kbeg;
+    const int RSC = g.R * g.S * g.C;
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
+    __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2);
+
+    if (tid < TB) {
+        const int m = b0 + tid;
+        const int n = m / (g.Ho * g.Wo), rem = m - n * (g.Ho * g.Wo), pp = rem / g.Wo, qq = rem - pp * g.Wo;
+        const int hb = pp * g.sh - g.ph, wb = qq * g.sw - g.pw;
+        rowtab[2 * tid] = (unsigned)(((n * g.H + hb) * g.W + wb) * g.C) * 2u;
+        rowtab[2 * tid + 1] = m < p.rowsB ? tap_mask(hb, wb, 1, g.R, g.S, g.H, g.W) : 0u;
+    }
+    if (p.flags & KF_BIAS)
+        for (int i = tid; i < TA; i += NT) bias_lds[i] = a0 + i < p.rowsA ? p.bias[a0 + i] : 0.f;
+    __syncthreads();
+
+    // lane l of instruction q of this wave fills chunk position (l % CH) of tile row
+    // rq = (wave*I + q)*RPI + l / CH; that position holds global chunk (l % CH) ^ swizzle(rq)
+    unsigned voffA[IA], voffB[IB], maskB[IB];
+#pragma unroll
+    for (int q = 0; q < IA; ++q) {
+        const int row = (wave * IA + q) * RPI + lane / CH;
+        const int c = (lane % CH) ^ ((row / RPS) % CH);
+        voffA[q] = ((unsigned)(a0 + row) * RSC + c * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < IB; ++q) {
+        const int row = (wave * IB + q) * RPI + lane / CH;
+        const int c = (lane % CH) ^ ((row / RPS) % CH);
+        const u32x2 e = *reinterpret_cast<const u32x2 *>(rowtab + 2 * row);
+        voffB[q] = e.x + c * 16;
+        maskB[q] = e.y;
+    }
+    const unsigned smem_base = lds_offset(smem);
+    const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
+
+    int kk = kbeg * BK;
+    int tap = kk / g.C, c0 = kk - tap * g.C;
+    int tr = tap / g.S, ts = tap - tr * g.S;
+    auto issue = [&](int stage) {   // loads of the next not-yet-issued step into `stage`
+        const unsigned ua = (unsigned)(tap * g.C + c0) * 2u;
+        const unsigned ub = (unsigned)((tr * g.W + ts) * g.C + c0) * 2u;
+        const unsigned bit = 1u << tap;
+        const unsigned sb = stage * STAGE;
+#pragma unroll
+        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, voffA[q] + ua);
+#pragma unroll
+        for (int q = 0; q < IB; ++q) dma16(rx, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
+        c0 += BK;
+        if (c0 >= g.C) { c0 = 0; ++tap; if (++ts == g.S) { ts = 0; ++tr; } }
+    };
+
+    f32x16 acc[FA][FB];
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
+
+    // fragment addresses: row (lane & 31) of a 32-row block, chunk (2*ks + (lane >> 5)) ^ swizzle(row);
+    // the swizzle term is the same for every 32-row block of the wave tile
+    const int rA = arow + (lane & 31), rB = brow + (lane & 31);
+    unsigned fa[KS], fb[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        fa[ks] = smem_base + rA * ROWB + (((2 * ks + (lane >> 5)) ^ ((rA / RPS) % CH)) << 4);
+        fb[ks] = smem_base + A_BYTES + rB * ROWB + (((2 * ks + (lane >> 5)) ^ ((rB / RPS) % CH)) << 4);
+    }
+
+    constexpr int LPS = IA + IB;   // loads per thread and step
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nsteps) issue(s);
+    for (int i = 0; i < nsteps; ++i) {
+        // loads of steps i+1 .. i+NS-2 may still be in flight
+        const int younger = min(nsteps - 1 - i, NS - 2);
+        if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS);
+        const unsigned sb = (i % NS) * STAGE;
+        // fragments are double-buffered in registers: the reads of slice ks+1 are issued before the
+        // matrix instructions of slice ks, which start once only those newer reads are outstanding
+        u32x4 fr_a[2][FA], fr_b[2][FB];
+        read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0] + sb, fb[0] + sb);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks < KS - 1) {
+                read_frags<FA, FB, 32 * ROWB>(fr_a[(ks + 1) & 1], fr_b[(ks + 1) & 1], fa[ks + 1 < KS ? ks + 1 : 0] + sb, fb[ks + 1 < KS ? ks + 1 : 0] + sb);
+                wait_frags<FA + FB, FA, FB>(fr_a[ks & 1], fr_b[ks & 1]);
+            } else {
+                wait_frags<0, FA, FB>(fr_a[ks & 1], fr_b[ks & 1]);
+            }
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii)
+#pragma unroll
+                for (int jj = 0; jj < FB; ++jj)
+                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr_a[ks & 1][ii]),
+                                                                         __builtin_bit_cast(bf16x8, fr_b[ks & 1][jj]), acc[ii][jj], 0, 0, 0);
+        }
+    }
+    __syncthreads();   // every wave is done reading the stages before they are reused for staging
+    if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
+        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
+    else
+        store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+}
+
+// ---------------------------------------------------------------------------------------
+// backward-filter with the same pipeline.  Both operands are reduction-major in LDS:
+// A [BK pixels][TA c_out], B [BK pixels][TB taps]; fragments come from the LDS transpose read.
+// Rows are T*2 bytes; the 64-byte segment g of reduction row t sits at segment g ^ swz(t) so that
+// the four rows one transpose read touches fall into distinct banks.  One direct-to-LDS
+// instruction fills 512/T reduction rows.  The x offsets change every step: threads t < BK keep a
+// table {pixel base, tap mask} for the steps in flight, written and read with inline assembly
+// for the same reason as the fragment reads.
+// ---------------------------------------------------------------------------------------
+template <int T> DEVFN int seg_swz(int t)
+{
+    constexpr int SPR = T / 32, RPS = T >= 128 ? 1 : 128 / T;   // segments per row, rows per 256 bytes
+    return (t / RPS) & (SPR >= 4 ? 3 : SPR - 1);
+}
+
+template <int OFF> DEVFN u32x2 lds_read_tr(unsigned addr)
+{
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+template <int TA, int TB, int BK, int WA, int WB, int NS>
+__global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
+{
+    constexpr int NT = 64 * WA * WB, NW = WA * WB, KS = BK / 16;
+    constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
+    constexpr int ROWA = TA * 2, ROWB = TB * 2;                  // bytes per reduction row
+    constexpr int A_BYTES = BK * ROWA, B_BYTES = BK * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int RPIA = 512 / TA, RPIB = 512 / TB;              // reduction rows per direct-to-LDS instruction
+    constexpr int IA = BK / RPIA / NW, IB = BK / RPIB / NW;
+    static_assert(IA * NW * RPIA == BK && IB * NW * RPIB == BK, "reduction rows must divide over the waves");
+    static_assert(BK <= 64, "one wavefront fills the pixel table");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const unsigned smem_base = lds_offset(smem);
+    const unsigned tab_base = smem_base + NS * STAGE;            // [NS][BK] x {base, mask}
+
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = logical_block(blockIdx.x, gridDim.x);
+    const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
+    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
+    const int nsteps = kend - kbeg;
+    const int M = p.red;
+    __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)M * g.K * 2);
+    __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2);
+
+    // lane l of instruction q fills chunk position l % (T/8) of reduction row tq = (wave*I + q)*RPI + l / (T/8)
+    unsigned voffA[IA];
+#pragma unroll
+    for (int q = 0; q < IA; ++q) {
+        const int t = (wave * IA + q) * RPIA + lane / (TA / 8);
+        const int c = (lane % (TA / 8)) ^ (seg_swz<TA>(t) << 2);
+        voffA[q] = ((unsigned)t * g.K + a0 + c * 8) * 2u;
+    }
+    unsigned coffB[IB], bitB[IB], tabB[IB];
+#pragma unroll
+    for (int q = 0; q < IB; ++q) {
+        const int t = (wave * IB + q) * RPIB + lane / (TB / 8);
+        const int c = (lane % (TB / 8)) ^ (seg_swz<TB>(t) << 2);
+        const int col = b0 + c * 8;
+        const int tapi = col / g.C, ch = col - tapi * g.C, r = tapi / g.S, s = tapi - r * g.S;
+        coffB[q] = (unsigned)((r * g.W + s) * g.C + ch) * 2u;
+        bitB[q] = col < p.rowsB ? 1u << tapi : 0u;
+        tabB[q] = tab_base + t * 8;
+    }
+    const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
+
+    // pixel table: thread t < BK owns pixel (step*BK + t) of the step it fills next
+    int pn = 0, pp = 0, pq = 0;
+    if (tid < BK) {
+        const int m = kbeg * BK + tid;
+        pn = m / (g.Ho * g.Wo);
+        const int rem = m - pn * (g.Ho * g.Wo);
+        pp = rem / g.Wo; pq = rem - pp * g.Wo;
+    }
+    auto fill_table = [&](int slot, int step) {
+        if (tid < BK) {
+            const int hb = pp * g.sh - g.ph, wb = pq * g.sw - g.pw;
+            u32x2 e;
+            e.x = (unsigned)(((pn * g.H + hb) * g.W + wb) * g.C) * 2u;
+            e.y = step * BK + tid < M ? tap_mask(hb, wb, 1, g.R, g.S, g.H, g.W) : 0u;
+            const unsigned addr = tab_base + (slot * BK + tid) * 8;
+            asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(e) : "memory");
+            pq += BK;
+            while (pq >= g.Wo) { pq -= g.Wo; if (++pp == g.Ho) { pp = 0; ++pn; } }
+        }
+    };
+    auto issue = [&](int stage, int step) {
+        const unsigned ua = (unsigned)step * BK * g.K * 2u;
+        const unsigned sb = stage * STAGE;
+        u32x2 e[IB];
+#pragma unroll
+        for (int q = 0; q < IB; ++q)
+            asm volatile("ds_read_b64 %0, %1" : "=v"(e[q]) : "v"(tabB[q] + stage * BK * 8));
+#pragma unroll
+        for (int q = 0; q < IA; ++q) dma16(rdy, ldsA_w + sb + q * 1024, voffA[q] + ua);
+        asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+        for (int q = 0; q < IB; ++q) asm volatile("" : "+v"(e[q]));
+#pragma unroll
+        for (int q = 0; q < IB; ++q) dma16(rx, ldsB_w + sb + q * 1024, (e[q].y & bitB[q]) ? e[q].x + coffB[q] : OOR);
+    };
+
+    f32x16 acc[FA][FB];
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
+
+    // transpose-read addresses: lane l of a 16-lane block points at reduction row ks*16 + 8*(l>>5) + (l&15)/4
+    // (and 4 rows further for the second half), operand rows row0 + 16*((l>>4)&1) + 4*(l&3) .. +3
+    unsigned fa[KS][FA], fb[KS][FB];
+    {
+        const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int t = ks * 16 + tl;   // the second read of a fragment is row t + 4, which has the same swizzle term
+#pragma unroll
+            for (int i = 0; i < FA; ++i) {
+                const int col = arow + i * 32 + cl;
+                fa[ks][i] = smem_base + t * ROWA + ((((col >> 5) ^ seg_swz<TA>(t)) << 6) | ((col & 31) << 1));
+            }
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                const int col = brow + j * 32 + cl;
+                fb[ks][j] = smem_base + A_BYTES + t * ROWB + ((((col >> 5) ^ seg_swz<TB>(t)) << 6) | ((col & 31) << 1));
+            }
+        }
+    }
+
+    constexpr int LPS = IA + IB;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (s < nsteps) fill_table(s, kbeg + s);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nsteps) issue(s, kbeg + s);
+    for (int i = 0; i < nsteps; ++i) {
+        const int younger = min(nsteps - 1 - i, NS - 2);
+        if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
+        else wait_vmcnt<0>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's table writes are done
+        __builtin_amdgcn_s_barrier();
+        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS, kbeg + i + NS - 1);
+        const unsigned sb = (i % NS) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x2 alo[FA], ahi[FA], blo[FB], bhi[FB];
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii) {
+                alo[ii] = lds_read_tr<0>(fa[ks][ii] + sb);
+                ahi[ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);   // 4 reduction rows further: same swizzle class
+            }
+#pragma unroll
+            for (int jj = 0; jj < FB; ++jj) {
+                blo[jj] = lds_read_tr<0>(fb[ks][jj] + sb);
+                bhi[jj] = lds_read_tr<4 * ROWB>(fb[ks][jj] + sb);
+            }
+            asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[ii])); asm volatile("" : "+v"(ahi[ii])); }
+#pragma unroll
+            for (int jj = 0; jj < FB; ++jj) { asm volatile("" : "+v"(blo[jj])); asm volatile("" : "+v"(bhi[jj])); }
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii)
+#pragma unroll
+                for (int jj = 0; jj < FB; ++jj) {
+                    const u32x4 av = {alo[ii].x, alo[ii].y, ahi[ii].x, ahi[ii].y}, bv = {blo[jj].x, blo[jj].y, bhi[jj].x, bhi[jj].y};
+                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
+                                                                         acc[ii][jj], 0, 0, 0);
+                }
+        }
+        // table of step i+NS goes into the slot whose table (step i) was consumed before this barrier
+        if (i + NS < nsteps) fill_table(i % NS, kbeg + i + NS);
+    }
+    store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+}
+
+struct DmaVariant { int TA, TB, BK, WA, WB, NS; };
+const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {128, 128, 32, 2, 2, 4},
+                           {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
+                           {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2}};
+constexpr int kNumDma = 12;
+typedef void (*KernelFn)(const KArgs);
+KernelFn pick_dma(int v)
+{
+    switch (v) {
+    case 0: return k_fwd_dma<128, 128, 64, 2, 2, 2>;
+    case 1: return k_fwd_dma<128, 128, 32, 2, 2, 2>;
+    case 2: return k_fwd_dma<128, 128, 32, 2, 2, 3>;
+    case 3: return k_fwd_dma<128, 128, 32, 2, 2, 4>;
+    case 4: return k_fwd_dma<64, 128, 64, 2, 2, 2>;
+    case 5: return k_fwd_dma<64, 128, 32, 2, 2, 3>;
+    case 6: return k_fwd_dma<128, 64, 64, 2, 2, 2>;
+    case 8: return k_fwd_dma<256, 256, 64, 2, 4, 2>;
+    case 9: return k_fwd_dma<256, 128, 64, 4, 2, 2>;
+    case 10: return k_fwd_dma<128, 256, 64, 2, 4, 2>;
+    case 11: return k_fwd_dma<256, 256, 64, 4, 2, 2>;
+    default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
+    }
+}
+const DmaVariant kDmaW[] = {{128, 128, 32, 2, 2, 2}, {128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {64, 128, 32, 2, 2, 2},
+                            {128, 64, 32, 2, 2, 2}, {64, 64, 32, 2, 2, 2}, {64, 128, 64, 2, 2, 2}, {256, 128, 32, 4, 2, 2}};
+constexpr int kNumDmaW = 8;
+KernelFn pick_dma_w(int v)
+{
+    switch (v) {
+    case 0: return k_wgrad_dma<128, 128, 32, 2, 2, 2>;
+    case 1: return k_wgrad_dma<128, 128, 64, 2, 2, 2>;
+    case 2: return k_wgrad_dma<128, 128, 32, 2, 2, 3>;
+    case 3: return k_wgrad_dma<64, 128, 32, 2, 2, 2>;
+    case 4: return k_wgrad_dma<128, 64, 32, 2, 2, 2>;
+    case 5: return k_wgrad_dma<64, 64, 32, 2, 2, 2>;
+    case 6: return k_wgrad_dma<64, 128, 64, 2, 2, 2>;
+    default: return k_wgrad_dma<256, 128, 32, 4, 2, 2>;
+    }
+}
+size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB) * d.BK * 2 + (size_t)d.NS * d.BK * 8; }
+
+size_t dma_lds_bytes(const DmaVariant &d)
+{
+    size_t stages = (size_t)d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
+    return (stages > epi ? stages : epi) + (size_t)d.TB * 8 + (size_t)d.TA * 4;
+}
+
+}  // namespace
+
+hipError_t dma_init()
+{
+    for (int v = 0; v < kNumDma; ++v) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)dma_lds_bytes(kDma[v]));
+        if (e != hipSuccess) return e;
+    }
+    for (int v = 0; v < kNumDmaW; ++v) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma_w(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)dma_w_lds_bytes(kDmaW[v]));
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// variant override 200 + v selects pipelined variant v; the built-in choice does not use them yet
+bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *pl)
+{
+    if (g.R * g.S > 32) return false;
+    int rowsA, rowsB, red;
+    const DmaVariant *d;
+    if (pass == PASS_FWD) {
+        if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
+        d = &kDma[force_variant - 200];
+        if (g.C % d->BK != 0) return false;
+        pl->variant = force_variant - 200;
+        rowsA = g.K; rowsB = g.N * g.Ho * g.Wo; red = g.R * g.S * g.C;
+    } else if (pass == PASS_WGRAD) {
+        if (force_variant < 300 || force_variant >= 300 + kNumDmaW) return false;
+        d = &kDmaW[force_variant - 300];
+        if (g.K % 8 || g.C % 8) return false;
+        pl->variant = force_variant - 300;
+        rowsA = g.K; rowsB = g.R * g.S * g.C; red = g.N * g.Ho * g.Wo;
+    } else return false;
+    pl->fast = true; pl->dma = true; pl->TA = d->TA; pl->TB = d->TB; pl->BK = d->BK;
+    pl->vecA = pl->vecB = true;
+    pl->tilesA = (rowsA + d->TA - 1) / d->TA;
+    pl->tilesB = (rowsB + d->TB - 1) / d->TB;
+    pl->steps_total = (red + d->BK - 1) / d->BK;
+    int splits;
+    if (force_splits > 0) splits = force_splits;
+    else {
+        long long tiles = (long long)pl->tilesA * pl->tilesB;
+        splits = tiles >= 512 ? 1 : (int)((512 + tiles - 1) / tiles);
+        int max_splits = pl->steps_total / 8;
+        if (max_splits < 1) max_splits = 1;
+        if (splits > max_splits) splits = max_splits;
+    }
+    if (splits > pl->steps_total) splits = pl->steps_total;
+    if (splits < 1) splits = 1;
+    pl->steps_per_split = (pl->steps_total + splits - 1) / splits;
+    pl->splits = (pl->steps_total + pl->steps_per_split - 1) / pl->steps_per_split;
+    return true;
+}
+
+void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
+{
+    const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
+    snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", pass == PASS_WGRAD ? "k_wgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
+             d.WB, d.NS);
+}
+
+hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
+{
+    KArgs p;
+    p.g = a.g;
+    if (a.pass == PASS_FWD) { p.rowsA = a.g.K; p.rowsB = a.g.N * a.g.Ho * a.g.Wo; p.red = a.g.R * a.g.S * a.g.C; }
+    else { p.rowsA = a.g.K; p.rowsB = a.g.R * a.g.S * a.g.C; p.red = a.g.N * a.g.Ho * a.g.Wo; }
+    p.tilesA = a.plan.tilesA; p.tilesB = a.plan.tilesB;
+    p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split; p.splits = a.plan.splits;
+    p.flags = a.flags;
+    p.x = a.x; p.w = a.w; p.dy = a.dy; p.ymask = nullptr; p.bias = a.bias; p.out = a.out; p.partial = a.partial;
+    const bool wg = a.pass == PASS_WGRAD;
+    const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
+    dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB, 1, 1);
+    hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || p.splits <= 1) return e;
+    return launch_split_reduce(a, p.rowsA, p.rowsB, st);
+}

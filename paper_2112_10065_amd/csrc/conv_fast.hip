@@ -468,7 +468,6 @@ bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         if (g.K % 8 || g.C % 8) return false;
         bk = 32;
     }
-    if (const char *e = getenv("DP_FAST_BK")) { if (atoi(e) == 32 && pass != PASS_WGRAD) bk = 32; if (atoi(e) == 64 && pass == PASS_WGRAD) bk = 64; }
     int rowsA, rowsB, red;
     extents(g, pass, &rowsA, &rowsB, &red);
     int v;
@@ -483,7 +482,7 @@ bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         else v = big >= 128 ? 0 : 3;
     }
     const FastVariant &fv = kFast[v];
-    pl->fast = true; pl->variant = v; pl->TA = fv.TA; pl->TB = fv.TB; pl->BK = bk;
+    pl->fast = true; pl->dma = false; pl->variant = v; pl->TA = fv.TA; pl->TB = fv.TB; pl->BK = bk;
     pl->vecA = pl->vecB = true;
     pl->tilesA = (rowsA + fv.TA - 1) / fv.TA;
     pl->tilesB = (rowsB + fv.TB - 1) / fv.TB;

@@ -628,7 +628,7 @@ void mfma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         }
     }
     const Variant &tv = kVariants[v];
-    pl->fast = false;
+    pl->fast = false; pl->dma = false;
     pl->variant = v; pl->TA = tv.TA; pl->TB = tv.TB; pl->BK = bk_of(pass);
     pl->tilesA = (rowsA + tv.TA - 1) / tv.TA;
     pl->tilesB = (rowsB + tv.TB - 1) / tv.TB;

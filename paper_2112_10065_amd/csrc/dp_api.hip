@@ -88,11 +88,18 @@ dp_status check_opt(const void *p, const char *name)
 void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
 {
     const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
-    if ((fv < 0 || fv >= 100) && fast_plan(g, pass, fv, fs, pl)) return;
+    pl->dma = false;
+    if (fv < 0 && auto_plan(g, pass, fs, pl)) return;
+    if (fv >= 200 && dma_plan(g, pass, fv, fs, pl)) return;
+    if (fv >= 100 && fast_plan(g, pass, fv, fs, pl)) return;
     mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
 }
 
-hipError_t launch_plan(const ConvArgs &a, hipStream_t st) { return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st); }
+hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
+{
+    if (a.plan.dma) return dma_launch(a, st);
+    return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st);
+}
 
 size_t ybytes(const ConvGeom &g) { return (size_t)g.N * g.Ho * g.Wo * g.K * 2; }
 
@@ -100,7 +107,7 @@ size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 dp_status ensure_init()
 {
-    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); });
+    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); if (g_init_err == hipSuccess) g_init_err = dma_init(); });
     if (g_init_err != hipSuccess) return hip_fail(g_init_err, "library initialisation (is a gfx950 device present?)");
     return DP_OK;
 }
@@ -251,7 +258,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     }
     GemmPlan pl;
     plan_for(g, pass, &pl);
-    if (name != nullptr && name_bytes > 0) { if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
+    if (name != nullptr && name_bytes > 0) { if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
 }

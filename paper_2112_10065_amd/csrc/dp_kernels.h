@@ -32,6 +32,7 @@ struct GemmPlan {
     int splits;           // grid.y
     bool vecA, vecB;      // 16-byte loads allowed for operand A / B
     bool fast;            // fast-path kernel (conv_fast.hip) instead of the generic one
+    bool dma;             // pipelined direct-to-LDS kernel (conv_dma.hip)
 };
 
 struct ConvArgs {
@@ -62,6 +63,12 @@ bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
 hipError_t fast_launch(const ConvArgs &a, hipStream_t st);
 void fast_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
 
+// conv_dma.hip : multi-stage direct-to-LDS pipeline (forward, c_in % 64 == 0)
+hipError_t dma_init();
+bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
+hipError_t dma_launch(const ConvArgs &a, hipStream_t st);
+void dma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
+
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
 hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,
                         const float *bias, float *y, hipStream_t st);
@@ -74,3 +81,6 @@ hipError_t f32_conv_wgrad(const ConvGeom &g, const float *x, const float *dy, co
 size_t rbg_workspace_bytes(long long rows, int k);
 hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask,
                       void *g_out, float *dbias, float *ws, hipStream_t st);
+
+// planner.hip : picks the cheapest fast-path variant and split for a pass (host-side cost model)
+bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *plan);

@@ -1,0 +1,103 @@
+// Kernel choice for one pass of one layer: enumerate the tile variants and reduction splits that
+// the shape allows, price each with a small analytic model calibrated on MI355X measurements,
+// take the cheapest.  Host code only.  The model:
+//
+//   blocks       = tiles * splits               concurrent = 256 CUs * blocks_per_CU(variant)
+//   t_block      = t0(variant) + steps_per_split * t_step(variant) * share
+//                  (share < 1 when fewer blocks than the variant could co-run share a CU)
+//   t            = launch + waves(blocks / concurrent) * t_block + t_reduce(splits)
+//   t_reduce     = second kernel that sums the fp32 partials: launch + (splits + 1) * out bytes / BW
+#include "dp_kernels.h"
+#include <cmath>
+
+namespace {
+
+struct Candidate {
+    int code;        // override code understood by fast_plan / dma_plan (100.., 200.., 300..)
+    int bpc;         // blocks that fit on one CU (LDS / registers)
+    float t_step;    // microseconds per reduction step and block on a fully shared CU
+    float t0;        // microseconds of prologue + epilogue per block
+};
+
+// forward / backward-data candidates
+const Candidate kPix[] = {
+    {208, 1, 1.55f, 8.0f},   // 256x256x64, 8 waves, direct-to-LDS
+    {200, 2, 1.08f, 5.0f},   // 128x128x64 direct-to-LDS
+    {204, 3, 0.85f, 4.5f},   // 64x128x64
+    {206, 3, 0.85f, 4.5f},   // 128x64x64
+    {207, 3, 0.62f, 4.0f},   // 64x64x64
+    {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
+    {101, 3, 1.05f, 4.5f},
+    {102, 3, 1.05f, 4.5f},
+    {103, 4, 0.75f, 4.0f},
+};
+// backward-filter candidates (reduction step 32 unless noted)
+const Candidate kWg[] = {
+    {300, 4, 0.95f, 4.0f},   // 128x128x32 direct-to-LDS
+    {303, 4, 0.70f, 3.5f},   // 64x128x32
+    {304, 4, 0.70f, 3.5f},   // 128x64x32
+    {305, 5, 0.50f, 3.0f},   // 64x64x32
+    {100, 3, 1.30f, 4.0f},
+    {101, 3, 1.00f, 3.5f},
+    {102, 3, 1.00f, 3.5f},
+    {103, 4, 0.80f, 3.0f},
+};
+const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64, 96, 128};
+
+bool family_plan(const ConvGeom &g, int pass, int code, int splits, GemmPlan *pl)
+{
+    if (code >= 200) return dma_plan(g, pass, code, splits, pl);
+    return fast_plan(g, pass, code, splits, pl);
+}
+
+double price(const ConvGeom &g, int pass, const Candidate &c, const GemmPlan &pl)
+{
+    const double blocks = (double)pl.tilesA * pl.tilesB * pl.splits;
+    const double conc = 256.0 * c.bpc;
+    double share = 1.0, waves;
+    if (blocks <= conc) {
+        const double r = std::ceil(blocks / 256.0);
+        share = 0.45 + 0.55 * r / c.bpc;
+        waves = 1.0;
+    } else {
+        const double w = blocks / conc;
+        waves = w >= 4.0 ? w : 0.5 * (w + std::ceil(w));
+    }
+    // a step of reduction length 32 costs about half of a 64 step for the pixel passes
+    double t_step = c.t_step;
+    if (pass != PASS_WGRAD && pl.BK == 32) t_step *= 0.6;
+    const double t_block = c.t0 + pl.steps_per_split * t_step * share;
+    double t = 3.0 + waves * t_block;
+    if (pl.splits > 1) {
+        double out_elems = pass == PASS_FWD ? (double)g.N * g.Ho * g.Wo * g.K
+                         : pass == PASS_DGRAD ? (double)g.N * g.H * g.W * g.C
+                                              : (double)g.K * g.R * g.S * g.C;
+        t += 3.0 + (pl.splits + 1.0) * out_elems * 4.0 / 4.0e6;   // ~4 TB/s for the partial traffic
+    }
+    return t;
+}
+
+}  // namespace
+
+// Fills *pl with the cheapest eligible fast-path plan; false if the shape has none.
+bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
+{
+    const Candidate *cands = pass == PASS_WGRAD ? kWg : kPix;
+    const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
+    double best = 1e30;
+    bool found = false;
+    for (int ci = 0; ci < ncand; ++ci) {
+        int last_splits = -1;
+        for (int s : kSplits) {
+            if (force_splits > 0 && s != kSplits[0]) break;
+            GemmPlan cand;
+            if (!family_plan(g, pass, cands[ci].code, force_splits > 0 ? force_splits : s, &cand)) break;
+            if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
+            last_splits = cand.splits;
+            if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;
+            const double t = price(g, pass, cands[ci], cand);
+            if (t < best) { best = t; *pl = cand; found = true; }
+        }
+    }
+    return found;
+}

@@ -121,6 +121,49 @@ def test_every_fast_variant_and_split(env, variant, splits):
             dp.dp_set_override(p, -1, 0)
 
 
+@pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211])
+@pytest.mark.parametrize("splits", [1, 2])
+def test_pipelined_forward_variants(env, variant, splits):
+    """Forward kernels with the multi-stage direct-to-LDS pipeline: every stage count / tile shape,
+    reductions shorter and longer than the pipeline depth, ragged pixel and channel tails."""
+    dp, U, orc = env
+    dp.dp_set_override(0, variant, splits)
+    try:
+        for tag, n, h, w, c, k, r, s_, pd in (("pipe_a", 2, 13, 12, 64, 96, 3, 3, (1, 1)), ("pipe_b", 1, 9, 9, 128, 200, 1, 1, (0, 0)),
+                                              ("pipe_c", 3, 10, 17, 64, 264, 1, 7, (0, 3))):
+            case = U.ConvCase(tag, n, h, w, c, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "dma" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            y = case.run_fwd()
+            torch.cuda.synchronize()
+            ref = orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd)
+            U.assert_bf16_close(U.to_np(y), ref, f"{tag} variant {variant} splits {splits}")
+    finally:
+        dp.dp_set_override(0, -1, 0)
+
+
+@pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307])
+@pytest.mark.parametrize("splits", [1, 3])
+def test_pipelined_backward_filter_variants(env, variant, splits):
+    """Backward-filter kernels with the direct-to-LDS pipeline and LDS transpose reads."""
+    dp, U, orc = env
+    dp.dp_set_override(2, variant, splits)
+    try:
+        for tag, n, h, w, c, k, r, s_, st, pd in (("pipew_a", 2, 13, 12, 64, 96, 3, 3, (1, 1), (1, 1)),
+                                                  ("pipew_b", 3, 15, 14, 40, 72, 3, 3, (2, 2), (1, 1)),
+                                                  ("pipew_c", 1, 9, 17, 136, 200, 1, 7, (1, 1), (0, 3))):
+            case = U.ConvCase(tag, n, h, w, c, k, r, s_, st, pd, bf16=True, bias=True, relu=True)
+            assert "wgrad_dma" in dp.dp_conv2d_kernel_info(case.desc, 2)[0]
+            y = case.run_fwd()
+            dw, db = case.run_wgrad(y)
+            torch.cuda.synchronize()
+            y_np = U.to_np(y)
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=y_np, stride=st, pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} variant {variant} splits {splits} dw")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} variant {variant} splits {splits} db")
+    finally:
+        dp.dp_set_override(2, -1, 0)
+
+
 def test_unfused_relu_gradient_flow(env):
     """dp_relu_bias_grad materialises the masked gradient once; both backward passes then take it
     with y_saved = NULL and must agree with the oracle's masked definitions."""
