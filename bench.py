@@ -222,10 +222,17 @@ def main():
                     fn(dp, d, ws)
                     e1.record(stream)
                     calls.append((l, n, pname, e0, e1))
+            torch.cuda.synchronize()   # keeps the number of pending events small (the runtime stalls on very long event queues)
     torch.cuda.synchronize()
     per = {}
     for l, n, pname, e0, e1 in calls:
         per.setdefault((l.name, n, pname), []).append(e0.elapsed_time(e1) * 1e3)  # microseconds
+    # per-call statistic: the median over the steps (a rare multi-millisecond stall between two
+    # events, unrelated to the kernels, would otherwise dominate a mean of five samples)
+    def med(v):
+        v = sorted(v)
+        return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
+    per = {k: [med(v)] * len(v) for k, v in per.items()}
     table = {}
     for (lname, n, pname), v in per.items():
         table.setdefault(lname, {}).setdefault(str(n), {})[pname + "_us"] = sum(v) / len(v)

@@ -439,12 +439,174 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
 }
 
+// ---------------------------------------------------------------------------------------
+// backward-data (stride 1, c_out % BK == 0) with the same pipeline: A = weights, reduction-major
+// [BK c_out rows][TA c_in] read through the LDS transpose read; B = dy pixel rows, K-major.
+// ---------------------------------------------------------------------------------------
+template <int TA, int TB, int BK, int WA, int WB, int NS>
+__global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
+{
+    constexpr int NT = 64 * WA * WB, NW = WA * WB;
+    constexpr int CH = BK / 8, RPI = 64 / CH, RPS = 128 / BK, ROWB = BK * 2, KS = BK / 16;
+    constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
+    constexpr int ROWA = TA * 2, RPIA = 512 / TA;
+    constexpr int A_BYTES = BK * ROWA, B_BYTES = TB * ROWB, STAGE = A_BYTES + B_BYTES;
+    constexpr int IA = BK / RPIA / NW, IB = TB / RPI / NW;
+    static_assert(IA * NW * RPIA == BK && IB * NW * RPI == TB, "tile rows must divide over the waves");
+    static_assert(TB <= NT, "one thread per pixel row fills the row table");
+    constexpr int TILE_BYTES = NS * STAGE > TB * (TA + 8) * 2 ? NS * STAGE : TB * (TA + 8) * 2;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    unsigned *rowtab = reinterpret_cast<unsigned *>(smem + TILE_BYTES);   // [TB][2]
+    float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // unused (no bias in this pass)
+
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = logical_block(blockIdx.x, gridDim.x);
+    const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
+    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
+    const int nsteps = kend - kbeg;
+    const int RSC = g.R * g.S * g.C;
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
+    __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+
+    if (tid < TB) {
+        const int m = b0 + tid;
+        const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
+        const int hb = hh + g.ph, wb = ww + g.pw;   // the output pixel of tap (r,s) is (hb - r, wb - s)
+        rowtab[2 * tid] = (unsigned)(((n * g.Ho + hb) * g.Wo + wb) * g.K) * 2u;
+        rowtab[2 * tid + 1] = m < p.rowsB ? tap_mask(hb, wb, -1, g.R, g.S, g.Ho, g.Wo) : 0u;
+    }
+    __syncthreads();
+
+    unsigned voffA[IA], voffB[IB], maskB[IB];
+#pragma unroll
+    for (int q = 0; q < IA; ++q) {
+        const int t = (wave * IA + q) * RPIA + lane / (TA / 8);
+        const int c = (lane % (TA / 8)) ^ (seg_swz<TA>(t) << 2);
+        voffA[q] = ((unsigned)t * RSC + a0 + c * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < IB; ++q) {
+        const int row = (wave * IB + q) * RPI + lane / CH;
+        const int c = (lane % CH) ^ ((row / RPS) % CH);
+        const u32x2 e = *reinterpret_cast<const u32x2 *>(rowtab + 2 * row);
+        voffB[q] = e.x + c * 16;
+        maskB[q] = e.y;
+    }
+    const unsigned smem_base = lds_offset(smem);
+    const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
+
+    int kk = kbeg * BK;
+    int tap = kk / g.K, c0 = kk - tap * g.K;
+    int tr = tap / g.S, ts = tap - tr * g.S;
+    auto issue = [&](int stage) {
+        const unsigned ua = ((unsigned)c0 * RSC + (unsigned)tap * g.C) * 2u;
+        const unsigned ub = (unsigned)(c0 - (tr * g.Wo + ts) * g.K) * 2u;
+        const unsigned bit = 1u << tap;
+        const unsigned sb = stage * STAGE;
+#pragma unroll
+        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, voffA[q] + ua);
+#pragma unroll
+        for (int q = 0; q < IB; ++q) dma16(rdy, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
+        c0 += BK;
+        if (c0 >= g.K) { c0 = 0; ++tap; if (++ts == g.S) { ts = 0; ++tr; } }
+    };
+
+    f32x16 acc[FA][FB];
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
+
+    unsigned fa[KS][FA], fb[KS];
+    {
+        const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+        const int rB = brow + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int t = ks * 16 + tl;
+#pragma unroll
+            for (int i = 0; i < FA; ++i) {
+                const int col = arow + i * 32 + cl;
+                fa[ks][i] = smem_base + t * ROWA + ((((col >> 5) ^ seg_swz<TA>(t)) << 6) | ((col & 31) << 1));
+            }
+            fb[ks] = smem_base + A_BYTES + rB * ROWB + (((2 * ks + (lane >> 5)) ^ ((rB / RPS) % CH)) << 4);
+        }
+    }
+
+    constexpr int LPS = IA + IB;
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+        if (s < nsteps) issue(s);
+    for (int i = 0; i < nsteps; ++i) {
+        const int younger = min(nsteps - 1 - i, NS - 2);
+        if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+        else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS);
+        const unsigned sb = (i % NS) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x2 alo[FA], ahi[FA];
+            u32x4 b[FB];
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii) {
+                alo[ii] = lds_read_tr<0>(fa[ks][ii] + sb);
+                ahi[ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);
+            }
+            if constexpr (FB >= 1) b[0] = lds_read16<0>(fb[ks] + sb);
+            if constexpr (FB >= 2) b[1] = lds_read16<32 * ROWB>(fb[ks] + sb);
+            if constexpr (FB >= 3) b[2] = lds_read16<64 * ROWB>(fb[ks] + sb);
+            if constexpr (FB >= 4) b[3] = lds_read16<96 * ROWB>(fb[ks] + sb);
+            asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[ii])); asm volatile("" : "+v"(ahi[ii])); }
+#pragma unroll
+            for (int jj = 0; jj < FB; ++jj) asm volatile("" : "+v"(b[jj]));
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii)
+#pragma unroll
+                for (int jj = 0; jj < FB; ++jj) {
+                    const u32x4 av = {alo[ii].x, alo[ii].y, ahi[ii].x, ahi[ii].y};
+                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b[jj]),
+                                                                         acc[ii][jj], 0, 0, 0);
+                }
+        }
+    }
+    __syncthreads();
+    if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
+        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
+    else
+        store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+}
+
 struct DmaVariant { int TA, TB, BK, WA, WB, NS; };
 const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {128, 128, 32, 2, 2, 4},
                            {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
                            {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2}};
 constexpr int kNumDma = 12;
 typedef void (*KernelFn)(const KArgs);
+KernelFn pick_dma_d(int v)
+{
+    switch (v) {
+    case 0: return k_dgrad_dma<128, 128, 64, 2, 2, 2>;
+    case 1: return k_dgrad_dma<128, 128, 32, 2, 2, 2>;
+    case 2: return k_dgrad_dma<128, 128, 32, 2, 2, 3>;
+    case 3: return k_dgrad_dma<128, 128, 32, 2, 2, 4>;
+    case 4: return k_dgrad_dma<64, 128, 64, 2, 2, 2>;
+    case 5: return k_dgrad_dma<64, 128, 32, 2, 2, 3>;
+    case 6: return k_dgrad_dma<128, 64, 64, 2, 2, 2>;
+    case 8: return k_dgrad_dma<256, 256, 64, 2, 4, 2>;
+    case 9: return k_dgrad_dma<256, 128, 64, 4, 2, 2>;
+    case 10: return k_dgrad_dma<128, 256, 64, 2, 4, 2>;
+    case 11: return k_dgrad_dma<256, 256, 64, 4, 2, 2>;
+    default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
+    }
+}
 KernelFn pick_dma(int v)
 {
     switch (v) {
@@ -495,6 +657,11 @@ hipError_t dma_init()
                                            (int)dma_lds_bytes(kDma[v]));
         if (e != hipSuccess) return e;
     }
+    for (int v = 0; v < kNumDma; ++v) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma_d(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)dma_lds_bytes(kDma[v]));
+        if (e != hipSuccess) return e;
+    }
     for (int v = 0; v < kNumDmaW; ++v) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma_w(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)dma_w_lds_bytes(kDmaW[v]));
@@ -515,6 +682,12 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         if (g.C % d->BK != 0) return false;
         pl->variant = force_variant - 200;
         rowsA = g.K; rowsB = g.N * g.Ho * g.Wo; red = g.R * g.S * g.C;
+    } else if (pass == PASS_DGRAD) {
+        if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
+        d = &kDma[force_variant - 200];
+        if (g.K % d->BK != 0 || g.C % 8 != 0 || g.sh != 1 || g.sw != 1) return false;
+        pl->variant = force_variant - 200;
+        rowsA = g.C; rowsB = g.N * g.H * g.W; red = g.R * g.S * g.K;
     } else if (pass == PASS_WGRAD) {
         if (force_variant < 300 || force_variant >= 300 + kNumDmaW) return false;
         d = &kDmaW[force_variant - 300];
@@ -546,7 +719,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
 void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
-    snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", pass == PASS_WGRAD ? "k_wgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
+    snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", pass == PASS_WGRAD ? "k_wgrad_dma" : pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
              d.WB, d.NS);
 }
 
@@ -555,6 +728,7 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     KArgs p;
     p.g = a.g;
     if (a.pass == PASS_FWD) { p.rowsA = a.g.K; p.rowsB = a.g.N * a.g.Ho * a.g.Wo; p.red = a.g.R * a.g.S * a.g.C; }
+    else if (a.pass == PASS_DGRAD) { p.rowsA = a.g.C; p.rowsB = a.g.N * a.g.H * a.g.W; p.red = a.g.R * a.g.S * a.g.K; }
     else { p.rowsA = a.g.K; p.rowsB = a.g.R * a.g.S * a.g.C; p.red = a.g.N * a.g.Ho * a.g.Wo; }
     p.tilesA = a.plan.tilesA; p.tilesB = a.plan.tilesB;
     p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split; p.splits = a.plan.splits;
@@ -563,7 +737,7 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     const bool wg = a.pass == PASS_WGRAD;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB, 1, 1);
-    hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
+    hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
     return launch_split_reduce(a, p.rowsA, p.rowsB, st);

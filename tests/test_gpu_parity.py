@@ -124,21 +124,30 @@ def test_every_fast_variant_and_split(env, variant, splits):
 @pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211])
 @pytest.mark.parametrize("splits", [1, 2])
 def test_pipelined_forward_variants(env, variant, splits):
-    """Forward kernels with the multi-stage direct-to-LDS pipeline: every stage count / tile shape,
-    reductions shorter and longer than the pipeline depth, ragged pixel and channel tails."""
+    """Forward and backward-data kernels with the multi-stage direct-to-LDS pipeline: every stage
+    count / tile shape, reductions shorter and longer than the pipeline depth, ragged tails."""
     dp, U, orc = env
     dp.dp_set_override(0, variant, splits)
+    dp.dp_set_override(1, variant, splits)
     try:
         for tag, n, h, w, c, k, r, s_, pd in (("pipe_a", 2, 13, 12, 64, 96, 3, 3, (1, 1)), ("pipe_b", 1, 9, 9, 128, 200, 1, 1, (0, 0)),
-                                              ("pipe_c", 3, 10, 17, 64, 264, 1, 7, (0, 3))):
+                                              ("pipe_c", 3, 10, 17, 64, 264, 1, 7, (0, 3)), ("pipe_d", 2, 12, 13, 192, 128, 3, 3, (1, 1))):
             case = U.ConvCase(tag, n, h, w, c, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
-            assert "dma" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            assert "fwd_dma" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
             y = case.run_fwd()
             torch.cuda.synchronize()
             ref = orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd)
             U.assert_bf16_close(U.to_np(y), ref, f"{tag} variant {variant} splits {splits}")
+            if k % 64 == 0 or (k % 32 == 0 and "32, 2, 2" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]):
+                assert "dgrad_dma" in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+            dx = case.run_dgrad(y)
+            torch.cuda.synchronize()
+            y_np = U.to_np(y)
+            U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=y_np, pad=pd),
+                                f"{tag} variant {variant} splits {splits} dx")
     finally:
         dp.dp_set_override(0, -1, 0)
+        dp.dp_set_override(1, -1, 0)
 
 
 @pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307])
