@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--batches", type=str, default="1,2,4,8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying one HIP graph per step")
+    ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="profiling aid: also run an elementwise fp32 copy kernel that reads and writes this many MiB")
     ap.add_argument("--table", type=str, default="", help="also write the per-layer time-vs-batch table (JSON) here")
     return ap.parse_args()
 
@@ -169,8 +172,17 @@ def main():
     batches = [int(b) for b in args.batches.split(",")]
     nmax = max(batches)
 
-    layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in W.vgg16_convs()]
-    layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in W.vgg16_linears()]
+    keep = set(args.layers.split(",")) if args.layers else None
+    layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in W.vgg16_convs() if keep is None or l.name in keep]
+    layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in W.vgg16_linears() if keep is None or l.name in keep]
+    if args.calibrate_copy_mb > 0:
+        # known-size traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters
+        n_el = args.calibrate_copy_mb * (1 << 20) // 4
+        src = torch.ones(n_el, device=dev, dtype=torch.float32)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
     ws_bytes = max(l.ws_bytes(dp, n) for l in layers for n in batches)
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     descs = {(l.name, n): l.desc(dp, n) for l in layers for n in batches}
@@ -276,7 +288,8 @@ def main():
         "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
         "config": {"workload": "VGG-16 13 conv + 3 FC layers, 224x224x3 input, per layer fwd + ReLU/bias-grad + dgrad + wgrad "
                                "(no dgrad for the first layer), "
-                               "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
+                               + ("layers " + args.layers + ", " if args.layers else "")
+                               + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
         "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": "eager" if args.no_graph else "hip_graph",
         "per_batch": per_batch,

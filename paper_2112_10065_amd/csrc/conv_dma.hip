@@ -293,9 +293,12 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
 
     const ConvGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tile = logical_block(blockIdx.x, gridDim.x);
+    // grid = (splits, tiles): consecutive workgroup ids go round-robin to the 8 XCDs, so with the
+    // split as the fast index (and a split count that is a multiple of 8) every block that reads a
+    // given pixel range of x and dy runs on the same XCD and shares that XCD's L2
+    const int tile = blockIdx.y, split = blockIdx.x;
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
-    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
+    const int kbeg = split * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
     const int nsteps = kend - kbeg;
     const int M = p.red;
     __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)M * g.K * 2);
@@ -436,7 +439,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
         // table of step i+NS goes into the slot whose table (step i) was consumed before this barrier
         if (i + NS < nsteps) fill_table(i % NS, kbeg + i + NS);
     }
-    store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+    store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, split);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -587,8 +590,9 @@ __global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
 struct DmaVariant { int TA, TB, BK, WA, WB, NS; };
 const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {128, 128, 32, 2, 2, 4},
                            {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
-                           {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2}};
-constexpr int kNumDma = 12;
+                           {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2},
+                           {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}};
+constexpr int kNumDma = 14;
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -604,6 +608,8 @@ KernelFn pick_dma_d(int v)
     case 9: return k_dgrad_dma<256, 128, 64, 4, 2, 2>;
     case 10: return k_dgrad_dma<128, 256, 64, 2, 4, 2>;
     case 11: return k_dgrad_dma<256, 256, 64, 4, 2, 2>;
+    case 12: return k_dgrad_dma<64, 256, 64, 1, 4, 2>;
+    case 13: return k_dgrad_dma<64, 256, 32, 1, 4, 2>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -621,12 +627,15 @@ KernelFn pick_dma(int v)
     case 9: return k_fwd_dma<256, 128, 64, 4, 2, 2>;
     case 10: return k_fwd_dma<128, 256, 64, 2, 4, 2>;
     case 11: return k_fwd_dma<256, 256, 64, 4, 2, 2>;
+    case 12: return k_fwd_dma<64, 256, 64, 1, 4, 2>;
+    case 13: return k_fwd_dma<64, 256, 32, 1, 4, 2>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
 const DmaVariant kDmaW[] = {{128, 128, 32, 2, 2, 2}, {128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {64, 128, 32, 2, 2, 2},
-                            {128, 64, 32, 2, 2, 2}, {64, 64, 32, 2, 2, 2}, {64, 128, 64, 2, 2, 2}, {256, 128, 32, 4, 2, 2}};
-constexpr int kNumDmaW = 8;
+                            {128, 64, 32, 2, 2, 2}, {64, 64, 32, 2, 2, 2}, {64, 128, 64, 2, 2, 2}, {256, 128, 32, 4, 2, 2},
+                            {64, 256, 32, 1, 4, 2}, {64, 256, 64, 1, 4, 2}};
+constexpr int kNumDmaW = 10;
 KernelFn pick_dma_w(int v)
 {
     switch (v) {
@@ -637,6 +646,8 @@ KernelFn pick_dma_w(int v)
     case 4: return k_wgrad_dma<128, 64, 32, 2, 2, 2>;
     case 5: return k_wgrad_dma<64, 64, 32, 2, 2, 2>;
     case 6: return k_wgrad_dma<64, 128, 64, 2, 2, 2>;
+    case 8: return k_wgrad_dma<64, 256, 32, 1, 4, 2>;
+    case 9: return k_wgrad_dma<64, 256, 64, 1, 4, 2>;
     default: return k_wgrad_dma<256, 128, 32, 4, 2, 2>;
     }
 }
@@ -737,6 +748,7 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     const bool wg = a.pass == PASS_WGRAD;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB, 1, 1);
+    if (wg) grid = dim3((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1);
     hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;

@@ -33,16 +33,18 @@ const Candidate kPix[] = {
 };
 // backward-filter candidates (reduction step 32 unless noted)
 const Candidate kWg[] = {
-    {300, 4, 0.95f, 4.0f},   // 128x128x32 direct-to-LDS
+    {300, 4, 1.00f, 4.0f},   // 128x128x32 direct-to-LDS
     {303, 4, 0.70f, 3.5f},   // 64x128x32
     {304, 4, 0.70f, 3.5f},   // 128x64x32
-    {305, 5, 0.50f, 3.0f},   // 64x64x32
+    {305, 5, 0.62f, 3.5f},   // 64x64x32
+    {308, 3, 1.45f, 4.0f},   // 64x256x32 (few output channels: widest tap tile)
+    {306, 3, 0.93f, 4.0f},   // 64x128x64
     {100, 3, 1.30f, 4.0f},
     {101, 3, 1.00f, 3.5f},
     {102, 3, 1.00f, 3.5f},
     {103, 4, 0.80f, 3.0f},
 };
-const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64, 96, 128};
+const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64, 96, 128, 192, 256};
 
 bool family_plan(const ConvGeom &g, int pass, int code, int splits, GemmPlan *pl)
 {
@@ -90,6 +92,9 @@ bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
         int last_splits = -1;
         for (int s : kSplits) {
             if (force_splits > 0 && s != kSplits[0]) break;
+            // backward-filter blocks of one split share their inputs through one XCD's L2 only if the
+            // split count is a multiple of the 8 XCDs
+            if (pass == PASS_WGRAD && force_splits <= 0 && s > 8 && (s % 8) != 0) continue;
             GemmPlan cand;
             if (!family_plan(g, pass, cands[ci].code, force_splits > 0 ? force_splits : s, &cand)) break;
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan

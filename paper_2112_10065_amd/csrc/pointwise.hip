@@ -34,7 +34,29 @@ __global__ __launch_bounds__(NT) void k_rbg_bf16(long long rows, int k, int cgb,
     const bool active = rsub < rpi && cg * 8 < k;
     float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if (active) {
-        for (long long r = (long long)blockIdx.y * rpi + rsub; r < rows; r += (long long)gridDim.y * rpi) {
+        const long long rstep = (long long)gridDim.y * rpi;
+        long long r = (long long)blockIdx.y * rpi + rsub;
+        // four rows per iteration: eight independent 16-byte loads in flight per thread
+        for (; r + 3 * rstep < rows; r += 4 * rstep) {
+            u32x4 v[4], y[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t o = (size_t)(r + u * rstep) * k + (size_t)cg * 8;
+                v[u] = *reinterpret_cast<const u32x4 *>(dy + o);
+                if (ym != nullptr) y[u] = *reinterpret_cast<const u32x4 *>(ym + o);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t o = (size_t)(r + u * rstep) * k + (size_t)cg * 8;
+                if (ym != nullptr) {
+                    v[u].x &= keep_bits(y[u].x); v[u].y &= keep_bits(y[u].y); v[u].z &= keep_bits(y[u].z); v[u].w &= keep_bits(y[u].w);
+                }
+                if (g_out != nullptr) *reinterpret_cast<u32x4 *>(g_out + o) = v[u];
+                acc[0] += bf16_lo(v[u].x); acc[1] += bf16_hi(v[u].x); acc[2] += bf16_lo(v[u].y); acc[3] += bf16_hi(v[u].y);
+                acc[4] += bf16_lo(v[u].z); acc[5] += bf16_hi(v[u].z); acc[6] += bf16_lo(v[u].w); acc[7] += bf16_hi(v[u].w);
+            }
+        }
+        for (; r < rows; r += rstep) {
             const size_t o = (size_t)r * k + (size_t)cg * 8;
             u32x4 v = *reinterpret_cast<const u32x4 *>(dy + o);
             if (ym != nullptr) {
