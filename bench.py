@@ -25,6 +25,26 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
+# the launches of each kernel in this same sweep: profiles/vgg16_sweep_hbm_traffic.md
+TRAFFIC_BYTES_PER_LAUNCH = {
+    "k_fwd_dma<128, 64, 64, 2, 2, 2>": 143350739,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2>": 140793862,
+    "k_dgrad_dma<256, 256, 64, 2, 4, 2>": 138248948,
+    "k_fwd_dma<256, 256, 64, 2, 4, 2>": 118748957,
+    "k_dgrad_dma<128, 128, 64, 2, 2, 2>": 76728969,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2>": 85178333,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2>": 69082756,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2>": 79982285,
+    "k_conv_gemm<2, 64, 128, 64, 2, 2, true, false>": 75509704,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>": 46310078,
+    "k_conv_fast<0, 64, 64, 64, 2, 2>": 47119806,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3>": 19810296,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3>": 23585470,
+    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>": 9228010,
+    "k_conv_gemm<0, 64, 128, 32, 2, 2, false, false>": 70995070
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -137,7 +157,7 @@ def cpu_baseline():
     import numpy as np
     import oracle
     from paper_2112_10065_amd import synth
-    sample = [("conv3_2", 56, 256, 256, 1), ("conv4_2", 28, 512, 512, 1), ("conv5_1", 14, 512, 512, 2)]
+    sample = [("conv2_2", 112, 128, 128, 1), ("conv3_2", 56, 256, 256, 4), ("conv4_2", 28, 512, 512, 4), ("conv5_1", 14, 512, 512, 4)]
     flops, secs = 0.0, 0.0
     for name, hw, c, k, n in sample:
         x, w, b = synth.conv_tensors(f"vgg/{name}", n, hw, hw, c, k, 3, 3)
@@ -150,7 +170,7 @@ def cpu_baseline():
         secs += time.perf_counter() - t0
         flops += 3 * 2.0 * n * hw * hw * k * 9 * c
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": "fp64 nested-loop oracle, fwd+dgrad+wgrad of VGG-16 conv3_2 (N=1), conv4_2 (N=1), conv5_1 (N=2); "
+            "sample": "fp64 nested-loop oracle, fwd+dgrad+wgrad of VGG-16 conv2_2 (N=1), conv3_2 (N=4), conv4_2 (N=4), conv5_1 (N=4); "
                       f"{flops / 1e9:.1f} GFLOP nominal in {secs:.1f} s"}
 
 
@@ -268,18 +288,21 @@ def main():
                 if splits != 1 or (l.name, n, pname) not in per:
                     continue
                 v = per[(l.name, n, pname)]
-                g = groups.setdefault(kname, {"us": 0.0, "launches": 0, "flops": 0.0})
+                g = groups.setdefault(kname, {"us": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
                 g["us"] += sum(v)
                 g["launches"] += len(v)
                 g["flops"] += l.flops(n) * len(v)
+                sp = l.spec   # algorithmic bytes: input activation + weights + output activation, bf16
+                g["bytes"] += 2.0 * (n * sp.h * sp.w * sp.c + sp.k * sp.r * sp.s * sp.c + n * l.ho * l.wo * sp.k) * len(v)
     roofline = None
     if groups:
         kname, g = max(groups.items(), key=lambda kv: kv[1]["us"])
         achieved = g["flops"] / g["us"] / 1e6
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": kname,
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kname), "kernel": kname,
                     "avg_launch_us": g["us"] / g["launches"], "launches": g["launches"],
-                    "flops_per_launch_avg": g["flops"] / g["launches"]}
+                    "flops_per_launch_avg": g["flops"] / g["launches"],
+                    "algorithmic_bytes_per_launch_avg": g["bytes"] / g["launches"]}
 
     out = {
         "metric": "conv+FC fwd/bwd TFLOP/s and % bf16 MFMA peak vs per-GPU batch 1-32 (VGG-16)",
