@@ -529,9 +529,17 @@ __global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float
     const size_t gstride = (size_t)gridDim.x * blockDim.x;
     if ((total & 3) == 0) {
         for (size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; e < total; e += gstride * 4) {
-            f32x4 s = *reinterpret_cast<const f32x4 *>(partial + e);
-            for (int sp = 1; sp < splits; ++sp) s += *reinterpret_cast<const f32x4 *>(partial + sp * total + e);
-            *reinterpret_cast<f32x4 *>(out + e) = s;
+            // four independent loads in flight; the sum order is fixed by the code, not by timing
+            f32x4 s0 = *reinterpret_cast<const f32x4 *>(partial + e), s1 = {0, 0, 0, 0}, s2 = {0, 0, 0, 0}, s3 = {0, 0, 0, 0};
+            int sp = 1;
+            for (; sp + 3 < splits; sp += 4) {
+                s1 += *reinterpret_cast<const f32x4 *>(partial + (size_t)sp * total + e);
+                s2 += *reinterpret_cast<const f32x4 *>(partial + (size_t)(sp + 1) * total + e);
+                s3 += *reinterpret_cast<const f32x4 *>(partial + (size_t)(sp + 2) * total + e);
+                s0 += *reinterpret_cast<const f32x4 *>(partial + (size_t)(sp + 3) * total + e);
+            }
+            for (; sp < splits; ++sp) s1 += *reinterpret_cast<const f32x4 *>(partial + (size_t)sp * total + e);
+            *reinterpret_cast<f32x4 *>(out + e) = (s0 + s1) + (s2 + s3);
         }
     } else {
         for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gstride) {
@@ -539,6 +547,32 @@ __global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float
             for (int sp = 1; sp < splits; ++sp) v += partial[sp * total + e];
             out[e] = v;
         }
+    }
+}
+
+// Many splits over a small output (long reductions into a small filter): 8 threads share one group
+// of four outputs, each sums every 8th partial, the 8 part sums are combined through LDS in order.
+__global__ __launch_bounds__(256) void k_reduce_flat_wide(const float *partial, float *out, size_t total, int splits)
+{
+    __shared__ f32x4 sm[8][32];
+    const int g = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const size_t e = ((size_t)blockIdx.x * 32 + g) * 4;
+    f32x4 s0 = {0, 0, 0, 0}, s1 = {0, 0, 0, 0};
+    if (e < total) {
+        int sp = part;
+        for (; sp + 8 < splits; sp += 16) {
+            s0 += *reinterpret_cast<const f32x4 *>(partial + (size_t)sp * total + e);
+            s1 += *reinterpret_cast<const f32x4 *>(partial + (size_t)(sp + 8) * total + e);
+        }
+        for (; sp < splits; sp += 8) s0 += *reinterpret_cast<const f32x4 *>(partial + (size_t)sp * total + e);
+    }
+    sm[part][g] = s0 + s1;
+    __syncthreads();
+    if (part == 0 && e < total) {
+        f32x4 s = sm[0][g];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) s += sm[i][g];
+        *reinterpret_cast<f32x4 *>(out + e) = s;
     }
 }
 
@@ -699,9 +733,13 @@ hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStrea
     unsigned nb = (unsigned)((work + 255) / 256);
     if (nb > 4096) nb = 4096;
     if (nb < 1) nb = 1;
-    if (a.pass == PASS_WGRAD)
-        hipLaunchKernelGGL(k_reduce_flat, dim3(nb), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits);
-    else
+    if (a.pass == PASS_WGRAD) {
+        if ((total & 3) == 0 && p.splits >= 16 && work <= 65536)
+            hipLaunchKernelGGL(k_reduce_flat_wide, dim3((unsigned)((work + 31) / 32)), dim3(256), 0, st, p.partial,
+                               reinterpret_cast<float *>(p.out), total, p.splits);
+        else
+            hipLaunchKernelGGL(k_reduce_flat, dim3(nb), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits);
+    } else
         hipLaunchKernelGGL(k_reduce_pixel_major, dim3(nb), dim3(256), 0, st, p);
     return hipGetLastError();
 }

@@ -147,6 +147,8 @@ __global__ __launch_bounds__(256) void k_rbg_final(int k, int row_blocks, const 
 
 int row_blocks_for(long long rows, int rows_per_iter, int col_blocks)
 {
+    // short inputs: one block per column group walks every row and writes the bias gradient itself
+    if ((rows + rows_per_iter - 1) / rows_per_iter <= 48) return 1;
     long long want = 1024 / (col_blocks > 0 ? col_blocks : 1);  // about four blocks per CU in total
     long long most = (rows + rows_per_iter - 1) / rows_per_iter;
     if (want > most) want = most;
@@ -166,7 +168,7 @@ size_t rbg_workspace_bytes(long long rows, int k)
 hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask, void *g_out, float *dbias,
                       float *ws, hipStream_t st)
 {
-    float *wsp = dbias != nullptr ? ws : nullptr;
+    float *wsp = dbias != nullptr ? ws : nullptr;   // replaced by dbias itself when a single row block is used
     int rb;
     if (bf16 && (k % 8) == 0) {
         int chunks = k / 8;
@@ -174,11 +176,13 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
         int rpi = NT / cgb;
         int col_blocks = (chunks + cgb - 1) / cgb;
         rb = row_blocks_for(rows, rpi, col_blocks);
+        if (rb == 1 && dbias != nullptr) wsp = dbias;
         hipLaunchKernelGGL(k_rbg_bf16, dim3(col_blocks, rb), dim3(NT), 0, st, rows, k, cgb, rpi,
                            (const unsigned short *)dy, (const unsigned short *)ymask, (unsigned short *)g_out, wsp);
     } else {
         int col_blocks = (k + 63) / 64;
         rb = row_blocks_for(rows, 1, col_blocks);
+        if (rb == 1 && dbias != nullptr) wsp = dbias;
         if (bf16)
             hipLaunchKernelGGL(k_rbg_cols<unsigned short>, dim3(col_blocks, rb), dim3(64), 0, st, rows, k,
                                (const unsigned short *)dy, (const unsigned short *)ymask, (unsigned short *)g_out, wsp);
@@ -187,7 +191,7 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
                                (const float *)ymask, (float *)g_out, wsp);
     }
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || dbias == nullptr) return e;
+    if (e != hipSuccess || dbias == nullptr || rb == 1) return e;
     hipLaunchKernelGGL(k_rbg_final, dim3((k + 31) / 32), dim3(256), 0, st, k, rb, ws, dbias);
     return hipGetLastError();
 }
