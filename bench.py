@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--batches", type=str, default="1,2,4,8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying one HIP graph per step")
+    ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception"],
+                    help="layer list; the metric and the default run are VGG-16, the others emit their own tables")
     ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="profiling aid: also run an elementwise fp32 copy kernel that reads and writes this many MiB")
@@ -97,7 +99,7 @@ class Layer:
     def desc(self, dp, n):
         l = self.spec
         if self.is_conv:
-            flags = dp.DP_BIAS | dp.DP_RELU | (dp.DP_DX_F32 if self.dx_f32 else 0)
+            flags = (dp.DP_BIAS if l.bias else 0) | dp.DP_RELU | (dp.DP_DX_F32 if self.dx_f32 else 0)
             return dp.conv_desc(n, l.h, l.w, l.c, l.k, l.r, l.s, (l.sh, l.sw), (l.ph, l.pw), dp.DP_BF16, flags)
         return dp.linear_desc(n, l.in_f, l.out_f, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
 
@@ -120,7 +122,7 @@ class Layer:
     # the three passes; each is one library call
     def fwd(self, dp, d, ws):
         if self.is_conv:
-            dp.dp_conv2d_fwd(d, self.x, self.w, self.bias, self.y, ws)
+            dp.dp_conv2d_fwd(d, self.x, self.w, self.bias if self.spec.bias else None, self.y, ws)
         else:
             dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws)
 
@@ -193,8 +195,10 @@ def main():
     nmax = max(batches)
 
     keep = set(args.layers.split(",")) if args.layers else None
-    layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in W.vgg16_convs() if keep is None or l.name in keep]
-    layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in W.vgg16_linears() if keep is None or l.name in keep]
+    convs = {"vgg16": W.vgg16_convs, "resnet50": W.resnet50_convs, "inception": W.inception_convs}[args.workload]()
+    linears = W.vgg16_linears() if args.workload == "vgg16" else []
+    layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in convs if keep is None or l.name in keep]
+    layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in linears if keep is None or l.name in keep]
     if args.calibrate_copy_mb > 0:
         # known-size traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters
         n_el = args.calibrate_copy_mb * (1 << 20) // 4
@@ -309,7 +313,9 @@ def main():
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "strong", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
-        "config": {"workload": "VGG-16 13 conv + 3 FC layers, 224x224x3 input, per layer fwd + ReLU/bias-grad + dgrad + wgrad "
+        "config": {"workload": {"vgg16": "VGG-16 13 conv + 3 FC layers, 224x224x3 input", "resnet50": "ResNet-50 conv layers (23 unique shapes), 224x224x3 input",
+                                "inception": "Inception-v3-style conv layers (18 shapes), 299x299x3 input"}[args.workload]
+                               + ", per layer fwd + ReLU/bias-grad + dgrad + wgrad "
                                "(no dgrad for the first layer), "
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",

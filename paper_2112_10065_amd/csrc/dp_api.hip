@@ -120,6 +120,25 @@ unsigned kflags(unsigned f, bool fwd)
     return k;
 }
 
+// The 1x1 geometry that a few-input-channel layer becomes after an explicit im2col (small_c.hip).
+ConvGeom im2col_geom(const ConvGeom &g, int kpad)
+{
+    return ConvGeom{g.N, g.Ho, g.Wo, kpad, g.K, 1, 1, 1, 1, 0, 0, g.Ho, g.Wo};
+}
+size_t xcol_bytes(const ConvGeom &g, int kpad) { return round256((size_t)g.N * g.Ho * g.Wo * kpad * 2); }
+bool use_small_c(const ConvGeom &g, int pass) { return g_force_variant[pass].load() < 0 && small_c_kpad(g) > 0; }
+
+size_t fwd_ws_bytes(const ConvGeom &g)
+{
+    if (use_small_c(g, PASS_FWD)) {
+        const int kpad = small_c_kpad(g);
+        return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2) + fwd_ws_bytes(im2col_geom(g, kpad));
+    }
+    GemmPlan pl;
+    plan_for(g, PASS_FWD, &pl);
+    return mfma_partial_bytes(g, PASS_FWD, pl);
+}
+
 // ---- the three passes on a validated geometry --------------------------------------
 dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, const void *w, const float *bias, void *y,
                   void *ws, size_t ws_bytes, hipStream_t st)
@@ -127,6 +146,17 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     if (dtype == DP_F32) {
         hipError_t e = f32_conv_fwd(g, kflags(flags, true), (const float *)x, (const float *)w, bias, (float *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
+    }
+    if (use_small_c(g, PASS_FWD)) {
+        const int kpad = small_c_kpad(g);
+        const size_t need = fwd_ws_bytes(g);
+        if (ws == nullptr || ws_bytes < need) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
+        bf16_t *xcol = (bf16_t *)ws, *wpad = (bf16_t *)((char *)ws + xcol_bytes(g, kpad));
+        const size_t used = xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2);
+        hipError_t e = small_c_im2col(g, kpad, (const bf16_t *)x, xcol, st);
+        if (e == hipSuccess) e = small_c_pad_weights(g, kpad, (const bf16_t *)w, wpad, st);
+        if (e != hipSuccess) return hip_fail(e, "im2col launch");
+        return run_fwd(im2col_geom(g, kpad), dtype, flags, xcol, wpad, bias, y, (char *)ws + used, ws_bytes - used, st);
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_FWD; a.flags = kflags(flags, true);
@@ -172,6 +202,10 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
 size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
 {
     size_t need = 0;
+    if (dtype == DP_BF16 && use_small_c(g, PASS_WGRAD)) {
+        const int kpad = small_c_kpad(g);
+        return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 4) + wgrad_ws_bytes(im2col_geom(g, kpad), dtype, with_db);
+    }
     if (dtype == DP_BF16) {
         GemmPlan pl;
         plan_for(g, PASS_WGRAD, &pl);
@@ -199,6 +233,21 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
             if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
         }
         return DP_OK;
+    }
+    if (use_small_c(g, PASS_WGRAD)) {
+        const int kpad = small_c_kpad(g);
+        bf16_t *xcol = (bf16_t *)ws;
+        float *dwpad = (float *)((char *)ws + xcol_bytes(g, kpad));
+        const size_t used = xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 4);
+        if (dw != nullptr) {
+            hipError_t e = small_c_im2col(g, kpad, (const bf16_t *)x, xcol, st);
+            if (e != hipSuccess) return hip_fail(e, "im2col launch");
+        }
+        dp_status s = run_wgrad(im2col_geom(g, kpad), dtype, xcol, dy, ym, dw != nullptr ? dwpad : nullptr, db, (char *)ws + used,
+                                ws_bytes - used, st);
+        if (s != DP_OK || dw == nullptr) return s;
+        hipError_t e = small_c_unpad_dw(g, kpad, dwpad, dw, st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "filter-gradient unpad launch");
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
@@ -256,6 +305,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }
+    if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
     GemmPlan pl;
     plan_for(g, pass, &pl);
     if (name != nullptr && name_bytes > 0) { if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
@@ -269,9 +319,10 @@ size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
     if (check_conv(desc, &g) != DP_OK || pass < 0 || pass > 2) return 0;
     if (pass == DP_PASS_WGRAD) return wgrad_ws_bytes(g, desc->io_dtype, true);
     if (desc->io_dtype == DP_F32) return 0;
+    if (pass == DP_PASS_FWD) return fwd_ws_bytes(g);
     GemmPlan pl;
     plan_for(g, pass, &pl);
-    return pass == DP_PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
+    return dgrad_ws_bytes(g, pl);
 }
 
 size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
@@ -283,7 +334,7 @@ size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
         for (int pass = 0; pass < 2; ++pass) {
             GemmPlan pl;
             plan_for(g, pass, &pl);
-            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
+            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : fwd_ws_bytes(g);
             if (b > need) need = b;
         }
     }
@@ -300,9 +351,7 @@ dp_status dp_conv2d_fwd(const dp_conv_desc *desc, const void *x, const void *w, 
     if (desc->flags & DP_BIAS) { if ((s = check_ptr(bias, "bias")) != DP_OK) return s; }
     if ((s = check_opt(ws, "ws")) != DP_OK) return s;
     if (desc->io_dtype == DP_BF16) {
-        GemmPlan pl;
-        plan_for(g, PASS_FWD, &pl);
-        size_t need = mfma_partial_bytes(g, PASS_FWD, pl);
+        size_t need = fwd_ws_bytes(g);
         if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
     }
     if ((s = ensure_init()) != DP_OK) return s;
@@ -428,7 +477,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
             for (int pass = 0; pass < 2; ++pass) {
                 GemmPlan pl;
                 plan_for(g, pass, &pl);
-                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : mfma_partial_bytes(g, pass, pl);
+                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : fwd_ws_bytes(g);
                 if (b > wsb) wsb = b;
             }
         const size_t dxes = (flags & DP_DX_F32) ? 4 : es;

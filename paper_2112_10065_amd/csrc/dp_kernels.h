@@ -84,3 +84,9 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
 
 // planner.hip : picks the cheapest fast-path variant and split for a pass (host-side cost model)
 bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *plan);
+
+// small_c.hip : explicit im2col for layers with very few input channels (c_in % 8 != 0, R*S*C <= 256)
+int small_c_kpad(const ConvGeom &g);   // padded reduction length, 0 if the layer does not qualify
+hipError_t small_c_im2col(const ConvGeom &g, int kpad, const bf16_t *x, bf16_t *xcol, hipStream_t st);
+hipError_t small_c_pad_weights(const ConvGeom &g, int kpad, const bf16_t *w, bf16_t *wpad, hipStream_t st);
+hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, float *dw, hipStream_t st);

@@ -26,6 +26,9 @@ const Candidate kPix[] = {
     {204, 3, 0.85f, 4.5f},   // 64x128x64
     {206, 3, 0.85f, 4.5f},   // 128x64x64
     {207, 3, 0.62f, 4.0f},   // 64x64x64
+    {201, 4, 1.08f, 4.5f},   // direct-to-LDS with reduction step 32 (channels % 32 only)
+    {205, 4, 0.85f, 4.0f},
+    {213, 3, 1.30f, 4.5f},
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},
@@ -97,6 +100,8 @@ bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
             if (pass == PASS_WGRAD && force_splits <= 0 && s > 8 && (s % 8) != 0) continue;
             GemmPlan cand;
             if (!family_plan(g, pass, cands[ci].code, force_splits > 0 ? force_splits : s, &cand)) break;
+            // reduction step 32 only where 64 does not divide the channel count
+            if (pass != PASS_WGRAD && cand.BK == 32 && ((pass == PASS_FWD ? g.C : g.K) % 64) == 0) break;
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
             last_splits = cand.splits;
             if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;

@@ -343,3 +343,56 @@ def test_profile_layer_rows(env):
     ld = dp.linear_desc(1, 4096, 1000, dp.DP_BF16, dp.DP_BIAS)
     rows = dp.dp_profile_layer(linear=ld, batches=(1, 32), warmup=1, iters=3)
     assert rows[1]["flops_per_pass"] == 2.0 * 32 * 4096 * 1000 and rows[0]["wgrad_us"] > 0
+
+
+# ---- ResNet-50 and Inception-v3-style layer lists (configurations 3 and 4), full size, spot-checked --------
+def _sampled_layer_check(dp, U, orc, l, n, tag):
+    st, pd = (l.sh, l.sw), (l.ph, l.pw)
+    dxf = l.c < 8
+    case = U.ConvCase(f"{tag}/{l.name}", n, l.h, l.w, l.c, l.k, l.r, l.s, st, pd, bf16=True, bias=l.bias, relu=True, dx_f32=dxf)
+    y = case.run_fwd()
+    dx = case.run_dgrad(y)
+    dw, db = case.run_wgrad(y)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(abs(hash(l.name)) % (1 << 31))
+    y_np = U.to_np(y)
+    idx = rng.integers(0, y_np.size, 1500)
+    idx[:16] = np.arange(16)
+    idx[16:32] = y_np.size - 1 - np.arange(16)
+    U.assert_bf16_close(y_np.ravel()[idx], orc.conv2d_fwd_at(case.x, case.w, case.b, True, st, pd, idx), f"{l.name} y")
+    dx_np = U.to_np(dx)
+    idx = rng.integers(0, dx_np.size, 1500)
+    idx[:16] = np.arange(16)
+    idx[16:32] = dx_np.size - 1 - np.arange(16)
+    U.assert_bf16_close(dx_np.ravel()[idx], orc.conv2d_bwd_data_at(case.dy, case.w, case.x.shape, y_np, st, pd, idx), f"{l.name} dx")
+    dw_np = U.to_np(dw)
+    idx = rng.integers(0, dw_np.size, 400)
+    idx[:8] = np.arange(8)
+    idx[8:16] = dw_np.size - 1 - np.arange(8)
+    U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, y_np, st, pd, idx), f"{l.name} dw")
+    _, rdb = orc.relu_bias_grad(case.dy, y_np)
+    U.assert_bf16_close(U.to_np(db), rdb, f"{l.name} db")
+
+
+def _resnet_layers():
+    from paper_2112_10065_amd import workloads
+    return workloads.resnet50_convs()
+
+
+def _inception_layers():
+    from paper_2112_10065_amd import workloads
+    return workloads.inception_convs()
+
+
+@pytest.mark.parametrize("li", range(23))
+def test_resnet50_layers_sampled(env, li):
+    dp, U, orc = env
+    l = _resnet_layers()[li]
+    _sampled_layer_check(dp, U, orc, l, 2 if l.h > 56 else 3, "resnet50")
+
+
+@pytest.mark.parametrize("li", range(18))
+def test_inception_layers_sampled(env, li):
+    dp, U, orc = env
+    l = _inception_layers()[li]
+    _sampled_layer_check(dp, U, orc, l, 1 if l.h > 100 else 4, "inception")
