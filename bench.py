@@ -53,6 +53,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batches", type=str, default="1,2,4,8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--side-streams", type=int, default=2, help="streams that run the filter gradients beside the backward chain")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying one HIP graph per step")
     ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception"],
                     help="layer list; the metric and the default run are VGG-16, the others emit their own tables")
@@ -120,27 +121,27 @@ class Layer:
         return n * self.ho * self.wo if self.is_conv else n
 
     # the three passes; each is one library call
-    def fwd(self, dp, d, ws):
+    def fwd(self, dp, d, ws, stream=None):
         if self.is_conv:
-            dp.dp_conv2d_fwd(d, self.x, self.w, self.bias if self.spec.bias else None, self.y, ws)
+            dp.dp_conv2d_fwd(d, self.x, self.w, self.bias if self.spec.bias else None, self.y, ws, stream)
         else:
-            dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws)
+            dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws, stream=stream)
 
-    def rgrad(self, dp, d, ws):
+    def rgrad(self, dp, d, ws, stream=None):
         """g = dy * [y > 0] and db = column sums of g, in one pointwise pass."""
-        dp.dp_relu_bias_grad(self.rows(d.n), self.k, dp.DP_BF16, self.dy, self.y, self.g, self.db, ws)
+        dp.dp_relu_bias_grad(self.rows(d.n), self.k, dp.DP_BF16, self.dy, self.y, self.g, self.db, ws, stream)
 
-    def dgrad(self, dp, d, ws):
+    def dgrad(self, dp, d, ws, stream=None):
         if self.is_conv:
-            dp.dp_conv2d_bwd_data(d, self.g, None, self.w, self.dx, ws)
+            dp.dp_conv2d_bwd_data(d, self.g, None, self.w, self.dx, ws, stream)
         else:
-            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.g, dx=self.dx, ws=ws)
+            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.g, dx=self.dx, ws=ws, stream=stream)
 
-    def wgrad(self, dp, d, ws):
+    def wgrad(self, dp, d, ws, stream=None):
         if self.is_conv:
-            dp.dp_conv2d_bwd_filter(d, self.x, self.g, None, self.dw, None, ws)
+            dp.dp_conv2d_bwd_filter(d, self.x, self.g, None, self.dw, None, ws, stream)
         else:
-            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws)
+            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws, stream=stream)
 
     def passes(self):
         """(name, method, counts nominal flops) of the calls that make up this layer's share of a step."""
@@ -211,31 +212,58 @@ def main():
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     descs = {(l.name, n): l.desc(dp, n) for l in layers for n in batches}
 
+    n_side = max(1, args.side_streams)
+    ws_side = [torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(n_side)]
+    side_streams = [torch.cuda.Stream() for _ in range(n_side)]   # default priority
+
     def step():
+        """One training-iteration-shaped pass per batch size: forward through the layers, then backward
+        from the last layer; the filter gradient of a layer depends only on that layer's masked
+        gradient, so it runs on a side stream beside the data-gradient chain (own workspace per stream)."""
+        main = torch.cuda.current_stream()
         for n in batches:
             for l in layers:
+                l.fwd(dp, descs[(l.name, n)], ws, main)
+            for li, l in enumerate(reversed(layers)):
                 d = descs[(l.name, n)]
-                for _, fn, _ in l.passes():
-                    fn(dp, d, ws)
+                l.rgrad(dp, d, ws, main)
+                ready = torch.cuda.Event()
+                ready.record(main)
+                side = side_streams[li % n_side]
+                side.wait_event(ready)
+                l.wgrad(dp, d, ws_side[li % n_side], side)
+                if l.needs_dx:
+                    l.dgrad(dp, d, ws, main)
+            for side in side_streams:
+                main.wait_stream(side)
 
     flops_step = sum(l.step_flops(n) for l in layers for n in batches)
     # One step is captured into a HIP graph and replayed (the paper runs whole iterations as
     # graphs for the same reason: at small per-GPU batch the kernels are shorter than a launch).
     # The library enqueues only kernels on the stream it is given: nothing else is recorded.
-    run_step = step
+    def timed(fn, reps):
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps
+
+    run_step, launch = step, "eager"
+    for _ in range(max(1, args.warmup)):
+        step()                           # also runs the library's one-time initialisation
     if not args.no_graph:
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()                       # library initialisation happens outside the capture
-        torch.cuda.current_stream().wait_stream(side)
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
+        with torch.cuda.graph(graph, stream=cap):
             step()
-        run_step = graph.replay
-    for _ in range(args.warmup):
-        run_step()
+        graph.replay()
+        # warm-up doubles as the choice of launch mode: both replay the same kernels on the same data
+        reps = max(1, args.warmup)
+        if timed(graph.replay, reps) < timed(step, reps):
+            run_step, launch = graph.replay, "hip_graph"
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -320,7 +348,7 @@ def main():
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
-        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": "eager" if args.no_graph else "hip_graph",
+        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch,
         "per_batch": per_batch,
         "roofline": roofline,
     }
