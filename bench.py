@@ -64,6 +64,25 @@ def parse():
     return ap.parse_args()
 
 
+class _BindProxy:
+    """Stands in for the binding module: every dp_* call is turned into a pre-marshalled callable."""
+
+    def __init__(self, dp, out):
+        self._dp, self._out = dp, out
+
+    def __getattr__(self, name):
+        attr = getattr(self._dp, name)
+        if not name.startswith("dp_"):
+            return attr
+
+        def rec(*args, **kw):
+            import inspect
+            ba = inspect.signature(attr).bind(*args, **kw)
+            ba.apply_defaults()
+            self._out.append(self._dp.bind(name, *ba.args))
+        return rec
+
+
 class Layer:
     """Device tensors of one layer at the largest batch; smaller batches use the leading samples."""
 
@@ -143,6 +162,12 @@ class Layer:
         else:
             dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws, stream=stream)
 
+    def bound(self, which, dp, d, ws, stream):
+        """Zero-argument callable issuing the C call of pass `which` (arguments marshalled once)."""
+        rec = []
+        getattr(self, which)(_BindProxy(dp, rec), d, ws, stream)
+        return rec[0]
+
     def passes(self):
         """(name, method, counts nominal flops) of the calls that make up this layer's share of a step."""
         out = [("fwd", self.fwd, True), ("rgrad", self.rgrad, False)]
@@ -216,26 +241,46 @@ def main():
     ws_side = [torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(n_side)]
     side_streams = [torch.cuda.Stream() for _ in range(n_side)]   # default priority
 
+    def build_step(main):
+        """Pre-marshalled launch list of one step on stream `main` (+ the side streams)."""
+        ops = []   # (kind, payload): "call" zero-arg launch, "fork" (event, side stream), "join"
+        for n in batches:
+            for l in layers:
+                ops.append(("call", l.bound("fwd", dp, descs[(l.name, n)], ws, main)))
+            for li, l in enumerate(reversed(layers)):
+                d = descs[(l.name, n)]
+                side, wss = side_streams[li % n_side], ws_side[li % n_side]
+                ops.append(("call", l.bound("rgrad", dp, d, ws, main)))
+                ops.append(("fork", (torch.cuda.Event(), side)))
+                ops.append(("call", l.bound("wgrad", dp, d, wss, side)))
+                if l.needs_dx:
+                    ops.append(("call", l.bound("dgrad", dp, d, ws, main)))
+            ops.append(("join", None))
+        return ops
+
+    def run_ops(ops, main):
+        for kind, payload in ops:
+            if kind == "call":
+                payload()
+            elif kind == "fork":
+                ev, side = payload
+                ev.record(main)
+                side.wait_event(ev)
+            else:
+                for side in side_streams:
+                    main.wait_stream(side)
+
+    _ops_cache = {}
+
     def step():
         """One training-iteration-shaped pass per batch size: forward through the layers, then backward
         from the last layer; the filter gradient of a layer depends only on that layer's masked
         gradient, so it runs on a side stream beside the data-gradient chain (own workspace per stream)."""
         main = torch.cuda.current_stream()
-        for n in batches:
-            for l in layers:
-                l.fwd(dp, descs[(l.name, n)], ws, main)
-            for li, l in enumerate(reversed(layers)):
-                d = descs[(l.name, n)]
-                l.rgrad(dp, d, ws, main)
-                ready = torch.cuda.Event()
-                ready.record(main)
-                side = side_streams[li % n_side]
-                side.wait_event(ready)
-                l.wgrad(dp, d, ws_side[li % n_side], side)
-                if l.needs_dx:
-                    l.dgrad(dp, d, ws, main)
-            for side in side_streams:
-                main.wait_stream(side)
+        key = main.cuda_stream
+        if key not in _ops_cache:
+            _ops_cache[key] = build_step(main)
+        run_ops(_ops_cache[key], main)
 
     flops_step = sum(l.step_flops(n) for l in layers for n in batches)
     # One step is captured into a HIP graph and replayed (the paper runs whole iterations as

@@ -177,3 +177,33 @@ def dp_profile_layer(conv=None, linear=None, batches=(1,), warmup=3, iters=10, s
                                 C.byref(linear) if linear is not None else None, arr, n, warmup, iters, rows,
                                 _stream(stream)))
     return [dict((f, getattr(r, f)) for f, _ in dp_profile_row._fields_) for r in rows]
+
+
+def bind(fn_name, *args):
+    """Pre-marshalled call: `fn_name` is an entry point of this module (e.g. "dp_conv2d_fwd"), `args` its
+    arguments in the order of the wrapper above.  Returns a zero-argument callable that issues exactly
+    that C call (descriptor, pointers, sizes and stream are resolved once), for launch-bound loops."""
+    cap = {}
+    g = globals()
+    saved = g["lib"]
+
+    class _Recorder:
+        def __getattr__(self, name):
+            def rec(*cargs):
+                cap["fn"], cap["args"] = getattr(saved, name), cargs
+                return DP_OK
+            return rec
+
+    g["lib"] = _Recorder()
+    try:
+        g[fn_name](*args)
+    finally:
+        g["lib"] = saved
+    fn, cargs = cap["fn"], cap["args"]
+    keep = args   # keeps descriptors / tensors alive as long as the callable
+
+    def call(_fn=fn, _a=cargs, _keep=keep):
+        st = _fn(*_a)
+        if st != DP_OK:
+            raise DpError(st, lib.dp_last_error().decode())
+    return call

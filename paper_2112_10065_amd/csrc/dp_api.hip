@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <unordered_map>
 
 namespace {
 
@@ -85,14 +86,40 @@ dp_status check_opt(const void *p, const char *name)
 
 // tile_variant override: -1 built-in choice (fast path when the shape allows), 0..99 generic
 // kernel variant, 100.. fast-path variant (falls back to the generic kernel if not eligible)
-void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
+void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl)
 {
-    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
     pl->dma = false;
     if (fv < 0 && auto_plan(g, pass, fs, pl)) return;
     if (fv >= 200 && dma_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 100 && fast_plan(g, pass, fv, fs, pl)) return;
     mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
+}
+
+// Planning prices a few hundred candidates; a training loop asks for the same few layers again and
+// again, so each thread remembers its plans.
+struct PlanKey {
+    int v[16];
+    bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
+};
+struct PlanKeyHash {
+    size_t operator()(const PlanKey &k) const
+    {
+        size_t h = 1469598103934665603ull;
+        for (int x : k.v) h = (h ^ (unsigned)x) * 1099511628211ull;
+        return h;
+    }
+};
+
+void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
+{
+    thread_local std::unordered_map<PlanKey, GemmPlan, PlanKeyHash> cache;
+    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
+    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs}};
+    auto it = cache.find(key);
+    if (it != cache.end()) { *pl = it->second; return; }
+    plan_uncached(g, pass, fv, fs, pl);
+    if (cache.size() > 4096) cache.clear();
+    cache.emplace(key, *pl);
 }
 
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
