@@ -87,6 +87,22 @@ double price(const ConvGeom &g, int pass, const Candidate &c, const GemmPlan &pl
 // Fills *pl with the cheapest eligible fast-path plan; false if the shape has none.
 bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
 {
+    // dense-layer-like shapes (a handful of pixel rows): the pass streams the weight matrix once and
+    // is bound by HBM; the smallest tile with about two blocks per CU does that best
+    if (pass != PASS_WGRAD && force_splits <= 0) {
+        const long long rowsB = pass == PASS_FWD ? (long long)g.N * g.Ho * g.Wo : (long long)g.N * g.H * g.W;
+        if (rowsB <= 64) {
+            for (int code : {207, 103}) {
+                GemmPlan one;
+                if (!family_plan(g, pass, code, 1, &one)) continue;
+                const long long tiles = (long long)one.tilesA * one.tilesB;
+                int splits = (int)((512 + tiles - 1) / tiles), max_splits = one.steps_total / 8;
+                if (max_splits < 1) max_splits = 1;
+                if (splits > max_splits) splits = max_splits;
+                if (family_plan(g, pass, code, splits, pl)) return true;
+            }
+        }
+    }
     const Candidate *cands = pass == PASS_WGRAD ? kWg : kPix;
     const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
     double best = 1e30;
