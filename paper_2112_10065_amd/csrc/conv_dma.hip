@@ -105,7 +105,7 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
                 if (p.flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                 const int pix = brow + j * 32 + (lane & 31);
                 *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) =
-                    u32x2{f32_to_bf16(v0) | (f32_to_bf16(v1) << 16), f32_to_bf16(v2) | (f32_to_bf16(v3) << 16)};
+                    u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
             }
         }
     __syncthreads();
@@ -215,29 +215,47 @@ __global__ __launch_bounds__(64 * WA * WB) void k_fwd_dma(const KArgs p)
     }
 
     constexpr int LPS = IA + IB;   // loads per thread and step
+    static_assert(KS % 2 == 0, "fragment double buffer assumes an even number of slices per step");
+    // All NS stages are filled up front.  The hand-over to the next step happens before the LAST
+    // slice of a step is multiplied: by then every fragment of the step is in registers, so after
+    // the barrier the stage is free (the loads of step i+NS go into it) and the first fragments of
+    // step i+1 are fetched while the matrix cores still work on step i.
 #pragma unroll
-    for (int s = 0; s < NS - 1; ++s)
+    for (int s = 0; s < NS; ++s)
         if (s < nsteps) issue(s);
-    for (int i = 0; i < nsteps; ++i) {
-        // loads of steps i+1 .. i+NS-2 may still be in flight
-        const int younger = min(nsteps - 1 - i, NS - 2);
-        if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+    u32x4 fr_a[2][FA], fr_b[2][FB];
+    auto wait_landed = [&](int step) {   // loads of `step` have landed; younger steps may be in flight
+        const int younger = min(step + NS - 1, nsteps - 1) - step;
+        if (NS >= 2 && younger == NS - 1) wait_vmcnt<(NS - 1) * LPS>();
+        else if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS >= 3 ? NS - 2 : 0) * LPS>();
         else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
         else wait_vmcnt<0>();
+    };
+    if (nsteps > 0) {
+        wait_landed(0);
         __builtin_amdgcn_s_barrier();
-        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS);
+        read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0], fb[0]);
+    }
+    for (int i = 0; i < nsteps; ++i) {
         const unsigned sb = (i % NS) * STAGE;
-        // fragments are double-buffered in registers: the reads of slice ks+1 are issued before the
-        // matrix instructions of slice ks, which start once only those newer reads are outstanding
-        u32x4 fr_a[2][FA], fr_b[2][FB];
-        read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0] + sb, fb[0] + sb);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (ks < KS - 1) {
                 read_frags<FA, FB, 32 * ROWB>(fr_a[(ks + 1) & 1], fr_b[(ks + 1) & 1], fa[ks + 1 < KS ? ks + 1 : 0] + sb, fb[ks + 1 < KS ? ks + 1 : 0] + sb);
                 wait_frags<FA + FB, FA, FB>(fr_a[ks & 1], fr_b[ks & 1]);
             } else {
-                wait_frags<0, FA, FB>(fr_a[ks & 1], fr_b[ks & 1]);
+                wait_frags<0, FA, FB>(fr_a[ks & 1], fr_b[ks & 1]);   // this wave has read all it needs of the stage
+                if (i + 1 < nsteps) {
+                    // step i+1 was issued before step i+2 .. i+NS-1, which may still be in flight
+                    const int younger = min(i + NS - 1, nsteps - 1) - (i + 1);
+                    if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+                    else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
+                    else wait_vmcnt<0>();
+                    __builtin_amdgcn_s_barrier();
+                    if (i + NS < nsteps) issue(i % NS);
+                    const unsigned sn = ((i + 1) % NS) * STAGE;
+                    read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0] + sn, fb[0] + sn);
+                }
             }
 #pragma unroll
             for (int ii = 0; ii < FA; ++ii)
@@ -591,8 +609,9 @@ struct DmaVariant { int TA, TB, BK, WA, WB, NS; };
 const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {128, 128, 32, 2, 2, 4},
                            {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
                            {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2},
-                           {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}};
-constexpr int kNumDma = 14;
+                           {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}, {256, 256, 32, 2, 4, 4}, {256, 256, 32, 2, 4, 3},
+                           {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8}};
+constexpr int kNumDma = 21;
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -610,6 +629,13 @@ KernelFn pick_dma_d(int v)
     case 11: return k_dgrad_dma<256, 256, 64, 4, 2, 2>;
     case 12: return k_dgrad_dma<64, 256, 64, 1, 4, 2>;
     case 13: return k_dgrad_dma<64, 256, 32, 1, 4, 2>;
+    case 14: return k_dgrad_dma<256, 256, 32, 2, 4, 4>;
+    case 15: return k_dgrad_dma<256, 256, 32, 2, 4, 3>;
+    case 16: return k_dgrad_dma<128, 32, 64, 4, 1, 6>;
+    case 17: return k_dgrad_dma<256, 32, 64, 4, 1, 4>;
+    case 18: return k_dgrad_dma<128, 32, 64, 4, 1, 4>;
+    case 19: return k_dgrad_dma<256, 64, 32, 4, 1, 6>;
+    case 20: return k_dgrad_dma<64, 32, 64, 2, 1, 8>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -629,13 +655,21 @@ KernelFn pick_dma(int v)
     case 11: return k_fwd_dma<256, 256, 64, 4, 2, 2>;
     case 12: return k_fwd_dma<64, 256, 64, 1, 4, 2>;
     case 13: return k_fwd_dma<64, 256, 32, 1, 4, 2>;
+    case 14: return k_fwd_dma<256, 256, 32, 2, 4, 4>;
+    case 15: return k_fwd_dma<256, 256, 32, 2, 4, 3>;
+    case 16: return k_fwd_dma<128, 32, 64, 4, 1, 6>;
+    case 17: return k_fwd_dma<256, 32, 64, 4, 1, 4>;
+    case 18: return k_fwd_dma<128, 32, 64, 4, 1, 4>;
+    case 19: return k_fwd_dma<256, 64, 32, 4, 1, 6>;
+    case 20: return k_fwd_dma<64, 32, 64, 2, 1, 8>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
 const DmaVariant kDmaW[] = {{128, 128, 32, 2, 2, 2}, {128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {64, 128, 32, 2, 2, 2},
                             {128, 64, 32, 2, 2, 2}, {64, 64, 32, 2, 2, 2}, {64, 128, 64, 2, 2, 2}, {256, 128, 32, 4, 2, 2},
-                            {64, 256, 32, 1, 4, 2}, {64, 256, 64, 1, 4, 2}};
-constexpr int kNumDmaW = 10;
+                            {64, 256, 32, 1, 4, 2}, {64, 256, 64, 1, 4, 2}, {256, 256, 32, 2, 4, 2}, {256, 256, 32, 2, 4, 3},
+                            {256, 256, 64, 2, 4, 2}, {256, 256, 32, 4, 2, 2}, {128, 256, 32, 2, 4, 2}, {128, 256, 32, 1, 4, 2}};
+constexpr int kNumDmaW = 16;
 KernelFn pick_dma_w(int v)
 {
     switch (v) {
@@ -648,6 +682,12 @@ KernelFn pick_dma_w(int v)
     case 6: return k_wgrad_dma<64, 128, 64, 2, 2, 2>;
     case 8: return k_wgrad_dma<64, 256, 32, 1, 4, 2>;
     case 9: return k_wgrad_dma<64, 256, 64, 1, 4, 2>;
+    case 10: return k_wgrad_dma<256, 256, 32, 2, 4, 2>;
+    case 11: return k_wgrad_dma<256, 256, 32, 2, 4, 3>;
+    case 12: return k_wgrad_dma<256, 256, 64, 2, 4, 2>;
+    case 13: return k_wgrad_dma<256, 256, 32, 4, 2, 2>;
+    case 14: return k_wgrad_dma<128, 256, 32, 2, 4, 2>;
+    case 15: return k_wgrad_dma<128, 256, 32, 1, 4, 2>;
     default: return k_wgrad_dma<256, 128, 32, 4, 2, 2>;
     }
 }

@@ -116,7 +116,7 @@ DEVFN void store_pixel_major_staged(const KArgs &p, const f32x16 (&acc)[FA][FB],
                 if (p.flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
                 const int pix = brow + j * 32 + (lane & 31);
                 *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) =
-                    u32x2{f32_to_bf16(v0) | (f32_to_bf16(v1) << 16), f32_to_bf16(v2) | (f32_to_bf16(v3) << 16)};
+                    u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
             }
         }
     __syncthreads();

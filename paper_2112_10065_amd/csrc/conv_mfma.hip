@@ -510,7 +510,7 @@ __global__ __launch_bounds__(256) void k_reduce_pixel_major(const KArgs p)
                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(p.out) + e) = f32x4{v[0], v[1], v[2], v[3]};
             else
                 *reinterpret_cast<u32x2 *>(reinterpret_cast<bf16_t *>(p.out) + e) =
-                    u32x2{f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16), f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16)};
+                    u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         }
     } else {
         for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += gstride) {

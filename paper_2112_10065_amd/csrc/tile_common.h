@@ -40,11 +40,14 @@ DEVFN u32x4 apply_mask(u32x4 v, u32x4 y)
 }
 DEVFN bf16_t mask1(bf16_t v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : (bf16_t)0; }
 
-DEVFN unsigned f32_to_bf16(float f)
+// fp32 -> bf16, round to nearest even, NaN stays NaN: the gfx950 conversion instruction
+// (v_cvt_pk_bf16_f32), which the compiler emits for these casts
+DEVFN unsigned f32_to_bf16(float f) { return __builtin_bit_cast(unsigned short, (__bf16)f); }
+DEVFN unsigned pack_bf16(float lo, float hi)
 {
-    unsigned u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
 // XCD-aware block order: hardware deals consecutive block ids round-robin to the 8 XCDs
@@ -122,7 +125,7 @@ DEVFN void store_pixel_major(const KArgs &p, const f32x16 (&acc)[FA][FB], int ar
                 } else {
                     bf16_t *dst = reinterpret_cast<bf16_t *>(p.out) + o;
                     if (vec4) {
-                        u32x2 pk{f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16), f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16)};
+                        u32x2 pk{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
                         *reinterpret_cast<u32x2 *>(dst) = pk;
                     } else
                         for (int e = 0; e < 4; ++e) if (ch + e < p.rowsA) dst[e] = (bf16_t)f32_to_bf16(v[e]);

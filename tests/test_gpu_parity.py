@@ -121,7 +121,7 @@ def test_every_fast_variant_and_split(env, variant, splits):
             dp.dp_set_override(p, -1, 0)
 
 
-@pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211, 212, 213])
+@pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211, 212, 213, 214, 215, 216, 217, 218, 219, 220])
 @pytest.mark.parametrize("splits", [1, 2])
 def test_pipelined_forward_variants(env, variant, splits):
     """Forward and backward-data kernels with the multi-stage direct-to-LDS pipeline: every stage
@@ -150,7 +150,7 @@ def test_pipelined_forward_variants(env, variant, splits):
         dp.dp_set_override(1, -1, 0)
 
 
-@pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307, 308, 309])
+@pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307, 308, 309, 310, 311, 312, 313, 314, 315])
 @pytest.mark.parametrize("splits", [1, 3])
 def test_pipelined_backward_filter_variants(env, variant, splits):
     """Backward-filter kernels with the direct-to-LDS pipeline and LDS transpose reads."""
