@@ -304,10 +304,13 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     constexpr int RPIA = 512 / TA, RPIB = 512 / TB;              // reduction rows per direct-to-LDS instruction
     constexpr int IA = BK / RPIA / NW, IB = BK / RPIB / NW;
     static_assert(IA * NW * RPIA == BK && IB * NW * RPIB == BK, "reduction rows must divide over the waves");
-    static_assert(BK <= 64, "one wavefront fills the pixel table");
+    // pixel table: {byte offset of the pixel's top-left tap in x, valid-tap mask} for TABN consecutive
+    // reduction rows, two such chunks (the one the loads in flight read and the next one)
+    constexpr int TABN = NT, SPC = TABN / BK;   // table entries and steps per chunk
+    static_assert(TABN % BK == 0 && SPC >= NS, "a chunk holds whole steps and at least one pipeline depth");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const unsigned smem_base = lds_offset(smem);
-    const unsigned tab_base = smem_base + NS * STAGE;            // [NS][BK] x {base, mask}
+    const unsigned tab_base = smem_base + NS * STAGE;            // [2][TABN] x {base, mask}
 
     const ConvGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -343,33 +346,25 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     }
     const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
 
-    // pixel table: thread t < BK owns pixel (step*BK + t) of the step it fills next
-    int pn = 0, pp = 0, pq = 0;
-    if (tid < BK) {
-        const int m = kbeg * BK + tid;
-        pn = m / (g.Ho * g.Wo);
-        const int rem = m - pn * (g.Ho * g.Wo);
-        pp = rem / g.Wo; pq = rem - pp * g.Wo;
-    }
-    auto fill_table = [&](int slot, int step) {
-        if (tid < BK) {
-            const int hb = pp * g.sh - g.ph, wb = pq * g.sw - g.pw;
-            u32x2 e;
-            e.x = (unsigned)(((pn * g.H + hb) * g.W + wb) * g.C) * 2u;
-            e.y = step * BK + tid < M ? tap_mask(hb, wb, 1, g.R, g.S, g.H, g.W) : 0u;
-            const unsigned addr = tab_base + (slot * BK + tid) * 8;
-            asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(e) : "memory");
-            pq += BK;
-            while (pq >= g.Wo) { pq -= g.Wo; if (++pp == g.Ho) { pp = 0; ++pn; } }
-        }
+    // every thread fills one entry of chunk `chunk` (reduction rows kbeg*BK + chunk*TABN + tid)
+    auto fill_table = [&](int chunk) {
+        const int m = kbeg * BK + chunk * TABN + tid;
+        const int n = m / (g.Ho * g.Wo), rem = m - n * (g.Ho * g.Wo), pp = rem / g.Wo, pq = rem - pp * g.Wo;
+        const int hb = pp * g.sh - g.ph, wb = pq * g.sw - g.pw;
+        u32x2 e;
+        e.x = (unsigned)(((n * g.H + hb) * g.W + wb) * g.C) * 2u;
+        e.y = m < M ? tap_mask(hb, wb, 1, g.R, g.S, g.H, g.W) : 0u;
+        const unsigned addr = tab_base + ((chunk & 1) * TABN + tid) * 8;
+        asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(e) : "memory");
     };
-    auto issue = [&](int stage, int step) {
-        const unsigned ua = (unsigned)step * BK * g.K * 2u;
+    auto issue = [&](int stage, int ls) {   // ls: step index relative to kbeg
+        const unsigned ua = (unsigned)(kbeg + ls) * BK * g.K * 2u;
         const unsigned sb = stage * STAGE;
+        const unsigned tb = (unsigned)(ls % (2 * SPC)) * BK * 8;
         u32x2 e[IB];
 #pragma unroll
         for (int q = 0; q < IB; ++q)
-            asm volatile("ds_read_b64 %0, %1" : "=v"(e[q]) : "v"(tabB[q] + stage * BK * 8));
+            asm volatile("ds_read_b64 %0, %1" : "=v"(e[q]) : "v"(tabB[q] + tb));
 #pragma unroll
         for (int q = 0; q < IA; ++q) dma16(rdy, ldsA_w + sb + q * 1024, voffA[q] + ua);
         asm volatile("s_waitcnt lgkmcnt(0)");
@@ -410,14 +405,12 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     }
 
     constexpr int LPS = IA + IB;
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-        if (s < nsteps) fill_table(s, kbeg + s);
+    fill_table(0);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
-        if (s < nsteps) issue(s, kbeg + s);
+        if (s < nsteps) issue(s, s);
     for (int i = 0; i < nsteps; ++i) {
         const int younger = min(nsteps - 1 - i, NS - 2);
         if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
@@ -425,37 +418,52 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
         else wait_vmcnt<0>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // this wave's table writes are done
         __builtin_amdgcn_s_barrier();
-        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS, kbeg + i + NS - 1);
+        // at the first step of chunk c the entries of chunk c-1 have all been read (the last load that
+        // used them was issued NS-1 steps ago, before a barrier): its half of the table takes chunk c+1,
+        // whose first reader is the issue NS-1 steps before that chunk starts, after at least one barrier
+        if (i % SPC == 0 && (i / SPC + 1) * SPC < nsteps + NS) fill_table(i / SPC + 1);
+        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS, i + NS - 1);
         const unsigned sb = (i % NS) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x2 alo[FA], ahi[FA], blo[FB], bhi[FB];
+        // fragments are double-buffered in registers: the transpose reads of slice ks+1 are issued
+        // before the matrix instructions of slice ks
+        u32x2 alo[2][FA], ahi[2][FA], blo[2][FB], bhi[2][FB];
+        auto read_slice = [&](int ks, int buf) {
 #pragma unroll
             for (int ii = 0; ii < FA; ++ii) {
-                alo[ii] = lds_read_tr<0>(fa[ks][ii] + sb);
-                ahi[ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);   // 4 reduction rows further: same swizzle class
+                alo[buf][ii] = lds_read_tr<0>(fa[ks][ii] + sb);
+                ahi[buf][ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);   // 4 reduction rows further: same swizzle class
             }
 #pragma unroll
             for (int jj = 0; jj < FB; ++jj) {
-                blo[jj] = lds_read_tr<0>(fb[ks][jj] + sb);
-                bhi[jj] = lds_read_tr<4 * ROWB>(fb[ks][jj] + sb);
+                blo[buf][jj] = lds_read_tr<0>(fb[ks][jj] + sb);
+                bhi[buf][jj] = lds_read_tr<4 * ROWB>(fb[ks][jj] + sb);
             }
-            asm volatile("s_waitcnt lgkmcnt(0)");
+        };
+        read_slice(0, 0);
 #pragma unroll
-            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[ii])); asm volatile("" : "+v"(ahi[ii])); }
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1;
+            if (ks < KS - 1) {
+                read_slice(ks + 1 < KS ? ks + 1 : 0, cur ^ 1);
+                static_assert(2 * (FA + FB) < 16, "lgkmcnt is a 4-bit counter");
+                asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * (FA + FB)));
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)");
+            }
 #pragma unroll
-            for (int jj = 0; jj < FB; ++jj) { asm volatile("" : "+v"(blo[jj])); asm volatile("" : "+v"(bhi[jj])); }
+            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[cur][ii])); asm volatile("" : "+v"(ahi[cur][ii])); }
+#pragma unroll
+            for (int jj = 0; jj < FB; ++jj) { asm volatile("" : "+v"(blo[cur][jj])); asm volatile("" : "+v"(bhi[cur][jj])); }
 #pragma unroll
             for (int ii = 0; ii < FA; ++ii)
 #pragma unroll
                 for (int jj = 0; jj < FB; ++jj) {
-                    const u32x4 av = {alo[ii].x, alo[ii].y, ahi[ii].x, ahi[ii].y}, bv = {blo[jj].x, blo[jj].y, bhi[jj].x, bhi[jj].y};
+                    const u32x4 av = {alo[cur][ii].x, alo[cur][ii].y, ahi[cur][ii].x, ahi[cur][ii].y};
+                    const u32x4 bv = {blo[cur][jj].x, blo[cur][jj].y, bhi[cur][jj].x, bhi[cur][jj].y};
                     acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
                                                                          acc[ii][jj], 0, 0, 0);
                 }
         }
-        // table of step i+NS goes into the slot whose table (step i) was consumed before this barrier
-        if (i + NS < nsteps) fill_table(i % NS, kbeg + i + NS);
     }
     store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, split);
 }
@@ -691,7 +699,7 @@ KernelFn pick_dma_w(int v)
     default: return k_wgrad_dma<256, 128, 32, 4, 2, 2>;
     }
 }
-size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB) * d.BK * 2 + (size_t)d.NS * d.BK * 8; }
+size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB) * d.BK * 2 + (size_t)2 * 64 * d.WA * d.WB * 8; }
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
