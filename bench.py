@@ -60,6 +60,8 @@ def parse():
     ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="profiling aid: also run an elementwise fp32 copy kernel that reads and writes this many MiB")
+    ap.add_argument("--no-autotune", action="store_true",
+                    help="keep the analytic kernel choice instead of timing the candidates once per layer shape before the warm-up")
     ap.add_argument("--table", type=str, default="", help="also write the per-layer time-vs-batch table (JSON) here")
     return ap.parse_args()
 
@@ -233,9 +235,20 @@ def main():
         for _ in range(3):
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
+    # Measured kernel choice: the first call per (layer, batch, pass) times the planner's candidates.
+    # It is switched on before the workspace query (the query then covers every candidate).
+    dp.dp_set_autotune(not args.no_autotune)
     ws_bytes = max(l.ws_bytes(dp, n) for l in layers for n in batches)
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     descs = {(l.name, n): l.desc(dp, n) for l in layers for n in batches}
+
+    if not args.no_autotune:
+        # one call of every pass, alone on the GPU, so that each measurement sees an idle device
+        for n in batches:
+            for l in layers:
+                for _, fn, _ in l.passes():
+                    fn(dp, descs[(l.name, n)], ws)
+                    torch.cuda.synchronize()
 
     n_side = max(1, args.side_streams)
     ws_side = [torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(n_side)]
@@ -393,7 +406,7 @@ def main():
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
-        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch,
+        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch, "kernel_choice": "model" if args.no_autotune else "measured",
         "per_batch": per_batch,
         "roofline": roofline,
     }

@@ -155,6 +155,16 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
  * used by the given pass; -1 / 0 restore the built-in choice.  Process-wide. */
 dp_status dp_set_override(int pass, int tile_variant, int splits);
 
+/* Measured kernel choice (the paper's layer profiler, Section 3 "profiling", applied to the
+ * library's own kernels): enabled != 0 makes the first launch of a pass on a new layer shape time
+ * the analytic model's best tile/split candidates on the caller's own buffers and stream (each
+ * candidate writes the same result; the stream is drained, so that one call blocks the host) and
+ * keeps the fastest for later calls of the calling thread.  Workspace queries made while it is on
+ * return the largest need of any candidate, so query after switching it on.  No measurement takes
+ * place while the stream is being captured (the model's choice is used), with a forced override,
+ * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */
+dp_status dp_set_autotune(int enabled);
+
 const char *dp_last_error(void); /* thread-local, static storage */
 const char *dp_version(void);
 

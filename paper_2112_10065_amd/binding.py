@@ -16,7 +16,8 @@ DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data",
            "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
-           "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_last_error", "dp_version"]
+           "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_last_error",
+           "dp_version"]
 
 
 class dp_conv_desc(C.Structure):
@@ -61,10 +62,11 @@ def _load():
     lib.dp_relu_bias_grad.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_profile_layer.argtypes = [P(dp_conv_desc), P(dp_linear_desc), P(i32), i32, i32, i32, P(dp_profile_row), vp]
     lib.dp_set_override.argtypes = [C.c_int, C.c_int, C.c_int]
+    lib.dp_set_autotune.argtypes = [C.c_int]
     lib.dp_conv2d_kernel_info.argtypes = [P(dp_conv_desc), C.c_int, C.c_char_p, sz, P(i32)]
     lib.dp_conv2d_kernel_info.restype = C.c_int
     for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
-                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override"):
+                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune"):
         getattr(lib, name).restype = C.c_int
     lib.dp_last_error.restype = C.c_char_p
     lib.dp_version.restype = C.c_char_p
@@ -119,6 +121,10 @@ def dp_last_error():
 
 def dp_set_override(pass_, tile_variant=-1, splits=0):
     _check(lib.dp_set_override(pass_, tile_variant, splits))
+
+
+def dp_set_autotune(enabled):
+    _check(lib.dp_set_autotune(1 if enabled else 0))
 
 
 def dp_conv2d_kernel_info(desc, pass_):

@@ -9,12 +9,14 @@
 #include <cstring>
 #include <mutex>
 #include <unordered_map>
+#include <vector>
 
 namespace {
 
 thread_local char g_err[512] = "";
 std::atomic<int> g_force_variant[3] = {{-1}, {-1}, {-1}};
 std::atomic<int> g_force_splits[3] = {{0}, {0}, {0}};
+std::atomic<int> g_autotune{0};
 std::once_flag g_init_once;
 hipError_t g_init_err = hipSuccess;
 
@@ -96,9 +98,10 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl)
 }
 
 // Planning prices a few hundred candidates; a training loop asks for the same few layers again and
-// again, so each thread remembers its plans.
+// again, so each thread remembers its plans.  With the measured choice switched on an entry also
+// keeps the model's best candidates until the first launch has timed them.
 struct PlanKey {
-    int v[16];
+    int v[17];
     bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
 };
 struct PlanKeyHash {
@@ -109,23 +112,89 @@ struct PlanKeyHash {
         return h;
     }
 };
+struct PlanEntry {
+    GemmPlan plan;                 // the plan in use (the model's until measured)
+    size_t part_cap = 0;           // bytes reserved for split partials: the largest any candidate needs
+    bool tuned = true;             // false: candidates wait for their timing run
+    std::vector<GemmPlan> cands;
+};
+constexpr int kTuneCandidates = 12;
 
-void plan_for(const ConvGeom &g, int pass, GemmPlan *pl)
+PlanEntry &plan_entry(const ConvGeom &g, int pass)
 {
-    thread_local std::unordered_map<PlanKey, GemmPlan, PlanKeyHash> cache;
-    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
-    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs}};
+    thread_local std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> cache;
+    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load(), at = g_autotune.load();
+    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at}};
     auto it = cache.find(key);
-    if (it != cache.end()) { *pl = it->second; return; }
-    plan_uncached(g, pass, fv, fs, pl);
+    if (it != cache.end()) return it->second;
     if (cache.size() > 4096) cache.clear();
-    cache.emplace(key, *pl);
+    PlanEntry e;
+    plan_uncached(g, pass, fv, fs, &e.plan);
+    e.part_cap = mfma_partial_bytes(g, pass, e.plan);
+    if (at != 0 && fv < 0 && e.plan.fast) {
+        GemmPlan list[kTuneCandidates];
+        const int n = auto_plan_list(g, pass, fs, list, kTuneCandidates);
+        if (n > 1) {
+            e.cands.assign(list, list + n);
+            e.tuned = false;
+            for (const GemmPlan &c : e.cands) {
+                const size_t b = mfma_partial_bytes(g, pass, c);
+                if (b > e.part_cap) e.part_cap = b;
+            }
+        }
+    }
+    return cache.emplace(key, std::move(e)).first->second;
 }
+
+void plan_for(const ConvGeom &g, int pass, GemmPlan *pl) { *pl = plan_entry(g, pass).plan; }
 
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 {
     if (a.plan.dma) return dma_launch(a, st);
     return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st);
+}
+
+// Measured choice: run every candidate on the caller's buffers (each writes the same result), keep
+// the fastest.  Blocks the host until the stream has drained; skipped while the stream is captured.
+void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st)
+{
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return; }
+    float best = 1e30f;
+    GemmPlan best_plan = pe.plan;
+    for (const GemmPlan &c : pe.cands) {
+        a.plan = c;
+        if (launch_plan(a, st) != hipSuccess) { (void)hipGetLastError(); continue; }   // warm-up, also checks the launch
+        // short kernels are timed over more launches: the event pair itself costs a few microseconds
+        float per_launch = 0.f;
+        bool ok = true;
+        for (int reps = 4; ok; reps = 24) {
+            ok = hipEventRecord(e0, st) == hipSuccess;
+            for (int r = 0; r < reps && ok; ++r) ok = launch_plan(a, st) == hipSuccess;
+            ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
+            float ms = 0.f;
+            ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            per_launch = ms / reps;
+            if (reps == 24 || ms > 0.4f) break;
+        }
+        if (!ok) { (void)hipGetLastError(); continue; }
+        if (per_launch < best) { best = per_launch; best_plan = c; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    pe.plan = best_plan;
+    pe.tuned = true;
+    pe.cands.clear();
+}
+
+hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st)
+{
+    if (!pe.tuned) tune_entry(a, pe, st);
+    a.plan = pe.plan;
+    return launch_plan(a, st);
 }
 
 size_t ybytes(const ConvGeom &g) { return (size_t)g.N * g.Ho * g.Wo * g.K * 2; }
@@ -161,9 +230,7 @@ size_t fwd_ws_bytes(const ConvGeom &g)
         const int kpad = small_c_kpad(g);
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2) + fwd_ws_bytes(im2col_geom(g, kpad));
     }
-    GemmPlan pl;
-    plan_for(g, PASS_FWD, &pl);
-    return mfma_partial_bytes(g, PASS_FWD, pl);
+    return plan_entry(g, PASS_FWD).part_cap;
 }
 
 // ---- the three passes on a validated geometry --------------------------------------
@@ -187,18 +254,20 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_FWD; a.flags = kflags(flags, true);
-    plan_for(g, PASS_FWD, &a.plan);
-    size_t need = mfma_partial_bytes(g, PASS_FWD, a.plan);
+    PlanEntry &pe = plan_entry(g, PASS_FWD);
+    a.plan = pe.plan;
+    size_t need = pe.part_cap;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.x = (const bf16_t *)x; a.w = (const bf16_t *)w; a.bias = bias; a.out = y; a.partial = (float *)ws;
-    hipError_t e = launch_plan(a, st);
+    hipError_t e = launch_entry(a, pe, st);
     return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
 }
 
-size_t dgrad_ws_bytes(const ConvGeom &g, const GemmPlan &pl)
+size_t dgrad_ws_bytes(const ConvGeom &g)
 {
-    size_t need = round256(mfma_partial_bytes(g, PASS_DGRAD, pl));
-    if (pl.fast) need += round256(ybytes(g));   // room for the masked gradient
+    const PlanEntry &pe = plan_entry(g, PASS_DGRAD);
+    size_t need = round256(pe.part_cap);
+    if (pe.plan.fast) need += round256(ybytes(g));   // room for the masked gradient
     return need;
 }
 
@@ -211,18 +280,19 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_DGRAD; a.flags = (flags & DP_DX_F32) ? KF_OUT_F32 : 0u;
-    plan_for(g, PASS_DGRAD, &a.plan);
-    size_t need = dgrad_ws_bytes(g, a.plan);
+    PlanEntry &pe = plan_entry(g, PASS_DGRAD);
+    a.plan = pe.plan;
+    size_t need = dgrad_ws_bytes(g);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
     if (a.plan.fast && ym != nullptr) {
         // the fast kernel takes a pre-masked gradient: materialise g = dy * [y_saved > 0] once
-        void *gbuf = (char *)ws + round256(mfma_partial_bytes(g, PASS_DGRAD, a.plan));
+        void *gbuf = (char *)ws + round256(pe.part_cap);
         hipError_t e = rbg_launch((long long)g.N * g.Ho * g.Wo, g.K, true, dy, ym, gbuf, nullptr, nullptr, st);
         if (e != hipSuccess) return hip_fail(e, "ReLU-gradient launch");
         a.dy = (const bf16_t *)gbuf; a.ymask = nullptr;
     }
-    hipError_t e = launch_plan(a, st);
+    hipError_t e = launch_entry(a, pe, st);
     return e == hipSuccess ? DP_OK : hip_fail(e, "backward-data launch");
 }
 
@@ -234,10 +304,9 @@ size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 4) + wgrad_ws_bytes(im2col_geom(g, kpad), dtype, with_db);
     }
     if (dtype == DP_BF16) {
-        GemmPlan pl;
-        plan_for(g, PASS_WGRAD, &pl);
-        need = round256(mfma_partial_bytes(g, PASS_WGRAD, pl));
-        if (pl.fast) need += round256(ybytes(g));
+        const PlanEntry &pe = plan_entry(g, PASS_WGRAD);
+        need = round256(pe.part_cap);
+        if (pe.plan.fast) need += round256(ybytes(g));
     }
     if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
     return need;
@@ -278,8 +347,9 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
-    plan_for(g, PASS_WGRAD, &a.plan);
-    const size_t part = round256(mfma_partial_bytes(g, PASS_WGRAD, a.plan));
+    PlanEntry &pe = plan_entry(g, PASS_WGRAD);
+    a.plan = pe.plan;
+    const size_t part = round256(pe.part_cap);
     const size_t gb = a.plan.fast ? round256(ybytes(g)) : 0;
     void *gbuf = (char *)ws + part;
     float *rws = (float *)((char *)ws + part + gb);
@@ -293,7 +363,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         db_done = true;
     }
     if (dw != nullptr) {
-        hipError_t e = launch_plan(a, st);
+        hipError_t e = launch_entry(a, pe, st);
         if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
     }
     if (db != nullptr && !db_done) {
@@ -317,6 +387,12 @@ dp_status dp_set_override(int pass, int tile_variant, int splits)
     if (pass < 0 || pass > 2) return fail(DP_ERR_UNSUPPORTED, "pass must be 0, 1 or 2");
     g_force_variant[pass].store(tile_variant);
     g_force_splits[pass].store(splits);
+    return DP_OK;
+}
+
+dp_status dp_set_autotune(int enabled)
+{
+    g_autotune.store(enabled != 0 ? 1 : 0);
     return DP_OK;
 }
 
@@ -349,7 +425,7 @@ size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
     if (pass == DP_PASS_FWD) return fwd_ws_bytes(g);
     GemmPlan pl;
     plan_for(g, pass, &pl);
-    return dgrad_ws_bytes(g, pl);
+    return dgrad_ws_bytes(g);
 }
 
 size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
@@ -361,7 +437,7 @@ size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
         for (int pass = 0; pass < 2; ++pass) {
             GemmPlan pl;
             plan_for(g, pass, &pl);
-            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : fwd_ws_bytes(g);
+            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g) : fwd_ws_bytes(g);
             if (b > need) need = b;
         }
     }
@@ -396,7 +472,7 @@ dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const voi
     if (desc->io_dtype == DP_BF16) {
         GemmPlan pl;
         plan_for(g, PASS_DGRAD, &pl);
-        size_t need = dgrad_ws_bytes(g, pl);
+        size_t need = dgrad_ws_bytes(g);
         if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     }
     if ((s = ensure_init()) != DP_OK) return s;
@@ -504,7 +580,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
             for (int pass = 0; pass < 2; ++pass) {
                 GemmPlan pl;
                 plan_for(g, pass, &pl);
-                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, pl) : fwd_ws_bytes(g);
+                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g) : fwd_ws_bytes(g);
                 if (b > wsb) wsb = b;
             }
         const size_t dxes = (flags & DP_DX_F32) ? 4 : es;

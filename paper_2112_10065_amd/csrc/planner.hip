@@ -29,6 +29,8 @@ const Candidate kPix[] = {
     {201, 4, 1.08f, 4.5f},   // direct-to-LDS with reduction step 32 (channels % 32 only)
     {205, 4, 0.85f, 4.0f},
     {213, 3, 1.30f, 4.5f},
+    {210, 1, 1.15f, 6.0f},   // 128x256x64, 8 waves
+    {212, 2, 1.30f, 4.5f},   // 64x256x64
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},
@@ -42,6 +44,10 @@ const Candidate kWg[] = {
     {305, 5, 0.62f, 3.5f},   // 64x64x32
     {308, 3, 1.45f, 4.0f},   // 64x256x32 (few output channels: widest tap tile)
     {306, 3, 0.93f, 4.0f},   // 64x128x64
+    {301, 2, 1.75f, 4.5f},   // 128x128x64
+    {307, 2, 1.60f, 5.0f},   // 256x128x32, 8 waves
+    {314, 2, 1.65f, 5.0f},   // 128x256x32, 8 waves
+    {312, 1, 2.90f, 7.0f},   // 256x256x64, 8 waves
     {100, 3, 1.30f, 4.0f},
     {101, 3, 1.00f, 3.5f},
     {102, 3, 1.00f, 3.5f},
@@ -84,9 +90,13 @@ double price(const ConvGeom &g, int pass, const Candidate &c, const GemmPlan &pl
 
 }  // namespace
 
-// Fills *pl with the cheapest eligible fast-path plan; false if the shape has none.
-bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
+// Eligible fast-path plans of a pass, cheapest first by the model, at most two split counts per tile
+// variant; returns how many were written (0: the shape has no fast-path plan).
+int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out, int max_out)
 {
+    struct Priced { double t; GemmPlan pl; int code; };
+    Priced all[512];
+    int n = 0;
     // dense-layer-like shapes (a handful of pixel rows): the pass streams the weight matrix once and
     // is bound by HBM; the smallest tile with about two blocks per CU does that best
     if (pass != PASS_WGRAD && force_splits <= 0) {
@@ -99,14 +109,12 @@ bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
                 int splits = (int)((512 + tiles - 1) / tiles), max_splits = one.steps_total / 8;
                 if (max_splits < 1) max_splits = 1;
                 if (splits > max_splits) splits = max_splits;
-                if (family_plan(g, pass, code, splits, pl)) return true;
+                if (family_plan(g, pass, code, splits, &all[n].pl)) { all[n].t = 0.0; all[n].code = code; ++n; break; }
             }
         }
     }
     const Candidate *cands = pass == PASS_WGRAD ? kWg : kPix;
     const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
-    double best = 1e30;
-    bool found = false;
     for (int ci = 0; ci < ncand; ++ci) {
         int last_splits = -1;
         for (int s : kSplits) {
@@ -121,9 +129,35 @@ bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
             last_splits = cand.splits;
             if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;
-            const double t = price(g, pass, cands[ci], cand);
-            if (t < best) { best = t; *pl = cand; found = true; }
+            if (n < 512) { all[n].t = price(g, pass, cands[ci], cand); all[n].pl = cand; all[n].code = cands[ci].code; ++n; }
         }
     }
-    return found;
+    // selection sort of the few that are wanted; per tile variant only its two cheapest splits
+    int written = 0;
+    int used_code[64], used_cnt[64], nused = 0;
+    double t_first = -1.0;   // the model's best time; plans it puts beyond 1.6x of that are not worth a measurement
+    while (written < max_out) {
+        int best = -1;
+        for (int i = 0; i < n; ++i) {
+            if (all[i].t < 0.0) continue;
+            if (best < 0 || all[i].t < all[best].t) best = i;
+        }
+        if (best < 0) break;
+        if (all[best].t > 0.0) {
+            if (t_first < 0.0) t_first = all[best].t;
+            else if (all[best].t > 1.6 * t_first) break;
+        }
+        int u = 0;
+        while (u < nused && used_code[u] != all[best].code) ++u;
+        if (u == nused && nused < 64) { used_code[nused] = all[best].code; used_cnt[nused] = 0; ++nused; }
+        if (u < 64 && used_cnt[u] < 2) { out[written++] = all[best].pl; ++used_cnt[u]; }
+        all[best].t = -1.0;
+    }
+    return written;
+}
+
+// Fills *pl with the cheapest eligible fast-path plan; false if the shape has none.
+bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
+{
+    return auto_plan_list(g, pass, force_splits, pl, 1) == 1;
 }

@@ -101,6 +101,7 @@ def test_profile_and_override_argument_errors(dp):
     assert lib.dp_profile_layer(C.byref(cd), None, bneg, 1, 1, 1, rows, None) == dp.DP_ERR_BAD_DESC
     assert lib.dp_set_override(5, 0, 0) == dp.DP_ERR_UNSUPPORTED
     assert lib.dp_set_override(0, -1, 0) == dp.DP_OK
+    assert lib.dp_set_autotune(1) == dp.DP_OK and lib.dp_set_autotune(0) == dp.DP_OK
 
 
 def test_no_gpu_fails_loudly(dp):

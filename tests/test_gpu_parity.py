@@ -208,6 +208,34 @@ def test_bitwise_deterministic(env):
     assert torch.equal(dw1, dw2) and torch.equal(db1, db2)
 
 
+def test_measured_kernel_choice(env):
+    """With the measured choice on, the first call of each pass times the candidates on the caller's
+    buffers: results must match the oracle on that call and on the next (cached plan), the workspace
+    the query asks for must suffice, and the choice must stay the same afterwards."""
+    dp, U, orc = env
+    dp.dp_set_autotune(True)
+    try:
+        for tag, n, h, w, c, k, pd in (("tune_a", 2, 28, 28, 64, 128, (1, 1)), ("tune_b", 1, 14, 14, 128, 192, (1, 1))):
+            case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
+            for rep in range(2):
+                y = case.run_fwd()
+                dw, db = case.run_wgrad(y)
+                dx = case.run_dgrad(y)
+                torch.cuda.synchronize()
+                y_np = U.to_np(y)
+                U.assert_bf16_close(y_np, orc.conv2d_fwd(case.x, case.w, case.b, relu=True, pad=pd), f"{tag} y rep {rep}")
+                U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=y_np, pad=pd), f"{tag} dx rep {rep}")
+                rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=y_np, pad=pd, want_db=True)
+                U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} dw rep {rep}")
+                U.assert_bf16_close(U.to_np(db), rdb, f"{tag} db rep {rep}")
+                info = [dp.dp_conv2d_kernel_info(case.desc, p) for p in range(3)]
+                if rep == 0:
+                    first = info
+                assert info == first
+    finally:
+        dp.dp_set_autotune(False)
+
+
 # ---- dense layers ----------------------------------------------------------------------------
 @pytest.mark.parametrize("n,i,o,bf16", [(5, 200, 136, True), (32, 1024, 512, True), (1, 4096, 1000, True),
                                         (3, 50, 20, False)])
