@@ -578,30 +578,42 @@ __global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
         __builtin_amdgcn_s_barrier();
         if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS);
         const unsigned sb = (i % NS) * STAGE;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x2 alo[FA], ahi[FA];
-            u32x4 b[FB];
+        // fragments are double-buffered in registers: the reads of slice ks+1 are issued before the
+        // matrix instructions of slice ks
+        u32x2 alo[2][FA], ahi[2][FA];
+        u32x4 b[2][FB];
+        auto read_slice = [&](int ks, int buf) {
 #pragma unroll
             for (int ii = 0; ii < FA; ++ii) {
-                alo[ii] = lds_read_tr<0>(fa[ks][ii] + sb);
-                ahi[ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);
+                alo[buf][ii] = lds_read_tr<0>(fa[ks][ii] + sb);
+                ahi[buf][ii] = lds_read_tr<4 * ROWA>(fa[ks][ii] + sb);
             }
-            if constexpr (FB >= 1) b[0] = lds_read16<0>(fb[ks] + sb);
-            if constexpr (FB >= 2) b[1] = lds_read16<32 * ROWB>(fb[ks] + sb);
-            if constexpr (FB >= 3) b[2] = lds_read16<64 * ROWB>(fb[ks] + sb);
-            if constexpr (FB >= 4) b[3] = lds_read16<96 * ROWB>(fb[ks] + sb);
-            asm volatile("s_waitcnt lgkmcnt(0)");
+            if constexpr (FB >= 1) b[buf][0] = lds_read16<0>(fb[ks] + sb);
+            if constexpr (FB >= 2) b[buf][1] = lds_read16<32 * ROWB>(fb[ks] + sb);
+            if constexpr (FB >= 3) b[buf][2] = lds_read16<64 * ROWB>(fb[ks] + sb);
+            if constexpr (FB >= 4) b[buf][3] = lds_read16<96 * ROWB>(fb[ks] + sb);
+        };
+        read_slice(0, 0);
 #pragma unroll
-            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[ii])); asm volatile("" : "+v"(ahi[ii])); }
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1;
+            if (ks < KS - 1) {
+                read_slice(ks + 1 < KS ? ks + 1 : 0, cur ^ 1);
+                static_assert(2 * FA + FB < 16, "lgkmcnt is a 4-bit counter");
+                asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(2 * FA + FB));
+            } else {
+                asm volatile("s_waitcnt lgkmcnt(0)");
+            }
 #pragma unroll
-            for (int jj = 0; jj < FB; ++jj) asm volatile("" : "+v"(b[jj]));
+            for (int ii = 0; ii < FA; ++ii) { asm volatile("" : "+v"(alo[cur][ii])); asm volatile("" : "+v"(ahi[cur][ii])); }
+#pragma unroll
+            for (int jj = 0; jj < FB; ++jj) asm volatile("" : "+v"(b[cur][jj]));
 #pragma unroll
             for (int ii = 0; ii < FA; ++ii)
 #pragma unroll
                 for (int jj = 0; jj < FB; ++jj) {
-                    const u32x4 av = {alo[ii].x, alo[ii].y, ahi[ii].x, ahi[ii].y};
-                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b[jj]),
+                    const u32x4 av = {alo[cur][ii].x, alo[cur][ii].y, ahi[cur][ii].x, ahi[cur][ii].y};
+                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, b[cur][jj]),
                                                                          acc[ii][jj], 0, 0, 0);
                 }
         }
