@@ -630,8 +630,9 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
                            {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2},
                            {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}, {256, 256, 32, 2, 4, 4}, {256, 256, 32, 2, 4, 3},
-                           {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8}};
-constexpr int kNumDma = 21;
+                           {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
+                           {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4}};
+constexpr int kNumDma = 26;
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -656,6 +657,11 @@ KernelFn pick_dma_d(int v)
     case 18: return k_dgrad_dma<128, 32, 64, 4, 1, 4>;
     case 19: return k_dgrad_dma<256, 64, 32, 4, 1, 6>;
     case 20: return k_dgrad_dma<64, 32, 64, 2, 1, 8>;
+    case 21: return k_dgrad_dma<64, 64, 128, 2, 2, 3>;
+    case 22: return k_dgrad_dma<64, 128, 128, 2, 2, 2>;
+    case 23: return k_dgrad_dma<128, 128, 128, 2, 2, 2>;
+    case 24: return k_dgrad_dma<128, 64, 128, 2, 2, 2>;
+    case 25: return k_dgrad_dma<64, 64, 128, 2, 2, 4>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -682,6 +688,11 @@ KernelFn pick_dma(int v)
     case 18: return k_fwd_dma<128, 32, 64, 4, 1, 4>;
     case 19: return k_fwd_dma<256, 64, 32, 4, 1, 6>;
     case 20: return k_fwd_dma<64, 32, 64, 2, 1, 8>;
+    case 21: return k_fwd_dma<64, 64, 128, 2, 2, 3>;
+    case 22: return k_fwd_dma<64, 128, 128, 2, 2, 2>;
+    case 23: return k_fwd_dma<128, 128, 128, 2, 2, 2>;
+    case 24: return k_fwd_dma<128, 64, 128, 2, 2, 2>;
+    case 25: return k_fwd_dma<64, 64, 128, 2, 2, 4>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }

@@ -31,6 +31,11 @@ const Candidate kPix[] = {
     {213, 3, 1.30f, 4.5f},
     {210, 1, 1.15f, 6.0f},   // 128x256x64, 8 waves
     {212, 2, 1.30f, 4.5f},   // 64x256x64
+    {221, 1, 0.70f, 4.0f},   // reduction step 128 (channels % 128 only): fewer, longer steps for small grids
+    {225, 1, 0.70f, 4.0f},
+    {222, 1, 1.10f, 4.5f},
+    {224, 1, 1.10f, 4.5f},
+    {223, 1, 1.90f, 5.0f},
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},
