@@ -26,23 +26,18 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
-# the launches of each kernel in this same sweep: profiles/vgg16_sweep_hbm_traffic.md
+# the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "k_fwd_dma<128, 64, 64, 2, 2, 2>": 143350739,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2>": 140793862,
-    "k_dgrad_dma<256, 256, 64, 2, 4, 2>": 138248948,
-    "k_fwd_dma<256, 256, 64, 2, 4, 2>": 118748957,
-    "k_dgrad_dma<128, 128, 64, 2, 2, 2>": 76728969,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2>": 85178333,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2>": 69082756,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2>": 79982285,
-    "k_conv_gemm<2, 64, 128, 64, 2, 2, true, false>": 75509704,
-    "k_conv_fast<1, 64, 64, 64, 2, 2>": 46310078,
-    "k_conv_fast<0, 64, 64, 64, 2, 2>": 47119806,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3>": 19810296,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3>": 23585470,
-    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>": 9228010,
-    "k_conv_gemm<0, 64, 128, 32, 2, 2, false, false>": 70995070
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2>": 145922296,
+    "k_fwd_dma<256, 256, 64, 2, 4, 2>": 128141396,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2>": 141863485,
+    "k_dgrad_dma<256, 256, 64, 2, 4, 2>": 147891706,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2>": 184859369,
+    "k_dgrad_dma<128, 128, 64, 2, 2, 2>": 139382353,
+    "k_fwd_dma<64, 256, 32, 1, 4, 2>": 308493922,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3>": 94537484,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3>": 209753553,
+    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>": 10963675
 }
 
 
@@ -227,14 +222,6 @@ def main():
     linears = W.vgg16_linears() if args.workload == "vgg16" else []
     layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in convs if keep is None or l.name in keep]
     layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in linears if keep is None or l.name in keep]
-    if args.calibrate_copy_mb > 0:
-        # known-size traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters
-        n_el = args.calibrate_copy_mb * (1 << 20) // 4
-        src = torch.ones(n_el, device=dev, dtype=torch.float32)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)
-        torch.cuda.synchronize()
     # Measured kernel choice: the first call per (layer, batch, pass) times the planner's candidates.
     # It is switched on before the workspace query (the query then covers every candidate).
     dp.dp_set_autotune(not args.no_autotune)
@@ -249,6 +236,17 @@ def main():
                 for _, fn, _ in l.passes():
                     fn(dp, descs[(l.name, n)], ws)
                     torch.cuda.synchronize()
+
+    if args.calibrate_copy_mb > 0:
+        # known-size traffic for scaling the profiler's FETCH_SIZE / WRITE_SIZE counters; in a kernel
+        # trace it also separates the measured-choice launches above from the steps below
+        n_el = args.calibrate_copy_mb * (1 << 20) // 4
+        src = torch.ones(n_el, device=dev, dtype=torch.float32)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     n_side = max(1, args.side_streams)
     ws_side = [torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(n_side)]
@@ -366,13 +364,14 @@ def main():
         fl = sum(l.step_flops(n) for l in layers)
         per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us}
 
-    # dominant kernel: the conv kernel instantiation with the largest total time among calls
-    # that are a single launch (no split reduction, no separate bias-gradient kernel)
+    # dominant kernel: the conv kernel instantiation with the largest total time among the calls at the
+    # largest batch of the sweep that are a single launch (no split reduction, no separate bias-gradient
+    # kernel); its figures below are over exactly those launches, each of which processes nmax samples
     groups = {}
     for l in layers:
         if not l.is_conv:
             continue
-        for n in batches:
+        for n in (nmax,):
             for pi, pname in enumerate(("fwd", "dgrad")):
                 kname, splits = dp.dp_conv2d_kernel_info(descs[(l.name, n)], pi)
                 if splits != 1 or (l.name, n, pname) not in per:
@@ -389,7 +388,7 @@ def main():
         kname, g = max(groups.items(), key=lambda kv: kv[1]["us"])
         achieved = g["flops"] / g["us"] / 1e6
         roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kname), "kernel": kname,
+                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kname), "kernel": kname, "samples_per_launch": nmax,
                     "avg_launch_us": g["us"] / g["launches"], "launches": g["launches"],
                     "flops_per_launch_avg": g["flops"] / g["launches"],
                     "algorithmic_bytes_per_launch_avg": g["bytes"] / g["launches"]}
