@@ -227,6 +227,7 @@ bool use_small_c(const ConvGeom &g, int pass) { return g_force_variant[pass].loa
 
 size_t fwd_ws_bytes(const ConvGeom &g)
 {
+    if (use_small_c(g, PASS_FWD) && small_c_direct(g)) return 0;
     if (use_small_c(g, PASS_FWD)) {
         const int kpad = small_c_kpad(g);
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2) + fwd_ws_bytes(im2col_geom(g, kpad));
@@ -241,6 +242,10 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     if (dtype == DP_F32) {
         hipError_t e = f32_conv_fwd(g, kflags(flags, true), (const float *)x, (const float *)w, bias, (float *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
+    }
+    if (use_small_c(g, PASS_FWD) && small_c_direct(g)) {
+        hipError_t e = small_c_fwd_direct(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
     }
     if (use_small_c(g, PASS_FWD)) {
         const int kpad = small_c_kpad(g);
@@ -300,6 +305,11 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
 size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
 {
     size_t need = 0;
+    if (dtype == DP_BF16 && use_small_c(g, PASS_WGRAD) && small_c_direct(g)) {
+        need = round256(small_c_wgrad_partial_bytes(g)) + round256(ybytes(g));
+        if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
+        return need;
+    }
     if (dtype == DP_BF16 && use_small_c(g, PASS_WGRAD)) {
         const int kpad = small_c_kpad(g);
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 4) + wgrad_ws_bytes(im2col_geom(g, kpad), dtype, with_db);
@@ -327,6 +337,28 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         }
         if (db != nullptr) {
             hipError_t e = rbg_launch(rows, g.K, false, dy, ym, nullptr, db, (float *)ws, st);
+            if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
+        }
+        return DP_OK;
+    }
+    if (use_small_c(g, PASS_WGRAD) && small_c_direct(g)) {
+        const size_t part = round256(small_c_wgrad_partial_bytes(g));
+        void *gbuf = (char *)ws + part;
+        float *rws = (float *)((char *)ws + part + round256(ybytes(g)));
+        const bf16_t *gsrc = (const bf16_t *)dy;
+        bool db_done = false;
+        if (ym != nullptr && dw != nullptr) {
+            hipError_t e = rbg_launch(rows, g.K, true, dy, ym, gbuf, db, rws, st);
+            if (e != hipSuccess) return hip_fail(e, "ReLU/bias-gradient launch");
+            gsrc = (const bf16_t *)gbuf;
+            db_done = true;
+        }
+        if (dw != nullptr) {
+            hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, gsrc, (float *)ws, dw, st);
+            if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
+        }
+        if (db != nullptr && !db_done) {
+            hipError_t e = rbg_launch(rows, g.K, true, dy, ym, nullptr, db, rws, st);
             if (e != hipSuccess) return hip_fail(e, "bias-gradient launch");
         }
         return DP_OK;
@@ -407,6 +439,11 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
         if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
         if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    if (pass != PASS_DGRAD && use_small_c(g, pass) && small_c_direct(g)) {
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", pass == PASS_FWD ? "k_fwd_direct" : "k_wgrad_direct");
+        if (splits != nullptr) *splits = pass == PASS_FWD ? 1 : small_c_wgrad_blocks(g);
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));

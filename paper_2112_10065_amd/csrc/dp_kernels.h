@@ -92,3 +92,10 @@ int small_c_kpad(const ConvGeom &g);   // padded reduction length, 0 if the laye
 hipError_t small_c_im2col(const ConvGeom &g, int kpad, const bf16_t *x, bf16_t *xcol, hipStream_t st);
 hipError_t small_c_pad_weights(const ConvGeom &g, int kpad, const bf16_t *w, bf16_t *wpad, hipStream_t st);
 hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, float *dw, hipStream_t st);
+// direct kernels without the im2col matrix (R*S*C <= 32, c_out % 8 == 0)
+bool small_c_direct(const ConvGeom &g);
+hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
+                              hipStream_t st);
+int small_c_wgrad_blocks(const ConvGeom &g);   // pixel-range blocks, each writes one fp32 partial
+size_t small_c_wgrad_partial_bytes(const ConvGeom &g);
+hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *partial, float *dw, hipStream_t st);

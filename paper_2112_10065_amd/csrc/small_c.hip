@@ -5,9 +5,15 @@
 // im2col of x into [pixels][Kpad] (Kpad = R*S*C rounded up to 32, zero filled) and zero-padded weights
 // [K][Kpad]: forward and backward-filter then are 1x1 convolutions with Kpad input channels.
 // The im2col buffer is R*S*C/ C * ... small next to the output (Kpad*2 bytes per pixel against K*2).
-#include "dp_kernels.h"
-
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+//
+// When the whole reduction fits one 32-wide slice pair (R*S*C <= 32: the 3x3 RGB stems) the im2col
+// matrix never goes to memory: k_fwd_direct builds the 256 x 32 tile of a block in LDS (one thread per
+// output pixel), multiplies it with weight fragments that stay in registers, and stores the output
+// tile through LDS with 16-byte rows; k_wgrad_direct does the same for the filter gradient with both
+// operands transposed on their way into LDS, one fp32 partial per block, and k_wgrad_direct_sum adds
+// the partials in block order.  Both passes then move little more than the output activation /
+// the upstream gradient once, which is what bounds these layers.
+#include "tile_common.h"
 
 namespace {
 
@@ -57,6 +63,217 @@ __global__ __launch_bounds__(256) void k_unpad_rows_f32(int rows, int len, int l
     }
 }
 
+// ---- direct kernels for R*S*C <= 32 ---------------------------------------------------------------
+constexpr int DT = 256;          // output pixels per tile (forward)
+constexpr int DLB = 40;          // im2col row pitch in bf16 (32 + 8: 80-byte rows keep 16-byte alignment, spread banks)
+constexpr int DLO = 72;          // staged output row pitch in bf16 (64 channels + 8)
+
+// element kk = (r*S + s)*C + c of the im2col row of output pixel (n, p, q), 0 outside the image
+DEVFN unsigned im2col_elem(const ConvGeom &g, const bf16_t *img, int hb, int wb, int r, int s, int c)
+{
+    const int ih = hb + r, iw = wb + s;
+    return ((unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W) ? img[(ih * g.W + iw) * g.C + c] : 0u;
+}
+
+// grid = (persistent blocks over pixel tiles, 64-row tiles of c_out); 4 waves, wave tile 64 c_out x 64 pixels
+__global__ __launch_bounds__(256) void k_fwd_direct(ConvGeom g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias,
+                                                    bf16_t *y, int tiles)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t lds[DT * DLO];   // im2col tile [256][40], later the output tile [256][72]
+    __shared__ float bias_lds[64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int a0 = blockIdx.y * 64, rsc = g.R * g.S * g.C, M = g.N * g.Ho * g.Wo;
+    if (tid < 64) bias_lds[tid] = ((flags & KF_BIAS) && a0 + tid < g.K) ? bias[a0 + tid] : 0.f;
+    // weight fragments: row a0 + i*32 + lane%32, reduction elements ks*16 + 8*(lane/32) .. +7
+    bf16x8 afr[2][2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int row = a0 + i * 32 + (lane & 31), kb = ks * 16 + 8 * (lane >> 5);
+            unsigned v[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned val = (row < g.K && kb + e < rsc) ? w[(size_t)row * rsc + kb + e] : 0u;
+                v[e >> 1] |= val << ((e & 1) * 16);
+            }
+            afr[ks][i] = __builtin_bit_cast(bf16x8, u32x4{v[0], v[1], v[2], v[3]});
+        }
+    for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        {   // im2col row of pixel tile*256 + tid
+            const int m = tile * DT + tid;
+            unsigned v[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = 0;
+            if (m < M) {
+                const int n = m / (g.Ho * g.Wo), rem = m - n * (g.Ho * g.Wo), p = rem / g.Wo, q = rem - p * g.Wo;
+                const int hb = p * g.sh - g.ph, wb = q * g.sw - g.pw;
+                const bf16_t *img = x + (size_t)n * g.H * g.W * g.C;
+                int r = 0, s = 0, c = 0;
+#pragma unroll
+                for (int kk = 0; kk < 32; ++kk) {
+                    if (kk < rsc) {
+                        v[kk >> 1] |= im2col_elem(g, img, hb, wb, r, s, c) << ((kk & 1) * 16);
+                        if (++c == g.C) { c = 0; if (++s == g.S) { s = 0; ++r; } }
+                    }
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<u32x4 *>(lds + tid * DLB + j * 8) = u32x4{v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+        }
+        __syncthreads();
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 b = *reinterpret_cast<const bf16x8 *>(lds + (wave * 64 + j * 32 + (lane & 31)) * DLB + ks * 16 + 8 * (lane >> 5));
+#pragma unroll
+                for (int i = 0; i < 2; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr[ks][i], b, acc[i][j], 0, 0, 0);
+            }
+        __syncthreads();   // the im2col tile has been read: its memory now takes the output tile
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int ch = i * 32 + 8 * gq + 4 * (lane >> 5);
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + ch);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y;
+                    float v2 = acc[i][j][4 * gq + 2] + bv.z, v3 = acc[i][j][4 * gq + 3] + bv.w;
+                    if (flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                    const int pix = wave * 64 + j * 32 + (lane & 31);
+                    *reinterpret_cast<u32x2 *>(lds + pix * DLO + ch) = u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
+                }
+            }
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int id = tid + it * 256, pix = id >> 3, cc = id & 7;
+            const int gp = tile * DT + pix, gc = a0 + cc * 8;
+            if (gp < M && gc < g.K)
+                *reinterpret_cast<u32x4 *>(y + (size_t)gp * g.K + gc) = *reinterpret_cast<const u32x4 *>(lds + pix * DLO + cc * 8);
+        }
+        __syncthreads();   // the output tile has been read before the next im2col tile overwrites it
+    }
+}
+
+// Filter gradient: block b sums pixels [b*ppb, (b+1)*ppb) in steps of 64; LDS holds both operands
+// reduction-contiguous: gT[64 c_out][64 + 8 pixels], xT[32 taps][64 + 8 pixels].  Wave w multiplies the
+// 16-pixel slice w of every step; the four waves' sums are added through LDS at the end.
+constexpr int WLS = 72;
+__global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *x, const bf16_t *dy, float *partial, int steps_per_block)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t gT[64 * WLS];
+    __shared__ __attribute__((aligned(16))) bf16_t xT[32 * WLS];
+    __shared__ float red[4][64][33];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int a0 = blockIdx.y * 64, rsc = g.R * g.S * g.C, M = g.N * g.Ho * g.Wo;
+    const int steps_total = (M + 63) / 64;
+    const int sbeg = blockIdx.x * steps_per_block, send = min(sbeg + steps_per_block, steps_total);
+    // loader roles: thread -> (pixel, 16 c_out) of the gradient tile, (pixel, 8 taps) of the im2col tile
+    const int gp = tid >> 2, gc = (tid & 3) * 16;
+    const int xp = tid & 63, xt = (tid >> 6) * 8;
+    int xr = 0, xs = 0, xc = 0;   // (r, s, c) of tap xt
+    { const int rs = xt / g.C; xc = xt - rs * g.C; xr = rs / g.S; xs = rs - xr * g.S; }
+    f32x16 acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    u32x4 gv[2];
+    unsigned xv[8];
+    auto load = [&](int step) {
+        const int m = step * 64 + gp;
+        gv[0] = gv[1] = u32x4{0, 0, 0, 0};
+        if (m < M) {
+            const bf16_t *src = dy + (size_t)m * g.K + a0 + gc;
+            if (a0 + gc + 8 <= g.K) gv[0] = *reinterpret_cast<const u32x4 *>(src);
+            if (a0 + gc + 16 <= g.K) gv[1] = *reinterpret_cast<const u32x4 *>(src + 8);
+        }
+        const int mx = step * 64 + xp;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xv[e] = 0;
+        if (mx < M) {
+            const int n = mx / (g.Ho * g.Wo), rem = mx - n * (g.Ho * g.Wo), p = rem / g.Wo, q = rem - p * g.Wo;
+            const int hb = p * g.sh - g.ph, wb = q * g.sw - g.pw;
+            const bf16_t *img = x + (size_t)n * g.H * g.W * g.C;
+            int r = xr, s = xs, c = xc;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (xt + e < rsc) {
+                    xv[e] = im2col_elem(g, img, hb, wb, r, s, c);
+                    if (++c == g.C) { c = 0; if (++s == g.S) { s = 0; ++r; } }
+                }
+            }
+        }
+    };
+    if (sbeg < send) load(sbeg);
+    for (int step = sbeg; step < send; ++step) {
+        // registers -> LDS, transposed
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const unsigned wv[4] = {gv[h].x, gv[h].y, gv[h].z, gv[h].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gT[(gc + h * 8 + e) * WLS + gp] = (bf16_t)((wv[e >> 1] >> ((e & 1) * 16)) & 0xffffu);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) xT[(xt + e) * WLS + xp] = (bf16_t)xv[e];
+        __syncthreads();
+        if (step + 1 < send) load(step + 1);   // in flight during the matrix instructions
+        const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xT + (lane & 31) * WLS + wave * 16 + 8 * (lane >> 5));
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(gT + (i * 32 + (lane & 31)) * WLS + wave * 16 + 8 * (lane >> 5));
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // D element v of lane l: row 8*(v/4) + 4*(l/32) + v%4 (c_out), column l%32 (tap)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) red[wave][i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3)][lane & 31] = acc[i][v];
+    __syncthreads();
+    float *out = partial + ((size_t)blockIdx.x * gridDim.y + blockIdx.y) * 64 * 32;
+    for (int id = tid; id < 64 * 32; id += 256) {
+        const int k = id >> 5, t = id & 31;
+        out[id] = (red[0][k][t] + red[1][k][t]) + (red[2][k][t] + red[3][k][t]);
+    }
+}
+
+// dw[k][t] = sum over blocks of partial[b][ktile][k % 64][t], in block order; grid = c_out, 256 threads:
+// thread (t, part) adds every 8th block, the 8 parts are then added in order
+__global__ __launch_bounds__(256) void k_wgrad_direct_sum(int K, int rsc, int nblocks, int ktiles, const float *partial, float *dw)
+{
+    __shared__ float sm[8][32];
+    const int k = blockIdx.x, t = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const float *src = partial + ((size_t)(k >> 6) * 64 + (k & 63)) * 32 + t;
+    float s0 = 0.f, s1 = 0.f;
+    int b = part;
+    for (; b + 8 < nblocks; b += 16) {
+        s0 += src[(size_t)b * ktiles * 64 * 32];
+        s1 += src[(size_t)(b + 8) * ktiles * 64 * 32];
+    }
+    if (b < nblocks) s0 += src[(size_t)b * ktiles * 64 * 32];
+    sm[part][t] = s0 + s1;
+    __syncthreads();
+    if (part == 0 && t < rsc) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += sm[i][t];
+        dw[(size_t)k * rsc + t] = s;
+    }
+}
+
 unsigned blocks_for(long long total)
 {
     long long nb = (total + 255) / 256;
@@ -72,6 +289,44 @@ int small_c_kpad(const ConvGeom &g)
     const int rsc = g.R * g.S * g.C;
     const int kpad = (rsc + 31) / 32 * 32;
     return kpad <= 256 ? kpad : 0;
+}
+
+bool small_c_direct(const ConvGeom &g) { return (g.C % 8) != 0 && g.R * g.S * g.C <= 32 && (g.K % 8) == 0; }
+
+hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
+                              hipStream_t st)
+{
+    const long long M = (long long)g.N * g.Ho * g.Wo;
+    const int tiles = (int)((M + DT - 1) / DT), ktiles = (g.K + 63) / 64;
+    int nb = tiles < 2048 ? tiles : 2048;   // persistent beyond eight blocks per CU
+    hipLaunchKernelGGL(k_fwd_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, flags, x, w, bias, y, tiles);
+    return hipGetLastError();
+}
+
+// blocks along the pixel range of the direct filter-gradient kernel, and the bytes of its fp32 partials
+int small_c_wgrad_blocks(const ConvGeom &g)
+{
+    const long long steps = ((long long)g.N * g.Ho * g.Wo + 63) / 64;
+    long long nb = (steps + 3) / 4;   // at least four 64-pixel steps per block
+    if (nb > 1024) nb = 1024;
+    const long long spb = (steps + nb - 1) / nb;
+    return (int)((steps + spb - 1) / spb);
+}
+size_t small_c_wgrad_partial_bytes(const ConvGeom &g)
+{
+    return (size_t)small_c_wgrad_blocks(g) * ((g.K + 63) / 64) * 64 * 32 * sizeof(float);
+}
+
+hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *partial, float *dw, hipStream_t st)
+{
+    const long long steps = ((long long)g.N * g.Ho * g.Wo + 63) / 64;
+    const int nb = small_c_wgrad_blocks(g), ktiles = (g.K + 63) / 64;
+    const int spb = (int)((steps + nb - 1) / nb);
+    hipLaunchKernelGGL(k_wgrad_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, x, dy, partial, spb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)g.K), dim3(256), 0, st, g.K, g.R * g.S * g.C, nb, ktiles, partial, dw);
+    return hipGetLastError();
 }
 
 hipError_t small_c_im2col(const ConvGeom &g, int kpad, const bf16_t *x, bf16_t *xcol, hipStream_t st)

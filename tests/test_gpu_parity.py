@@ -61,6 +61,9 @@ BF16_CASES = [
     ("vgg_like_128_256", 3, 14, 14, 128, 256, 3, 3, (1, 1), (1, 1), True, True, False),
     ("rgb_3x3", 2, 20, 22, 3, 64, 3, 3, (1, 1), (1, 1), True, True, True),
     ("stem_7x7_s2", 2, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3), False, False, True),
+    ("rgb_3x3_s2_k32", 3, 23, 21, 3, 32, 3, 3, (2, 2), (0, 0), False, True, True),
+    ("rgb_3x3_k136", 1, 37, 19, 3, 136, 3, 3, (1, 1), (1, 1), True, True, True),
+    ("gray_5x5", 2, 18, 18, 1, 16, 5, 5, (1, 1), (2, 2), True, False, True),
     ("res_1x1", 2, 14, 14, 256, 64, 1, 1, (1, 1), (0, 0), False, False, False),
     ("res_1x1_s2", 2, 14, 14, 128, 256, 1, 1, (2, 2), (0, 0), False, False, False),
     ("res_3x3_s2", 2, 15, 15, 64, 64, 3, 3, (2, 2), (1, 1), False, True, False),
