@@ -75,14 +75,24 @@ DEVFN unsigned im2col_elem(const ConvGeom &g, const bf16_t *img, int hb, int wb,
     return ((unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W) ? img[(ih * g.W + iw) * g.C + c] : 0u;
 }
 
-// grid = (persistent blocks over pixel tiles, 64-row tiles of c_out); 4 waves, wave tile 64 c_out x 64 pixels
-__global__ __launch_bounds__(256) void k_fwd_direct(ConvGeom g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias,
-                                                    bf16_t *y, int tiles)
+// Forward.  A tile is 8 x 32 output pixels of one image.  Its input patch ((7*sh + R) rows of
+// (31*sw + S)*C elements) is copied once into LDS with coalesced loads (zero outside the image); every
+// thread then gathers the 32-element im2col row of its pixel from the patch.
+// grid = (persistent blocks over tiles, 64-row tiles of c_out); 4 waves, wave tile 64 c_out x 64 pixels.
+// patch offset r*PWE + s*C + c of reduction element kk (0 beyond R*S*C), passed by value: it lives in scalar registers
+struct TapTable { unsigned short off[32]; };
+constexpr int DPF = 16;          // patch elements per thread (prefetched in registers)
+constexpr int DPATCH = DPF * 256;   // patch elements; they fit beside the im2col tile (<= 8192)
+__global__ __launch_bounds__(256, 3) void k_fwd_direct(ConvGeom g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias,
+                                                    bf16_t *y, int tiles, int tiles_x, int tiles_y, unsigned inv_c, TapTable taps)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t lds[DT * DLO];   // im2col tile [256][40], later the output tile [256][72]
+    // [0, 20 KB): im2col tile [256][40]; [20 KB, 36 KB): input patch; afterwards the whole array is the output tile [256][72]
+    __shared__ __attribute__((aligned(16))) bf16_t lds[DT * DLO];
     __shared__ float bias_lds[64];
+    bf16_t *patch = lds + DT * DLB;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int a0 = blockIdx.y * 64, rsc = g.R * g.S * g.C, M = g.N * g.Ho * g.Wo;
+    const int a0 = blockIdx.y * 64, rsc = g.R * g.S * g.C;
+    const int PH = 7 * g.sh + g.R, PWE = (31 * g.sw + g.S) * g.C, PN = PH * PWE;
     if (tid < 64) bias_lds[tid] = ((flags & KF_BIAS) && a0 + tid < g.K) ? bias[a0 + tid] : 0.f;
     // weight fragments: row a0 + i*32 + lane%32, reduction elements ks*16 + 8*(lane/32) .. +7
     bf16x8 afr[2][2];
@@ -99,24 +109,44 @@ __global__ __launch_bounds__(256) void k_fwd_direct(ConvGeom g, unsigned flags, 
             }
             afr[ks][i] = __builtin_bit_cast(bf16x8, u32x4{v[0], v[1], v[2], v[3]});
         }
+    const int py = tid >> 5, px = tid & 31;
+    const int goff = (py * g.sh) * PWE + (px * g.sw) * g.C;   // patch element of this pixel's tap (0, 0), channel 0
+    // the patch of the next tile is fetched into registers while the current tile is processed
+    unsigned short pf[DPF];
+    auto fetch = [&](int tile) {
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        const int h0 = ty * 8 * g.sh - g.ph, w0 = tx * 32 * g.sw - g.pw;
+        int pr = tid / PWE, pe = tid - pr * PWE;   // element idx = pr*PWE + pe holds x[n][h0 + pr][w0 + pe / C][pe % C]
+#pragma unroll
+        for (int e = 0; e < DPF; ++e) {
+            const int wrel = inv_c != 0 ? (int)__umulhi((unsigned)pe, inv_c) : pe, c = pe - wrel * g.C;   // inv_c == 0: one channel
+            const int ih = h0 + pr, iw = w0 + wrel;
+            unsigned short val = 0;
+            if (tid + e * 256 < PN && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W)
+                val = x[((size_t)(n * g.H + ih) * g.W + iw) * g.C + c];
+            pf[e] = val;
+            pe += 256;
+            while (pe >= PWE) { pe -= PWE; ++pr; }
+        }
+    };
+    if ((int)blockIdx.x < tiles) fetch(blockIdx.x);
     for (int tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-        {   // im2col row of pixel tile*256 + tid
-            const int m = tile * DT + tid;
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        const int p0 = ty * 8, q0 = tx * 32;
+#pragma unroll
+        for (int e = 0; e < DPF; ++e)
+            if (tid + e * 256 < PN) patch[tid + e * 256] = pf[e];
+        __syncthreads();
+        if (tile + (int)gridDim.x < tiles) fetch(tile + gridDim.x);
+        {   // im2col row of pixel (py, px): 32 independent LDS reads at wave-uniform offsets, no control flow
             unsigned v[16];
+            int gl = goff;
+            asm volatile("" : "+v"(gl));   // keeps the 32 addresses from being hoisted out of the tile loop (they would spill)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) v[e] = 0;
-            if (m < M) {
-                const int n = m / (g.Ho * g.Wo), rem = m - n * (g.Ho * g.Wo), p = rem / g.Wo, q = rem - p * g.Wo;
-                const int hb = p * g.sh - g.ph, wb = q * g.sw - g.pw;
-                const bf16_t *img = x + (size_t)n * g.H * g.W * g.C;
-                int r = 0, s = 0, c = 0;
-#pragma unroll
-                for (int kk = 0; kk < 32; ++kk) {
-                    if (kk < rsc) {
-                        v[kk >> 1] |= im2col_elem(g, img, hb, wb, r, s, c) << ((kk & 1) * 16);
-                        if (++c == g.C) { c = 0; if (++s == g.S) { s = 0; ++r; } }
-                    }
-                }
+            for (int kk = 0; kk < 32; kk += 2) {
+                const unsigned lo = patch[gl + taps.off[kk]] & (kk < rsc ? 0xffffu : 0u);
+                const unsigned hi = patch[gl + taps.off[kk + 1]] & (kk + 1 < rsc ? 0xffffu : 0u);
+                v[kk >> 1] = lo | (hi << 16);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
@@ -138,7 +168,7 @@ __global__ __launch_bounds__(256) void k_fwd_direct(ConvGeom g, unsigned flags, 
 #pragma unroll
                 for (int i = 0; i < 2; ++i) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(afr[ks][i], b, acc[i][j], 0, 0, 0);
             }
-        __syncthreads();   // the im2col tile has been read: its memory now takes the output tile
+        __syncthreads();   // im2col tile and patch have been read: their memory now takes the output tile
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -158,11 +188,11 @@ __global__ __launch_bounds__(256) void k_fwd_direct(ConvGeom g, unsigned flags, 
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int id = tid + it * 256, pix = id >> 3, cc = id & 7;
-            const int gp = tile * DT + pix, gc = a0 + cc * 8;
-            if (gp < M && gc < g.K)
-                *reinterpret_cast<u32x4 *>(y + (size_t)gp * g.K + gc) = *reinterpret_cast<const u32x4 *>(lds + pix * DLO + cc * 8);
+            const int p = p0 + (pix >> 5), q = q0 + (pix & 31), gc = a0 + cc * 8;
+            if (p < g.Ho && q < g.Wo && gc < g.K)
+                *reinterpret_cast<u32x4 *>(y + ((size_t)(n * g.Ho + p) * g.Wo + q) * g.K + gc) = *reinterpret_cast<const u32x4 *>(lds + pix * DLO + cc * 8);
         }
-        __syncthreads();   // the output tile has been read before the next im2col tile overwrites it
+        __syncthreads();   // the output tile has been read before the next patch overwrites it
     }
 }
 
@@ -250,26 +280,29 @@ __global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *
     }
 }
 
-// dw[k][t] = sum over blocks of partial[b][ktile][k % 64][t], in block order; grid = c_out, 256 threads:
-// thread (t, part) adds every 8th block, the 8 parts are then added in order
-__global__ __launch_bounds__(256) void k_wgrad_direct_sum(int K, int rsc, int nblocks, int ktiles, const float *partial, float *dw)
+// dw[k][t] = sum over blocks of partial[b][ktile][k % 64][t] in a fixed order; grid = c_out, 1024 threads:
+// thread (t, part) adds every 32nd block with four loads in flight, the 32 parts are then added in order
+__global__ __launch_bounds__(1024) void k_wgrad_direct_sum(int K, int rsc, int nblocks, int ktiles, const float *partial, float *dw)
 {
-    __shared__ float sm[8][32];
+    __shared__ float sm[32][33];
     const int k = blockIdx.x, t = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const size_t bstride = (size_t)ktiles * 64 * 32;
     const float *src = partial + ((size_t)(k >> 6) * 64 + (k & 63)) * 32 + t;
-    float s0 = 0.f, s1 = 0.f;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int b = part;
-    for (; b + 8 < nblocks; b += 16) {
-        s0 += src[(size_t)b * ktiles * 64 * 32];
-        s1 += src[(size_t)(b + 8) * ktiles * 64 * 32];
+    for (; b + 96 < nblocks; b += 128) {
+        s0 += src[(size_t)b * bstride];
+        s1 += src[(size_t)(b + 32) * bstride];
+        s2 += src[(size_t)(b + 64) * bstride];
+        s3 += src[(size_t)(b + 96) * bstride];
     }
-    if (b < nblocks) s0 += src[(size_t)b * ktiles * 64 * 32];
-    sm[part][t] = s0 + s1;
+    for (; b < nblocks; b += 32) s0 += src[(size_t)b * bstride];
+    sm[part][t] = (s0 + s1) + (s2 + s3);
     __syncthreads();
     if (part == 0 && t < rsc) {
         float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) s += sm[i][t];
+        for (int i = 0; i < 32; ++i) s += sm[i][t];
         dw[(size_t)k * rsc + t] = s;
     }
 }
@@ -291,15 +324,27 @@ int small_c_kpad(const ConvGeom &g)
     return kpad <= 256 ? kpad : 0;
 }
 
-bool small_c_direct(const ConvGeom &g) { return (g.C % 8) != 0 && g.R * g.S * g.C <= 32 && (g.K % 8) == 0; }
+bool small_c_direct(const ConvGeom &g)
+{
+    if ((g.C % 8) == 0 || g.R * g.S * g.C > 32 || (g.K % 8) != 0) return false;
+    return (long long)(7 * g.sh + g.R) * ((31 * g.sw + g.S) * g.C) <= DPATCH;   // the forward kernel's input patch fits its LDS slot
+}
 
 hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
                               hipStream_t st)
 {
-    const long long M = (long long)g.N * g.Ho * g.Wo;
-    const int tiles = (int)((M + DT - 1) / DT), ktiles = (g.K + 63) / 64;
-    int nb = tiles < 2048 ? tiles : 2048;   // persistent beyond eight blocks per CU
-    hipLaunchKernelGGL(k_fwd_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, flags, x, w, bias, y, tiles);
+    const int tiles_x = (g.Wo + 31) / 32, tiles_y = (g.Ho + 7) / 8, ktiles = (g.K + 63) / 64;
+    const long long tiles = (long long)g.N * tiles_x * tiles_y;
+    const int nb = (int)(tiles < 2048 ? tiles : 2048);   // persistent beyond eight blocks per CU
+    const unsigned inv_c = g.C == 1 ? 0u : (unsigned)((0x100000000ull + g.C - 1) / g.C);   // __umulhi(e, inv_c) == e / C for e < 65536
+    TapTable taps;
+    const int pwe = (31 * g.sw + g.S) * g.C;
+    for (int kk = 0; kk < 32; ++kk) {
+        const int rs = kk / g.C, c = kk - rs * g.C, r = rs / g.S, s2 = rs - r * g.S;
+        taps.off[kk] = kk < g.R * g.S * g.C ? (unsigned short)(r * pwe + s2 * g.C + c) : (unsigned short)0;
+    }
+    hipLaunchKernelGGL(k_fwd_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, flags, x, w, bias, y, (int)tiles,
+                       tiles_x, tiles_y, inv_c, taps);
     return hipGetLastError();
 }
 
@@ -325,7 +370,7 @@ hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t
     hipLaunchKernelGGL(k_wgrad_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, x, dy, partial, spb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)g.K), dim3(256), 0, st, g.K, g.R * g.S * g.C, nb, ktiles, partial, dw);
+    hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)g.K), dim3(1024), 0, st, g.K, g.R * g.S * g.C, nb, ktiles, partial, dw);
     return hipGetLastError();
 }
 
