@@ -1,0 +1,347 @@
+// Forward / backward-data kernels for stride-1 layers whose reduction has exactly 64 channels per
+// tap (VGG conv1_2, conv2_1): the tiled kernels re-fetch every input pixel once per filter tap, and
+// with only R*S reduction steps per tile that traffic through the per-CU global->LDS path is what
+// bounds them.  Here a block owns a TH x TW patch of output pixels of one image (TH*TW = 256) and
+// copies the input patch with its halo ((TH+R-1) x (TW+S-1) pixels x 64 channels, zero outside the
+// image) into LDS ONCE; the R*S taps then read their pixel rows from that patch at shifted positions.
+// Only the weight tile of each tap still streams through the NS-stage pipeline.
+//
+// Patch layout: pixel pp = pr*(TW+S-1) + pc occupies 128 bytes; its 16-byte channel chunk c sits at
+// chunk position c ^ (pp & 7), which makes the fragment reads of 32 consecutive pixels conflict-free.
+// A direct-to-LDS instruction fills 8 consecutive patch pixels.
+#include "dma_common.h"
+#include <cstdio>
+
+namespace {
+
+constexpr int HALO_TB = 256;        // output pixels per tile
+constexpr int HALO_PP = 352;        // patch pixels the LDS slot holds (44 KiB): 10x34 and 18x18 fit
+
+// PASS_FWD : A = weights [c_out][tap][64 c_in] (rows K-major in LDS), patch from x.
+// PASS_DGRAD: A = weights [64 c_out][tap][c_in] kept reduction-major in LDS and read with the LDS
+//             transpose read, patch from dy; tap (r, s) of the filter meets patch offset (R-1-r, S-1-s).
+template <int PASS, int TA, int WA, int WB, int NS>
+__global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, int tiles_x, int tiles_y)
+{
+    constexpr int NT = 64 * WA * WB, NW = WA * WB, TB = HALO_TB;
+    constexpr int KS = 4;                                     // 16-wide slices per 64-channel step
+    constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
+    constexpr int A_BYTES = TA * 128;                         // one tap's weight tile (either orientation)
+    constexpr int IA = A_BYTES / 1024 / NW;                   // weight copies per wave and step
+    constexpr int IP = (HALO_PP * 128 / 1024 + NW - 1) / NW;  // patch copies per wave
+    constexpr int PATCH_BYTES = IP * NW * 1024;
+    static_assert(IA * NW * 1024 == A_BYTES, "weight tile must divide over the waves");
+    constexpr int STAGES_END = PATCH_BYTES + NS * A_BYTES, EPI = TB * (TA + 8) * 2;
+    constexpr int TILE_BYTES = STAGES_END > EPI ? STAGES_END : EPI;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    float *bias_lds = reinterpret_cast<float *>(smem + TILE_BYTES);   // [TA]
+
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int R = g.R, S = g.S, TW = 1 << tws, TH = TB >> tws, PW = TW + S - 1, PP = (TH + R - 1) * PW;
+    const int tile = logical_block(blockIdx.x, gridDim.x);
+    const int a0 = (tile % p.tilesA) * TA, bt = tile / p.tilesA;
+    const int n = bt / (tiles_x * tiles_y), trem = bt - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+    const int p0 = ty * TH, q0 = tx * TW;
+    // image the patch is cut from, its extent, and the patch origin
+    const int IH = PASS == PASS_FWD ? g.H : g.Ho, IW = PASS == PASS_FWD ? g.W : g.Wo;
+    const int h0 = PASS == PASS_FWD ? p0 - g.ph : p0 + g.ph - (R - 1), w0 = PASS == PASS_FWD ? q0 - g.pw : q0 + g.pw - (S - 1);
+    const int OH = PASS == PASS_FWD ? g.Ho : g.H, OW = PASS == PASS_FWD ? g.Wo : g.W;   // output image
+    const int RSC = R * S * g.C;
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
+    __amdgpu_buffer_rsrc_t rsrc_in = PASS == PASS_FWD ? make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2)
+                                                      : make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+    const unsigned smem_base = lds_offset(smem);
+
+    if ((p.flags & KF_BIAS) && PASS == PASS_FWD)
+        for (int i = tid; i < TA; i += NT) bias_lds[i] = a0 + i < p.rowsA ? p.bias[a0 + i] : 0.f;
+
+    // ---- patch: all copies issued up front -------------------------------------------------
+#pragma unroll
+    for (int q = 0; q < IP; ++q) {
+        const int id = (wave * IP + q) * 64 + lane, pp = id >> 3, c = (id & 7) ^ (pp & 7);
+        const int pr = pp / PW, pc = pp - pr * PW, ih = h0 + pr, iw = w0 + pc;
+        const bool ok = pp < PP && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
+        const unsigned voff = ok ? (unsigned)(((n * IH + ih) * IW + iw) * 64 + c * 8) * 2u : OOR;
+        dma16(rsrc_in, smem_base + (wave * IP + q) * 1024, voff);
+    }
+
+    // ---- weight tile of one tap ----------------------------------------------------------------
+    unsigned voffA[IA];
+#pragma unroll
+    for (int q = 0; q < IA; ++q) {
+        if (PASS == PASS_FWD) {   // row = c_out, 8 rows per copy, chunk swizzle by row pair
+            const int row = (wave * IA + q) * 8 + lane / 8;
+            const int c = (lane % 8) ^ ((row / 2) % 8);
+            voffA[q] = ((unsigned)(a0 + row) * RSC + c * 8) * 2u;
+        } else {                  // row = c_out (reduction), TA c_in per row, 512/TA rows per copy, segment swizzle
+            const int t = (wave * IA + q) * (512 / TA) + lane / (TA / 8);
+            const int c = (lane % (TA / 8)) ^ (seg_swz<TA>(t) << 2);
+            voffA[q] = ((unsigned)t * RSC + a0 + c * 8) * 2u;
+        }
+    }
+    const unsigned ldsA_w = smem_base + PATCH_BYTES + wave * IA * 1024;
+    auto issueA = [&](int stage, int step) {   // filter tap of reduction step `step`
+        const int tap = PASS == PASS_FWD ? step : (R * S - 1 - step);
+        const unsigned ua = (unsigned)tap * g.C * 2u;
+#pragma unroll
+        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + stage * A_BYTES + q * 1024, voffA[q] + ua);
+    };
+
+    f32x16 acc[FA][FB];
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
+
+    // fragment addresses of the weight tile
+    unsigned fa[KS][PASS == PASS_FWD ? 1 : FA];
+    if (PASS == PASS_FWD) {
+        const int rA = arow + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            fa[ks][0] = smem_base + PATCH_BYTES + rA * 128 + (((2 * ks + (lane >> 5)) ^ ((rA / 2) % 8)) << 4);
+    } else {
+        const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int t = ks * 16 + tl;
+#pragma unroll
+            for (int i = 0; i < (PASS == PASS_FWD ? 1 : FA); ++i) {
+                const int col = arow + i * 32 + cl;
+                fa[ks][i] = smem_base + PATCH_BYTES + t * (TA * 2) + ((((col >> 5) ^ seg_swz<TA>(t)) << 6) | ((col & 31) << 1));
+            }
+        }
+    }
+    // patch pixel of this lane's row in each of its B fragments, at patch offset (0, 0)
+    int pp0[FB];
+#pragma unroll
+    for (int j = 0; j < FB; ++j) {
+        const int jj = brow + j * 32 + (lane & 31);
+        pp0[j] = (jj >> tws) * PW + (jj & (TW - 1));
+    }
+    const unsigned hsel = lane >> 5;
+
+    const int nsteps = R * S;
+    constexpr int LPS = IA;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+        if (s < nsteps) issueA(s, s);
+
+    u32x4 fr_a[2][FA], fr_b[2][FB];
+    u32x2 tr_lo[2][FA], tr_hi[2][FA];
+    unsigned brow_addr[FB], bsw[FB];
+    auto set_tap = [&](int step) {   // patch rows of reduction step `step` (patch offset r*PW + s)
+        const int r = step / S, s = step - r * S;
+        const int off = r * PW + s;
+#pragma unroll
+        for (int j = 0; j < FB; ++j) {
+            const int pp = pp0[j] + off;
+            brow_addr[j] = smem_base + pp * 128;
+            bsw[j] = pp & 7;
+        }
+    };
+    auto read_slice = [&](int ks, int buf, unsigned sb) {
+        if constexpr (PASS == PASS_FWD) {
+            if constexpr (FA >= 1) fr_a[buf][0] = lds_read16<0>(fa[ks][0] + sb);
+            if constexpr (FA >= 2) fr_a[buf][1] = lds_read16<32 * 128>(fa[ks][0] + sb);
+            if constexpr (FA >= 3) fr_a[buf][2] = lds_read16<64 * 128>(fa[ks][0] + sb);
+            if constexpr (FA >= 4) fr_a[buf][3] = lds_read16<96 * 128>(fa[ks][0] + sb);
+        } else {
+#pragma unroll
+            for (int i = 0; i < FA; ++i) {
+                tr_lo[buf][i] = lds_read_tr<0>(fa[ks][i] + sb);
+                tr_hi[buf][i] = lds_read_tr<4 * TA * 2>(fa[ks][i] + sb);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < FB; ++j) fr_b[buf][j] = lds_read16<0>(brow_addr[j] + (((2 * ks + hsel) ^ bsw[j]) << 4));
+    };
+    constexpr int RPS_ = (PASS == PASS_FWD ? FA : 2 * FA) + FB;   // LDS reads per slice
+    static_assert(RPS_ < 16, "lgkmcnt is a 4-bit counter");
+    auto wait_slice = [&](int buf, bool newer_in_flight) {
+        if (newer_in_flight) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(RPS_));
+        else asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+        for (int i = 0; i < FA; ++i) {
+            if constexpr (PASS == PASS_FWD) asm volatile("" : "+v"(fr_a[buf][i]));
+            else { asm volatile("" : "+v"(tr_lo[buf][i])); asm volatile("" : "+v"(tr_hi[buf][i])); }
+        }
+#pragma unroll
+        for (int j = 0; j < FB; ++j) asm volatile("" : "+v"(fr_b[buf][j]));
+    };
+
+    // patch and the first weight tile have landed; later weight tiles may be in flight
+    {
+        const int younger = min(NS - 1, nsteps - 1);
+        if (NS >= 2 && younger == NS - 1) wait_vmcnt<(NS - 1) * LPS>();
+        else if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS >= 3 ? NS - 2 : 0) * LPS>();
+        else wait_vmcnt<0>();
+    }
+    __syncthreads();   // also publishes bias_lds
+    set_tap(0);
+    read_slice(0, 0, 0);
+    for (int i = 0; i < nsteps; ++i) {
+        const unsigned sb = (i % NS) * A_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int cur = ks & 1;
+            if (ks < KS - 1) {
+                read_slice(ks + 1 < KS ? ks + 1 : 0, cur ^ 1, sb);
+                wait_slice(cur, true);
+            } else {
+                wait_slice(cur, false);   // this wave has read all it needs of the weight stage
+                if (i + 1 < nsteps) {
+                    const int younger = min(i + NS - 1, nsteps - 1) - (i + 1);
+                    if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+                    else wait_vmcnt<0>();
+                    __builtin_amdgcn_s_barrier();
+                    if (i + NS < nsteps) issueA(i % NS, i + NS);
+                    set_tap(i + 1);
+                    read_slice(0, 0, ((i + 1) % NS) * A_BYTES);
+                }
+            }
+#pragma unroll
+            for (int ii = 0; ii < FA; ++ii)
+#pragma unroll
+                for (int jj = 0; jj < FB; ++jj) {
+                    u32x4 av;
+                    if constexpr (PASS == PASS_FWD) av = fr_a[cur][ii];
+                    else av = u32x4{tr_lo[cur][ii].x, tr_lo[cur][ii].y, tr_hi[cur][ii].x, tr_hi[cur][ii].y};
+                    acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                         __builtin_bit_cast(bf16x8, fr_b[cur][jj]), acc[ii][jj], 0, 0, 0);
+                }
+        }
+    }
+    __syncthreads();   // every wave is done reading patch and stages before they are reused for staging
+
+    // ---- epilogue: bias / ReLU / bf16 through LDS, 16-byte rows to the NHWC output ------------
+    constexpr int LSO = TA + 8;
+    bf16_t *stage = reinterpret_cast<bf16_t *>(smem);
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int ch = arow + i * 32 + 8 * gq + 4 * (lane >> 5);
+            f32x4 bv = {0.f, 0.f, 0.f, 0.f};
+            if ((p.flags & KF_BIAS) && PASS == PASS_FWD) bv = *reinterpret_cast<const f32x4 *>(bias_lds + ch);
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y;
+                float v2 = acc[i][j][4 * gq + 2] + bv.z, v3 = acc[i][j][4 * gq + 3] + bv.w;
+                if ((p.flags & KF_RELU) && PASS == PASS_FWD) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                const int pix = brow + j * 32 + (lane & 31);
+                *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) = u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
+            }
+        }
+    __syncthreads();
+    constexpr int CPR = TA / 8;
+    bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+#pragma unroll
+    for (int id = tid; id < TB * CPR; id += NT) {
+        const int pix = id / CPR, cc = id % CPR;
+        const int pr = p0 + (pix >> tws), qc = q0 + (pix & (TW - 1)), gc = a0 + cc * 8;
+        if (pr < OH && qc < OW && gc < p.rowsA)
+            *reinterpret_cast<u32x4 *>(out + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc) =
+                *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+    }
+}
+
+struct HaloVariant { int TA, WA, WB, NS; };
+const HaloVariant kHalo[] = {{64, 1, 4, 2}, {128, 2, 2, 2}, {64, 1, 4, 3}};
+constexpr int kNumHalo = 3;
+typedef void (*HaloFn)(const KArgs, int, int, int);
+HaloFn pick_halo(int pass, int v)
+{
+    if (pass == PASS_FWD) {
+        switch (v) {
+        case 1: return k_halo<PASS_FWD, 128, 2, 2, 2>;
+        case 2: return k_halo<PASS_FWD, 64, 1, 4, 3>;
+        default: return k_halo<PASS_FWD, 64, 1, 4, 2>;
+        }
+    }
+    switch (v) {
+    case 1: return k_halo<PASS_DGRAD, 128, 2, 2, 2>;
+    case 2: return k_halo<PASS_DGRAD, 64, 1, 4, 3>;
+    default: return k_halo<PASS_DGRAD, 64, 1, 4, 2>;
+    }
+}
+size_t halo_lds_bytes(const HaloVariant &h)
+{
+    const int nw = h.WA * h.WB;
+    const size_t ip = (HALO_PP * 128 / 1024 + nw - 1) / nw;
+    const size_t stages = ip * nw * 1024 + (size_t)h.NS * h.TA * 128, epi = (size_t)HALO_TB * (h.TA + 8) * 2;
+    return (stages > epi ? stages : epi) + (size_t)h.TA * 4;
+}
+// tile shape with the least padded area: 8 x 32 (tws 5) or 16 x 16 (tws 4) output pixels
+int halo_tws(int oh, int ow)
+{
+    const long long a5 = (long long)((oh + 7) / 8 * 8) * ((ow + 31) / 32 * 32), a4 = (long long)((oh + 15) / 16 * 16) * ((ow + 15) / 16 * 16);
+    return a4 < a5 ? 4 : 5;
+}
+
+}  // namespace
+
+hipError_t halo_init()
+{
+    for (int pass = 0; pass < 2; ++pass)
+        for (int v = 0; v < kNumHalo; ++v) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_halo(pass, v)), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               (int)halo_lds_bytes(kHalo[v]));
+            if (e != hipSuccess) return e;
+        }
+    return hipSuccess;
+}
+
+// variant override 400 + v; forward needs c_in == 64, backward-data c_out == 64; stride 1; no reduction split
+bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *pl)
+{
+    if (force_variant < 400 || force_variant >= 400 + kNumHalo || force_splits > 1) return false;
+    if (pass != PASS_FWD && pass != PASS_DGRAD) return false;
+    if (g.sh != 1 || g.sw != 1 || g.R * g.S > 32) return false;
+    const int red_c = pass == PASS_FWD ? g.C : g.K, rowsA = pass == PASS_FWD ? g.K : g.C;
+    if (red_c != 64 || (rowsA % 8) != 0) return false;
+    if (pass == PASS_DGRAD && (g.ph > g.R - 1 || g.pw > g.S - 1)) return false;
+    const int oh = pass == PASS_FWD ? g.Ho : g.H, ow = pass == PASS_FWD ? g.Wo : g.W;
+    const int tws = halo_tws(oh, ow), tw = 1 << tws, th = HALO_TB >> tws;
+    if ((th + g.R - 1) * (tw + g.S - 1) > HALO_PP) return false;
+    const HaloVariant &h = kHalo[force_variant - 400];
+    pl->variant = force_variant - 400;
+    pl->fast = true; pl->dma = true; pl->halo = true;
+    pl->TA = h.TA; pl->TB = HALO_TB; pl->BK = 64; pl->vecA = pl->vecB = true;
+    pl->tilesA = (rowsA + h.TA - 1) / h.TA;
+    pl->tilesB = g.N * ((oh + th - 1) / th) * ((ow + tw - 1) / tw);
+    pl->steps_total = pl->steps_per_split = g.R * g.S;
+    pl->splits = 1;
+    return true;
+}
+
+void halo_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
+{
+    const HaloVariant &h = kHalo[pl.variant];
+    snprintf(name, name_bytes, "k_halo<%d, %d, %d, %d, %d>", pass, h.TA, h.WA, h.WB, h.NS);
+}
+
+hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
+{
+    KArgs p;
+    p.g = a.g;
+    const bool fwd = a.pass == PASS_FWD;
+    p.rowsA = fwd ? a.g.K : a.g.C;
+    p.rowsB = fwd ? a.g.N * a.g.Ho * a.g.Wo : a.g.N * a.g.H * a.g.W;
+    p.red = a.g.R * a.g.S * 64;
+    p.tilesA = a.plan.tilesA; p.tilesB = a.plan.tilesB;
+    p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split; p.splits = 1;
+    p.flags = a.flags;
+    p.x = a.x; p.w = a.w; p.dy = a.dy; p.ymask = nullptr; p.bias = a.bias; p.out = a.out; p.partial = a.partial;
+    const int oh = fwd ? a.g.Ho : a.g.H, ow = fwd ? a.g.Wo : a.g.W;
+    const int tws = halo_tws(oh, ow), tw = 1 << tws, th = HALO_TB >> tws;
+    const int tiles_x = (ow + tw - 1) / tw, tiles_y = (oh + th - 1) / th;
+    const HaloVariant &h = kHalo[a.plan.variant];
+    dim3 grid((unsigned)(p.tilesA * p.tilesB), 1, 1), block(64 * h.WA * h.WB, 1, 1);
+    hipLaunchKernelGGL(pick_halo(a.pass, a.plan.variant), grid, block, halo_lds_bytes(h), st, p, tws, tiles_x, tiles_y);
+    return hipGetLastError();
+}

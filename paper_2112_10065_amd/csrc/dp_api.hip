@@ -91,7 +91,9 @@ dp_status check_opt(const void *p, const char *name)
 void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl)
 {
     pl->dma = false;
+    pl->halo = false;
     if (fv < 0 && auto_plan(g, pass, fs, pl)) return;
+    if (fv >= 400 && halo_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 200 && dma_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 100 && fast_plan(g, pass, fv, fs, pl)) return;
     mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
@@ -150,6 +152,7 @@ void plan_for(const ConvGeom &g, int pass, GemmPlan *pl) { *pl = plan_entry(g, p
 
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 {
+    if (a.plan.halo) return halo_launch(a, st);
     if (a.plan.dma) return dma_launch(a, st);
     return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st);
 }
@@ -204,7 +207,7 @@ size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 dp_status ensure_init()
 {
-    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); if (g_init_err == hipSuccess) g_init_err = dma_init(); });
+    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); if (g_init_err == hipSuccess) g_init_err = dma_init(); if (g_init_err == hipSuccess) g_init_err = halo_init(); });
     if (g_init_err != hipSuccess) return hip_fail(g_init_err, "library initialisation (is a gfx950 device present?)");
     return DP_OK;
 }
@@ -449,7 +452,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
     GemmPlan pl;
     plan_for(g, pass, &pl);
-    if (name != nullptr && name_bytes > 0) { if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
+    if (name != nullptr && name_bytes > 0) { if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes); else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
 }

@@ -33,6 +33,7 @@ struct GemmPlan {
     bool vecA, vecB;      // 16-byte loads allowed for operand A / B
     bool fast;            // fast-path kernel (conv_fast.hip) instead of the generic one
     bool dma;             // pipelined direct-to-LDS kernel (conv_dma.hip)
+    bool halo = false;    // input-patch kernel (conv_halo.hip); implies dma
 };
 
 struct ConvArgs {
@@ -68,6 +69,12 @@ hipError_t dma_init();
 bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
 hipError_t dma_launch(const ConvArgs &a, hipStream_t st);
 void dma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
+
+// conv_halo.hip : input patch with halo resident in LDS (stride 1, 64 reduction channels per tap)
+hipError_t halo_init();
+bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
+hipError_t halo_launch(const ConvArgs &a, hipStream_t st);
+void halo_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
 
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
 hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,

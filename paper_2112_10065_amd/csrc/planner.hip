@@ -36,6 +36,9 @@ const Candidate kPix[] = {
     {222, 1, 1.10f, 4.5f},
     {224, 1, 1.10f, 4.5f},
     {223, 1, 1.90f, 5.0f},
+    {400, 2, 0.75f, 5.5f},   // input patch resident in LDS: 64 x 256 tile (64 reduction channels per tap, stride 1)
+    {401, 2, 1.20f, 6.0f},   // same, 128 x 256
+    {402, 2, 0.75f, 5.5f},
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},
@@ -62,6 +65,8 @@ const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64, 96, 
 
 bool family_plan(const ConvGeom &g, int pass, int code, int splits, GemmPlan *pl)
 {
+    pl->halo = false;
+    if (code >= 400) return halo_plan(g, pass, code, splits, pl);
     if (code >= 200) return dma_plan(g, pass, code, splits, pl);
     return fast_plan(g, pass, code, splits, pl);
 }

@@ -156,6 +156,39 @@ def test_pipelined_forward_variants(env, variant, splits):
         dp.dp_set_override(1, -1, 0)
 
 
+@pytest.mark.parametrize("variant", [400, 401, 402])
+def test_input_patch_variants(env, variant):
+    """Kernels that keep the input patch (with halo) of a 256-pixel tile in LDS: 64 reduction channels per
+    tap, stride 1; both tile shapes (8x32, 16x16), ragged image edges, several c_out / c_in tiles, 1xS filters."""
+    dp, U, orc = env
+    dp.dp_set_override(0, variant, 0)
+    dp.dp_set_override(1, variant, 0)
+    try:
+        # forward: c_in = 64
+        for tag, n, h, w, k, r, s_, pd in (("patch_a", 2, 13, 12, 96, 3, 3, (1, 1)), ("patch_b", 1, 37, 40, 64, 3, 3, (1, 1)),
+                                           ("patch_c", 2, 9, 33, 136, 1, 7, (0, 3)), ("patch_d", 3, 20, 70, 200, 3, 3, (0, 0))):
+            case = U.ConvCase(tag, n, h, w, 64, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "k_halo<0" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            y = case.run_fwd()
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd), f"{tag} variant {variant}")
+        # backward-data: c_out = 64
+        for tag, n, h, w, c, r, s_, pd in (("patchd_a", 2, 13, 12, 96, 3, 3, (1, 1)), ("patchd_b", 1, 37, 40, 64, 3, 3, (1, 1)),
+                                           ("patchd_c", 2, 9, 33, 136, 1, 7, (0, 3)), ("patchd_d", 3, 20, 70, 200, 3, 3, (0, 0))):
+            case = U.ConvCase(tag, n, h, w, c, 64, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "k_halo<1" in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+            y = case.run_fwd()
+            dx = case.run_dgrad(y)
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), pad=pd), f"{tag} variant {variant} dx")
+        # a patch that does not fit (5x5 filter) falls back to another kernel
+        case = U.ConvCase("patch_big", 1, 20, 20, 64, 64, 5, 5, (1, 1), (2, 2), bf16=True, bias=True, relu=True)
+        assert "k_halo" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+    finally:
+        dp.dp_set_override(0, -1, 0)
+        dp.dp_set_override(1, -1, 0)
+
+
 @pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307, 308, 309, 310, 311, 312, 313, 314, 315])
 @pytest.mark.parametrize("splits", [1, 3])
 def test_pipelined_backward_filter_variants(env, variant, splits):
