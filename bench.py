@@ -154,7 +154,11 @@ class Layer:
             dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.g, dx=self.dx, ws=ws, stream=stream)
 
     def wgrad(self, dp, d, ws, stream=None):
-        if self.is_conv:
+        if self.is_conv and not self.needs_dx:
+            # first layer: nothing else consumes the masked gradient, so the ReLU mask and the bias
+            # gradient ride along in the filter-gradient call (y_saved and dbias given)
+            dp.dp_conv2d_bwd_filter(d, self.x, self.dy, self.y, self.dw, self.db, ws, stream)
+        elif self.is_conv:
             dp.dp_conv2d_bwd_filter(d, self.x, self.g, None, self.dw, None, ws, stream)
         else:
             dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws, stream=stream)
@@ -167,9 +171,9 @@ class Layer:
 
     def passes(self):
         """(name, method, counts nominal flops) of the calls that make up this layer's share of a step."""
-        out = [("fwd", self.fwd, True), ("rgrad", self.rgrad, False)]
+        out = [("fwd", self.fwd, True)]
         if self.needs_dx:
-            out.append(("dgrad", self.dgrad, True))
+            out += [("rgrad", self.rgrad, False), ("dgrad", self.dgrad, True)]
         out.append(("wgrad", self.wgrad, True))
         return out
 
@@ -261,7 +265,8 @@ def main():
             for li, l in enumerate(reversed(layers)):
                 d = descs[(l.name, n)]
                 side, wss = side_streams[li % n_side], ws_side[li % n_side]
-                ops.append(("call", l.bound("rgrad", dp, d, ws, main)))
+                if l.needs_dx:
+                    ops.append(("call", l.bound("rgrad", dp, d, ws, main)))
                 ops.append(("fork", (torch.cuda.Event(), side)))
                 ops.append(("call", l.bound("wgrad", dp, d, wss, side)))
                 if l.needs_dx:
@@ -401,7 +406,7 @@ def main():
         "config": {"workload": {"vgg16": "VGG-16 13 conv + 3 FC layers, 224x224x3 input", "resnet50": "ResNet-50 conv layers (23 unique shapes), 224x224x3 input",
                                 "inception": "Inception-v3-style conv layers (18 shapes), 299x299x3 input"}[args.workload]
                                + ", per layer fwd + ReLU/bias-grad + dgrad + wgrad "
-                               "(no dgrad for the first layer), "
+                               "(first layer: no dgrad, ReLU/bias-grad fused into its wgrad call), "
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},

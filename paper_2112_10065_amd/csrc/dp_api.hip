@@ -309,7 +309,7 @@ size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
 {
     size_t need = 0;
     if (dtype == DP_BF16 && use_small_c(g, PASS_WGRAD) && small_c_direct(g)) {
-        need = round256(small_c_wgrad_partial_bytes(g)) + round256(ybytes(g));
+        need = round256(small_c_wgrad_partial_bytes(g));
         if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
         return need;
     }
@@ -346,19 +346,13 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
     }
     if (use_small_c(g, PASS_WGRAD) && small_c_direct(g)) {
         const size_t part = round256(small_c_wgrad_partial_bytes(g));
-        void *gbuf = (char *)ws + part;
-        float *rws = (float *)((char *)ws + part + round256(ybytes(g)));
-        const bf16_t *gsrc = (const bf16_t *)dy;
+        float *rws = (float *)((char *)ws + part);   // bias-gradient scratch of the db-only case
         bool db_done = false;
-        if (ym != nullptr && dw != nullptr) {
-            hipError_t e = rbg_launch(rows, g.K, true, dy, ym, gbuf, db, rws, st);
-            if (e != hipSuccess) return hip_fail(e, "ReLU/bias-gradient launch");
-            gsrc = (const bf16_t *)gbuf;
-            db_done = true;
-        }
         if (dw != nullptr) {
-            hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, gsrc, (float *)ws, dw, st);
+            // the kernel masks dy with the saved output while loading it and sums the bias gradient on the way
+            hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)ym, (float *)ws, dw, db, st);
             if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
+            db_done = true;
         }
         if (db != nullptr && !db_done) {
             hipError_t e = rbg_launch(rows, g.K, true, dy, ym, nullptr, db, rws, st);

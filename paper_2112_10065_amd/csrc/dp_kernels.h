@@ -105,4 +105,6 @@ hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x
                               hipStream_t st);
 int small_c_wgrad_blocks(const ConvGeom &g);   // pixel-range blocks, each writes one fp32 partial
 size_t small_c_wgrad_partial_bytes(const ConvGeom &g);
-hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *partial, float *dw, hipStream_t st);
+// ymask (saved output, may be NULL) masks dy on the fly; db (may be NULL) receives the bias gradient of the masked dy
+hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *ymask, float *partial, float *dw,
+                                float *db, hipStream_t st);

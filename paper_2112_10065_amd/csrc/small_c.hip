@@ -200,7 +200,8 @@ __global__ __launch_bounds__(256, 3) void k_fwd_direct(ConvGeom g, unsigned flag
 // reduction-contiguous: gT[64 c_out][64 + 8 pixels], xT[32 taps][64 + 8 pixels].  Wave w multiplies the
 // 16-pixel slice w of every step; the four waves' sums are added through LDS at the end.
 constexpr int WLS = 72;
-__global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *x, const bf16_t *dy, float *partial, int steps_per_block)
+__global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *x, const bf16_t *dy, const bf16_t *ym, float *partial,
+                                                      float *db_partial, int steps_per_block)
 {
     __shared__ __attribute__((aligned(16))) bf16_t gT[64 * WLS];
     __shared__ __attribute__((aligned(16))) bf16_t xT[32 * WLS];
@@ -219,19 +220,29 @@ __global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
-    u32x4 gv[2];
-    unsigned xv[8];
-    auto load = [&](int step) {
+    // two register sets: the loads of steps s+1 and s+2 are in flight while step s is multiplied
+    struct Regs { u32x4 gv[2], yv[2]; unsigned xv[8]; };
+    Regs ra, rb;
+    float dbacc[16];   // bias gradient: this thread's 16 channels over its pixels
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dbacc[e] = 0.f;
+    auto load = [&](int step, Regs &rg) {
         const int m = step * 64 + gp;
-        gv[0] = gv[1] = u32x4{0, 0, 0, 0};
+        rg.gv[0] = rg.gv[1] = u32x4{0, 0, 0, 0};
+        rg.yv[0] = rg.yv[1] = u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};   // "positive": keeps everything
         if (m < M) {
             const bf16_t *src = dy + (size_t)m * g.K + a0 + gc;
-            if (a0 + gc + 8 <= g.K) gv[0] = *reinterpret_cast<const u32x4 *>(src);
-            if (a0 + gc + 16 <= g.K) gv[1] = *reinterpret_cast<const u32x4 *>(src + 8);
+            if (a0 + gc + 8 <= g.K) rg.gv[0] = *reinterpret_cast<const u32x4 *>(src);
+            if (a0 + gc + 16 <= g.K) rg.gv[1] = *reinterpret_cast<const u32x4 *>(src + 8);
+            if (ym != nullptr) {   // ReLU gradient fused: the mask is applied when the registers go to LDS
+                const bf16_t *ys = ym + (size_t)m * g.K + a0 + gc;
+                if (a0 + gc + 8 <= g.K) rg.yv[0] = *reinterpret_cast<const u32x4 *>(ys);
+                if (a0 + gc + 16 <= g.K) rg.yv[1] = *reinterpret_cast<const u32x4 *>(ys + 8);
+            }
         }
         const int mx = step * 64 + xp;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) xv[e] = 0;
+        for (int e = 0; e < 8; ++e) rg.xv[e] = 0;
         if (mx < M) {
             const int n = mx / (g.Ho * g.Wo), rem = mx - n * (g.Ho * g.Wo), p = rem / g.Wo, q = rem - p * g.Wo;
             const int hb = p * g.sh - g.ph, wb = q * g.sw - g.pw;
@@ -240,32 +251,50 @@ __global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 if (xt + e < rsc) {
-                    xv[e] = im2col_elem(g, img, hb, wb, r, s, c);
+                    rg.xv[e] = im2col_elem(g, img, hb, wb, r, s, c);
                     if (++c == g.C) { c = 0; if (++s == g.S) { s = 0; ++r; } }
                 }
             }
         }
     };
-    if (sbeg < send) load(sbeg);
-    for (int step = sbeg; step < send; ++step) {
-        // registers -> LDS, transposed
+    auto stash = [&](Regs &rg) {   // registers -> LDS, transposed; mask and bias gradient on the way
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const unsigned wv[4] = {gv[h].x, gv[h].y, gv[h].z, gv[h].w};
+            const u32x4 mv = apply_mask(rg.gv[h], rg.yv[h]);
+            const unsigned wv[4] = {mv.x, mv.y, mv.z, mv.w};
 #pragma unroll
             for (int e = 0; e < 8; ++e) gT[(gc + h * 8 + e) * WLS + gp] = (bf16_t)((wv[e >> 1] >> ((e & 1) * 16)) & 0xffffu);
+            if (db_partial != nullptr) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dbacc[h * 8 + e] += __uint_as_float((e & 1) ? (wv[e >> 1] & 0xffff0000u) : (wv[e >> 1] << 16));
+            }
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) xT[(xt + e) * WLS + xp] = (bf16_t)xv[e];
-        __syncthreads();
-        if (step + 1 < send) load(step + 1);   // in flight during the matrix instructions
+        for (int e = 0; e < 8; ++e) xT[(xt + e) * WLS + xp] = (bf16_t)rg.xv[e];
+    };
+    auto multiply = [&]() {
         const bf16x8 b = *reinterpret_cast<const bf16x8 *>(xT + (lane & 31) * WLS + wave * 16 + 8 * (lane >> 5));
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const bf16x8 a = *reinterpret_cast<const bf16x8 *>(gT + (i * 32 + (lane & 31)) * WLS + wave * 16 + 8 * (lane >> 5));
             acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
         }
+    };
+    if (sbeg < send) load(sbeg, ra);
+    if (sbeg + 1 < send) load(sbeg + 1, rb);
+    for (int step = sbeg; step < send; step += 2) {
+        stash(ra);
         __syncthreads();
+        if (step + 2 < send) load(step + 2, ra);
+        multiply();
+        __syncthreads();
+        if (step + 1 < send) {
+            stash(rb);
+            __syncthreads();
+            if (step + 3 < send) load(step + 3, rb);
+            multiply();
+            __syncthreads();
+        }
     }
     // D element v of lane l: row 8*(v/4) + 4*(l/32) + v%4 (c_out), column l%32 (tap)
 #pragma unroll
@@ -278,13 +307,43 @@ __global__ __launch_bounds__(256) void k_wgrad_direct(ConvGeom g, const bf16_t *
         const int k = id >> 5, t = id & 31;
         out[id] = (red[0][k][t] + red[1][k][t]) + (red[2][k][t] + red[3][k][t]);
     }
+    if (db_partial != nullptr) {
+        // 64 threads (one per pixel slot) hold sums for the same 16 channels: add them in slot order
+        __syncthreads();
+        float *flat = &red[0][0][0];   // [64 pixel slots][64 channels]
+#pragma unroll
+        for (int e = 0; e < 16; ++e) flat[gp * 64 + gc + e] = dbacc[e];
+        __syncthreads();
+        if (tid < 64) {
+            float s = 0.f;
+            for (int slot = 0; slot < 64; ++slot) s += flat[slot * 64 + tid];
+            db_partial[((size_t)blockIdx.x * gridDim.y + blockIdx.y) * 64 + tid] = s;
+        }
+    }
 }
 
 // dw[k][t] = sum over blocks of partial[b][ktile][k % 64][t] in a fixed order; grid = c_out, 1024 threads:
 // thread (t, part) adds every 32nd block with four loads in flight, the 32 parts are then added in order
-__global__ __launch_bounds__(1024) void k_wgrad_direct_sum(int K, int rsc, int nblocks, int ktiles, const float *partial, float *dw)
+// blocks K .. K + ktiles - 1 (present when the bias gradient is wanted) add db_partial[b][ktile][64] the same way
+__global__ __launch_bounds__(1024) void k_wgrad_direct_sum(int K, int rsc, int nblocks, int ktiles, const float *partial, float *dw,
+                                                           const float *db_partial, float *db)
 {
     __shared__ float sm[32][33];
+    if ((int)blockIdx.x >= K) {
+        __shared__ float sd[16][64];
+        const int kt = blockIdx.x - K, ch = threadIdx.x & 63, part = threadIdx.x >> 6;   // 16 parts
+        float s = 0.f;
+        for (int b = part; b < nblocks; b += 16) s += db_partial[((size_t)b * ktiles + kt) * 64 + ch];
+        sd[part][ch] = s;
+        __syncthreads();
+        if (part == 0 && kt * 64 + ch < K) {
+            float tot = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) tot += sd[i][ch];
+            db[kt * 64 + ch] = tot;
+        }
+        return;
+    }
     const int k = blockIdx.x, t = threadIdx.x & 31, part = threadIdx.x >> 5;
     const size_t bstride = (size_t)ktiles * 64 * 32;
     const float *src = partial + ((size_t)(k >> 6) * 64 + (k & 63)) * 32 + t;
@@ -357,20 +416,23 @@ int small_c_wgrad_blocks(const ConvGeom &g)
     const long long spb = (steps + nb - 1) / nb;
     return (int)((steps + spb - 1) / spb);
 }
-size_t small_c_wgrad_partial_bytes(const ConvGeom &g)
+size_t small_c_wgrad_partial_bytes(const ConvGeom &g)   // filter-gradient partials, then bias-gradient partials
 {
-    return (size_t)small_c_wgrad_blocks(g) * ((g.K + 63) / 64) * 64 * 32 * sizeof(float);
+    return (size_t)small_c_wgrad_blocks(g) * ((g.K + 63) / 64) * 64 * (32 + 1) * sizeof(float);
 }
 
-hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *partial, float *dw, hipStream_t st)
+hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *ymask, float *partial, float *dw,
+                                float *db, hipStream_t st)
 {
     const long long steps = ((long long)g.N * g.Ho * g.Wo + 63) / 64;
     const int nb = small_c_wgrad_blocks(g), ktiles = (g.K + 63) / 64;
     const int spb = (int)((steps + nb - 1) / nb);
-    hipLaunchKernelGGL(k_wgrad_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, x, dy, partial, spb);
+    float *dbp = db != nullptr ? partial + (size_t)nb * ktiles * 64 * 32 : nullptr;
+    hipLaunchKernelGGL(k_wgrad_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, x, dy, ymask, partial, dbp, spb);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)g.K), dim3(1024), 0, st, g.K, g.R * g.S * g.C, nb, ktiles, partial, dw);
+    hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)(g.K + (db != nullptr ? ktiles : 0))), dim3(1024), 0, st, g.K, g.R * g.S * g.C, nb,
+                       ktiles, partial, dw, dbp, db);
     return hipGetLastError();
 }
 
