@@ -173,6 +173,11 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
     if (bf16 && (k % 8) == 0) {
         int chunks = k / 8;
         int cgb = chunks < NT ? chunks : NT;
+        // few rows, many columns (dense layers): narrower column groups give more blocks, each of which
+        // covers several rows per iteration instead of walking the rows one by one
+        int want_rpi = 1;
+        while (want_rpi < 32 && (long long)want_rpi * 4 < rows) want_rpi *= 2;
+        if (rows <= 128 && NT / want_rpi < cgb) cgb = NT / want_rpi;
         int rpi = NT / cgb;
         int col_blocks = (chunks + cgb - 1) / cgb;
         rb = row_blocks_for(rows, rpi, col_blocks);
