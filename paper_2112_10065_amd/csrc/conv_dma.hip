@@ -22,10 +22,13 @@ namespace {
 
 template <int FA, int FB, int TA, int TB, int NT>
 DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *stage, const float *bias_lds, int a0, int b0,
-                        int arow, int brow, int tid)
+                        int arow, int brow, int tid, bool writer = true)
 {
+    // `writer`: this wave holds finished sums (false for the extra reduction groups of a block, which only
+    // help with the copy-out below)
     constexpr int LSO = TA + 8;
     const int lane = tid & 63;
+    if (writer)
 #pragma unroll
     for (int i = 0; i < FA; ++i)
 #pragma unroll
@@ -58,27 +61,35 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
 // Tiles: A [TA][BK] (weights rows), B [TB][BK] (pixel rows), unpadded, chunk-swizzled:
 // CH = BK/8 chunks per row; chunk c of row `row` sits at position c ^ ((row / RPS) % CH), RPS = rows
 // per 256 bytes.  One direct-to-LDS instruction fills RPI = 64/CH consecutive rows.
-template <int TA, int TB, int BK, int WA, int WB, int NS>
-__global__ __launch_bounds__(64 * WA * WB) void k_fwd_dma(const KArgs p)
+// KG > 1: the block holds KG groups of WA*WB waves; group g runs the same pipeline on its own LDS stages
+// over the g-th part of the block's reduction range, and the groups' sums are added through LDS in group
+// order before the epilogue: a reduction split without partials in memory or a second kernel, for grids
+// too small to fill the chip with one tile per block.
+template <int TA, int TB, int BK, int WA, int WB, int NS, int KG = 1>
+__global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
 {
-    constexpr int NT = 64 * WA * WB, NW = WA * WB;
+    constexpr int NT = 64 * WA * WB * KG, NW = WA * WB;
     constexpr int CH = BK / 8, RPI = 64 / CH, RPS = 128 / BK, ROWB = BK * 2, KS = BK / 16;
     constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
     constexpr int A_BYTES = TA * ROWB, B_BYTES = TB * ROWB, STAGE = A_BYTES + B_BYTES;
     constexpr int IA = TA / RPI / NW, IB = TB / RPI / NW;   // direct-to-LDS instructions per wave and step
     static_assert(IA * NW * RPI == TA && IB * NW * RPI == TB, "tile rows must divide over the waves");
     static_assert(TB <= NT, "one thread per pixel row fills the row table");
-    constexpr int TILE_BYTES = NS * STAGE > TB * (TA + 8) * 2 ? NS * STAGE : TB * (TA + 8) * 2;  // stages / staged epilogue
+    constexpr int GSUM = (KG - 1) * NW * FA * FB * 16 * 64 * 4;   // accumulators of the extra groups on their way to group 0
+    constexpr int STAGES_ALL = KG * NS * STAGE > GSUM ? KG * NS * STAGE : GSUM;
+    constexpr int TILE_BYTES = STAGES_ALL > TB * (TA + 8) * 2 ? STAGES_ALL : TB * (TA + 8) * 2;  // stages / staged epilogue
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     unsigned *rowtab = reinterpret_cast<unsigned *>(smem + TILE_BYTES);   // [TB][2]
     float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // [TA]
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, grp = (tid >> 6) / NW, wave = (tid >> 6) % NW;
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
-    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
-    const int nsteps = kend - kbeg;
+    const int bbeg = blockIdx.y * p.steps_per_split, bend = min(bbeg + p.steps_per_split, p.steps_total);
+    // every group runs nsteps pipeline steps (same barrier count); steps past its range copy zeros
+    const int nsteps = (bend - bbeg + KG - 1) / KG;
+    const int kbeg = bbeg + grp * nsteps, live = max(0, min(bend - kbeg, nsteps));
     const int RSC = g.R * g.S * g.C;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
     __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2);
@@ -111,19 +122,22 @@ __global__ __launch_bounds__(64 * WA * WB) void k_fwd_dma(const KArgs p)
         voffB[q] = e.x + c * 16;
         maskB[q] = e.y;
     }
-    const unsigned smem_base = lds_offset(smem);
+    const unsigned smem_base = lds_offset(smem) + grp * NS * STAGE;   // this group's stages
     const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
 
     int kk = kbeg * BK;
     int tap = kk / g.C, c0 = kk - tap * g.C;
     int tr = tap / g.S, ts = tap - tr * g.S;
+    int issued = 0;
     auto issue = [&](int stage) {   // loads of the next not-yet-issued step into `stage`
+        const bool on = KG == 1 || issued < live;
+        ++issued;
         const unsigned ua = (unsigned)(tap * g.C + c0) * 2u;
         const unsigned ub = (unsigned)((tr * g.W + ts) * g.C + c0) * 2u;
-        const unsigned bit = 1u << tap;
+        const unsigned bit = on ? 1u << (tap & 31) : 0u;
         const unsigned sb = stage * STAGE;
 #pragma unroll
-        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, voffA[q] + ua);
+        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
 #pragma unroll
         for (int q = 0; q < IB; ++q) dma16(rx, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
         c0 += BK;
@@ -201,9 +215,32 @@ __global__ __launch_bounds__(64 * WA * WB) void k_fwd_dma(const KArgs p)
         }
     }
     __syncthreads();   // every wave is done reading the stages before they are reused for staging
+    if constexpr (KG > 1) {
+        // groups 1 .. KG-1 hand their sums to group 0 through LDS ([group][wave][register][lane]), added in group order
+        float *gs = reinterpret_cast<float *>(smem);
+        if (grp > 0) {
+#pragma unroll
+            for (int i = 0; i < FA; ++i)
+#pragma unroll
+                for (int j = 0; j < FB; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) gs[((((grp - 1) * NW + wave) * FA * FB + i * FB + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (grp == 0) {
+            for (int gq = 0; gq < KG - 1; ++gq)
+#pragma unroll
+                for (int i = 0; i < FA; ++i)
+#pragma unroll
+                    for (int j = 0; j < FB; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] += gs[(((gq * NW + wave) * FA * FB + i * FB + j) * 16 + v) * 64 + lane];
+        }
+        __syncthreads();   // the sums have been read before the staged epilogue overwrites them
+    }
     if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
-        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
-    else
+        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0);
+    else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
 }
 
@@ -394,10 +431,10 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
 // backward-data (stride 1, c_out % BK == 0) with the same pipeline: A = weights, reduction-major
 // [BK c_out rows][TA c_in] read through the LDS transpose read; B = dy pixel rows, K-major.
 // ---------------------------------------------------------------------------------------
-template <int TA, int TB, int BK, int WA, int WB, int NS>
-__global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
+template <int TA, int TB, int BK, int WA, int WB, int NS, int KG = 1>   // KG: reduction groups per block, as in k_fwd_dma
+__global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
 {
-    constexpr int NT = 64 * WA * WB, NW = WA * WB;
+    constexpr int NT = 64 * WA * WB * KG, NW = WA * WB;
     constexpr int CH = BK / 8, RPI = 64 / CH, RPS = 128 / BK, ROWB = BK * 2, KS = BK / 16;
     constexpr int FA = TA / WA / 32, FB = TB / WB / 32;
     constexpr int ROWA = TA * 2, RPIA = 512 / TA;
@@ -405,17 +442,20 @@ __global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
     constexpr int IA = BK / RPIA / NW, IB = TB / RPI / NW;
     static_assert(IA * NW * RPIA == BK && IB * NW * RPI == TB, "tile rows must divide over the waves");
     static_assert(TB <= NT, "one thread per pixel row fills the row table");
-    constexpr int TILE_BYTES = NS * STAGE > TB * (TA + 8) * 2 ? NS * STAGE : TB * (TA + 8) * 2;
+    constexpr int GSUM = (KG - 1) * NW * FA * FB * 16 * 64 * 4;
+    constexpr int STAGES_ALL = KG * NS * STAGE > GSUM ? KG * NS * STAGE : GSUM;
+    constexpr int TILE_BYTES = STAGES_ALL > TB * (TA + 8) * 2 ? STAGES_ALL : TB * (TA + 8) * 2;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     unsigned *rowtab = reinterpret_cast<unsigned *>(smem + TILE_BYTES);   // [TB][2]
     float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // unused (no bias in this pass)
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, grp = (tid >> 6) / NW, wave = (tid >> 6) % NW;
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
-    const int kbeg = blockIdx.y * p.steps_per_split, kend = min(kbeg + p.steps_per_split, p.steps_total);
-    const int nsteps = kend - kbeg;
+    const int bbeg = blockIdx.y * p.steps_per_split, bend = min(bbeg + p.steps_per_split, p.steps_total);
+    const int nsteps = (bend - bbeg + KG - 1) / KG;
+    const int kbeg = bbeg + grp * nsteps, live = max(0, min(bend - kbeg, nsteps));
     const int RSC = g.R * g.S * g.C;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
     __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
@@ -444,19 +484,22 @@ __global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
         voffB[q] = e.x + c * 16;
         maskB[q] = e.y;
     }
-    const unsigned smem_base = lds_offset(smem);
+    const unsigned smem_base = lds_offset(smem) + grp * NS * STAGE;   // this group's stages
     const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
 
     int kk = kbeg * BK;
     int tap = kk / g.K, c0 = kk - tap * g.K;
     int tr = tap / g.S, ts = tap - tr * g.S;
+    int issued = 0;
     auto issue = [&](int stage) {
+        const bool on = KG == 1 || issued < live;
+        ++issued;
         const unsigned ua = ((unsigned)c0 * RSC + (unsigned)tap * g.C) * 2u;
         const unsigned ub = (unsigned)(c0 - (tr * g.Wo + ts) * g.K) * 2u;
-        const unsigned bit = 1u << tap;
+        const unsigned bit = on ? 1u << (tap & 31) : 0u;
         const unsigned sb = stage * STAGE;
 #pragma unroll
-        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, voffA[q] + ua);
+        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
 #pragma unroll
         for (int q = 0; q < IB; ++q) dma16(rdy, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
         c0 += BK;
@@ -541,20 +584,43 @@ __global__ __launch_bounds__(64 * WA * WB) void k_dgrad_dma(const KArgs p)
         }
     }
     __syncthreads();
+    if constexpr (KG > 1) {
+        float *gs = reinterpret_cast<float *>(smem);
+        if (grp > 0) {
+#pragma unroll
+            for (int i = 0; i < FA; ++i)
+#pragma unroll
+                for (int j = 0; j < FB; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) gs[((((grp - 1) * NW + wave) * FA * FB + i * FB + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (grp == 0) {
+            for (int gq = 0; gq < KG - 1; ++gq)
+#pragma unroll
+                for (int i = 0; i < FA; ++i)
+#pragma unroll
+                    for (int j = 0; j < FB; ++j)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] += gs[(((gq * NW + wave) * FA * FB + i * FB + j) * 16 + v) * 64 + lane];
+        }
+        __syncthreads();
+    }
     if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
-        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
-    else
+        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0);
+    else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
 }
 
-struct DmaVariant { int TA, TB, BK, WA, WB, NS; };
+struct DmaVariant { int TA, TB, BK, WA, WB, NS, KG = 1; };
 const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {128, 128, 32, 2, 2, 3}, {128, 128, 32, 2, 2, 4},
                            {64, 128, 64, 2, 2, 2}, {64, 128, 32, 2, 2, 3}, {128, 64, 64, 2, 2, 2}, {64, 64, 64, 2, 2, 3},
                            {256, 256, 64, 2, 4, 2}, {256, 128, 64, 4, 2, 2}, {128, 256, 64, 2, 4, 2}, {256, 256, 64, 4, 2, 2},
                            {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}, {256, 256, 32, 2, 4, 4}, {256, 256, 32, 2, 4, 3},
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
-                           {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4}};
-constexpr int kNumDma = 26;
+                           {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
+                           {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2}};
+constexpr int kNumDma = 30;
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -584,6 +650,10 @@ KernelFn pick_dma_d(int v)
     case 23: return k_dgrad_dma<128, 128, 128, 2, 2, 2>;
     case 24: return k_dgrad_dma<128, 64, 128, 2, 2, 2>;
     case 25: return k_dgrad_dma<64, 64, 128, 2, 2, 4>;
+    case 26: return k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>;
+    case 27: return k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>;
+    case 28: return k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>;
+    case 29: return k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -615,6 +685,10 @@ KernelFn pick_dma(int v)
     case 23: return k_fwd_dma<128, 128, 128, 2, 2, 2>;
     case 24: return k_fwd_dma<128, 64, 128, 2, 2, 2>;
     case 25: return k_fwd_dma<64, 64, 128, 2, 2, 4>;
+    case 26: return k_fwd_dma<64, 64, 64, 2, 2, 2, 4>;
+    case 27: return k_fwd_dma<64, 64, 64, 2, 2, 2, 2>;
+    case 28: return k_fwd_dma<64, 128, 64, 2, 2, 2, 2>;
+    case 29: return k_fwd_dma<128, 64, 64, 2, 2, 2, 2>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -648,7 +722,9 @@ size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
-    size_t stages = (size_t)d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
+    size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
+    const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
+    if (gsum > stages) stages = gsum;
     return (stages > epi ? stages : epi) + (size_t)d.TB * 8 + (size_t)d.TA * 4;
 }
 
@@ -723,8 +799,9 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
 void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
-    snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", pass == PASS_WGRAD ? "k_wgrad_dma" : pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
-             d.WB, d.NS);
+    const char *kn = pass == PASS_WGRAD ? "k_wgrad_dma" : pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma";
+    if (d.KG > 1) snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", kn, d.TA, d.TB, d.BK, d.WA, d.WB, d.NS, d.KG);
+    else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", kn, d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
 }
 
 hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
@@ -740,7 +817,7 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     p.x = a.x; p.w = a.w; p.dy = a.dy; p.ymask = nullptr; p.bias = a.bias; p.out = a.out; p.partial = a.partial;
     const bool wg = a.pass == PASS_WGRAD;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
-    dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB, 1, 1);
+    dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB * d.KG, 1, 1);
     if (wg) grid = dim3((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1);
     hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
     hipError_t e = hipGetLastError();

@@ -17,6 +17,7 @@ struct Candidate {
     int bpc;         // blocks that fit on one CU (LDS / registers)
     float t_step;    // microseconds per reduction step and block on a fully shared CU
     float t0;        // microseconds of prologue + epilogue per block
+    int kg = 1;      // reduction groups inside a block: each group walks 1/kg of the block's steps
 };
 
 // forward / backward-data candidates
@@ -36,6 +37,10 @@ const Candidate kPix[] = {
     {222, 1, 1.10f, 4.5f},
     {224, 1, 1.10f, 4.5f},
     {223, 1, 1.90f, 5.0f},
+    {226, 1, 0.62f, 5.0f, 4},   // 64x64x64 with 4 / 2 reduction groups per block (no partials in memory)
+    {227, 2, 0.62f, 4.5f, 2},
+    {228, 1, 0.85f, 5.0f, 2},
+    {229, 1, 0.85f, 5.0f, 2},
     {400, 2, 0.75f, 5.5f},   // input patch resident in LDS: 64 x 256 tile (64 reduction channels per tap, stride 1)
     {401, 2, 1.20f, 6.0f},   // same, 128 x 256
     {402, 2, 0.75f, 5.5f},
@@ -87,7 +92,7 @@ double price(const ConvGeom &g, int pass, const Candidate &c, const GemmPlan &pl
     // a step of reduction length 32 costs about half of a 64 step for the pixel passes
     double t_step = c.t_step;
     if (pass != PASS_WGRAD && pl.BK == 32) t_step *= 0.6;
-    const double t_block = c.t0 + pl.steps_per_split * t_step * share;
+    const double t_block = c.t0 + (pl.steps_per_split + c.kg - 1) / c.kg * t_step * share;
     double t = 3.0 + waves * t_block;
     if (pl.splits > 1) {
         double out_elems = pass == PASS_FWD ? (double)g.N * g.Ho * g.Wo * g.K

@@ -124,7 +124,7 @@ def test_every_fast_variant_and_split(env, variant, splits):
             dp.dp_set_override(p, -1, 0)
 
 
-@pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211, 212, 213, 214, 215, 216, 217, 218, 219, 220, 221, 222, 223, 224, 225])
+@pytest.mark.parametrize("variant", [200, 201, 202, 203, 204, 205, 206, 207, 208, 209, 210, 211, 212, 213, 214, 215, 216, 217, 218, 219, 220, 221, 222, 223, 224, 225, 226, 227, 228, 229])
 @pytest.mark.parametrize("splits", [1, 2])
 def test_pipelined_forward_variants(env, variant, splits):
     """Forward and backward-data kernels with the multi-stage direct-to-LDS pipeline: every stage
@@ -136,7 +136,7 @@ def test_pipelined_forward_variants(env, variant, splits):
         for tag, n, h, w, c, k, r, s_, pd in (("pipe_a", 2, 13, 12, 64, 96, 3, 3, (1, 1)), ("pipe_b", 1, 9, 9, 128, 200, 1, 1, (0, 0)),
                                               ("pipe_c", 3, 10, 17, 64, 264, 1, 7, (0, 3)), ("pipe_d", 2, 12, 13, 192, 128, 3, 3, (1, 1)),
                                               ("pipe_e", 2, 11, 9, 256, 128, 3, 3, (1, 1))):
-            if variant >= 221 and c % 128 != 0:
+            if 221 <= variant <= 225 and c % 128 != 0:
                 continue   # these variants reduce 128 channels per step
             case = U.ConvCase(tag, n, h, w, c, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
             assert "fwd_dma" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
