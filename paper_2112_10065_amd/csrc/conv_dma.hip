@@ -799,9 +799,10 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
 void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
-    const char *kn = pass == PASS_WGRAD ? "k_wgrad_dma" : pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma";
-    if (d.KG > 1) snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", kn, d.TA, d.TB, d.BK, d.WA, d.WB, d.NS, d.KG);
-    else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d>", kn, d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
+    // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
+    if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
+    else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
+                  d.WB, d.NS, d.KG);
 }
 
 hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
