@@ -340,9 +340,20 @@ FULL = [("conv1_1", 224, 3, 64, 8, True), ("conv1_2", 224, 64, 64, 4, False), ("
         ("conv5_1", 14, 512, 512, 2, False), ("conv5_1", 14, 512, 512, 32, False)]
 
 
+@pytest.mark.parametrize("tuned", [False, True], ids=["model", "measured"])
 @pytest.mark.parametrize("name,hw,c,k,n,dxf", FULL, ids=[f"{f[0]}_n{f[4]}" for f in FULL])
-def test_vgg_layer_full_size_sampled(env, name, hw, c, k, n, dxf):
+def test_vgg_layer_full_size_sampled(env, name, hw, c, k, n, dxf, tuned):
+    """Full-size VGG-16 layers, sampled against the oracle's spot evaluation; `measured` is the kernel choice
+    bench.py times (the first call of each pass measures the candidates on these very buffers)."""
     dp, U, orc = env
+    dp.dp_set_autotune(tuned)
+    try:
+        _full_size_case(dp, U, orc, name, hw, c, k, n, dxf)
+    finally:
+        dp.dp_set_autotune(False)
+
+
+def _full_size_case(dp, U, orc, name, hw, c, k, n, dxf):
     case = U.ConvCase(f"vgg/{name}", n, hw, hw, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=dxf)
     y = case.run_fwd()
     dx = case.run_dgrad(y)
