@@ -428,7 +428,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
 }
 
 // ---------------------------------------------------------------------------------------
-// backward-data (stride 1, c_out % BK == 0) with the same pipeline: A = weights, reduction-major
+// backward-data (c_out % BK == 0; any stride) with the same pipeline: A = weights, reduction-major
 // [BK c_out rows][TA c_in] read through the LDS transpose read; B = dy pixel rows, K-major.
 // ---------------------------------------------------------------------------------------
 template <int TA, int TB, int BK, int WA, int WB, int NS, int KG = 1>   // KG: reduction groups per block, as in k_fwd_dma
@@ -463,9 +463,23 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     if (tid < TB) {
         const int m = b0 + tid;
         const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
-        const int hb = hh + g.ph, wb = ww + g.pw;   // the output pixel of tap (r,s) is (hb - r, wb - s)
-        rowtab[2 * tid] = (unsigned)(((n * g.Ho + hb) * g.Wo + wb) * g.K) * 2u;
-        rowtab[2 * tid + 1] = m < p.rowsB ? tap_mask(hb, wb, -1, g.R, g.S, g.Ho, g.Wo) : 0u;
+        // the output pixel of tap (r, s) is ((hb - r) / sh, (wb - s) / sw) when both divisions are exact; for such a tap
+        // (hb - r) / sh == hb / sh - r / sh, so the row base uses hb / sh and every tap adds a wave-uniform offset
+        const int hb = hh + g.ph, wb = ww + g.pw;
+        rowtab[2 * tid] = (unsigned)(((n * g.Ho + hb / g.sh) * g.Wo + wb / g.sw) * g.K) * 2u;
+        unsigned mask = 0;
+        if (m < p.rowsB) {
+            unsigned smask = 0;
+            for (int s = 0; s < g.S; ++s) {
+                const int d = wb - s;
+                if (d >= 0 && d % g.sw == 0 && d / g.sw < g.Wo) smask |= 1u << s;
+            }
+            for (int r = 0; r < g.R; ++r) {
+                const int d = hb - r;
+                if (d >= 0 && d % g.sh == 0 && d / g.sh < g.Ho) mask |= smask << (r * g.S);
+            }
+        }
+        rowtab[2 * tid + 1] = mask;
     }
     __syncthreads();
 
@@ -495,7 +509,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
         const bool on = KG == 1 || issued < live;
         ++issued;
         const unsigned ua = ((unsigned)c0 * RSC + (unsigned)tap * g.C) * 2u;
-        const unsigned ub = (unsigned)(c0 - (tr * g.Wo + ts) * g.K) * 2u;
+        const unsigned ub = (unsigned)(c0 - ((tr / g.sh) * g.Wo + ts / g.sw) * g.K) * 2u;
         const unsigned bit = on ? 1u << (tap & 31) : 0u;
         const unsigned sb = stage * STAGE;
 #pragma unroll
@@ -765,7 +779,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
     } else if (pass == PASS_DGRAD) {
         if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
         d = &kDma[force_variant - 200];
-        if (g.K % d->BK != 0 || g.C % 8 != 0 || g.sh != 1 || g.sw != 1) return false;
+        if (g.K % d->BK != 0 || g.C % 8 != 0) return false;   // any stride: taps that miss the stride grid are masked out
         pl->variant = force_variant - 200;
         rowsA = g.C; rowsB = g.N * g.H * g.W; red = g.R * g.S * g.K;
     } else if (pass == PASS_WGRAD) {

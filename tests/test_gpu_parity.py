@@ -156,6 +156,21 @@ def test_pipelined_forward_variants(env, variant, splits):
         dp.dp_set_override(1, -1, 0)
 
 
+@pytest.mark.parametrize("tag,n,h,w,c,k,r,s_,st,pd", [
+    ("sd_3x3_s2", 2, 15, 15, 64, 64, 3, 3, (2, 2), (1, 1)), ("sd_1x1_s2", 1, 14, 17, 128, 128, 1, 1, (2, 2), (0, 0)),
+    ("sd_3x3_s21", 2, 13, 12, 64, 192, 3, 3, (2, 1), (1, 0)), ("sd_5x5_s3", 1, 20, 20, 256, 128, 5, 5, (3, 3), (2, 2))])
+def test_strided_backward_data_pipelined(env, tag, n, h, w, c, k, r, s_, st, pd):
+    """Strided layers run backward-data on the pipelined kernel: taps that miss the stride grid of an input
+    pixel are masked out (zero rows), the rest address dy at (hb/sh - r/sh, wb/sw - s/sw)."""
+    dp, U, orc = env
+    case = U.ConvCase(tag, n, h, w, c, k, r, s_, st, pd, bf16=True, bias=False, relu=True)
+    assert "dgrad_dma" in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+    y = case.run_fwd()
+    dx = case.run_dgrad(y)
+    torch.cuda.synchronize()
+    U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), stride=st, pad=pd), f"{tag} dx")
+
+
 @pytest.mark.parametrize("variant", [400, 401, 402])
 def test_input_patch_variants(env, variant):
     """Kernels that keep the input patch (with halo) of a 256-pixel tile in LDS: 64 reduction channels per
