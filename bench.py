@@ -371,15 +371,17 @@ def main():
         fl = sum(l.step_flops(n) for l in layers)
         per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us}
 
-    # dominant kernel: the conv kernel instantiation with the largest total time among the calls at the
-    # largest batch of the sweep that are a single launch (no split reduction, no separate bias-gradient
-    # kernel); its figures below are over exactly those launches, each of which processes nmax samples
+    # dominant kernel: the conv kernel instantiation with the largest total time among the forward calls at
+    # the largest batch of the sweep that are a single launch (no split reduction); its figures below are
+    # over exactly those launches, each of which processes nmax samples.  (Forward only: the forward and
+    # backward-data instantiations of one tile shape take nearly the same time, and which of the two came
+    # out on top used to change from run to run.)
     groups = {}
     for l in layers:
         if not l.is_conv:
             continue
         for n in (nmax,):
-            for pi, pname in enumerate(("fwd", "dgrad")):
+            for pi, pname in enumerate(("fwd",)):
                 kname, splits = dp.dp_conv2d_kernel_info(descs[(l.name, n)], pi)
                 if splits != 1 or (l.name, n, pname) not in per:
                     continue
