@@ -179,6 +179,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
         const int younger = min(NS - 1, nsteps - 1);
         if (NS >= 2 && younger == NS - 1) wait_vmcnt<(NS - 1) * LPS>();
         else if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS >= 3 ? NS - 2 : 0) * LPS>();
+        else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
         else wait_vmcnt<0>();
     }
     __syncthreads();   // also publishes bias_lds
@@ -197,6 +198,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
                 if (i + 1 < nsteps) {
                     const int younger = min(i + NS - 1, nsteps - 1) - (i + 1);
                     if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
+                    else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
                     else wait_vmcnt<0>();
                     __builtin_amdgcn_s_barrier();
                     if (i + NS < nsteps) issueA(i % NS, i + NS);
@@ -251,8 +253,8 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
 }
 
 struct HaloVariant { int TA, WA, WB, NS; };
-const HaloVariant kHalo[] = {{64, 1, 4, 2}, {128, 2, 2, 2}, {64, 1, 4, 3}};
-constexpr int kNumHalo = 3;
+const HaloVariant kHalo[] = {{64, 1, 4, 2}, {128, 2, 2, 2}, {64, 1, 4, 3}, {64, 1, 4, 4}};
+constexpr int kNumHalo = 4;
 typedef void (*HaloFn)(const KArgs, int, int, int);
 HaloFn pick_halo(int pass, int v)
 {
@@ -260,12 +262,14 @@ HaloFn pick_halo(int pass, int v)
         switch (v) {
         case 1: return k_halo<PASS_FWD, 128, 2, 2, 2>;
         case 2: return k_halo<PASS_FWD, 64, 1, 4, 3>;
+        case 3: return k_halo<PASS_FWD, 64, 1, 4, 4>;
         default: return k_halo<PASS_FWD, 64, 1, 4, 2>;
         }
     }
     switch (v) {
     case 1: return k_halo<PASS_DGRAD, 128, 2, 2, 2>;
     case 2: return k_halo<PASS_DGRAD, 64, 1, 4, 3>;
+    case 3: return k_halo<PASS_DGRAD, 64, 1, 4, 4>;
     default: return k_halo<PASS_DGRAD, 64, 1, 4, 2>;
     }
 }

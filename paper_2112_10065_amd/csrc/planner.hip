@@ -44,6 +44,7 @@ const Candidate kPix[] = {
     {400, 2, 0.75f, 5.5f},   // input patch resident in LDS: 64 x 256 tile (64 reduction channels per tap, stride 1)
     {401, 2, 1.20f, 6.0f},   // same, 128 x 256
     {402, 2, 0.75f, 5.5f},
+    {403, 2, 0.72f, 5.5f},
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},

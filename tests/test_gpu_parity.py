@@ -171,7 +171,7 @@ def test_strided_backward_data_pipelined(env, tag, n, h, w, c, k, r, s_, st, pd)
     U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), stride=st, pad=pd), f"{tag} dx")
 
 
-@pytest.mark.parametrize("variant", [400, 401, 402])
+@pytest.mark.parametrize("variant", [400, 401, 402, 403])
 def test_input_patch_variants(env, variant):
     """Kernels that keep the input patch (with halo) of a 256-pixel tile in LDS: 64 reduction channels per
     tap, stride 1; both tile shapes (8x32, 16x16), ragged image edges, several c_out / c_in tiles, 1xS filters."""
