@@ -53,7 +53,9 @@ typedef enum { DP_F32 = 0, DP_BF16 = 1 } dp_dtype;
 enum {
     DP_BIAS = 1u,          /* forward adds bias[c_out] */
     DP_RELU = 2u,          /* forward applies max(.,0) after the bias */
-    DP_DETERMINISTIC = 4u, /* accepted; results are always deterministic */
+    DP_DETERMINISTIC = 4u, /* results are bitwise reproducible for a given kernel choice in any case (ordered
+                              reductions, no float atomics); this flag also keeps the call on the analytic kernel
+                              choice when dp_set_autotune is on, so that the choice cannot differ between processes */
     DP_DX_F32 = 8u         /* bf16 path only: dx is written as fp32 instead of bf16 */
 };
 

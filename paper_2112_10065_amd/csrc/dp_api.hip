@@ -17,6 +17,7 @@ thread_local char g_err[512] = "";
 std::atomic<int> g_force_variant[3] = {{-1}, {-1}, {-1}};
 std::atomic<int> g_force_splits[3] = {{0}, {0}, {0}};
 std::atomic<int> g_autotune{0};
+thread_local bool g_analytic_only = false;   // the descriptor of the running call asks for DP_DETERMINISTIC
 std::once_flag g_init_once;
 hipError_t g_init_err = hipSuccess;
 
@@ -49,6 +50,7 @@ dp_status check_conv(const dp_conv_desc *d, ConvGeom *g)
         d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
         return fail(DP_ERR_BAD_DESC, "sizes must be positive and pads non-negative");
     if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return fail(DP_ERR_BAD_DESC, "filter larger than padded input: empty output");
+    g_analytic_only = (d->flags & DP_DETERMINISTIC) != 0;
     g->N = d->n; g->H = d->h; g->W = d->w; g->C = d->c_in; g->K = d->c_out; g->R = d->r; g->S = d->s;
     g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
     g->Ho = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
@@ -69,6 +71,7 @@ dp_status check_linear(const dp_linear_desc *d, ConvGeom *g)
     if ((long long)d->in_features * d->out_features > kMaxElems || (long long)d->n * d->in_features > kMaxElems ||
         (long long)d->n * d->out_features > kMaxElems)
         return fail(DP_ERR_BAD_DESC, "a tensor has 2^31 or more elements");
+    g_analytic_only = (d->flags & DP_DETERMINISTIC) != 0;
     // a dense layer is a 1x1 convolution on a 1x1 image
     *g = ConvGeom{d->n, 1, 1, d->in_features, d->out_features, 1, 1, 1, 1, 0, 0, 1, 1};
     return DP_OK;
@@ -125,7 +128,8 @@ constexpr int kTuneCandidates = 12;
 PlanEntry &plan_entry(const ConvGeom &g, int pass)
 {
     thread_local std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> cache;
-    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load(), at = g_autotune.load();
+    const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
+    const int at = g_analytic_only ? 0 : g_autotune.load();
     PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at}};
     auto it = cache.find(key);
     if (it != cache.end()) return it->second;

@@ -286,6 +286,11 @@ def test_measured_kernel_choice(env):
                 if rep == 0:
                     first = info
                 assert info == first
+        # DP_DETERMINISTIC keeps a call on the analytic choice even while the measured choice is on
+        d_det = dp.conv_desc(2, 28, 28, 64, 128, 3, 3, (1, 1), (1, 1), dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU | dp.DP_DETERMINISTIC)
+        while_on = [dp.dp_conv2d_kernel_info(d_det, p) for p in range(3)]
+        dp.dp_set_autotune(False)
+        assert while_on == [dp.dp_conv2d_kernel_info(d_det, p) for p in range(3)]
     finally:
         dp.dp_set_autotune(False)
 
