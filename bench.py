@@ -2,15 +2,16 @@
 """Benchmark: VGG-16 per-layer training compute (conv + FC, forward and backward) at the
 strong-scaling per-GPU batches 1..32 on one MI355X.
 
-A step = one pass of the whole hot path: for every per-GPU batch N in {1,2,4,8,16,32} and
-every one of the 16 compute layers: forward (bias+ReLU fused), ReLU-gradient + bias-gradient
-(one pointwise pass that yields the masked upstream gradient), backward-data, backward-filter.
-The first layer's backward-data is not part of the step (a training step never needs the
-gradient of the input image); it is timed separately for the per-layer table.  Inputs are seeded synthetic tensors already
-resident in HBM.  value = nominal flops of the step / time (TFLOP/s); nominal flops per
-pass = 2*N*Ho*Wo*K*R*S*C (padding taps counted), three passes per layer.
+A step = one pass of the whole hot path: for every per-GPU batch N in {1,2,4,8,16,32}: forward
+through the 16 compute layers (bias+ReLU fused), then backward from the last layer: per layer the
+ReLU-gradient + bias-gradient (one pointwise pass that yields the masked upstream gradient),
+backward-filter (on a side stream) and backward-data.  The first layer needs no backward-data (a
+training step never uses the gradient of the input image), so its ReLU mask and bias gradient ride
+along in its backward-filter call.  Inputs are seeded synthetic tensors already resident in HBM.
+value = nominal flops of the step / time (TFLOP/s); nominal flops per pass =
+2*N*Ho*Wo*K*R*S*C (padding taps counted), three passes per layer (two for the first).
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value (TFLOP/s), ms_per_step, per_batch, roofline, cpu_baseline.
 """
 import argparse
 import json
@@ -97,7 +98,7 @@ class Layer:
             self.w = (torch.randn((l.k, l.r, l.s, l.c), generator=gen, device=dev) * (2.0 / fan_in) ** 0.5).to(bf)
             self.dy = torch.randn((nmax, self.ho, self.wo, l.k), generator=gen, device=dev, dtype=torch.float32).to(bf)
             self.y = torch.empty((nmax, self.ho, self.wo, l.k), device=dev, dtype=bf)
-            self.dx_f32 = l.c < 8   # first layer: input gradient kept in fp32
+            self.dx_f32 = l.c < 8   # first layer: input gradient kept in fp32 (bf16 cannot resolve it to the parity tolerance; a training step never needs it)
             self.dx = torch.empty((nmax, l.h, l.w, l.c), device=dev, dtype=torch.float32 if self.dx_f32 else bf)
             self.dw = torch.empty((l.k, l.r, l.s, l.c), device=dev, dtype=torch.float32)
             self.k = l.k
