@@ -252,6 +252,137 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Backward-filter with the input patch in LDS (stride 1, 64 input channels, up to 16 taps).
+// The tiled kernel copies, for every 64 pixels of reduction, the x rows of each tap again; here a
+// block copies the x patch of a 256-pixel tile once, next to the tile's 256 x 64 slice of dy, and
+// wave t accumulates tap t: dW[k][t][c] += sum over the tile's pixels of dy[pixel][k] * x[pixel + tap t][c]
+// (64 c_out x 64 c_in per wave = 4 matrix tiles).  Both operands are pixel-major in LDS (rows of 128
+// bytes, 64-byte segment swizzle by (row/2)&1) and read with the LDS transpose read.  Blocks are
+// persistent: they walk tiles blockIdx.x, +gridDim.x, ... with the next tile's copies in flight
+// (two LDS buffers), keep their sums in registers, and write ONE fp32 partial per block, which the
+// split-reduce kernel adds in block order.  grid = (blocks, 64-row tiles of c_out).
+// ---------------------------------------------------------------------------------------
+constexpr int WH_BUF = HALO_PP * 128 + HALO_TB * 128;   // patch + dy slice of one tile: 76 KiB
+
+__global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nwaves = blockDim.x >> 6;   // wave = tap
+    const int R = g.R, S = g.S, TW = 1 << tws, TH = HALO_TB >> tws, PW = TW + S - 1, PP = (TH + R - 1) * PW;
+    const int a0 = blockIdx.y * 64;
+    const unsigned smem_base = lds_offset(smem);
+    __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+    __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2);
+    constexpr int NPI = HALO_PP / 8, NDI = HALO_TB / 8;   // copies (8 rows each) of the patch / of the dy slice
+
+    auto issue_tile = [&](int tile, int buf) {
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        const int p0 = ty * TH, q0 = tx * TW;
+        const unsigned base = smem_base + buf * WH_BUF;
+        for (int ii = wave; ii < NPI + NDI; ii += nwaves) {
+            unsigned voff = OOR;
+            if (ii < NPI) {   // patch rows 8*ii .. +7
+                const int pp = ii * 8 + (lane >> 3), c = (lane & 7) ^ (seg_swz<64>(pp) << 2);
+                const int pr = pp / PW, pc = pp - pr * PW, ih = p0 - g.ph + pr, iw = q0 - g.pw + pc;
+                if (pp < PP && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W)
+                    voff = (unsigned)(((n * g.H + ih) * g.W + iw) * 64 + c * 8) * 2u;
+                dma16(rx, base + ii * 1024, voff);
+            } else {          // dy rows (tile pixels) 8*d .. +7, c_out a0 .. a0+63
+                const int d = ii - NPI, j = d * 8 + (lane >> 3), c = (lane & 7) ^ (seg_swz<64>(j) << 2);
+                const int pr = p0 + (j >> tws), qc = q0 + (j & (TW - 1));
+                if (pr < g.Ho && qc < g.Wo && a0 + c * 8 + 8 <= g.K)
+                    voff = (unsigned)(((n * g.Ho + pr) * g.Wo + qc) * g.K + a0 + c * 8) * 2u;
+                dma16(rdy, base + HALO_PP * 128 + d * 1024, voff);
+            }
+        }
+    };
+
+    f32x16 acc[2][2];   // [c_out half][c_in half]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // transpose-read lane roles: reduction row tl (+4 for the second read), operand columns cl .. cl+3
+    const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+    const int tr = wave / S, ts = wave - tr * S;        // this wave's tap
+    const int tapoff = tr * PW + ts;
+    unsigned a_lane[2];   // dy: row tl of slice 0, column half i; later slices add 16 rows = 2048 bytes
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int col = i * 32 + cl;
+        a_lane[i] = HALO_PP * 128 + tl * 128 + ((((col >> 5) ^ seg_swz<64>(tl)) << 6) | ((col & 31) << 1));
+    }
+
+    int tile = blockIdx.x;
+    if (tile < tiles) issue_tile(tile, 0);
+    for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();   // tile `it` has landed everywhere; the other buffer is no longer read
+        if (tile + (int)gridDim.x < tiles) issue_tile(tile + gridDim.x, (it + 1) & 1);
+        const unsigned base = smem_base + (it & 1) * WH_BUF;
+        // fragments are double-buffered in registers: the transpose reads of slice sl+1 are issued before the
+        // matrix instructions of slice sl
+        u32x2 alo[2][2], ahi[2][2], blo[2][2], bhi[2][2];
+        auto read_slice = [&](int sl, int buf) {
+            const int j = sl * 16 + tl;
+            const int pp = (j >> tws) * PW + (j & (TW - 1)) + tapoff;
+            const unsigned brow = base + pp * 128, bsw = seg_swz<64>(pp);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                alo[buf][i] = lds_read_tr<0>(base + a_lane[i] + sl * 2048);
+                ahi[buf][i] = lds_read_tr<4 * 128>(base + a_lane[i] + sl * 2048);
+            }
+#pragma unroll
+            for (int jf = 0; jf < 2; ++jf) {
+                const int col = jf * 32 + cl;
+                const unsigned addr = brow + ((((col >> 5) ^ bsw) << 6) | ((col & 31) << 1));
+                blo[buf][jf] = lds_read_tr<0>(addr);
+                bhi[buf][jf] = lds_read_tr<4 * 128>(addr);
+            }
+        };
+        auto multiply = [&](int buf, bool newer_in_flight) {
+            if (newer_in_flight) asm volatile("s_waitcnt lgkmcnt(8)");
+            else asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                asm volatile("" : "+v"(alo[buf][i])); asm volatile("" : "+v"(ahi[buf][i]));
+                asm volatile("" : "+v"(blo[buf][i])); asm volatile("" : "+v"(bhi[buf][i]));
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int jf = 0; jf < 2; ++jf) {
+                    const u32x4 av = {alo[buf][i].x, alo[buf][i].y, ahi[buf][i].x, ahi[buf][i].y};
+                    const u32x4 bv = {blo[buf][jf].x, blo[buf][jf].y, bhi[buf][jf].x, bhi[buf][jf].y};
+                    acc[i][jf] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv), acc[i][jf], 0, 0, 0);
+                }
+        };
+        read_slice(0, 0);
+        for (int sl = 0; sl < HALO_TB / 16; sl += 2) {
+            read_slice(sl + 1, 1);
+            multiply(0, true);
+            if (sl + 2 < HALO_TB / 16) read_slice(sl + 2, 0);
+            multiply(1, sl + 2 < HALO_TB / 16);
+        }
+    }
+    // partial[block][c_out][tap][c_in]; accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
+    float *out = p.partial + (size_t)blockIdx.x * p.rowsA * p.rowsB;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int jf = 0; jf < 2; ++jf)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = a0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                if (k < p.rowsA) out[(size_t)k * p.rowsB + wave * 64 + jf * 32 + (lane & 31)] = acc[i][jf][v];
+            }
+}
+
 struct HaloVariant { int TA, WA, WB, NS; };
 const HaloVariant kHalo[] = {{64, 1, 4, 2}, {128, 2, 2, 2}, {64, 1, 4, 3}, {64, 1, 4, 4}};
 constexpr int kNumHalo = 4;
@@ -291,6 +422,10 @@ int halo_tws(int oh, int ow)
 
 hipError_t halo_init()
 {
+    {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_wgrad_halo), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WH_BUF);
+        if (e != hipSuccess) return e;
+    }
     for (int pass = 0; pass < 2; ++pass)
         for (int v = 0; v < kNumHalo; ++v) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_halo(pass, v)), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -303,6 +438,24 @@ hipError_t halo_init()
 // variant override 400 + v; forward needs c_in == 64, backward-data c_out == 64; stride 1; no reduction split
 bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *pl)
 {
+    if (pass == PASS_WGRAD) {   // 410: input-patch filter gradient; force_splits = number of persistent blocks
+        if (force_variant != 410 || g.sh != 1 || g.sw != 1 || g.C != 64 || (g.K % 8) != 0 || g.R * g.S > 16) return false;
+        const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
+        if ((th + g.R - 1) * (tw + g.S - 1) > HALO_PP) return false;
+        const long long tiles = (long long)g.N * ((g.Ho + th - 1) / th) * ((g.Wo + tw - 1) / tw);
+        const int ktiles = (g.K + 63) / 64;
+        int blocks = force_splits > 1 ? force_splits : 256 / ktiles;   // default: one persistent block per CU
+        if (blocks > tiles) blocks = (int)tiles;
+        if (blocks < 2) return false;   // the split-reduce kernel writes the result
+        pl->variant = 10;
+        pl->fast = true; pl->dma = true; pl->halo = true;
+        pl->TA = 64; pl->TB = 64 * g.R * g.S; pl->BK = 16; pl->vecA = pl->vecB = true;
+        pl->tilesA = ktiles; pl->tilesB = 1;
+        pl->steps_total = (int)tiles * (HALO_TB / 16);
+        pl->steps_per_split = (int)((tiles + blocks - 1) / blocks) * (HALO_TB / 16);
+        pl->splits = blocks;
+        return true;
+    }
     if (force_variant < 400 || force_variant >= 400 + kNumHalo || force_splits > 1) return false;
     if (pass != PASS_FWD && pass != PASS_DGRAD) return false;
     if (g.sh != 1 || g.sw != 1 || g.R * g.S > 32) return false;
@@ -325,6 +478,7 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
 
 void halo_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
+    if (pass == PASS_WGRAD) { snprintf(name, name_bytes, "k_wgrad_halo"); return; }
     const HaloVariant &h = kHalo[pl.variant];
     snprintf(name, name_bytes, "k_halo<%d, %d, %d, %d, %d>", pass, h.TA, h.WA, h.WB, h.NS);
 }
@@ -333,6 +487,20 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
 {
     KArgs p;
     p.g = a.g;
+    if (a.pass == PASS_WGRAD) {
+        const ConvGeom &g = a.g;
+        p.rowsA = g.K; p.rowsB = g.R * g.S * g.C; p.red = g.N * g.Ho * g.Wo;
+        p.tilesA = a.plan.tilesA; p.tilesB = 1; p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split;
+        p.splits = a.plan.splits; p.flags = a.flags;
+        p.x = a.x; p.w = nullptr; p.dy = a.dy; p.ymask = nullptr; p.bias = nullptr; p.out = a.out; p.partial = a.partial;
+        const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
+        const int tiles_x = (g.Wo + tw - 1) / tw, tiles_y = (g.Ho + th - 1) / th;
+        hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * g.R * g.S), 2 * WH_BUF, st, p, tws,
+                           tiles_x, tiles_y, g.N * tiles_x * tiles_y);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return launch_split_reduce(a, p.rowsA, p.rowsB, st);
+    }
     const bool fwd = a.pass == PASS_FWD;
     p.rowsA = fwd ? a.g.K : a.g.C;
     p.rowsB = fwd ? a.g.N * a.g.Ho * a.g.Wo : a.g.N * a.g.H * a.g.W;

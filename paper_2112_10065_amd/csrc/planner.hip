@@ -62,6 +62,7 @@ const Candidate kWg[] = {
     {307, 2, 1.60f, 5.0f},   // 256x128x32, 8 waves
     {314, 2, 1.65f, 5.0f},   // 128x256x32, 8 waves
     {312, 1, 2.90f, 7.0f},   // 256x256x64, 8 waves
+    {410, 1, 0.13f, 6.0f},   // input patch in LDS, persistent blocks (64 input channels, stride 1); a step = 16 pixels
     {100, 3, 1.30f, 4.0f},
     {101, 3, 1.00f, 3.5f},
     {102, 3, 1.00f, 3.5f},

@@ -171,6 +171,27 @@ def test_strided_backward_data_pipelined(env, tag, n, h, w, c, k, r, s_, st, pd)
     U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), stride=st, pad=pd), f"{tag} dx")
 
 
+@pytest.mark.parametrize("blocks", [0, 3, 40])
+def test_input_patch_filter_gradient(env, blocks):
+    """Filter gradient with the input patch in LDS and persistent blocks (64 input channels, stride 1): both
+    tile shapes, ragged edges, c_out below / above one 64-row tile, 1xS filters, more blocks than tiles."""
+    dp, U, orc = env
+    dp.dp_set_override(2, 410, blocks)
+    try:
+        for tag, n, h, w, k, r, s_, pd in (("patchw_a", 2, 13, 12, 96, 3, 3, (1, 1)), ("patchw_b", 1, 37, 40, 64, 3, 3, (1, 1)),
+                                           ("patchw_c", 2, 9, 33, 136, 1, 7, (0, 3)), ("patchw_d", 3, 20, 70, 40, 3, 3, (0, 0))):
+            case = U.ConvCase(tag, n, h, w, 64, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "k_wgrad_halo" in dp.dp_conv2d_kernel_info(case.desc, 2)[0]
+            y = case.run_fwd()
+            dw, db = case.run_wgrad(y)
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=U.to_np(y), pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} blocks {blocks} dw")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} blocks {blocks} db")
+    finally:
+        dp.dp_set_override(2, -1, 0)
+
+
 @pytest.mark.parametrize("variant", [400, 401, 402, 403])
 def test_input_patch_variants(env, variant):
     """Kernels that keep the input patch (with halo) of a 256-pixel tile in LDS: 64 reduction channels per
