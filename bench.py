@@ -29,18 +29,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 123685311,
-    "k_dgrad_dma<256, 256, 64, 2, 4, 2, 1>": 147902895,
-    "k_halo<0, 64, 1, 4, 3>": 206879037,
-    "k_halo<1, 64, 1, 4, 2>": 412274600,
-    "k_fwd_direct": 226674121,
-    "k_dgrad_dma<128, 128, 64, 2, 2, 2, 1>": 163619044,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>": 78997901,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 213573408,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>": 51863027,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>": 25736136,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>": 38688617,
-    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>": 10963676
+    "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 124770100,
+    "k_halo<0, 64, 1, 4, 4>": 412037494,
+    "k_fwd_direct": 226676163,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 187893931,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>": 51863996,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>": 11448657
 }
 
 
