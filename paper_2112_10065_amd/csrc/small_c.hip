@@ -3,16 +3,17 @@
 // of 8, so no 16-byte load is aligned.  These layers are bound by the output activation traffic,
 // not by the matrix cores; the cheapest correct way to put them on the fast kernels is an explicit
 // im2col of x into [pixels][Kpad] (Kpad = R*S*C rounded up to 32, zero filled) and zero-padded weights
-// [K][Kpad]: forward and backward-filter then are 1x1 convolutions with Kpad input channels.
-// The im2col buffer is R*S*C/ C * ... small next to the output (Kpad*2 bytes per pixel against K*2).
+// [K][Kpad]: forward and backward-filter then are 1x1 convolutions with Kpad input channels
+// (the im2col matrix costs Kpad*2 bytes per output pixel next to the output's K*2).
 //
 // When the whole reduction fits one 32-wide slice pair (R*S*C <= 32: the 3x3 RGB stems) the im2col
-// matrix never goes to memory: k_fwd_direct builds the 256 x 32 tile of a block in LDS (one thread per
-// output pixel), multiplies it with weight fragments that stay in registers, and stores the output
-// tile through LDS with 16-byte rows; k_wgrad_direct does the same for the filter gradient with both
-// operands transposed on their way into LDS, one fp32 partial per block, and k_wgrad_direct_sum adds
-// the partials in block order.  Both passes then move little more than the output activation /
-// the upstream gradient once, which is what bounds these layers.
+// matrix never goes to memory: k_fwd_direct copies the input patch of an 8 x 32 pixel tile into LDS,
+// gathers the 256 x 32 im2col tile from it (one thread per output pixel), multiplies it with weight
+// fragments that stay in registers, and stores the output tile through LDS with 16-byte rows;
+// k_wgrad_direct does the same for the filter gradient with both operands transposed on their way into
+// LDS (and, when asked, the ReLU mask applied and the bias gradient summed on the way), one fp32 partial
+// per block, and k_wgrad_direct_sum adds the partials in block order.  Both passes then move little more
+// than the output activation / the upstream gradient once, which is what bounds these layers.
 #include "tile_common.h"
 
 namespace {
