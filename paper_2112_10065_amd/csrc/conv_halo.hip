@@ -7,7 +7,7 @@
 // Only the weight tile of each tap still streams through the NS-stage pipeline.
 //
 // Patch layout: pixel pp = pr*(TW+S-1) + pc occupies 128 bytes; its 16-byte channel chunk c sits at
-// chunk position c ^ (pp & 7), which makes the fragment reads of 32 consecutive pixels conflict-free.
+// chunk position c ^ ((pp >> 1) & 7) (two 128-byte rows span the 64 banks), which makes the fragment reads of 32 consecutive pixels conflict-free.
 // A direct-to-LDS instruction fills 8 consecutive patch pixels.
 #include "dma_common.h"
 #include <cstdio>
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
     // ---- patch: all copies issued up front -------------------------------------------------
 #pragma unroll
     for (int q = 0; q < IP; ++q) {
-        const int id = (wave * IP + q) * 64 + lane, pp = id >> 3, c = (id & 7) ^ (pp & 7);
+        const int id = (wave * IP + q) * 64 + lane, pp = id >> 3, c = (id & 7) ^ ((pp >> 1) & 7);
         const int pr = pp / PW, pc = pp - pr * PW, ih = h0 + pr, iw = w0 + pc;
         const bool ok = pp < PP && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
         const unsigned voff = ok ? (unsigned)(((n * IH + ih) * IW + iw) * 64 + c * 8) * 2u : OOR;
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
         for (int j = 0; j < FB; ++j) {
             const int pp = pp0[j] + off;
             brow_addr[j] = smem_base + pp * 128;
-            bsw[j] = pp & 7;
+            bsw[j] = (pp >> 1) & 7;
         }
     };
     auto read_slice = [&](int ks, int buf, unsigned sb) {
@@ -383,6 +383,245 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
             }
 }
 
+// ---------------------------------------------------------------------------------------
+// 3x3 (nine-tap) forward / backward-data with 64 reduction channels per tap, weights stationary in
+// REGISTERS.  A block has four waves, one per SIMD, so each may use the whole register file: a wave
+// keeps the fragments of all 64 output channels for all nine taps (72 fragments, 288 registers) and
+// multiplies them with 64 pixels of the tile; nothing but the input patch goes through LDS (512 bytes
+// read per matrix instruction, half of what a 32-channel wave would need) and no barrier separates
+// the taps.  Blocks are persistent (one per CU and 64-channel tile) and keep three patch buffers:
+// while tile i is multiplied, the patches of tiles i+1 and i+2 are on their way.  The accumulators go
+// straight to the NHWC output: a lane pair exchanges halves so that each lane stores 16 bytes.  One
+// barrier per tile.
+// ---------------------------------------------------------------------------------------
+constexpr int WS_PATCH = HALO_PP * 128;   // 44 KiB per patch buffer
+constexpr int WS_LDS = 3 * WS_PATCH + 64 * 4;
+constexpr int WS_DEPTH = 3;               // fragment reads run this many 16-channel slices ahead of the matrix cores
+constexpr int WS_CPW = HALO_PP / 8 / 4;   // patch copies per wave
+static_assert(WS_CPW * 4 * 8 == HALO_PP, "patch copies divide evenly over the four waves");
+static_assert(WS_PATCH + 9 * 8192 <= 3 * WS_PATCH, "the weights are staged behind the first patch buffer");
+
+template <int PASS>
+__global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int TW = 1 << tws, TH = HALO_TB >> tws, PW = TW + 2, PP = (TH + 2) * PW;
+    const int a0 = blockIdx.y * 64;
+    const int IH = PASS == PASS_FWD ? g.H : g.Ho, IW = PASS == PASS_FWD ? g.W : g.Wo;
+    const int OH = PASS == PASS_FWD ? g.Ho : g.H, OW = PASS == PASS_FWD ? g.Wo : g.W;
+    const int RSC = 9 * g.C;
+    const unsigned smem_base = lds_offset(smem);
+    float *bias_lds = reinterpret_cast<float *>(smem + 3 * WS_PATCH);
+    __amdgpu_buffer_rsrc_t rin = PASS == PASS_FWD ? make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2)
+                                                  : make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
+    if (tid < 64) bias_lds[tid] = (PASS == PASS_FWD && (p.flags & KF_BIAS) && a0 + tid < p.rowsA) ? p.bias[a0 + tid] : 0.f;
+
+    // patch copies of this lane: copy q of a wave fills patch pixels (wave*WS_CPW + q)*8 .. +7; the lane's
+    // pixel (row, column) and channel chunk are fixed, only the tile origin changes
+    unsigned pk[WS_CPW];
+#pragma unroll
+    for (int q = 0; q < WS_CPW; ++q) {
+        const int pp = (wave * WS_CPW + q) * 8 + (lane >> 3), c = (lane & 7) ^ ((pp >> 1) & 7);
+        const int pr = pp / PW, pc = pp - pr * PW;
+        pk[q] = (unsigned)pr | ((unsigned)pc << 8) | ((unsigned)c << 16) | (pp < PP ? 1u << 24 : 0u);
+    }
+    auto issue_patch = [&](int tile, int buf) {
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        const int h0 = PASS == PASS_FWD ? ty * TH - g.ph : ty * TH + g.ph - 2, w0 = PASS == PASS_FWD ? tx * TW - g.pw : tx * TW + g.pw - 2;
+        const int nbase = n * IH;
+#pragma unroll
+        for (int q = 0; q < WS_CPW; ++q) {
+            const int ih = h0 + (int)(pk[q] & 255u), iw = w0 + (int)((pk[q] >> 8) & 255u), c = (pk[q] >> 16) & 7;
+            const bool ok = (pk[q] >> 24) != 0 && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
+            dma16(rin, smem_base + buf * WS_PATCH + (wave * WS_CPW + q) * 1024, ok ? (unsigned)(((nbase + ih) * IW + iw) * 64 + c * 8) * 2u : OOR);
+        }
+    };
+    int tile = blockIdx.x;
+    const int stride = gridDim.x;
+    if (tile < tiles) issue_patch(tile, 0);
+
+    // ---- weights: through LDS (behind the first patch buffer) into registers ------------------------
+    // forward: the tile of step st is [64 c_out][64 c_in], chunk swizzle by row pair; backward-data: the tile
+    // of step st (filter tap 8 - st) is [64 c_out][64 c_in] with c_out the reduction, read transposed
+    const unsigned wst = smem_base + WS_PATCH;
+#pragma unroll
+    for (int q = 0; q < 18; ++q) {
+        const int id = wave * 18 + q, st = id >> 3, row = (id & 7) * 8 + (lane >> 3);
+        unsigned voff;
+        if (PASS == PASS_FWD) {
+            const int c = (lane & 7) ^ ((row >> 1) & 7);
+            voff = a0 + row < p.rowsA ? ((unsigned)(a0 + row) * RSC + st * 64 + c * 8) * 2u : OOR;
+        } else {
+            const int c = (lane & 7) ^ (seg_swz<64>(row) << 2);
+            voff = a0 + c * 8 < p.rowsA ? ((unsigned)row * RSC + (8 - st) * g.C + a0 + c * 8) * 2u : OOR;
+        }
+        dma16(rw, wst + id * 1024, voff);
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+    // (plain LDS loads here: the compiler places their waits; the hand-counted reads start with the tile loop)
+    u32x4 afr[9][4][2];   // [step][slice][32-row half]
+    {
+        const char *wl = smem + WS_PATCH;
+        typedef short v4s __attribute__((ext_vector_type(4)));
+        typedef __attribute__((address_space(3))) v4s *lds_v4s;
+        const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+#pragma unroll
+        for (int st = 0; st < 9; ++st)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    if (PASS == PASS_FWD) {
+                        const int row = i * 32 + (lane & 31);
+                        afr[st][ks][i] = *reinterpret_cast<const u32x4 *>(wl + st * 8192 + row * 128 + (((2 * ks + (lane >> 5)) ^ ((row >> 1) & 7)) << 4));
+                    } else {
+                        const int t = ks * 16 + tl, col = i * 32 + cl;
+                        const char *a = wl + st * 8192 + t * 128 + ((((col >> 5) ^ seg_swz<64>(t)) << 6) | ((col & 31) << 1));
+                        const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a));
+                        const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s)(a + 4 * 128));
+                        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+                        afr[st][ks][i] = u32x4{l2.x, l2.y, h2.x, h2.y};
+                    }
+                }
+    }
+    __syncthreads();   // the staging area is free for patches; the first patch has landed (waited above)
+    if (tile + stride < tiles) issue_patch(tile + stride, 1);
+
+    int pp0[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int jj = wave * 64 + j * 32 + (lane & 31);
+        pp0[j] = (jj >> tws) * PW + (jj & (TW - 1));
+    }
+    const unsigned hsel = lane >> 5;
+    bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+
+    // A wave that issues a memory instruction into a full queue stalls, matrix instructions included, so the
+    // copies of the patch two tiles ahead and the stores of the previous tile's output (held packed in
+    // registers meanwhile) are spread over the 36 slices of the running tile instead of issued in a burst.
+    u32x4 ost[8];           // previous tile: [pixel fragment j][channel half i][group pair gp], 8 channels of one pixel each
+    bf16_t *optr[2] = {out, out};   // this lane's output row of fragment j (previous tile), at channel a0
+    bool ook[2] = {false, false};
+    bool have_prev = false;
+    auto store_one = [&](int k) {
+        const int j = k >> 2, i = (k >> 1) & 1, gp = k & 1;
+        const int ch = i * 32 + 8 * (2 * gp + (int)hsel);
+        if (ook[j] && a0 + ch < p.rowsA) asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(optr[j] + ch), "v"(ost[k]) : "memory");
+    };
+
+    for (int it = 0; tile < tiles; tile += stride, ++it) {
+        // buffer (it + 2) % 3 held tile it - 1, which every wave had finished before the last barrier
+        const bool more1 = tile + stride < tiles, more2 = tile + 2 * stride < tiles;
+        int nh0 = 0, nw0 = 0, nnb = 0;   // origin of the patch two tiles ahead
+        if (more2) {
+            const int t2 = tile + 2 * stride;
+            const int n = t2 / (tiles_x * tiles_y), trem = t2 - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+            nh0 = PASS == PASS_FWD ? ty * TH - g.ph : ty * TH + g.ph - 2;
+            nw0 = PASS == PASS_FWD ? tx * TW - g.pw : tx * TW + g.pw - 2;
+            nnb = n * IH;
+        }
+        const unsigned nbuf = smem_base + ((it + 2) % 3) * WS_PATCH + wave * WS_CPW * 1024;
+        auto copy_one = [&](int q) {
+            const int ih = nh0 + (int)(pk[q] & 255u), iw = nw0 + (int)((pk[q] >> 8) & 255u), c = (pk[q] >> 16) & 7;
+            const bool ok = (pk[q] >> 24) != 0 && (unsigned)ih < (unsigned)IH && (unsigned)iw < (unsigned)IW;
+            dma16(rin, nbuf + q * 1024, ok ? (unsigned)(((nnb + ih) * IW + iw) * 64 + c * 8) * 2u : OOR);
+        };
+        const unsigned base = smem_base + (it % 3) * WS_PATCH;
+        asm volatile("" : "+v"(pp0[0]), "+v"(pp0[1]));   // keeps the 72 read addresses from being computed ahead of the loop
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        u32x4 fb[WS_DEPTH + 1][2];   // [buffer][pixel fragment]
+        auto read_b = [&](int sl) {
+            const int st = sl >> 2, ks = sl & 3;
+            const int off = (st / 3) * PW + (st % 3);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int pp = pp0[j] + off;
+                fb[sl % (WS_DEPTH + 1)][j] = lds_read16<0>(base + pp * 128 + (((2 * ks + hsel) ^ ((pp >> 1) & 7)) << 4));
+            }
+        };
+#pragma unroll
+        for (int sl = 0; sl < WS_DEPTH; ++sl) read_b(sl);
+#pragma unroll
+        for (int sl = 0; sl < 36; ++sl) {
+            if (sl + WS_DEPTH < 36) read_b(sl + WS_DEPTH);
+            constexpr int kFull = 2 * WS_DEPTH;
+            const int newer = 2 * (35 - sl < WS_DEPTH ? 35 - sl : WS_DEPTH);   // reads issued after this slice's
+            if (newer == kFull) asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(kFull));
+            else if (newer == 4) asm volatile("s_waitcnt lgkmcnt(4)");
+            else if (newer == 2) asm volatile("s_waitcnt lgkmcnt(2)");
+            else asm volatile("s_waitcnt lgkmcnt(0)");
+            const int cur = sl % (WS_DEPTH + 1);
+            asm volatile("" : "+v"(fb[cur][0]));
+            asm volatile("" : "+v"(fb[cur][1]));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, afr[sl >> 2][sl & 3][i]),
+                                                                       __builtin_bit_cast(bf16x8, fb[cur][j]), acc[i][j], 0, 0, 0);
+            if (sl % 3 == 1 && sl / 3 < WS_CPW) {
+                if (more2) copy_one(sl / 3);
+            }
+            if (sl % 4 == 2 && sl / 4 < 8) {
+                if (have_prev) store_one(sl / 4);
+            }
+        }
+        // this wave's share of the next patch has landed: of the loads issued after it (the copies above) none can
+        // still be outstanding once at most that many operations are
+        if (more1) {
+            if (more2) wait_vmcnt<WS_CPW>();
+            else wait_vmcnt<0>();
+        }
+        // accumulator element v of lane l is channel i*32 + 8*(v/4) + 4*(l/32) + v%4 of pixel l%32 of fragment j; the lanes
+        // l and l+32 swap halves of two channel groups, after which each holds 8 consecutive channels of one group
+        {
+            const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int pix = wave * 64 + j * 32 + (lane & 31);
+                const int pr = ty * TH + (pix >> tws), qc = tx * TW + (pix & (TW - 1));
+                ook[j] = pr < OH && qc < OW;
+                optr[j] = out + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + a0;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp) {
+                        unsigned pkd[2][2];   // [group 2gp, 2gp+1][channel pair]
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const int gq = 2 * gp + e;
+                            const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + i * 32 + 8 * gq + 4 * hsel);
+                            float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y, v2 = acc[i][j][4 * gq + 2] + bv.z,
+                                  v3 = acc[i][j][4 * gq + 3] + bv.w;
+                            if (PASS == PASS_FWD && (p.flags & KF_RELU)) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                            pkd[e][0] = pack_bf16(v0, v1);
+                            pkd[e][1] = pack_bf16(v2, v3);
+                        }
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(pkd[0][0], pkd[1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(pkd[0][1], pkd[1][1], false, false);
+                        ost[j * 4 + i * 2 + gp] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                    }
+            }
+            have_prev = true;
+        }
+        __builtin_amdgcn_s_barrier();   // all shares of the next patch have landed; this tile's buffer is free (no fence: copies and stores stay in flight)
+    }
+    if (have_prev) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) store_one(k);
+    }
+}
+
 struct HaloVariant { int TA, WA, WB, NS; };
 const HaloVariant kHalo[] = {{64, 1, 4, 2}, {128, 2, 2, 2}, {64, 1, 4, 3}, {64, 1, 4, 4}};
 constexpr int kNumHalo = 4;
@@ -426,6 +665,12 @@ hipError_t halo_init()
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_wgrad_halo), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WH_BUF);
         if (e != hipSuccess) return e;
     }
+    {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_halo_ws<PASS_FWD>), hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_halo_ws<PASS_DGRAD>), hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS);
+        if (e != hipSuccess) return e;
+    }
     for (int pass = 0; pass < 2; ++pass)
         for (int v = 0; v < kNumHalo; ++v) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_halo(pass, v)), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -456,8 +701,27 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         pl->splits = blocks;
         return true;
     }
-    if (force_variant < 400 || force_variant >= 400 + kNumHalo || force_splits > 1) return false;
     if (pass != PASS_FWD && pass != PASS_DGRAD) return false;
+    pl->blocks = 0;
+    if (force_variant == 404) {   // weights in registers, persistent blocks; force_splits = blocks per 64-row tile
+        const int red_c = pass == PASS_FWD ? g.C : g.K, rowsA = pass == PASS_FWD ? g.K : g.C;
+        if (g.sh != 1 || g.sw != 1 || g.R != 3 || g.S != 3 || red_c != 64 || (rowsA % 8) != 0) return false;
+        if (pass == PASS_DGRAD && (g.ph > 2 || g.pw > 2)) return false;
+        const int oh = pass == PASS_FWD ? g.Ho : g.H, ow = pass == PASS_FWD ? g.Wo : g.W;
+        const int tws = halo_tws(oh, ow), tw = 1 << tws, th = HALO_TB >> tws;
+        const long long tiles = (long long)g.N * ((oh + th - 1) / th) * ((ow + tw - 1) / tw);
+        if (tiles > 0x7fffff) return false;
+        pl->variant = 4;
+        pl->fast = true; pl->dma = true; pl->halo = true;
+        pl->TA = 64; pl->TB = HALO_TB; pl->BK = 64; pl->vecA = pl->vecB = true;
+        pl->tilesA = (rowsA + 63) / 64;
+        pl->tilesB = (int)tiles;
+        pl->steps_total = pl->steps_per_split = 9;
+        pl->splits = 1;
+        pl->blocks = force_splits > 1 ? force_splits : 0;
+        return true;
+    }
+    if (force_variant < 400 || force_variant >= 400 + kNumHalo || force_splits > 1) return false;
     if (g.sh != 1 || g.sw != 1 || g.R * g.S > 32) return false;
     const int red_c = pass == PASS_FWD ? g.C : g.K, rowsA = pass == PASS_FWD ? g.K : g.C;
     if (red_c != 64 || (rowsA % 8) != 0) return false;
@@ -479,6 +743,7 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
 void halo_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
     if (pass == PASS_WGRAD) { snprintf(name, name_bytes, "k_wgrad_halo"); return; }
+    if (pl.variant == 4) { snprintf(name, name_bytes, "k_halo_ws<%d>", pass); return; }
     const HaloVariant &h = kHalo[pl.variant];
     snprintf(name, name_bytes, "k_halo<%d, %d, %d, %d, %d>", pass, h.TA, h.WA, h.WB, h.NS);
 }
@@ -512,6 +777,14 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
     const int oh = fwd ? a.g.Ho : a.g.H, ow = fwd ? a.g.Wo : a.g.W;
     const int tws = halo_tws(oh, ow), tw = 1 << tws, th = HALO_TB >> tws;
     const int tiles_x = (ow + tw - 1) / tw, tiles_y = (oh + th - 1) / th;
+    if (a.plan.variant == 4) {
+        int blocks = a.plan.blocks > 0 ? a.plan.blocks : 256 / p.tilesA;   // default: one persistent block per CU
+        if (blocks < 1) blocks = 1;
+        if (blocks > p.tilesB) blocks = p.tilesB;
+        hipLaunchKernelGGL(fwd ? k_halo_ws<PASS_FWD> : k_halo_ws<PASS_DGRAD>, dim3((unsigned)blocks, (unsigned)p.tilesA), dim3(256), WS_LDS, st, p,
+                           tws, tiles_x, tiles_y, p.tilesB);
+        return hipGetLastError();
+    }
     const HaloVariant &h = kHalo[a.plan.variant];
     dim3 grid((unsigned)(p.tilesA * p.tilesB), 1, 1), block(64 * h.WA * h.WB, 1, 1);
     hipLaunchKernelGGL(pick_halo(a.pass, a.plan.variant), grid, block, halo_lds_bytes(h), st, p, tws, tiles_x, tiles_y);

@@ -125,21 +125,41 @@ struct PlanEntry {
 };
 constexpr int kTuneCandidates = 12;
 
-PlanEntry &plan_entry(const ConvGeom &g, int pass)
+// bf16_out = false: the caller wants fp32 results, which the input-patch kernels (bf16 staging) do not write
+PlanEntry &plan_entry(const ConvGeom &g, int pass, bool bf16_out = true)
 {
     thread_local std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> cache;
     const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
     const int at = g_analytic_only ? 0 : g_autotune.load();
-    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at}};
+    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (bf16_out ? 0 : 2)}};
     auto it = cache.find(key);
     if (it != cache.end()) return it->second;
     if (cache.size() > 4096) cache.clear();
     PlanEntry e;
     plan_uncached(g, pass, fv, fs, &e.plan);
+    const bool patch_ok = bf16_out || pass == PASS_WGRAD;
+    if (!patch_ok && e.plan.halo) {   // the best plan by the model that is not an input-patch kernel
+        GemmPlan list[kTuneCandidates];
+        const int n = fv < 0 ? auto_plan_list(g, pass, fs, list, kTuneCandidates) : 0;
+        int pick = -1;
+        for (int i = 0; i < n && pick < 0; ++i)
+            if (!list[i].halo) pick = i;
+        if (pick >= 0) e.plan = list[pick];
+        else {
+            e.plan.dma = e.plan.halo = false;
+            if (!fast_plan(g, pass, -1, fs, &e.plan)) mfma_plan(g, pass, -1, fs, &e.plan);
+        }
+    }
     e.part_cap = mfma_partial_bytes(g, pass, e.plan);
     if (at != 0 && fv < 0 && e.plan.fast) {
         GemmPlan list[kTuneCandidates];
-        const int n = auto_plan_list(g, pass, fs, list, kTuneCandidates);
+        int n = auto_plan_list(g, pass, fs, list, kTuneCandidates);
+        if (!patch_ok) {
+            int m = 0;
+            for (int i = 0; i < n; ++i)
+                if (!list[i].halo) list[m++] = list[i];
+            n = m;
+        }
         if (n > 1) {
             e.cands.assign(list, list + n);
             e.tuned = false;
@@ -152,7 +172,6 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass)
     return cache.emplace(key, std::move(e)).first->second;
 }
 
-void plan_for(const ConvGeom &g, int pass, GemmPlan *pl) { *pl = plan_entry(g, pass).plan; }
 
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 {
@@ -276,9 +295,9 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
 }
 
-size_t dgrad_ws_bytes(const ConvGeom &g)
+size_t dgrad_ws_bytes(const ConvGeom &g, bool bf16_out)
 {
-    const PlanEntry &pe = plan_entry(g, PASS_DGRAD);
+    const PlanEntry &pe = plan_entry(g, PASS_DGRAD, bf16_out);
     size_t need = round256(pe.part_cap);
     if (pe.plan.fast) need += round256(ybytes(g));   // room for the masked gradient
     return need;
@@ -293,9 +312,9 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_DGRAD; a.flags = (flags & DP_DX_F32) ? KF_OUT_F32 : 0u;
-    PlanEntry &pe = plan_entry(g, PASS_DGRAD);
+    PlanEntry &pe = plan_entry(g, PASS_DGRAD, !(flags & DP_DX_F32));
     a.plan = pe.plan;
-    size_t need = dgrad_ws_bytes(g);
+    size_t need = dgrad_ws_bytes(g, !(flags & DP_DX_F32));
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
     if (a.plan.fast && ym != nullptr) {
@@ -448,8 +467,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
-    GemmPlan pl;
-    plan_for(g, pass, &pl);
+    const GemmPlan pl = plan_entry(g, pass, pass != PASS_DGRAD || !(desc->flags & DP_DX_F32)).plan;
     if (name != nullptr && name_bytes > 0) { if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes); else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
@@ -462,9 +480,7 @@ size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
     if (pass == DP_PASS_WGRAD) return wgrad_ws_bytes(g, desc->io_dtype, true);
     if (desc->io_dtype == DP_F32) return 0;
     if (pass == DP_PASS_FWD) return fwd_ws_bytes(g);
-    GemmPlan pl;
-    plan_for(g, pass, &pl);
-    return dgrad_ws_bytes(g);
+    return dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32));
 }
 
 size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
@@ -474,9 +490,7 @@ size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
     size_t need = wgrad_ws_bytes(g, desc->io_dtype, true);
     if (desc->io_dtype == DP_BF16) {
         for (int pass = 0; pass < 2; ++pass) {
-            GemmPlan pl;
-            plan_for(g, pass, &pl);
-            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g) : fwd_ws_bytes(g);
+            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32)) : fwd_ws_bytes(g);
             if (b > need) need = b;
         }
     }
@@ -509,9 +523,7 @@ dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const voi
     if ((s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(w, "w")) != DP_OK || (s = check_ptr(dx, "dx")) != DP_OK) return s;
     if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK) return s;
     if (desc->io_dtype == DP_BF16) {
-        GemmPlan pl;
-        plan_for(g, PASS_DGRAD, &pl);
-        size_t need = dgrad_ws_bytes(g);
+        size_t need = dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32));
         if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     }
     if ((s = ensure_init()) != DP_OK) return s;
@@ -617,9 +629,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
         size_t wsb = wgrad_ws_bytes(g, dtype, true);
         if (dtype == DP_BF16)
             for (int pass = 0; pass < 2; ++pass) {
-                GemmPlan pl;
-                plan_for(g, pass, &pl);
-                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g) : fwd_ws_bytes(g);
+                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, !(flags & DP_DX_F32)) : fwd_ws_bytes(g);
                 if (b > wsb) wsb = b;
             }
         const size_t dxes = (flags & DP_DX_F32) ? 4 : es;

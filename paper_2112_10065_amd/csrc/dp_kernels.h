@@ -34,6 +34,7 @@ struct GemmPlan {
     bool fast;            // fast-path kernel (conv_fast.hip) instead of the generic one
     bool dma;             // pipelined direct-to-LDS kernel (conv_dma.hip)
     bool halo = false;    // input-patch kernel (conv_halo.hip); implies dma
+    int blocks = 0;       // persistent kernels: blocks per row tile (0: one per CU)
 };
 
 struct ConvArgs {

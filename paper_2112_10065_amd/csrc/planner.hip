@@ -45,6 +45,7 @@ const Candidate kPix[] = {
     {401, 2, 1.20f, 6.0f},   // same, 128 x 256
     {402, 2, 0.75f, 5.5f},
     {403, 2, 0.72f, 5.5f},
+    {404, 1, 0.27f, 0.8f},   // 3x3 only: persistent blocks, weights in registers
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},

@@ -58,6 +58,7 @@ def test_fp32_strided_asymmetric(env):
 BF16_CASES = [
     # tag, n, h, w, c, k, r, s, stride, pad, bias, relu, dx_f32
     ("vgg_like_64", 2, 28, 28, 64, 64, 3, 3, (1, 1), (1, 1), True, True, False),
+    ("vgg_like_64_dx_f32", 2, 28, 28, 64, 64, 3, 3, (1, 1), (1, 1), True, True, True),
     ("vgg_like_128_256", 3, 14, 14, 128, 256, 3, 3, (1, 1), (1, 1), True, True, False),
     ("rgb_3x3", 2, 20, 22, 3, 64, 3, 3, (1, 1), (1, 1), True, True, True),
     ("stem_7x7_s2", 2, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3), False, False, True),
@@ -220,6 +221,44 @@ def test_input_patch_variants(env, variant):
         # a patch that does not fit (5x5 filter) falls back to another kernel
         case = U.ConvCase("patch_big", 1, 20, 20, 64, 64, 5, 5, (1, 1), (2, 2), bf16=True, bias=True, relu=True)
         assert "k_halo" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+    finally:
+        dp.dp_set_override(0, -1, 0)
+        dp.dp_set_override(1, -1, 0)
+
+
+@pytest.mark.parametrize("blocks", [0, 1, 7])
+def test_input_patch_stationary_weights(env, blocks):
+    """3x3, stride 1, 64 reduction channels: persistent kernel with the weight fragments in registers.  Block
+    counts below the tile count make every block walk several tiles (both patch buffers, delayed stores)."""
+    dp, U, orc = env
+    dp.dp_set_override(0, 404, blocks)
+    dp.dp_set_override(1, 404, blocks)
+    try:
+        for tag, n, h, w, k, pd in (("ws_a", 2, 13, 12, 96, (1, 1)), ("ws_b", 1, 37, 40, 64, (1, 1)), ("ws_c", 3, 20, 70, 200, (0, 0)),
+                                    ("ws_d", 2, 16, 16, 8, (2, 2))):
+            case = U.ConvCase(tag, n, h, w, 64, k, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "k_halo_ws<0>" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            y = case.run_fwd()
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd), f"{tag} blocks {blocks}")
+        for tag, n, h, w, c, pd in (("wsd_a", 2, 13, 12, 96, (1, 1)), ("wsd_b", 1, 37, 40, 64, (1, 1)), ("wsd_c", 3, 20, 70, 200, (0, 0)),
+                                    ("wsd_d", 2, 16, 16, 8, (2, 2))):
+            case = U.ConvCase(tag, n, h, w, c, 64, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert "k_halo_ws<1>" in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+            y = case.run_fwd()
+            dx = case.run_dgrad(y)
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), pad=pd), f"{tag} blocks {blocks} dx")
+        # other filter shapes and fp32 gradients are not this kernel's
+        case = U.ConvCase("ws_1x7", 1, 9, 33, 64, 64, 1, 7, (1, 1), (0, 3), bf16=True, bias=True, relu=True)
+        assert "k_halo_ws" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+        case = U.ConvCase("ws_f32", 2, 13, 12, 72, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=True)
+        assert "k_halo" not in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+        y = case.run_fwd()
+        dx = case.run_dgrad(y)
+        torch.cuda.synchronize()
+        assert dx.dtype == torch.float32
+        U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), pad=(1, 1)), "ws_f32 dx")
     finally:
         dp.dp_set_override(0, -1, 0)
         dp.dp_set_override(1, -1, 0)
