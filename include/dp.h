@@ -167,6 +167,45 @@ dp_status dp_set_override(int pass, int tile_variant, int splits);
  * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */
 dp_status dp_set_autotune(int enabled);
 
+/* ---- Burst-parallel plan of a chain of layers (host only: no GPU call, all pointers host) -------
+ * Paper section 4.2, algorithm "Search Linear": dynamic programming over
+ *   S[i][g] = shortest time to complete layers 1..i with layer i on g GPUs,
+ *   T[i][g] = time spent on layer i while minimising S[i][g],
+ * admitting a predecessor GPU count h only while its GPU-sec amplification
+ *   Amp(i-1,h) = T[i-1][h] * h / comp(i-1,1)
+ * is within max(best amplification admitted so far, amp_limit) and S[i-1][h] + comm does not exceed
+ * the best so far (ties take the later h; the first h scanned is always admitted).  Layer 0 does not
+ * exist: S[0][g] = 0 and Amp(0,h) = 0.  The last layer's GPU count is chosen by the same admission
+ * scan with zero transition cost, then the predecessors are traced back.
+ * Tables are dense row-major doubles; index a / b runs over gpu_counts. */
+typedef struct {
+    int32_t n_layers;          /* L >= 1 */
+    int32_t n_gpu_counts;      /* G >= 1 */
+    const int32_t *gpu_counts; /* [G] strictly ascending, gpu_counts[0] == 1 */
+    const double *comp;        /* [L][G] comp(i,g): forward+backward time of layer i on g GPUs, > 0, e.g. the
+                                  dp_profile_layer times at per-GPU batch B/g */
+    const double *comm;        /* [L][G][G] comm[i][b][a]: transition from layer i-1 on gpu_counts[b] to layer i
+                                  on gpu_counts[a] (i = 0: into the first layer); NULL = all zero */
+    const double *sync;        /* [L][G] sync(i,g): gradient synchronisation of layer i; NULL = all zero */
+    double amp_limit;          /* GPU-sec amplification limit; INFINITY = none (plain shortest path) */
+} dp_plan_desc;
+
+/* gpus_per_layer [L]: GPU count of each layer; iteration_time: S[L][g_L]; S_out / T_out: [(L+1)][G]
+ * including row 0, either may be NULL.  DP_ERR_NULL / DP_ERR_BAD_DESC on missing or malformed input
+ * (non-ascending counts, first count != 1, non-finite or non-positive comp, negative costs). */
+dp_status dp_plan_chain(const dp_plan_desc *desc, int32_t *gpus_per_layer, double *iteration_time,
+                        double *S_out, double *T_out);
+
+/* Closed-form costs of paper section 4.1 (payload over per-GPU bandwidth plus a propagation delay, full
+ * bisection).  act_bytes[i]: bytes of the global batch entering layer i (act_bytes[0], the network input, is
+ * never redistributed: comm[0] = 0); param_bytes[i]: gradient bytes of layer i.
+ *   comm (g != h) = 2 * (act_bytes * (1/min(g,h) - 1/max(g,h)) / bandwidth + delay)   forward + backward
+ *   sync (g > 1)  = 2 * (param_bytes * (g-1)/g / bandwidth + delay)                   reduce-scatter + all-gather
+ * comm_out [L][G][G], sync_out [L][G]. */
+dp_status dp_plan_cost_tables(int32_t n_layers, int32_t n_gpu_counts, const int32_t *gpu_counts,
+                              const double *act_bytes, const double *param_bytes, double bandwidth,
+                              double delay, double *comm_out, double *sync_out);
+
 const char *dp_last_error(void); /* thread-local, static storage */
 const char *dp_version(void);
 

@@ -16,8 +16,8 @@ DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data",
            "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
-           "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_last_error",
-           "dp_version"]
+           "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
+           "dp_plan_cost_tables", "dp_last_error", "dp_version"]
 
 
 class dp_conv_desc(C.Structure):
@@ -34,6 +34,12 @@ class dp_profile_row(C.Structure):
     _fields_ = [("batch", C.c_int32), ("fwd_us", C.c_float), ("dgrad_us", C.c_float), ("wgrad_us", C.c_float),
                 ("flops_per_pass", C.c_double), ("min_bytes_fwd", C.c_double), ("min_bytes_dgrad", C.c_double),
                 ("min_bytes_wgrad", C.c_double)]
+
+
+class dp_plan_desc(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("n_gpu_counts", C.c_int32), ("gpu_counts", C.POINTER(C.c_int32)),
+                ("comp", C.POINTER(C.c_double)), ("comm", C.POINTER(C.c_double)), ("sync", C.POINTER(C.c_double)),
+                ("amp_limit", C.c_double)]
 
 
 class DpError(RuntimeError):
@@ -65,8 +71,12 @@ def _load():
     lib.dp_set_autotune.argtypes = [C.c_int]
     lib.dp_conv2d_kernel_info.argtypes = [P(dp_conv_desc), C.c_int, C.c_char_p, sz, P(i32)]
     lib.dp_conv2d_kernel_info.restype = C.c_int
+    pd = P(C.c_double)
+    lib.dp_plan_chain.argtypes = [P(dp_plan_desc), P(i32), pd, pd, pd]
+    lib.dp_plan_cost_tables.argtypes = [i32, i32, P(i32), pd, pd, C.c_double, C.c_double, pd, pd]
     for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
-                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune"):
+                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
+                 "dp_plan_cost_tables"):
         getattr(lib, name).restype = C.c_int
     lib.dp_last_error.restype = C.c_char_p
     lib.dp_version.restype = C.c_char_p
@@ -125,6 +135,50 @@ def dp_set_override(pass_, tile_variant=-1, splits=0):
 
 def dp_set_autotune(enabled):
     _check(lib.dp_set_autotune(1 if enabled else 0))
+
+
+def _doubles(rows, n):
+    """Flat C array of n doubles from a (nested) Python sequence, or None."""
+    if rows is None:
+        return None
+    flat = []
+
+    def walk(v):
+        if isinstance(v, (list, tuple)):
+            for e in v:
+                walk(e)
+        else:
+            flat.append(float(v))
+    walk(rows)
+    if len(flat) != n:
+        raise ValueError(f"expected {n} values, got {len(flat)}")
+    return (C.c_double * n)(*flat)
+
+
+def dp_plan_chain(gpu_counts, comp, comm=None, sync=None, amp_limit=float("inf")):
+    """Host-only.  comp [L][G], comm [L][G][G] or None, sync [L][G] or None (nested sequences).
+    Returns {"gpus": [L], "time": float, "S": [L+1][G], "T": [L+1][G]}."""
+    L, G = len(comp), len(gpu_counts)
+    gc = (C.c_int32 * G)(*gpu_counts)
+    d = dp_plan_desc(L, G, gc, _doubles(comp, L * G), _doubles(comm, L * G * G), _doubles(sync, L * G), float(amp_limit))
+    out = (C.c_int32 * L)()
+    t = C.c_double(0.0)
+    S = (C.c_double * ((L + 1) * G))()
+    T = (C.c_double * ((L + 1) * G))()
+    _check(lib.dp_plan_chain(C.byref(d), out, C.byref(t), S, T))
+    rows = lambda a: [[a[i * G + j] for j in range(G)] for i in range(L + 1)]
+    return {"gpus": list(out), "time": t.value, "S": rows(S), "T": rows(T)}
+
+
+def dp_plan_cost_tables(gpu_counts, act_bytes, param_bytes, bandwidth, delay):
+    """Host-only.  Returns (comm [L][G][G], sync [L][G]) as nested lists."""
+    L, G = len(param_bytes), len(gpu_counts)
+    gc = (C.c_int32 * G)(*gpu_counts)
+    comm = (C.c_double * (L * G * G))()
+    sync = (C.c_double * (L * G))()
+    _check(lib.dp_plan_cost_tables(L, G, gc, _doubles(act_bytes, L), _doubles(param_bytes, L), float(bandwidth), float(delay), comm, sync))
+    return ([[[comm[(i * G + b) * G + a] for a in range(G)] for b in range(G)] for i in range(L)],
+            [[sync[i * G + a] for a in range(G)] for i in range(L)])
 
 
 def dp_conv2d_kernel_info(desc, pass_):

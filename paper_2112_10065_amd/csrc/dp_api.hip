@@ -30,6 +30,19 @@ dp_status fail(dp_status st, const char *fmt, ...)
     return st;
 }
 
+}  // namespace
+
+// error text for the host-only entry points in other files
+void dp_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+namespace {
+
 dp_status hip_fail(hipError_t e, const char *what)
 {
     return fail(DP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
