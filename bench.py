@@ -54,6 +54,7 @@ def parse():
                     help="profiling aid: also run an elementwise fp32 copy kernel that reads and writes this many MiB")
     ap.add_argument("--no-autotune", action="store_true",
                     help="keep the analytic kernel choice instead of timing the candidates once per layer shape before the warm-up")
+    ap.add_argument("--no-glue", action="store_true", help="skip the separate timing of pooling, loss and SGD update")
     ap.add_argument("--table", type=str, default="", help="also write the per-layer time-vs-batch table (JSON) here")
     return ap.parse_args()
 
@@ -176,6 +177,57 @@ class Layer:
 
     def step_flops(self, n):
         return self.flops(n) * sum(1 for _, _, c in self.passes() if c)
+
+
+def glue_times(dp, torch, dev, batches):
+    """The layers between the conv/FC layers of a whole VGG-16 step, timed apart from the headline step
+    (they carry no nominal flops): the five 2x2 max-pools forward + backward per batch, the loss, and one
+    SGD-with-momentum update of all 138 M parameters.  HIP events around 10 back-to-back launches each."""
+    pools = [(224, 64), (112, 128), (56, 256), (28, 512), (14, 512)]
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, reps=10):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / reps
+
+    out = {"pool_fwd_bwd_us": {}, "loss_us": {}}
+    nmax = max(batches)
+    bufs = []
+    for hw, c in pools:
+        x = torch.relu(torch.randn((nmax, hw, hw, c), device=dev)).to(torch.bfloat16)
+        dy = torch.randn((nmax, hw // 2, hw // 2, c), device=dev).to(torch.bfloat16)
+        bufs.append((hw, c, x, dy, torch.empty_like(dy), torch.empty_like(x)))
+    z = torch.randn((nmax, 1000), device=dev).to(torch.bfloat16)
+    labels = (torch.arange(nmax, device=dev, dtype=torch.int32) * 37) % 1000
+    loss, dz = torch.zeros(4, device=dev), torch.empty_like(z)
+    for n in batches:
+        def pool_pass():
+            for hw, c, x, dy, y, dx in bufs:
+                dp.dp_maxpool2x2_fwd(n, hw, hw, c, dp.DP_BF16, x, y)
+                dp.dp_maxpool2x2_bwd(n, hw, hw, c, dp.DP_BF16, x, dy, dx)
+        out["pool_fwd_bwd_us"][str(n)] = timed(pool_pass)
+        out["loss_us"][str(n)] = timed(lambda: dp.dp_softmax_xent(n, 1000, dp.DP_BF16, z, labels, loss, dz))
+    # HBM figure of the largest pool at the largest batch: forward reads x and writes y (1.25 x), backward
+    # reads x and dy and writes dx (2.25 x)
+    hw, c, x, dy, y, dx = bufs[0]
+    t = timed(lambda: (dp.dp_maxpool2x2_fwd(nmax, hw, hw, c, dp.DP_BF16, x, y), dp.dp_maxpool2x2_bwd(nmax, hw, hw, c, dp.DP_BF16, x, dy, dx)))
+    out["pool1_gb_per_s"] = 3.5 * x.numel() * 2 / t / 1e3
+    del bufs, x, dy, y, dx
+    from paper_2112_10065_amd import workloads as W
+    count = W.vgg16_param_count()
+    g = torch.randn(count, device=dev)
+    m, w32, w16 = torch.zeros_like(g), torch.randn(count, device=dev), torch.empty(count, device=dev, dtype=torch.bfloat16)
+    t = timed(lambda: dp.dp_sgd_update(count, 0.01, 0.9, g, m, w32, w16))
+    out["sgd_update_us"] = t
+    out["sgd_gb_per_s"] = 22.0 * count / t / 1e3   # reads grad, momentum, weights; writes momentum, weights, bf16 copy
+    out["hbm_peak_gb_per_s"] = 8000.0
+    return out
 
 
 def cpu_baseline():
@@ -413,6 +465,8 @@ def main():
         "per_batch": per_batch,
         "roofline": roofline,
     }
+    if args.workload == "vgg16" and not args.layers and not args.no_glue:
+        out["glue"] = glue_times(dp, torch, dev, batches)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     if args.table:

@@ -167,6 +167,34 @@ dp_status dp_set_override(int pass, int tile_variant, int splits);
  * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */
 dp_status dp_set_autotune(int enabled);
 
+/* ---- Glue layers of a whole training step (paper Table 1 counts VGG-16's pooling layers among its 21
+ * layers; the paper gives no arithmetic for them).  Pointwise, HBM-bound, asynchronous on hip_stream, no
+ * workspace, deterministic.  Device pointers, 16-byte aligned. ---------------------------------------- */
+
+/* 2x2 max pooling at stride 2 without padding, NHWC: y[n,p,q,c] = max of x[n,2p..2p+1,2q..2q+1,c];
+ * y is [n, h/2, w/2, c] (a trailing odd row / column of x is dropped; with h < 2 or w < 2 there is no
+ * window, y is empty and may be NULL).  io_dtype DP_BF16 or DP_F32. */
+dp_status dp_maxpool2x2_fwd(int32_t n, int32_t h, int32_t w, int32_t c, int32_t io_dtype, const void *x, void *y,
+                            void *hip_stream);
+/* dx[n,h,w,c] = dy of its window if x there is the window's FIRST maximum in row-major order
+ * ((0,0),(0,1),(1,0),(1,1)), else 0; every element of dx is written (dy may be NULL when there is no
+ * window).  x is the forward input. */
+dp_status dp_maxpool2x2_bwd(int32_t n, int32_t h, int32_t w, int32_t c, int32_t io_dtype, const void *x,
+                            const void *dy, void *dx, void *hip_stream);
+
+/* Softmax cross-entropy with integer labels: *loss = mean over the n rows of logsumexp(z_r) - z_r[label_r]
+ * (fp32, device); dz = (softmax(z) - onehot(label)) / n in io_dtype (may be NULL).  z [n, classes] in
+ * io_dtype; labels [n] int32 on the device, each in [0, classes) (a label outside contributes
+ * logsumexp only and no one-hot term).  fp32 arithmetic; rows are summed in a fixed order. */
+dp_status dp_softmax_xent(int32_t n, int32_t classes, int32_t io_dtype, const void *z, const int32_t *labels,
+                          float *loss, void *dz, void *hip_stream);
+
+/* SGD with momentum on fp32 master weights, in place: mom = momentum*mom + grad; w32 -= lr*mom; if
+ * w_bf16 is not NULL it receives w32 rounded to nearest-even bf16 (the copy the next forward reads).
+ * No dampening, Nesterov term or weight decay.  count elements. */
+dp_status dp_sgd_update(int64_t count, float lr, float momentum, const float *grad, float *mom, float *w32,
+                        void *w_bf16, void *hip_stream);
+
 /* ---- Burst-parallel plan of a chain of layers (host only: no GPU call, all pointers host) -------
  * Paper section 4.2, algorithm "Search Linear": dynamic programming over
  *   S[i][g] = shortest time to complete layers 1..i with layer i on g GPUs,

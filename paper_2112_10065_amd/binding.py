@@ -17,7 +17,8 @@ DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data",
            "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
            "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
-           "dp_plan_cost_tables", "dp_last_error", "dp_version"]
+           "dp_plan_cost_tables", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
+           "dp_last_error", "dp_version"]
 
 
 class dp_conv_desc(C.Structure):
@@ -74,9 +75,13 @@ def _load():
     pd = P(C.c_double)
     lib.dp_plan_chain.argtypes = [P(dp_plan_desc), P(i32), pd, pd, pd]
     lib.dp_plan_cost_tables.argtypes = [i32, i32, P(i32), pd, pd, C.c_double, C.c_double, pd, pd]
+    lib.dp_maxpool2x2_fwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.dp_maxpool2x2_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp]
+    lib.dp_softmax_xent.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.dp_sgd_update.argtypes = [i64, C.c_float, C.c_float, vp, vp, vp, vp, vp]
     for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
                  "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
-                 "dp_plan_cost_tables"):
+                 "dp_plan_cost_tables", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update"):
         getattr(lib, name).restype = C.c_int
     lib.dp_last_error.restype = C.c_char_p
     lib.dp_version.restype = C.c_char_p
@@ -135,6 +140,22 @@ def dp_set_override(pass_, tile_variant=-1, splits=0):
 
 def dp_set_autotune(enabled):
     _check(lib.dp_set_autotune(1 if enabled else 0))
+
+
+def dp_maxpool2x2_fwd(n, h, w, c, io_dtype, x, y, stream=None):
+    _check(lib.dp_maxpool2x2_fwd(n, h, w, c, io_dtype, _ptr(x), _ptr(y), _stream(stream)))
+
+
+def dp_maxpool2x2_bwd(n, h, w, c, io_dtype, x, dy, dx, stream=None):
+    _check(lib.dp_maxpool2x2_bwd(n, h, w, c, io_dtype, _ptr(x), _ptr(dy), _ptr(dx), _stream(stream)))
+
+
+def dp_softmax_xent(n, classes, io_dtype, z, labels, loss, dz=None, stream=None):
+    _check(lib.dp_softmax_xent(n, classes, io_dtype, _ptr(z), _ptr(labels), _ptr(loss), _ptr(dz), _stream(stream)))
+
+
+def dp_sgd_update(count, lr, momentum, grad, mom, w32, w_bf16=None, stream=None):
+    _check(lib.dp_sgd_update(count, lr, momentum, _ptr(grad), _ptr(mom), _ptr(w32), _ptr(w_bf16), _stream(stream)))
 
 
 def _doubles(rows, n):

@@ -112,3 +112,21 @@ def test_no_gpu_fails_loudly(dp):
     d = dp.conv_desc(1, 8, 8, 8, 8, 3, 3, (1, 1), (1, 1), dp.DP_BF16, 0)
     assert dp.lib.dp_conv2d_fwd(C.byref(d), A, A, None, A, None, 0, None) == dp.DP_ERR_HIP
     assert dp.lib.dp_last_error() != b""
+
+
+def test_glue_argument_errors(dp):
+    lib = dp.lib
+    assert lib.dp_maxpool2x2_fwd(1, 4, 4, 8, dp.DP_BF16, None, A, None) == dp.DP_ERR_NULL
+    assert lib.dp_maxpool2x2_fwd(1, 4, 4, 8, dp.DP_BF16, A, None, None) == dp.DP_ERR_NULL
+    assert lib.dp_maxpool2x2_fwd(1, 4, 4, 8, 5, A, A, None) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_maxpool2x2_fwd(0, 4, 4, 8, dp.DP_BF16, A, A, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_maxpool2x2_fwd(1, 4, 4, 8, dp.DP_BF16, A + 2, A, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_maxpool2x2_bwd(1, 4, 4, 8, dp.DP_BF16, A, None, A, None) == dp.DP_ERR_NULL
+    assert lib.dp_maxpool2x2_bwd(1, 4, 4, 8, dp.DP_BF16, A, A, None, None) == dp.DP_ERR_NULL
+    assert lib.dp_softmax_xent(4, 10, dp.DP_F32, A, None, A, None, None) == dp.DP_ERR_NULL
+    assert lib.dp_softmax_xent(4, 0, dp.DP_F32, A, A, A, None, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_softmax_xent(4, 10, 9, A, A, A, None, None) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_sgd_update(16, 0.1, 0.9, None, A, A, None, None) == dp.DP_ERR_NULL
+    assert lib.dp_sgd_update(-1, 0.1, 0.9, A, A, A, None, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_sgd_update(16, 0.1, 0.9, A, A + 4, A, None, None) == dp.DP_ERR_BAD_DESC
+    assert lib.dp_sgd_update(0, 0.1, 0.9, A, A, A, None, None) == dp.DP_OK   # nothing to do, nothing launched
