@@ -3,11 +3,13 @@
 strong-scaling per-GPU batches 1..32 on one MI355X.
 
 A step = one pass of the whole hot path: for every per-GPU batch N in {1,2,4,8,16,32}: forward
-through the 16 compute layers (bias+ReLU fused), then backward from the last layer: per layer the
-ReLU-gradient + bias-gradient (one pointwise pass that yields the masked upstream gradient),
-backward-filter (on a side stream) and backward-data.  The first layer needs no backward-data (a
-training step never uses the gradient of the input image), so its ReLU mask and bias gradient ride
-along in its backward-filter call.  Inputs are seeded synthetic tensors already resident in HBM.
+through the 16 compute layers (bias+ReLU fused), then backward from the last layer: per layer
+backward-data, whose epilogue also applies the backward of the ReLU in front of the layer
+(dx *= [x > 0], DP_RELU_IN), and, on a side stream, backward-filter with the bias gradient.  The
+gradient a layer receives is therefore already masked by its own output: every ReLU of the network is
+differentiated once, by the layer behind it, and no layer needs a pointwise pass of its own.  The first
+layer needs no backward-data (a training step never uses the gradient of the input image).  Inputs are
+seeded synthetic tensors already resident in HBM.
 value = nominal flops of the step / time (TFLOP/s); nominal flops per pass =
 2*N*Ho*Wo*K*R*S*C (padding taps counted), three passes per layer (two for the first).
 
@@ -108,15 +110,15 @@ class Layer:
             self.k = l.out_f
         self.bias = (torch.rand((self.k,), generator=gen, device=dev) * 0.2 - 0.1).float()
         self.db = torch.empty((self.k,), device=dev, dtype=torch.float32)
-        self.g = torch.empty_like(self.dy)          # masked upstream gradient dy * [y > 0]
         self.needs_dx = not (is_conv and spec.c < 8)  # the network input needs no gradient
 
     def desc(self, dp, n):
         l = self.spec
         if self.is_conv:
             flags = (dp.DP_BIAS if l.bias else 0) | dp.DP_RELU | (dp.DP_DX_F32 if self.dx_f32 else 0)
+            flags |= dp.DP_RELU_IN if self.needs_dx else 0
             return dp.conv_desc(n, l.h, l.w, l.c, l.k, l.r, l.s, (l.sh, l.sw), (l.ph, l.pw), dp.DP_BF16, flags)
-        return dp.linear_desc(n, l.in_f, l.out_f, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
+        return dp.linear_desc(n, l.in_f, l.out_f, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU | dp.DP_RELU_IN)
 
     def flops(self, n):
         l = self.spec
@@ -141,25 +143,22 @@ class Layer:
         else:
             dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, bias=self.bias, y=self.y, ws=ws, stream=stream)
 
-    def rgrad(self, dp, d, ws, stream=None):
-        """g = dy * [y > 0] and db = column sums of g, in one pointwise pass."""
-        dp.dp_relu_bias_grad(self.rows(d.n), self.k, dp.DP_BF16, self.dy, self.y, self.g, self.db, ws, stream)
-
+    # Every layer but the first reads the output of a ReLU (directly or max-pooled).  Its backward-data call
+    # applies that ReLU's backward in its epilogue (DP_RELU_IN: dx *= [x > 0]), so the gradient a layer
+    # receives (dy here) is already masked by its own output and no layer runs a pointwise pass of its own;
+    # each of the 15 ReLUs of the network is differentiated exactly once, by the layer behind it.
     def dgrad(self, dp, d, ws, stream=None):
         if self.is_conv:
-            dp.dp_conv2d_bwd_data(d, self.g, None, self.w, self.dx, ws, stream)
+            dp.dp_conv2d_bwd_data_relu(d, self.dy, None, self.w, self.x, self.dx, ws, stream)
         else:
-            dp.dp_linear_fwd_bwd(d, W=self.w, dy=self.g, dx=self.dx, ws=ws, stream=stream)
+            dp.dp_linear_fwd_bwd(d, x=self.x, W=self.w, dy=self.dy, dx=self.dx, ws=ws, stream=stream)
 
     def wgrad(self, dp, d, ws, stream=None):
-        if self.is_conv and not self.needs_dx:
-            # first layer: nothing else consumes the masked gradient, so the ReLU mask and the bias
-            # gradient ride along in the filter-gradient call (y_saved and dbias given)
-            dp.dp_conv2d_bwd_filter(d, self.x, self.dy, self.y, self.dw, self.db, ws, stream)
-        elif self.is_conv:
-            dp.dp_conv2d_bwd_filter(d, self.x, self.g, None, self.dw, None, ws, stream)
+        """Filter and bias gradient from the (already masked) incoming gradient."""
+        if self.is_conv:
+            dp.dp_conv2d_bwd_filter(d, self.x, self.dy, None, self.dw, self.db, ws, stream)
         else:
-            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.g, dW=self.dw, ws=ws, stream=stream)
+            dp.dp_linear_fwd_bwd(d, x=self.x, dy=self.dy, dW=self.dw, dbias=self.db, ws=ws, stream=stream)
 
     def bound(self, which, dp, d, ws, stream):
         """Zero-argument callable issuing the C call of pass `which` (arguments marshalled once)."""
@@ -171,7 +170,7 @@ class Layer:
         """(name, method, counts nominal flops) of the calls that make up this layer's share of a step."""
         out = [("fwd", self.fwd, True)]
         if self.needs_dx:
-            out += [("rgrad", self.rgrad, False), ("dgrad", self.dgrad, True)]
+            out.append(("dgrad", self.dgrad, True))
         out.append(("wgrad", self.wgrad, True))
         return out
 
@@ -314,8 +313,6 @@ def main():
             for li, l in enumerate(reversed(layers)):
                 d = descs[(l.name, n)]
                 side, wss = side_streams[li % n_side], ws_side[li % n_side]
-                if l.needs_dx:
-                    ops.append(("call", l.bound("rgrad", dp, d, ws, main)))
                 ops.append(("fork", (torch.cuda.Event(), side)))
                 ops.append(("call", l.bound("wgrad", dp, d, wss, side)))
                 if l.needs_dx:
@@ -456,8 +453,8 @@ def main():
         "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
         "config": {"workload": {"vgg16": "VGG-16 13 conv + 3 FC layers, 224x224x3 input", "resnet50": "ResNet-50 conv layers (23 unique shapes), 224x224x3 input",
                                 "inception": "Inception-v3-style conv layers (18 shapes), 299x299x3 input"}[args.workload]
-                               + ", per layer fwd + ReLU/bias-grad + dgrad + wgrad "
-                               "(first layer: no dgrad, ReLU/bias-grad fused into its wgrad call), "
+                               + ", per layer fwd (bias + ReLU fused) + dgrad (backward of the ReLU in front of the layer fused, "
+                               "so incoming gradients are already masked) + wgrad with bias gradient (first layer: no dgrad), "
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},

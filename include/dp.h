@@ -56,7 +56,11 @@ enum {
     DP_DETERMINISTIC = 4u, /* results are bitwise reproducible for a given kernel choice in any case (ordered
                               reductions, no float atomics); this flag also keeps the call on the analytic kernel
                               choice when dp_set_autotune is on, so that the choice cannot differ between processes */
-    DP_DX_F32 = 8u         /* bf16 path only: dx is written as fp32 instead of bf16 */
+    DP_DX_F32 = 8u,        /* bf16 path only: dx is written as fp32 instead of bf16 */
+    DP_RELU_IN = 16u       /* the layer's input x is the output of a ReLU: backward-data also applies that ReLU's
+                              backward, dx *= [x > 0], in its epilogue (needs the saved input: dp_conv2d_bwd_data_relu,
+                              or x in dp_linear_fwd_bwd).  The gradient then reaches the preceding layer already
+                              masked, so that layer passes y_saved = NULL and needs no pointwise pass of its own */
 };
 
 enum { DP_PASS_FWD = 0, DP_PASS_DGRAD = 1, DP_PASS_WGRAD = 2 };
@@ -73,7 +77,7 @@ typedef struct {
 typedef struct {
     int32_t n, in_features, out_features;
     int32_t io_dtype; /* dp_dtype */
-    uint32_t flags;   /* DP_BIAS, DP_RELU, DP_DX_F32 */
+    uint32_t flags;   /* DP_BIAS, DP_RELU, DP_DX_F32, DP_RELU_IN */
 } dp_linear_desc;
 
 /* Bytes of device scratch the given pass (DP_PASS_*) of this layer needs.
@@ -96,6 +100,16 @@ dp_status dp_conv2d_fwd(const dp_conv_desc *desc, const void *x, const void *w, 
 dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const void *y_saved_or_null,
                              const void *w, void *dx, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* The same with the backward of the ReLU in front of the layer fused into the epilogue (activation work
+ * fused into the producing kernel): with DP_RELU_IN in desc->flags, dx[n,h,w,c] is set to 0 where
+ * x_saved[n,h,w,c] <= 0.  x_saved [n,h,w,c_in] in io_dtype is the layer's forward input (post-ReLU output
+ * of the preceding layer, or its 2x2 max-pooled version: masking the pooled gradient by [pooled > 0] and
+ * then routing it through the pooling backward equals routing first and masking by [unpooled > 0]).
+ * Without the flag x_saved is ignored and may be NULL; dp_conv2d_bwd_data rejects the flag (no x_saved). */
+dp_status dp_conv2d_bwd_data_relu(const dp_conv_desc *desc, const void *dy, const void *y_saved_or_null,
+                                  const void *w, const void *x_saved, void *dx, void *ws, size_t ws_bytes,
+                                  void *hip_stream);
+
 /* Backward filter: dw[k,r,s,c] = sum_{n,p,q} g[n,p,q,k] * x[n, p*sh-ph+r, q*sw-pw+s, c];
  * dbias[k] = sum_{n,p,q} g[n,p,q,k] if dbias is given.  g as in dp_conv2d_bwd_data.
  * dw [c_out,r,s,c_in] fp32, dbias [c_out] fp32.  These are the per-layer gradients that
@@ -109,7 +123,8 @@ dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const vo
  *   g = dy * [y_saved > 0] (or dy);  dx = g W; dW = g^T x; dbias = sum_n g
  *                                                            each if its pointer != NULL
  * x [n,in], W [out,in], dy / y / y_saved [n,out], dx [n,in], dW [out,in] fp32, dbias [out] fp32.
- * Backward outputs need dy; dW needs x.  At least one output must be requested. */
+ * Backward outputs need dy; dW needs x.  At least one output must be requested.
+ * With DP_RELU_IN, dx is multiplied by [x > 0] (needs x). */
 dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const void *W,
                             const float *bias, const void *dy, const void *y_saved_or_null,
                             void *y, void *dx, float *dW, float *dbias,

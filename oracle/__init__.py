@@ -79,6 +79,12 @@ def conv2d_bwd_data(dy, w, xshape, y_saved=None, stride=(1, 1), pad=(0, 0)):
     return dx
 
 
+def relu_in_backward(dx, x_in):
+    """Backward of the ReLU that produced a layer's input, applied to that layer's data gradient:
+    dx * [x_in > 0] (derivative 0 at 0, as for the output-side mask)."""
+    return _d(dx) * (_d(x_in) > 0)
+
+
 def conv2d_bwd_filter(x, dy, wshape, y_saved=None, stride=(1, 1), pad=(0, 0), want_db=False):
     x, dy, y_saved = _d(x), _d(dy), _d(y_saved)
     d = _desc(x.shape, wshape, stride, pad)

@@ -11,10 +11,10 @@ from . import build as _build
 
 DP_OK, DP_ERR_NULL, DP_ERR_BAD_DESC, DP_ERR_UNSUPPORTED, DP_ERR_WORKSPACE, DP_ERR_HIP = range(6)
 DP_F32, DP_BF16 = 0, 1
-DP_BIAS, DP_RELU, DP_DETERMINISTIC, DP_DX_F32 = 1, 2, 4, 8
+DP_BIAS, DP_RELU, DP_DETERMINISTIC, DP_DX_F32, DP_RELU_IN = 1, 2, 4, 8, 16
 DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 
-EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data",
+EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_data_relu",
            "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
            "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
            "dp_plan_cost_tables", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
@@ -62,6 +62,8 @@ def _load():
     lib.dp_linear_workspace_bytes.argtypes = [P(dp_linear_desc)]
     lib.dp_conv2d_fwd.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, sz, vp]
     lib.dp_conv2d_bwd_data.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_conv2d_bwd_data_relu.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_conv2d_bwd_data_relu.restype = C.c_int
     lib.dp_conv2d_bwd_filter.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_linear_fwd_bwd.argtypes = [P(dp_linear_desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_relu_bias_grad_workspace_bytes.restype = sz
@@ -229,6 +231,12 @@ def dp_conv2d_fwd(desc, x, w, bias, y, ws=None, stream=None):
 def dp_conv2d_bwd_data(desc, dy, y_saved, w, dx, ws=None, stream=None):
     p, b = _ws(ws)
     _check(lib.dp_conv2d_bwd_data(C.byref(desc), _ptr(dy), _ptr(y_saved), _ptr(w), _ptr(dx), p, b, _stream(stream)))
+
+
+def dp_conv2d_bwd_data_relu(desc, dy, y_saved, w, x_saved, dx, ws=None, stream=None):
+    p, b = _ws(ws)
+    _check(lib.dp_conv2d_bwd_data_relu(C.byref(desc), _ptr(dy), _ptr(y_saved), _ptr(w), _ptr(x_saved), _ptr(dx), p, b,
+                                       _stream(stream)))
 
 
 def dp_conv2d_bwd_filter(desc, x, dy, y_saved, dw, dbias=None, ws=None, stream=None):

@@ -126,8 +126,11 @@ DEVFN void store_pixel_major_staged(const KArgs &p, const f32x16 (&acc)[FA][FB],
     for (int id = tid; id < TB * CPR; id += NT) {
         const int pix = id / CPR, cc = id % CPR;
         const int gp = b0 + pix, gc = a0 + cc * 8;
-        if (gp < p.rowsB && gc < p.rowsA)
-            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+        if (gp < p.rowsB && gc < p.rowsA) {
+            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+            if (p.flags & KF_MASK_IN) v = apply_mask(v, ldg16(p.x + (size_t)gp * p.rowsA + gc));
+            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = v;
+        }
     }
 }
 

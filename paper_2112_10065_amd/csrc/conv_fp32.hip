@@ -35,7 +35,7 @@ __device__ __forceinline__ float gm(const float *dy, const float *ym, size_t i)
     return (ym != nullptr && !(ym[i] > 0.f)) ? 0.f : dy[i];
 }
 
-__global__ __launch_bounds__(256) void k_f32_dgrad(ConvGeom g, const float *dy, const float *ym, const float *w, float *dx)
+__global__ __launch_bounds__(256) void k_f32_dgrad(ConvGeom g, const float *dy, const float *ym, const float *w, const float *xin, float *dx)
 {
     const long long total = (long long)g.N * g.H * g.W * g.C;
     for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (long long)gridDim.x * blockDim.x) {
@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void k_f32_dgrad(ConvGeom g, const float *dy, 
                     acc = fmaf(gm(dy, ym, gb + k), w[(((size_t)k * g.R + r) * g.S + s) * g.C + c], acc);
             }
         }
-        dx[e] = acc;
+        dx[e] = (xin == nullptr || xin[e] > 0.f) ? acc : 0.f;   // backward of the ReLU that produced the layer's input
     }
 }
 
@@ -102,9 +102,9 @@ hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const
     return hipGetLastError();
 }
 
-hipError_t f32_conv_dgrad(const ConvGeom &g, const float *dy, const float *ymask, const float *w, float *dx, hipStream_t st)
+hipError_t f32_conv_dgrad(const ConvGeom &g, const float *dy, const float *ymask, const float *w, const float *xin, float *dx, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_f32_dgrad, dim3(blocks_for((long long)g.N * g.H * g.W * g.C)), dim3(256), 0, st, g, dy, ymask, w, dx);
+    hipLaunchKernelGGL(k_f32_dgrad, dim3(blocks_for((long long)g.N * g.H * g.W * g.C)), dim3(256), 0, st, g, dy, ymask, w, xin, dx);
     return hipGetLastError();
 }
 

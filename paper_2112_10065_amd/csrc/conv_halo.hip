@@ -246,9 +246,12 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
     for (int id = tid; id < TB * CPR; id += NT) {
         const int pix = id / CPR, cc = id % CPR;
         const int pr = p0 + (pix >> tws), qc = q0 + (pix & (TW - 1)), gc = a0 + cc * 8;
-        if (pr < OH && qc < OW && gc < p.rowsA)
-            *reinterpret_cast<u32x4 *>(out + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc) =
-                *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+        if (pr < OH && qc < OW && gc < p.rowsA) {
+            const size_t o = ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc;
+            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+            if (PASS == PASS_DGRAD && (p.flags & KF_MASK_IN)) v = apply_mask(v, ldg16(p.x + o));
+            *reinterpret_cast<u32x4 *>(out + o) = v;
+        }
     }
 }
 

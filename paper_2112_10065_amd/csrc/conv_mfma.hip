@@ -506,6 +506,7 @@ __global__ __launch_bounds__(256) void k_reduce_pixel_major(const KArgs p)
             const int ch = (int)(e % p.rowsA);
             if (p.flags & KF_BIAS) for (int i = 0; i < 4; ++i) v[i] += p.bias[ch + i];
             if (p.flags & KF_RELU) for (int i = 0; i < 4; ++i) v[i] = v[i] > 0.f ? v[i] : 0.f;
+            if (p.flags & KF_MASK_IN) for (int i = 0; i < 4; ++i) v[i] = mask1f(v[i], p.x[e + i]);
             if (p.flags & KF_OUT_F32)
                 *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(p.out) + e) = f32x4{v[0], v[1], v[2], v[3]};
             else
@@ -518,6 +519,7 @@ __global__ __launch_bounds__(256) void k_reduce_pixel_major(const KArgs p)
             for (int sp = 1; sp < p.splits; ++sp) v += p.partial[sp * total + e];
             if (p.flags & KF_BIAS) v += p.bias[e % p.rowsA];
             if (p.flags & KF_RELU) v = v > 0.f ? v : 0.f;
+            if (p.flags & KF_MASK_IN) v = mask1f(v, p.x[e]);
             if (p.flags & KF_OUT_F32) reinterpret_cast<float *>(p.out)[e] = v;
             else reinterpret_cast<bf16_t *>(p.out)[e] = (bf16_t)f32_to_bf16(v);
         }
@@ -727,7 +729,7 @@ hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStrea
 {
     KArgs p{};
     p.rowsA = rowsA; p.rowsB = rowsB; p.splits = a.plan.splits; p.flags = a.flags;
-    p.bias = a.bias; p.out = a.out; p.partial = a.partial;
+    p.bias = a.bias; p.out = a.out; p.partial = a.partial; p.x = a.x;
     size_t total = (size_t)rowsA * rowsB;
     size_t work = (total + 3) / 4;
     unsigned nb = (unsigned)((work + 255) / 256);

@@ -51,7 +51,10 @@ dp_status hip_fail(hipError_t e, const char *what)
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 constexpr long long kMaxElems = (1ll << 31) - 1;
-constexpr unsigned kKnownFlags = DP_BIAS | DP_RELU | DP_DETERMINISTIC | DP_DX_F32;
+constexpr unsigned kKnownFlags = DP_BIAS | DP_RELU | DP_DETERMINISTIC | DP_DX_F32 | DP_RELU_IN;
+// kernels a backward-data call may not use: bit 0 the input-patch kernels (they stage bf16, the caller wants fp32),
+// bit 1 the stationary-weight kernel (it has no fused input-ReLU mask)
+int dgrad_restr(unsigned flags) { return ((flags & DP_DX_F32) ? 1 : 0) | ((flags & DP_RELU_IN) ? 2 : 0); }
 
 dp_status check_conv(const dp_conv_desc *d, ConvGeom *g)
 {
@@ -138,25 +141,25 @@ struct PlanEntry {
 };
 constexpr int kTuneCandidates = 12;
 
-// bf16_out = false: the caller wants fp32 results, which the input-patch kernels (bf16 staging) do not write
-PlanEntry &plan_entry(const ConvGeom &g, int pass, bool bf16_out = true)
+// restr: see dgrad_restr
+PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
 {
     thread_local std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> cache;
     const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
     const int at = g_analytic_only ? 0 : g_autotune.load();
-    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (bf16_out ? 0 : 2)}};
+    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (restr << 1)}};
     auto it = cache.find(key);
     if (it != cache.end()) return it->second;
     if (cache.size() > 4096) cache.clear();
     PlanEntry e;
     plan_uncached(g, pass, fv, fs, &e.plan);
-    const bool patch_ok = bf16_out || pass == PASS_WGRAD;
-    if (!patch_ok && e.plan.halo) {   // the best plan by the model that is not an input-patch kernel
+    auto banned = [&](const GemmPlan &pl) { return pl.halo && pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && pl.variant == 4)); };
+    if (banned(e.plan)) {   // the best plan by the model that is allowed
         GemmPlan list[kTuneCandidates];
         const int n = fv < 0 ? auto_plan_list(g, pass, fs, list, kTuneCandidates) : 0;
         int pick = -1;
         for (int i = 0; i < n && pick < 0; ++i)
-            if (!list[i].halo) pick = i;
+            if (!banned(list[i])) pick = i;
         if (pick >= 0) e.plan = list[pick];
         else {
             e.plan.dma = e.plan.halo = false;
@@ -167,10 +170,10 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass, bool bf16_out = true)
     if (at != 0 && fv < 0 && e.plan.fast) {
         GemmPlan list[kTuneCandidates];
         int n = auto_plan_list(g, pass, fs, list, kTuneCandidates);
-        if (!patch_ok) {
+        if (restr != 0) {
             int m = 0;
             for (int i = 0; i < n; ++i)
-                if (!list[i].halo) list[m++] = list[i];
+                if (!banned(list[i])) list[m++] = list[i];
             n = m;
         }
         if (n > 1) {
@@ -308,26 +311,29 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
 }
 
-size_t dgrad_ws_bytes(const ConvGeom &g, bool bf16_out)
+size_t dgrad_ws_bytes(const ConvGeom &g, int restr)
 {
-    const PlanEntry &pe = plan_entry(g, PASS_DGRAD, bf16_out);
+    const PlanEntry &pe = plan_entry(g, PASS_DGRAD, restr);
     size_t need = round256(pe.part_cap);
     if (pe.plan.fast) need += round256(ybytes(g));   // room for the masked gradient
     return need;
 }
 
-dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy, const void *ym, const void *w, void *dx,
-                    void *ws, size_t ws_bytes, hipStream_t st)
+// xin: the layer's saved input when flags has DP_RELU_IN (dx *= [xin > 0]), else ignored
+dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy, const void *ym, const void *w, const void *xin,
+                    void *dx, void *ws, size_t ws_bytes, hipStream_t st)
 {
+    if (!(flags & DP_RELU_IN)) xin = nullptr;
     if (dtype == DP_F32) {
-        hipError_t e = f32_conv_dgrad(g, (const float *)dy, (const float *)ym, (const float *)w, (float *)dx, st);
+        hipError_t e = f32_conv_dgrad(g, (const float *)dy, (const float *)ym, (const float *)w, (const float *)xin, (float *)dx, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 backward-data launch");
     }
     ConvArgs a{};
-    a.g = g; a.pass = PASS_DGRAD; a.flags = (flags & DP_DX_F32) ? KF_OUT_F32 : 0u;
-    PlanEntry &pe = plan_entry(g, PASS_DGRAD, !(flags & DP_DX_F32));
+    a.g = g; a.pass = PASS_DGRAD; a.flags = ((flags & DP_DX_F32) ? KF_OUT_F32 : 0u) | (xin != nullptr ? KF_MASK_IN : 0u);
+    a.x = (const bf16_t *)xin;
+    PlanEntry &pe = plan_entry(g, PASS_DGRAD, dgrad_restr(flags));
     a.plan = pe.plan;
-    size_t need = dgrad_ws_bytes(g, !(flags & DP_DX_F32));
+    size_t need = dgrad_ws_bytes(g, dgrad_restr(flags));
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
     if (a.plan.fast && ym != nullptr) {
@@ -480,7 +486,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
-    const GemmPlan pl = plan_entry(g, pass, pass != PASS_DGRAD || !(desc->flags & DP_DX_F32)).plan;
+    const GemmPlan pl = plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0).plan;
     if (name != nullptr && name_bytes > 0) { if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes); else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
@@ -493,7 +499,7 @@ size_t dp_conv2d_workspace_bytes(const dp_conv_desc *desc, int pass)
     if (pass == DP_PASS_WGRAD) return wgrad_ws_bytes(g, desc->io_dtype, true);
     if (desc->io_dtype == DP_F32) return 0;
     if (pass == DP_PASS_FWD) return fwd_ws_bytes(g);
-    return dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32));
+    return dgrad_ws_bytes(g, dgrad_restr(desc->flags));
 }
 
 size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
@@ -503,7 +509,7 @@ size_t dp_linear_workspace_bytes(const dp_linear_desc *desc)
     size_t need = wgrad_ws_bytes(g, desc->io_dtype, true);
     if (desc->io_dtype == DP_BF16) {
         for (int pass = 0; pass < 2; ++pass) {
-            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32)) : fwd_ws_bytes(g);
+            size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, dgrad_restr(desc->flags)) : fwd_ws_bytes(g);
             if (b > need) need = b;
         }
     }
@@ -530,17 +536,24 @@ dp_status dp_conv2d_fwd(const dp_conv_desc *desc, const void *x, const void *w, 
 dp_status dp_conv2d_bwd_data(const dp_conv_desc *desc, const void *dy, const void *y_saved, const void *w, void *dx, void *ws,
                              size_t ws_bytes, void *hip_stream)
 {
+    return dp_conv2d_bwd_data_relu(desc, dy, y_saved, w, nullptr, dx, ws, ws_bytes, hip_stream);
+}
+
+dp_status dp_conv2d_bwd_data_relu(const dp_conv_desc *desc, const void *dy, const void *y_saved, const void *w, const void *x_saved,
+                                  void *dx, void *ws, size_t ws_bytes, void *hip_stream)
+{
     ConvGeom g;
     dp_status s;
     if ((s = check_conv(desc, &g)) != DP_OK) return s;
     if ((s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(w, "w")) != DP_OK || (s = check_ptr(dx, "dx")) != DP_OK) return s;
+    if (desc->flags & DP_RELU_IN) { if ((s = check_ptr(x_saved, "x_saved (DP_RELU_IN)")) != DP_OK) return s; }
     if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(ws, "ws")) != DP_OK) return s;
     if (desc->io_dtype == DP_BF16) {
-        size_t need = dgrad_ws_bytes(g, !(desc->flags & DP_DX_F32));
+        size_t need = dgrad_ws_bytes(g, dgrad_restr(desc->flags));
         if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     }
     if ((s = ensure_init()) != DP_OK) return s;
-    return run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, w, dx, ws, ws_bytes, (hipStream_t)hip_stream);
+    return run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, w, x_saved, dx, ws, ws_bytes, (hipStream_t)hip_stream);
 }
 
 dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const void *dy, const void *y_saved, float *dw,
@@ -566,7 +579,7 @@ dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const voi
     if ((s = check_linear(desc, &g)) != DP_OK) return s;
     if (y == nullptr && dx == nullptr && dW == nullptr && dbias == nullptr) return fail(DP_ERR_NULL, "no output requested");
     const bool bwd = dx != nullptr || dW != nullptr || dbias != nullptr;
-    if (y != nullptr || dW != nullptr) { if ((s = check_ptr(x, "x")) != DP_OK) return s; }
+    if (y != nullptr || dW != nullptr || (dx != nullptr && (desc->flags & DP_RELU_IN))) { if ((s = check_ptr(x, "x")) != DP_OK) return s; }
     if (y != nullptr || dx != nullptr) { if ((s = check_ptr(W, "W")) != DP_OK) return s; }
     if (y != nullptr && (desc->flags & DP_BIAS)) { if ((s = check_ptr(bias, "bias")) != DP_OK) return s; }
     if (bwd) { if ((s = check_ptr(dy, "dy")) != DP_OK) return s; }
@@ -579,7 +592,7 @@ dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const voi
     hipStream_t st = (hipStream_t)hip_stream;
     // the passes run back to back on one stream and reuse the same workspace
     if (y != nullptr && (s = run_fwd(g, desc->io_dtype, desc->flags, x, W, bias, y, ws, ws_bytes, st)) != DP_OK) return s;
-    if (dx != nullptr && (s = run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, W, dx, ws, ws_bytes, st)) != DP_OK) return s;
+    if (dx != nullptr && (s = run_dgrad(g, desc->io_dtype, desc->flags, dy, y_saved, W, x, dx, ws, ws_bytes, st)) != DP_OK) return s;
     if ((dW != nullptr || dbias != nullptr) && (s = run_wgrad(g, desc->io_dtype, x, dy, y_saved, dW, dbias, ws, ws_bytes, st)) != DP_OK) return s;
     return DP_OK;
 }
@@ -642,7 +655,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
         size_t wsb = wgrad_ws_bytes(g, dtype, true);
         if (dtype == DP_BF16)
             for (int pass = 0; pass < 2; ++pass) {
-                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, !(flags & DP_DX_F32)) : fwd_ws_bytes(g);
+                size_t b = pass == PASS_DGRAD ? dgrad_ws_bytes(g, dgrad_restr(flags)) : fwd_ws_bytes(g);
                 if (b > wsb) wsb = b;
             }
         const size_t dxes = (flags & DP_DX_F32) ? 4 : es;
@@ -661,7 +674,7 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
             for (int it = 0; it < warmup + iters && result == DP_OK; ++it) {
                 if (it == warmup && (e = hipEventRecord(ev0, st)) != hipSuccess) { result = hip_fail(e, "hipEventRecord"); break; }
                 if (pass == 0) result = run_fwd(g, dtype, flags, x, w, (const float *)bias, y, ws, wsb, st);
-                else if (pass == 1) result = run_dgrad(g, dtype, flags, dy, ym, w, dx, ws, wsb, st);
+                else if (pass == 1) result = run_dgrad(g, dtype, flags, dy, ym, w, x, dx, ws, wsb, st);
                 else result = run_wgrad(g, dtype, x, dy, ym, (float *)dw, (float *)db, ws, wsb, st);
             }
             if (result != DP_OK) break;

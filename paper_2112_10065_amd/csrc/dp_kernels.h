@@ -10,6 +10,7 @@ enum : unsigned {
     KF_BIAS = 1u,     // add bias in the epilogue
     KF_RELU = 2u,     // max(.,0) in the epilogue
     KF_OUT_F32 = 4u,  // final output stored as fp32 instead of bf16
+    KF_MASK_IN = 8u,  // backward-data: dx *= [x > 0], x = the layer's saved input (output of the preceding ReLU)
 };
 
 enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
@@ -42,7 +43,7 @@ struct ConvArgs {
     GemmPlan plan;
     int pass;
     unsigned flags;
-    const bf16_t *x;      // fwd: x       dgrad: -        wgrad: x
+    const bf16_t *x;      // fwd: x       dgrad: saved input for KF_MASK_IN, else -        wgrad: x
     const bf16_t *w;      // fwd: w       dgrad: w        wgrad: -
     const bf16_t *dy;     // fwd: -       dgrad: dy       wgrad: dy
     const bf16_t *ymask;  // saved post-ReLU output or nullptr (dgrad, wgrad)
@@ -80,8 +81,8 @@ void halo_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_by
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
 hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,
                         const float *bias, float *y, hipStream_t st);
-hipError_t f32_conv_dgrad(const ConvGeom &g, const float *dy, const float *ymask, const float *w,
-                          float *dx, hipStream_t st);
+hipError_t f32_conv_dgrad(const ConvGeom &g, const float *dy, const float *ymask, const float *w, const float *xin,
+                          float *dx, hipStream_t st);   // xin (may be NULL): dx *= [xin > 0]
 hipError_t f32_conv_wgrad(const ConvGeom &g, const float *x, const float *dy, const float *ymask,
                           float *dw, hipStream_t st);
 

@@ -38,6 +38,7 @@ DEVFN u32x4 apply_mask(u32x4 v, u32x4 y)
     v.x &= keep_bits(y.x); v.y &= keep_bits(y.y); v.z &= keep_bits(y.z); v.w &= keep_bits(y.w);
     return v;
 }
+DEVFN float mask1f(float v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : 0.f; }
 DEVFN bf16_t mask1(bf16_t v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : (bf16_t)0; }
 
 // fp32 -> bf16, round to nearest even, NaN stays NaN: the gfx950 conversion instruction
@@ -117,6 +118,8 @@ DEVFN void store_pixel_major(const KArgs &p, const f32x16 (&acc)[FA][FB], int ar
                     for (int e = 0; e < 4; ++e) if (ch + e < p.rowsA) v[e] += p.bias[ch + e];
                 if (p.flags & KF_RELU)
                     for (int e = 0; e < 4; ++e) v[e] = v[e] > 0.f ? v[e] : 0.f;
+                if (p.flags & KF_MASK_IN)
+                    for (int e = 0; e < 4; ++e) if (ch + e < p.rowsA) v[e] = mask1f(v[e], p.x[o + e]);
                 if (p.flags & KF_OUT_F32) {
                     float *dst = reinterpret_cast<float *>(p.out) + o;
                     if (vec4) *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};

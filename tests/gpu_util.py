@@ -80,6 +80,16 @@ class ConvCase:
         dp.dp_conv2d_bwd_data(self.desc, self.dyd, y_saved, self.wd, dx, ws if ws is not None else self.ws())
         return dx
 
+    def run_dgrad_relu_in(self, y_saved, ws=None):
+        """Backward-data with the backward of the ReLU in front of the layer fused in: dx * [x > 0]."""
+        n, h, w, c, k, r, s = self.shape
+        d = dp.dp_conv_desc.from_buffer_copy(self.desc)
+        d.flags |= dp.DP_RELU_IN
+        dx = torch.full((n, h, w, c), 3.0, dtype=torch.float32 if self.dx_f32 else self.tdt, device=DEV)
+        wsb = workspace(max(dp.dp_conv2d_workspace_bytes(d, p) for p in range(3))) if ws is None else ws
+        dp.dp_conv2d_bwd_data_relu(d, self.dyd, y_saved, self.wd, self.xd, dx, wsb)
+        return dx
+
     def run_wgrad(self, y_saved, want_db=True, ws=None):
         n, h, w, c, k, r, s = self.shape
         dw = torch.empty((k, r, s, c), dtype=torch.float32, device=DEV)

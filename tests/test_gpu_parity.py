@@ -226,6 +226,77 @@ def test_input_patch_variants(env, variant):
         dp.dp_set_override(1, -1, 0)
 
 
+RELU_IN_CASES = [
+    # tag, n, h, w, c, k, r, s, stride, pad, bf16, dx_f32, (variant, splits) overrides of the backward-data pass
+    ("mask_pipe", 2, 13, 12, 72, 128, 3, 3, (1, 1), (1, 1), True, False, [(-1, 0), (200, 1), (200, 3), (204, 1), (226, 1), (100, 1), (103, 2), (0, 1), (2, 3)]),
+    ("mask_patch", 2, 20, 33, 96, 64, 3, 3, (1, 1), (1, 1), True, False, [(-1, 0), (400, 0), (403, 0), (404, 0)]),
+    ("mask_stride2", 2, 15, 15, 64, 64, 3, 3, (2, 2), (1, 1), True, False, [(-1, 0), (200, 1), (200, 2)]),
+    ("mask_1x1", 3, 14, 14, 256, 64, 1, 1, (1, 1), (0, 0), True, False, [(-1, 0), (207, 2)]),
+    ("mask_odd_channels", 2, 9, 10, 24, 40, 3, 3, (1, 1), (1, 1), True, False, [(-1, 0), (1, 2)]),
+    ("mask_c12", 1, 8, 8, 12, 16, 3, 3, (1, 1), (1, 1), True, False, [(-1, 0)]),
+    ("mask_dx_f32", 2, 13, 12, 72, 64, 3, 3, (1, 1), (1, 1), True, True, [(-1, 0), (200, 1), (200, 3), (404, 0)]),
+    ("mask_fp32", 2, 9, 8, 5, 7, 3, 3, (1, 1), (1, 1), False, False, [(-1, 0)]),
+]
+
+
+@pytest.mark.parametrize("spec", RELU_IN_CASES, ids=[c[0] for c in RELU_IN_CASES])
+def test_backward_data_with_fused_input_relu(env, spec):
+    """DP_RELU_IN: dx * [x > 0] leaves in the epilogue of every backward-data kernel family (staged and direct
+    stores, split reductions, input-patch kernels; the stationary-weight kernel hands over to another one)."""
+    dp, U, orc = env
+    tag, n, h, w, c, k, r, s_, st, pd, bf16, dxf, overrides = spec
+    case = U.ConvCase(tag, n, h, w, c, k, r, s_, st, pd, bf16=bf16, bias=True, relu=True, dx_f32=dxf)
+    # the layer's input as a ReLU would leave it: about half zeros
+    x = np.maximum(case.x, 0.0).astype(np.float32)
+    case.x = x
+    case.xd = U.bf16_dev(U.synth.f32_to_bf16_bits(x)) if bf16 else torch.from_numpy(x).to(U.DEV)
+    y = case.run_fwd()
+    torch.cuda.synchronize()
+    want = orc.relu_in_backward(orc.conv2d_bwd_data(case.dy, case.w, x.shape, y_saved=U.to_np(y), stride=st, pad=pd), x)
+    assert (want == 0).mean() > 0.3
+    for variant, splits in overrides:
+        dp.dp_set_override(1, variant, splits)
+        try:
+            dx = case.run_dgrad_relu_in(y)
+            torch.cuda.synchronize()
+        finally:
+            dp.dp_set_override(1, -1, 0)
+        got = U.to_np(dx)
+        assert np.array_equal(got == 0, want == 0) or np.abs(got[(got == 0) != (want == 0)]).max() < 1e-30, f"{tag} {variant}/{splits}: mask differs"
+        if bf16:
+            U.assert_bf16_close(got, want, f"{tag} variant {variant} splits {splits}")
+        else:
+            U.assert_f32_close(got, want, f"{tag} fp32")
+    # without the flag the saved input is ignored; the flag without a saved input is an error
+    dx_plain = torch.empty_like(dx)
+    dp.dp_conv2d_bwd_data_relu(case.desc, case.dyd, y, case.wd, case.xd, dx_plain, case.ws())
+    torch.cuda.synchronize()
+    ref_plain = orc.conv2d_bwd_data(case.dy, case.w, x.shape, y_saved=U.to_np(y), stride=st, pad=pd)
+    (U.assert_bf16_close if bf16 else U.assert_f32_close)(U.to_np(dx_plain), ref_plain, f"{tag} unmasked")
+    d = dp.dp_conv_desc.from_buffer_copy(case.desc)
+    d.flags |= dp.DP_RELU_IN
+    with pytest.raises(dp.DpError):
+        dp.dp_conv2d_bwd_data(d, case.dyd, y, case.wd, dx_plain, case.ws())
+
+
+def test_dense_backward_with_fused_input_relu(env):
+    dp, U, orc = env
+    for n, i, o in ((4, 256, 72), (32, 1024, 1000), (1, 4096, 1000)):
+        x, W, b = U.synth.linear_tensors(f"fcmask/{n}/{i}/{o}", n, i, o)
+        x = np.maximum(U.synth.round_bf16(x), 0.0)
+        W = U.synth.round_bf16(W)
+        dy = U.synth.round_bf16(U.synth.upstream_grad(f"fcmask/{n}/{i}/{o}", (n, o)))
+        xd, Wd, dyd = (U.bf16_dev(U.synth.f32_to_bf16_bits(a)) for a in (x, W, dy))
+        d = dp.linear_desc(n, i, o, dp.DP_BF16, dp.DP_RELU_IN)
+        dx = torch.empty((n, i), dtype=torch.bfloat16, device=U.DEV)
+        ws = U.workspace(dp.dp_linear_workspace_bytes(d))
+        dp.dp_linear_fwd_bwd(d, x=xd, W=Wd, dy=dyd, dx=dx, ws=ws)
+        torch.cuda.synchronize()
+        want = orc.relu_in_backward(orc.linear_bwd(x, W, dy)[0], x)
+        U.assert_bf16_close(U.to_np(dx), want, f"dense {n}x{i}x{o}")
+        assert np.array_equal(U.to_np(dx) == 0, want == 0)
+
+
 @pytest.mark.parametrize("blocks", [0, 1, 7])
 def test_input_patch_stationary_weights(env, blocks):
     """3x3, stride 1, 64 reduction channels: persistent kernel with the weight fragments in registers.  Block
