@@ -31,12 +31,11 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 134968821,
-    "k_halo_ws<0>": 320770711,
-    "k_fwd_direct": 226674838,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 213924371,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>": 220347557,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>": 36822106
+    "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 127196741,
+    "k_halo_ws<0>": 270301755,
+    "k_fwd_direct": 226680849,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 213703338,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>": 12021069
 }
 
 

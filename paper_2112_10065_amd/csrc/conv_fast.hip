@@ -119,18 +119,45 @@ DEVFN void store_pixel_major_staged(const KArgs &p, const f32x16 (&acc)[FA][FB],
                     u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
             }
         }
-    __syncthreads();
     constexpr int CPR = TA / 8;
     bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+    if (p.flags & KF_MASK_IN) {
+        // fused backward of the input ReLU: the saved-input vectors are requested in groups of eight before
+        // they are needed (the first group before the staging barrier), so that their latency overlaps
+        constexpr int ITERS = (TB * CPR + NT - 1) / NT, GRP = ITERS < 8 ? ITERS : 8;
+        static_assert(ITERS % GRP == 0, "copy-out iterations come in whole groups");
+        u32x4 xm[GRP];
+        auto fetch = [&](int g0) {
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) {
+                const int id = tid + (g0 + u) * NT, pix = id / CPR, cc = id % CPR;
+                const int gp = b0 + pix, gc = a0 + cc * 8;
+                xm[u] = (id < TB * CPR && gp < p.rowsB && gc < p.rowsA) ? ldg16(p.x + (size_t)gp * p.rowsA + gc) : u32x4{0, 0, 0, 0};
+            }
+        };
+        fetch(0);
+        __syncthreads();
+#pragma unroll
+        for (int g0 = 0; g0 < ITERS; g0 += GRP) {
+            if (g0 > 0) fetch(g0);
+#pragma unroll
+            for (int u = 0; u < GRP; ++u) {
+                const int id = tid + (g0 + u) * NT, pix = id / CPR, cc = id % CPR;
+                const int gp = b0 + pix, gc = a0 + cc * 8;
+                if (id < TB * CPR && gp < p.rowsB && gc < p.rowsA)
+                    *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) =
+                        apply_mask(*reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8), xm[u]);
+            }
+        }
+        return;
+    }
+    __syncthreads();
 #pragma unroll
     for (int id = tid; id < TB * CPR; id += NT) {
         const int pix = id / CPR, cc = id % CPR;
         const int gp = b0 + pix, gc = a0 + cc * 8;
-        if (gp < p.rowsB && gc < p.rowsA) {
-            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
-            if (p.flags & KF_MASK_IN) v = apply_mask(v, ldg16(p.x + (size_t)gp * p.rowsA + gc));
-            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = v;
-        }
+        if (gp < p.rowsB && gc < p.rowsA)
+            *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
     }
 }
 

@@ -239,19 +239,39 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
                 *reinterpret_cast<u32x2 *>(stage + pix * LSO + ch) = u32x2{pack_bf16(v0, v1), pack_bf16(v2, v3)};
             }
         }
-    __syncthreads();
     constexpr int CPR = TA / 8;
     bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
+    if (PASS == PASS_DGRAD && (p.flags & KF_MASK_IN)) {
+        // fused backward of the input ReLU: all saved-input vectors of this thread are requested before the
+        // staging barrier, so that their latency overlaps
+        constexpr int ITERS = TB * CPR / NT;
+        static_assert(TB * CPR % NT == 0 && ITERS <= 16, "copy-out iterations");
+        u32x4 xm[ITERS];
+#pragma unroll
+        for (int u = 0; u < ITERS; ++u) {
+            const int id = tid + u * NT, pix = id / CPR, cc = id % CPR;
+            const int pr = p0 + (pix >> tws), qc = q0 + (pix & (TW - 1)), gc = a0 + cc * 8;
+            xm[u] = (pr < OH && qc < OW && gc < p.rowsA) ? ldg16(p.x + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc) : u32x4{0, 0, 0, 0};
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < ITERS; ++u) {
+            const int id = tid + u * NT, pix = id / CPR, cc = id % CPR;
+            const int pr = p0 + (pix >> tws), qc = q0 + (pix & (TW - 1)), gc = a0 + cc * 8;
+            if (pr < OH && qc < OW && gc < p.rowsA)
+                *reinterpret_cast<u32x4 *>(out + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc) =
+                    apply_mask(*reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8), xm[u]);
+        }
+        return;
+    }
+    __syncthreads();
 #pragma unroll
     for (int id = tid; id < TB * CPR; id += NT) {
         const int pix = id / CPR, cc = id % CPR;
         const int pr = p0 + (pix >> tws), qc = q0 + (pix & (TW - 1)), gc = a0 + cc * 8;
-        if (pr < OH && qc < OW && gc < p.rowsA) {
-            const size_t o = ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc;
-            u32x4 v = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
-            if (PASS == PASS_DGRAD && (p.flags & KF_MASK_IN)) v = apply_mask(v, ldg16(p.x + o));
-            *reinterpret_cast<u32x4 *>(out + o) = v;
-        }
+        if (pr < OH && qc < OW && gc < p.rowsA)
+            *reinterpret_cast<u32x4 *>(out + ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + gc) =
+                *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
     }
 }
 

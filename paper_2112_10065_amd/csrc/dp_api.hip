@@ -107,12 +107,14 @@ dp_status check_opt(const void *p, const char *name)
 
 // tile_variant override: -1 built-in choice (fast path when the shape allows), 0..99 generic
 // kernel variant, 100.. fast-path variant (falls back to the generic kernel if not eligible)
-void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl)
+void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, int restr)
 {
     pl->dma = false;
     pl->halo = false;
-    if (fv < 0 && auto_plan(g, pass, fs, pl)) return;
-    if (fv >= 400 && halo_plan(g, pass, fv, fs, pl)) return;
+    if (fv < 0 && auto_plan(g, pass, fs, pl, restr)) return;
+    // a forced input-patch variant the call may not use falls through to the next family
+    const bool patch_banned = pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && fv == 404));
+    if (fv >= 400 && !patch_banned && halo_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 200 && dma_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 100 && fast_plan(g, pass, fv, fs, pl)) return;
     mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
@@ -152,30 +154,11 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
     if (it != cache.end()) return it->second;
     if (cache.size() > 4096) cache.clear();
     PlanEntry e;
-    plan_uncached(g, pass, fv, fs, &e.plan);
-    auto banned = [&](const GemmPlan &pl) { return pl.halo && pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && pl.variant == 4)); };
-    if (banned(e.plan)) {   // the best plan by the model that is allowed
-        GemmPlan list[kTuneCandidates];
-        const int n = fv < 0 ? auto_plan_list(g, pass, fs, list, kTuneCandidates) : 0;
-        int pick = -1;
-        for (int i = 0; i < n && pick < 0; ++i)
-            if (!banned(list[i])) pick = i;
-        if (pick >= 0) e.plan = list[pick];
-        else {
-            e.plan.dma = e.plan.halo = false;
-            if (!fast_plan(g, pass, -1, fs, &e.plan)) mfma_plan(g, pass, -1, fs, &e.plan);
-        }
-    }
+    plan_uncached(g, pass, fv, fs, &e.plan, restr);
     e.part_cap = mfma_partial_bytes(g, pass, e.plan);
     if (at != 0 && fv < 0 && e.plan.fast) {
         GemmPlan list[kTuneCandidates];
-        int n = auto_plan_list(g, pass, fs, list, kTuneCandidates);
-        if (restr != 0) {
-            int m = 0;
-            for (int i = 0; i < n; ++i)
-                if (!banned(list[i])) list[m++] = list[i];
-            n = m;
-        }
+        const int n = auto_plan_list(g, pass, fs, list, kTuneCandidates, restr);
         if (n > 1) {
             e.cands.assign(list, list + n);
             e.tuned = false;

@@ -92,9 +92,10 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
                       void *g_out, float *dbias, float *ws, hipStream_t st);
 
 // planner.hip : picks the cheapest fast-path variant and split for a pass (host-side cost model)
-bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *plan);
+bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *plan, int restr = 0);
 // the cheapest plans by the model, best first (input of the measured choice); returns the count
-int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out, int max_out);
+// restr: kernels the call may not use (bit 0: input-patch kernels, bit 1: the stationary-weight kernel)
+int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out, int max_out, int restr = 0);
 
 // small_c.hip : explicit im2col for layers with very few input channels (c_in % 8 != 0, R*S*C <= 256)
 int small_c_kpad(const ConvGeom &g);   // padded reduction length, 0 if the layer does not qualify

@@ -45,7 +45,7 @@ const Candidate kPix[] = {
     {401, 2, 1.20f, 6.0f},   // same, 128 x 256
     {402, 2, 0.75f, 5.5f},
     {403, 2, 0.72f, 5.5f},
-    {404, 1, 0.27f, 0.8f},   // 3x3 only: persistent blocks, weights in registers
+    {404, 1, 0.50f, 0.8f},   // 3x3 only: persistent blocks, weights in registers
     {100, 2, 1.40f, 5.0f},   // register-staged fallbacks (also reduction step 32)
     {101, 3, 1.05f, 4.5f},
     {102, 3, 1.05f, 4.5f},
@@ -110,7 +110,7 @@ double price(const ConvGeom &g, int pass, const Candidate &c, const GemmPlan &pl
 
 // Eligible fast-path plans of a pass, cheapest first by the model, at most two split counts per tile
 // variant; returns how many were written (0: the shape has no fast-path plan).
-int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out, int max_out)
+int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out, int max_out, int restr)
 {
     struct Priced { double t; GemmPlan pl; int code; };
     Priced all[512];
@@ -134,6 +134,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
     const Candidate *cands = pass == PASS_WGRAD ? kWg : kPix;
     const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
     for (int ci = 0; ci < ncand; ++ci) {
+        if (pass != PASS_WGRAD && cands[ci].code >= 400 && ((restr & 1) || ((restr & 2) && cands[ci].code == 404))) continue;
         int last_splits = -1;
         for (int s : kSplits) {
             if (force_splits > 0 && s != kSplits[0]) break;
@@ -175,7 +176,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
 }
 
 // Fills *pl with the cheapest eligible fast-path plan; false if the shape has none.
-bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl)
+bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *pl, int restr)
 {
-    return auto_plan_list(g, pass, force_splits, pl, 1) == 1;
+    return auto_plan_list(g, pass, force_splits, pl, 1, restr) == 1;
 }
