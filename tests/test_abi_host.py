@@ -130,3 +130,16 @@ def test_glue_argument_errors(dp):
     assert lib.dp_sgd_update(-1, 0.1, 0.9, A, A, A, None, None) == dp.DP_ERR_BAD_DESC
     assert lib.dp_sgd_update(16, 0.1, 0.9, A, A + 4, A, None, None) == dp.DP_ERR_BAD_DESC
     assert lib.dp_sgd_update(0, 0.1, 0.9, A, A, A, None, None) == dp.DP_OK   # nothing to do, nothing launched
+
+
+def test_fused_input_relu_argument_errors(dp):
+    lib = dp.lib
+    d = dp.conv_desc(2, 16, 16, 16, 16, 3, 3, (1, 1), (1, 1), dp.DP_BF16, dp.DP_RELU_IN)
+    assert lib.dp_conv2d_bwd_data(C.byref(d), A, None, A, A, None, 0, None) == dp.DP_ERR_NULL        # no saved input to mask with
+    assert b"x_saved" in lib.dp_last_error()
+    assert lib.dp_conv2d_bwd_data_relu(C.byref(d), A, None, A, None, A, None, 0, None) == dp.DP_ERR_NULL
+    assert lib.dp_conv2d_bwd_data_relu(C.byref(d), A, None, A, A + 8, A, None, 0, None) == dp.DP_ERR_BAD_DESC  # misaligned
+    ld = dp.linear_desc(4, 64, 32, dp.DP_BF16, dp.DP_RELU_IN)
+    assert lib.dp_linear_fwd_bwd(C.byref(ld), None, A, None, A, None, None, A, None, None, None, 0, None) == dp.DP_ERR_NULL  # dx needs x
+    # the flag changes which kernels a call may use, so the workspace query takes it into account without failing
+    assert dp.dp_conv2d_workspace_bytes(d, 1) >= 0
