@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--side-streams", type=int, default=2, help="streams that run the filter gradients beside the backward chain")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying one HIP graph per step")
-    ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception"],
+    ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception", "wrn101_2"],
                     help="layer list; the metric and the default run are VGG-16, the others emit their own tables")
     ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
@@ -269,7 +269,7 @@ def main():
     nmax = max(batches)
 
     keep = set(args.layers.split(",")) if args.layers else None
-    convs = {"vgg16": W.vgg16_convs, "resnet50": W.resnet50_convs, "inception": W.inception_convs}[args.workload]()
+    convs = {"vgg16": W.vgg16_convs, "resnet50": W.resnet50_convs, "inception": W.inception_convs, "wrn101_2": W.wrn101_2_convs}[args.workload]()
     linears = W.vgg16_linears() if args.workload == "vgg16" else []
     layers = [Layer(torch, dp, l, nmax, gen, dev, True) for l in convs if keep is None or l.name in keep]
     layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in linears if keep is None or l.name in keep]
@@ -451,7 +451,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "strong", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic (seeded N(0,1) activations/gradients, He-normal weights)",
         "config": {"workload": {"vgg16": "VGG-16 13 conv + 3 FC layers, 224x224x3 input", "resnet50": "ResNet-50 conv layers (23 unique shapes), 224x224x3 input",
-                                "inception": "Inception-v3-style conv layers (18 shapes), 299x299x3 input"}[args.workload]
+                                "inception": "Inception-v3-style conv layers (18 shapes), 299x299x3 input",
+                                "wrn101_2": "wide ResNet-101-2 conv layers (24 unique shapes), 400x400x3 input"}[args.workload]
                                + ", per layer fwd (bias + ReLU fused) + dgrad (backward of the ReLU in front of the layer fused, "
                                "so incoming gradients are already masked) + wgrad with bias gradient (first layer: no dgrad), "
                                + ("layers " + args.layers + ", " if args.layers else "")

@@ -1,8 +1,8 @@
 """Layer shapes of the synthetic workloads (no arithmetic).
 
-VGG-16 / ResNet-50 / Inception-v3-style layer lists stand in for the models the
-paper trains (paper, Table 1: VGG-16 at 3x224x224; Inception-v3 at 3x299x299;
-its wide ResNet is replaced by ResNet-50 at 224).  Per-GPU batch sizes are the
+VGG-16 / ResNet-50 / Inception-v3-style / wide-ResNet-101-2 layer lists stand in for the
+models the paper trains (paper, Table 1: VGG-16 at 3x224x224; Inception-v3 at 3x299x299;
+WRN-101-2 at 3x400x400; ResNet-50 at 224 is the smaller stand-in the parity configs name).  Per-GPU batch sizes are the
 strong-scaling shards global_batch / g with g a power of two (paper, section 6
 "Restricting GPU counts to powers of two").
 """
@@ -71,6 +71,39 @@ def resnet50_convs():
     add("s4_proj_1024_2048_s2", 14, 1024, 2048, 1, 2)
     add("s4_1x1_2048_512", 7, 2048, 512, count=2)
     add("s4_3x3_512", 7, 512, 512, 3, 1, 2)
+    return L
+
+
+def wrn101_2_convs():
+    """Unique conv shapes of a wide ResNet-101-2 at 400x400 input (the paper's second image model, Table 1):
+    bottlenecks with doubled inner widths 128/256/512/1024, outputs 256/512/1024/2048, 3/4/23/3 blocks,
+    stride 2 on the 3x3; spatial sizes 200 (stem) -> 100 -> 50 -> 25 -> 13."""
+    L = [_c("stem7x7_400", 400, 3, 64, 7, 7, 2, 3, 3, bias=False)]
+    def add(name, hw, c, k, r=1, st=1, count=1):
+        L.append(_c(name, hw, c, k, r, r, st, r // 2, r // 2, bias=False, count=count))
+    add("w1_1x1_64_128", 100, 64, 128)
+    add("w1_3x3_128", 100, 128, 128, 3, 1, 3)
+    add("w1_1x1_128_256", 100, 128, 256, count=3)
+    add("w1_proj_64_256", 100, 64, 256)
+    add("w1_1x1_256_128", 100, 256, 128, count=2)
+    add("w2_1x1_256_256", 100, 256, 256)
+    add("w2_3x3_256_s2", 100, 256, 256, 3, 2)
+    add("w2_1x1_256_512", 50, 256, 512, count=4)
+    add("w2_proj_256_512_s2", 100, 256, 512, 1, 2)
+    add("w2_1x1_512_256", 50, 512, 256, count=3)
+    add("w2_3x3_256", 50, 256, 256, 3, 1, 3)
+    add("w3_1x1_512_512", 50, 512, 512)
+    add("w3_3x3_512_s2", 50, 512, 512, 3, 2)
+    add("w3_1x1_512_1024", 25, 512, 1024, count=23)
+    add("w3_proj_512_1024_s2", 50, 512, 1024, 1, 2)
+    add("w3_1x1_1024_512", 25, 1024, 512, count=22)
+    add("w3_3x3_512", 25, 512, 512, 3, 1, 22)
+    add("w4_1x1_1024_1024", 25, 1024, 1024)
+    add("w4_3x3_1024_s2", 25, 1024, 1024, 3, 2)
+    add("w4_1x1_1024_2048", 13, 1024, 2048, count=3)
+    add("w4_proj_1024_2048_s2", 25, 1024, 2048, 1, 2)
+    add("w4_1x1_2048_1024", 13, 2048, 1024, count=2)
+    add("w4_3x3_1024", 13, 1024, 1024, 3, 1, 2)
     return L
 
 

@@ -625,3 +625,12 @@ def test_inception_layers_sampled(env, li):
     dp, U, orc = env
     l = _inception_layers()[li]
     _sampled_layer_check(dp, U, orc, l, 1 if l.h > 100 else 4, "inception")
+
+
+@pytest.mark.parametrize("li", range(24))
+def test_wrn101_2_layers_sampled(env, li):
+    """Wide ResNet-101-2 at 400x400 (the paper's second image model): every unique conv shape, sampled."""
+    dp, U, orc = env
+    from paper_2112_10065_amd import workloads
+    l = workloads.wrn101_2_convs()[li]
+    _sampled_layer_check(dp, U, orc, l, 1 if l.h > 100 else 2, "wrn101_2")
