@@ -525,6 +525,26 @@ def _full_size_case(dp, U, orc, name, hw, c, k, n, dxf):
     dw_np = U.to_np(dw)
     idx = rng.integers(0, dw_np.size, 600)
     U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, y_np, (1, 1), (1, 1), idx), f"{name} dw")
+    # the calls of bench.py's step: the incoming gradient is taken as already masked (no saved output), backward-data
+    # applies the backward of the ReLU in front of the layer, the filter-gradient call also sums the bias gradient
+    del dx, dw
+    if not dxf:
+        dx = case.run_dgrad_relu_in(None)
+    dw, db = case.run_wgrad(None)
+    torch.cuda.synchronize()
+    if not dxf:
+        dx_np = U.to_np(dx)
+        idx = rng.integers(0, dx_np.size, 3000)
+        idx[:32] = np.arange(32)
+        idx[32:64] = dx_np.size - 1 - np.arange(32)
+        want = orc.conv2d_bwd_data_at(case.dy, case.w, case.x.shape, None, (1, 1), (1, 1), idx) * (case.x.ravel()[idx] > 0)
+        U.assert_bf16_close(dx_np.ravel()[idx], want, f"{name} dx with the input ReLU")
+        assert not dx_np.ravel()[idx][case.x.ravel()[idx] <= 0].any()
+    dw_np = U.to_np(dw)
+    idx = rng.integers(0, dw_np.size, 600)
+    U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, None, (1, 1), (1, 1), idx), f"{name} dw unmasked")
+    rel, _ = U.errs(U.to_np(db), case.dy.reshape(-1, case.dy.shape[-1]).astype(np.float64).sum(axis=0))
+    assert rel <= U.BF16_REL, f"{name} db rel_l2={rel:.3e}"
 
 
 def test_fc6_full_size_sampled(env):
