@@ -371,6 +371,16 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
+    // fused bias gradient: the blocks of the first tap tile also multiply their dy^T fragments with ones; the WB
+    // waves that share a row range take turns over its FA fragments (fragment ii belongs to wave column ii % WB)
+    constexpr int DBF = (FA + WB - 1) / WB;
+    const bool do_db = (p.flags & KF_DB) != 0 && b0 == 0;
+    const int wb_ = wave / WA;
+    f32x16 accdb[DBF];
+#pragma unroll
+    for (int i = 0; i < DBF; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accdb[i][v] = 0.f;
 
     // transpose-read addresses: lane l of a 16-lane block points at reduction row ks*16 + 8*(l>>5) + (l&15)/4
     // (and 4 rows further for the second half), operand rows row0 + 16*((l>>4)&1) + 4*(l&3) .. +3
@@ -452,9 +462,22 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
                     acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv),
                                                                          acc[ii][jj], 0, 0, 0);
                 }
+            if (do_db) {
+#pragma unroll
+                for (int ii = 0; ii < FA; ++ii)
+                    if (ii % WB == wb_) {
+                        const u32x4 av = {alo[cur][ii].x, alo[cur][ii].y, ahi[cur][ii].x, ahi[cur][ii].y};
+                        accdb[ii / WB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), ones_bf16(), accdb[ii / WB], 0, 0, 0);
+                    }
+            }
         }
     }
     store_row_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, split);
+    if (do_db) {
+#pragma unroll
+        for (int ii = 0; ii < FA; ++ii)
+            if (ii % WB == wb_) store_db_fragment(accdb[ii / WB], p.dbp + (size_t)split * p.rowsA, a0 + arow + ii * 32, p.rowsA, lane);
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -861,11 +884,13 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     p.flags = a.flags;
     p.x = a.x; p.w = a.w; p.dy = a.dy; p.ymask = nullptr; p.bias = a.bias; p.out = a.out; p.partial = a.partial;
     const bool wg = a.pass == PASS_WGRAD;
+    p.dbp = p.splits > 1 ? a.db_partial : a.db_out;
+    if (!wg || p.dbp == nullptr || !plan_sums_bias_gradient(a.plan)) p.flags &= ~KF_DB;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB * d.KG, 1, 1);
     if (wg) grid = dim3((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1);
     hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
-    return launch_split_reduce(a, p.rowsA, p.rowsB, st);
+    return launch_split_reduce(a, p.rowsA, p.rowsB, st, (p.flags & KF_DB) != 0);
 }

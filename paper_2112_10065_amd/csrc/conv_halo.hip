@@ -781,6 +781,7 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         p.tilesA = a.plan.tilesA; p.tilesB = 1; p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split;
         p.splits = a.plan.splits; p.flags = a.flags;
         p.x = a.x; p.w = nullptr; p.dy = a.dy; p.ymask = nullptr; p.bias = nullptr; p.out = a.out; p.partial = a.partial;
+        p.dbp = nullptr; p.flags &= ~KF_DB;   // this kernel does not sum the bias gradient (its tap waves are evenly loaded as they are)
         const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
         const int tiles_x = (g.Wo + tw - 1) / tw, tiles_y = (g.Ho + th - 1) / th;
         hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * g.R * g.S), 2 * WH_BUF, st, p, tws,

@@ -526,9 +526,22 @@ __global__ __launch_bounds__(256) void k_reduce_pixel_major(const KArgs p)
     }
 }
 
-__global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float *out, size_t total, int splits)
+// Blocks nb1 .. gridDim.x-1 of the two backward-filter reductions sum a second, small array in split order
+// (the fused bias gradient: partial2 [splits][total2] -> out2 [total2]), one column per thread.
+DEVFN void reduce_second(int blk, const float *partial2, float *out2, int total2, int splits)
 {
-    const size_t gstride = (size_t)gridDim.x * blockDim.x;
+    const int col = blk * 256 + threadIdx.x;
+    if (col >= total2) return;
+    float v = partial2[col];
+    for (int sp = 1; sp < splits; ++sp) v += partial2[(size_t)sp * total2 + col];
+    out2[col] = v;
+}
+
+__global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float *out, size_t total, int splits, int nb1,
+                                                      const float *partial2, float *out2, int total2)
+{
+    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, splits); return; }
+    const size_t gstride = (size_t)nb1 * blockDim.x;
     if ((total & 3) == 0) {
         for (size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; e < total; e += gstride * 4) {
             // four independent loads in flight; the sum order is fixed by the code, not by timing
@@ -554,8 +567,10 @@ __global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float
 
 // Many splits over a small output (long reductions into a small filter): 8 threads share one group
 // of four outputs, each sums every 8th partial, the 8 part sums are combined through LDS in order.
-__global__ __launch_bounds__(256) void k_reduce_flat_wide(const float *partial, float *out, size_t total, int splits)
+__global__ __launch_bounds__(256) void k_reduce_flat_wide(const float *partial, float *out, size_t total, int splits, int nb1,
+                                                           const float *partial2, float *out2, int total2)
 {
+    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, splits); return; }
     __shared__ f32x4 sm[8][32];
     const int g = threadIdx.x & 31, part = threadIdx.x >> 5;
     const size_t e = ((size_t)blockIdx.x * 32 + g) * 4;
@@ -725,7 +740,7 @@ hipError_t mfma_launch(const ConvArgs &a, hipStream_t st)
     return e;
 }
 
-hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStream_t st)
+hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStream_t st, bool with_db)
 {
     KArgs p{};
     p.rowsA = rowsA; p.rowsB = rowsB; p.splits = a.plan.splits; p.flags = a.flags;
@@ -736,11 +751,15 @@ hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStrea
     if (nb > 4096) nb = 4096;
     if (nb < 1) nb = 1;
     if (a.pass == PASS_WGRAD) {
-        if ((total & 3) == 0 && p.splits >= 16 && work <= 65536)
-            hipLaunchKernelGGL(k_reduce_flat_wide, dim3((unsigned)((work + 31) / 32)), dim3(256), 0, st, p.partial,
-                               reinterpret_cast<float *>(p.out), total, p.splits);
-        else
-            hipLaunchKernelGGL(k_reduce_flat, dim3(nb), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits);
+        const bool db = with_db && a.db_partial != nullptr && a.db_out != nullptr;
+        const unsigned nb2 = db ? (unsigned)((rowsA + 255) / 256) : 0u;
+        if ((total & 3) == 0 && p.splits >= 16 && work <= 65536) {
+            const unsigned nbw = (unsigned)((work + 31) / 32);
+            hipLaunchKernelGGL(k_reduce_flat_wide, dim3(nbw + nb2), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits,
+                               (int)nbw, a.db_partial, a.db_out, rowsA);
+        } else
+            hipLaunchKernelGGL(k_reduce_flat, dim3(nb + nb2), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits, (int)nb,
+                               a.db_partial, a.db_out, rowsA);
     } else
         hipLaunchKernelGGL(k_reduce_pixel_major, dim3(nb), dim3(256), 0, st, p);
     return hipGetLastError();

@@ -172,6 +172,15 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
 }
 
 
+}  // namespace
+
+// the pipelined backward-filter kernels (conv_dma.hip); their scratch [splits][c_out] fits the bias-gradient
+// workspace for up to 512 splits.  (Tried and dropped for the input-patch kernel: the extra matrix instructions
+// unbalance its one-wave-per-tap blocks and cost more than the separate column-sum pass.)
+bool plan_sums_bias_gradient(const GemmPlan &plan) { return plan.dma && !plan.halo && plan.splits <= 512; }
+
+namespace {
+
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 {
     if (a.plan.halo) return halo_launch(a, st);
@@ -418,8 +427,14 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         db_done = true;
     }
     if (dw != nullptr) {
+        // unmasked gradient and a bias gradient wanted: the pipelined kernels sum it on the
+        // matrix cores beside dW (no second pass over dy); whether the plan that finally ran is one of them is
+        // known only after the launch, because the first call of a shape may measure several candidates
+        const bool want_fused = db != nullptr && !db_done && ym == nullptr;
+        if (want_fused) { a.flags |= KF_DB; a.db_out = db; a.db_partial = rws; }
         hipError_t e = launch_entry(a, pe, st);
         if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
+        if (want_fused && plan_sums_bias_gradient(a.plan)) db_done = true;
     }
     if (db != nullptr && !db_done) {
         hipError_t e = rbg_launch(rows, g.K, true, dy, ym, nullptr, db, rws, st);

@@ -10,6 +10,7 @@ enum : unsigned {
     KF_BIAS = 1u,     // add bias in the epilogue
     KF_RELU = 2u,     // max(.,0) in the epilogue
     KF_OUT_F32 = 4u,  // final output stored as fp32 instead of bf16
+    KF_DB = 16u,      // backward-filter: also sum the bias gradient (kernels that cannot leave db_done unset)
     KF_MASK_IN = 8u,  // backward-data: dx *= [x > 0], x = the layer's saved input (output of the preceding ReLU)
 };
 
@@ -50,6 +51,8 @@ struct ConvArgs {
     const float *bias;    // fwd
     void *out;            // fwd: y, dgrad: dx (bf16 or fp32), wgrad: dw (fp32)
     float *partial;       // [splits][rowsB][rowsA] (fwd/dgrad) or [splits][rowsA][rowsB] (wgrad)
+    float *db_out = nullptr;      // KF_DB: bias gradient [rowsA]
+    float *db_partial = nullptr;  // KF_DB: [splits][rowsA] scratch for split plans
 };
 
 // conv_mfma.hip
@@ -58,13 +61,17 @@ void mfma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
 size_t mfma_partial_bytes(const ConvGeom &g, int pass, const GemmPlan &plan);
 hipError_t mfma_launch(const ConvArgs &a, hipStream_t st);
 void mfma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
-hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStream_t st);  // sums a.partial into a.out
+// sums a.partial into a.out; with_db: also a.db_partial [splits][rowsA] into a.db_out (backward-filter)
+hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStream_t st, bool with_db = false);
 
 // conv_fast.hip : fast path for channel counts that are multiples of the reduction step
 hipError_t fast_init();
 bool fast_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
 hipError_t fast_launch(const ConvArgs &a, hipStream_t st);
 void fast_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
+
+// true if this backward-filter plan's kernel sums the bias gradient itself when KF_DB is set
+bool plan_sums_bias_gradient(const GemmPlan &plan);
 
 // conv_dma.hip : multi-stage direct-to-LDS pipeline (forward, c_in % 64 == 0)
 hipError_t dma_init();

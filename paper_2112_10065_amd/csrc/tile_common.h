@@ -22,6 +22,7 @@ struct KArgs {
     const float *bias;
     void *out;
     float *partial;
+    float *dbp;   // KF_DB: bias-gradient sums of split s go to dbp[s * rowsA + row]
 };
 
 DEVFN u32x4 ldg16(const bf16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }
@@ -37,6 +38,19 @@ DEVFN u32x4 apply_mask(u32x4 v, u32x4 y)
 {
     v.x &= keep_bits(y.x); v.y &= keep_bits(y.y); v.z &= keep_bits(y.z); v.w &= keep_bits(y.w);
     return v;
+}
+// Bias gradient through the matrix cores: multiplying a dy^T fragment (32 c_out x 16 pixels) with an all-ones
+// operand sums its pixels; every column of the result holds the same 32 sums.
+DEVFN bf16x8 ones_bf16() { return __builtin_bit_cast(bf16x8, u32x4{0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u}); }
+// lanes 0 and 32 hold column 0: element v is row 8*(v/4) + 4*(lane/32) + v%4 of the fragment
+DEVFN void store_db_fragment(const f32x16 &acc, float *dst, int row0, int rows, int lane)
+{
+    if ((lane & 31) != 0) return;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = row0 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        if (row < rows) dst[row] = acc[v];
+    }
 }
 DEVFN float mask1f(float v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : 0.f; }
 DEVFN bf16_t mask1(bf16_t v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : (bf16_t)0; }

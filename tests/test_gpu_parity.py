@@ -189,6 +189,11 @@ def test_input_patch_filter_gradient(env, blocks):
             rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=U.to_np(y), pad=pd, want_db=True)
             U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} blocks {blocks} dw")
             U.assert_bf16_close(U.to_np(db), rdb, f"{tag} blocks {blocks} db")
+            dw, db = case.run_wgrad(None)   # no saved output: two of the tap waves also sum the bias gradient
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=None, pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} blocks {blocks} dw, unmasked")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} blocks {blocks} db, fused")
     finally:
         dp.dp_set_override(2, -1, 0)
 
@@ -354,6 +359,14 @@ def test_pipelined_backward_filter_variants(env, variant, splits):
             rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=y_np, stride=st, pad=pd, want_db=True)
             U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} variant {variant} splits {splits} dw")
             U.assert_bf16_close(U.to_np(db), rdb, f"{tag} variant {variant} splits {splits} db")
+            # no saved output: the kernel itself sums the bias gradient (ones operand on the matrix cores)
+            dw, db = case.run_wgrad(None)
+            db.fill_(7.0)
+            dw, db = case.run_wgrad(None)
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=None, stride=st, pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} variant {variant} splits {splits} dw, unmasked")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} variant {variant} splits {splits} db, fused")
     finally:
         dp.dp_set_override(2, -1, 0)
 
