@@ -22,8 +22,11 @@ namespace {
 
 template <int FA, int FB, int TA, int TB, int NT>
 DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *stage, const float *bias_lds, int a0, int b0,
-                        int arow, int brow, int tid, bool writer = true)
+                        int arow, int brow, int tid, bool writer = true, const int *rowpix = nullptr, bool all_zero = false)
 {
+    // all_zero: the tile's sums are known to be zero (no tap reaches it), so the input-ReLU mask need not be read
+    // rowpix (LDS, backward-data): output row of each tile row, -1 for none; else tile row i is output row b0 + i
+    auto out_row = [&](int pix) { const int gp = rowpix != nullptr ? rowpix[pix] : b0 + pix; return (rowpix != nullptr || gp < p.rowsB) ? gp : -1; };
     // `writer`: this wave holds finished sums (false for the extra reduction groups of a block, which only
     // help with the copy-out below)
     constexpr int LSO = TA + 8;
@@ -48,7 +51,7 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
         }
     constexpr int CPR = TA / 8;
     bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
-    if (p.flags & KF_MASK_IN) {
+    if ((p.flags & KF_MASK_IN) && !all_zero) {
         // fused backward of the input ReLU: the saved-input vectors are requested in groups of eight before
         // they are needed (the first group before the staging barrier), so that their latency overlaps
         constexpr int ITERS = (TB * CPR + NT - 1) / NT, GRP = ITERS < 8 ? ITERS : 8;
@@ -58,8 +61,8 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
 #pragma unroll
             for (int u = 0; u < GRP; ++u) {
                 const int id = tid + (g0 + u) * NT, pix = id / CPR, cc = id % CPR;
-                const int gp = b0 + pix, gc = a0 + cc * 8;
-                xm[u] = (id < TB * CPR && gp < p.rowsB && gc < p.rowsA) ? ldg16(p.x + (size_t)gp * p.rowsA + gc) : u32x4{0, 0, 0, 0};
+                const int gp = id < TB * CPR ? out_row(pix) : -1, gc = a0 + cc * 8;
+                xm[u] = (gp >= 0 && gc < p.rowsA) ? ldg16(p.x + (size_t)gp * p.rowsA + gc) : u32x4{0, 0, 0, 0};
             }
         };
         fetch(0);
@@ -70,8 +73,8 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
 #pragma unroll
             for (int u = 0; u < GRP; ++u) {
                 const int id = tid + (g0 + u) * NT, pix = id / CPR, cc = id % CPR;
-                const int gp = b0 + pix, gc = a0 + cc * 8;
-                if (id < TB * CPR && gp < p.rowsB && gc < p.rowsA)
+                const int gp = id < TB * CPR ? out_row(pix) : -1, gc = a0 + cc * 8;
+                if (gp >= 0 && gc < p.rowsA)
                     *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) =
                         apply_mask(*reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8), xm[u]);
             }
@@ -82,8 +85,8 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
 #pragma unroll
     for (int id = tid; id < TB * CPR; id += NT) {
         const int pix = id / CPR, cc = id % CPR;
-        const int gp = b0 + pix, gc = a0 + cc * 8;
-        if (gp < p.rowsB && gc < p.rowsA)
+        const int gp = out_row(pix), gc = a0 + cc * 8;
+        if (gp >= 0 && gc < p.rowsA)
             *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
     }
 }
@@ -505,23 +508,54 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     const ConvGeom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, grp = (tid >> 6) / NW, wave = (tid >> 6) % NW;
     const int tile = logical_block(blockIdx.x, gridDim.x);
-    const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
-    const int bbeg = blockIdx.y * p.steps_per_split, bend = min(bbeg + p.steps_per_split, p.steps_total);
-    const int nsteps = (bend - bbeg + KG - 1) / KG;
+    const int a0 = (tile % p.tilesA) * TA, tb = tile / p.tilesA, b0 = tb * TB;
+    // Stride phases (p.ph_on): a tile holds input pixels of one phase (h % sh, w % sw) = (pa, pb) only.  Of the R*S taps
+    // only those with r = (pa + ph) mod sh, s = (pb + pw) mod sw can hit the output grid for such a pixel, so the
+    // reduction walks that sub-lattice of taps: 1/(sh*sw) of the steps the masked form multiplies.
+    int pa = 0, pb = 0, Hc = g.H, Wc = g.W, ml0 = b0;           // phase, its pixel grid, first phase-local row of the tile
+    int tap_r0 = 0, tap_s0 = 0, step_r = 1, step_s = 1, tap_ns = g.S, ntaps = g.R * g.S;
+    if (p.ph_on) {
+        int cls = 0;
+        while (cls + 1 < g.sh * g.sw && tb >= p.ph_tile0[cls + 1]) ++cls;
+        pa = cls / g.sw; pb = cls - pa * g.sw;
+        Hc = (g.H - pa + g.sh - 1) / g.sh; Wc = (g.W - pb + g.sw - 1) / g.sw;
+        ml0 = (tb - p.ph_tile0[cls]) * TB;
+        tap_r0 = (pa + g.ph) % g.sh; tap_s0 = (pb + g.pw) % g.sw; step_r = g.sh; step_s = g.sw;
+        const int tap_nr = tap_r0 < g.R ? (g.R - tap_r0 + g.sh - 1) / g.sh : 0;
+        tap_ns = tap_s0 < g.S ? (g.S - tap_s0 + g.sw - 1) / g.sw : 0;
+        ntaps = tap_nr * tap_ns;
+    }
+    const int steps_tile = p.ph_on ? ntaps * (g.K / BK) : p.steps_total;
+    const int bbeg = blockIdx.y * p.steps_per_split, bend = min(bbeg + p.steps_per_split, steps_tile);
+    const int nsteps = (max(bend - bbeg, 0) + KG - 1) / KG;
     const int kbeg = bbeg + grp * nsteps, live = max(0, min(bend - kbeg, nsteps));
     const int RSC = g.R * g.S * g.C;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2);
     __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+    int *rowpix = reinterpret_cast<int *>(bias_lds + TA);   // [TB] linear index of each tile row's input pixel, -1: none
 
     if (tid < TB) {
-        const int m = b0 + tid;
-        const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
+        int n, hh, ww;
+        bool valid;
+        if (p.ph_on) {
+            const int ml = ml0 + tid, per = Hc * Wc;
+            valid = per > 0 && ml < g.N * per;
+            n = valid ? ml / per : 0;
+            const int rem = ml - n * per, i = Wc > 0 ? rem / Wc : 0;
+            hh = i * g.sh + pa; ww = (rem - i * Wc) * g.sw + pb;
+        } else {
+            const int m = b0 + tid;
+            valid = m < p.rowsB;
+            n = m / (g.H * g.W);
+            const int rem = m - n * (g.H * g.W);
+            hh = rem / g.W; ww = rem - hh * g.W;
+        }
         // the output pixel of tap (r, s) is ((hb - r) / sh, (wb - s) / sw) when both divisions are exact; for such a tap
         // (hb - r) / sh == hb / sh - r / sh, so the row base uses hb / sh and every tap adds a wave-uniform offset
         const int hb = hh + g.ph, wb = ww + g.pw;
         rowtab[2 * tid] = (unsigned)(((n * g.Ho + hb / g.sh) * g.Wo + wb / g.sw) * g.K) * 2u;
         unsigned mask = 0;
-        if (m < p.rowsB) {
+        if (valid) {
             unsigned smask = 0;
             for (int s = 0; s < g.S; ++s) {
                 const int d = wb - s;
@@ -533,6 +567,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
             }
         }
         rowtab[2 * tid + 1] = mask;
+        rowpix[tid] = valid ? (n * g.H + hh) * g.W + ww : -1;
     }
     __syncthreads();
 
@@ -554,9 +589,12 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     const unsigned smem_base = lds_offset(smem) + grp * NS * STAGE;   // this group's stages
     const unsigned ldsA_w = smem_base + wave * IA * 1024, ldsB_w = smem_base + A_BYTES + wave * IB * 1024;
 
+    // position in the tap sub-lattice: list index li -> (tap_r0 + (li / tap_ns) * step_r, tap_s0 + (li % tap_ns) * step_s)
     int kk = kbeg * BK;
-    int tap = kk / g.K, c0 = kk - tap * g.K;
-    int tr = tap / g.S, ts = tap - tr * g.S;
+    const int li0 = kk / g.K;
+    int c0 = kk - li0 * g.K;
+    int tr = tap_r0 + (tap_ns > 0 ? li0 / tap_ns : 0) * step_r, ts = tap_s0 + (tap_ns > 0 ? li0 % tap_ns : 0) * step_s;
+    int tap = tr * g.S + ts;
     int issued = 0;
     auto issue = [&](int stage) {
         const bool on = KG == 1 || issued < live;
@@ -570,7 +608,12 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
 #pragma unroll
         for (int q = 0; q < IB; ++q) dma16(rdy, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
         c0 += BK;
-        if (c0 >= g.K) { c0 = 0; ++tap; if (++ts == g.S) { ts = 0; ++tr; } }
+        if (c0 >= g.K) {
+            c0 = 0;
+            ts += step_s;
+            if (ts >= g.S) { ts = tap_s0; tr += step_r; }
+            tap = tr * g.S + ts;
+        }
     };
 
     f32x16 acc[FA][FB];
@@ -674,7 +717,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
         __syncthreads();
     }
     if (p.splits == 1 && !(p.flags & KF_OUT_F32) && (p.rowsA & 7) == 0)
-        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0);
+        store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0, rowpix, steps_tile == 0);
     else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
 }
@@ -792,7 +835,7 @@ size_t dma_lds_bytes(const DmaVariant &d)
     size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
     const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
     if (gsum > stages) stages = gsum;
-    return (stages > epi ? stages : epi) + (size_t)d.TB * 8 + (size_t)d.TA * 4;
+    return (stages > epi ? stages : epi) + (size_t)d.TB * 8 + (size_t)d.TA * 4 + (size_t)d.TB * 4;   // + row table, bias, row map
 }
 
 }  // namespace
@@ -818,6 +861,27 @@ hipError_t dma_init()
 }
 
 // variant override 200 + v selects pipelined variant v; the built-in choice does not use them yet
+// Strided backward-data by phase: B tiles and reduction steps (of BK) per phase (a, b) = (h % sh, w % sw).
+// Returns the number of phases (sh * sw <= 4).
+static int phase_layout(const ConvGeom &g, int TB, int BK, int tile0[5], int *max_steps)
+{
+    const int nph = g.sh * g.sw;
+    int t = 0, ms = 0;
+    for (int c = 0; c < nph; ++c) {
+        const int a = c / g.sw, b = c % g.sw;
+        const long long hc = g.H > a ? (g.H - a + g.sh - 1) / g.sh : 0, wc = g.W > b ? (g.W - b + g.sw - 1) / g.sw : 0;
+        const long long rows = (long long)g.N * hc * wc;
+        tile0[c] = t;
+        t += (int)((rows + TB - 1) / TB);
+        const int r0 = (a + g.ph) % g.sh, s0 = (b + g.pw) % g.sw;
+        const int nr = r0 < g.R ? (g.R - r0 + g.sh - 1) / g.sh : 0, ns = s0 < g.S ? (g.S - s0 + g.sw - 1) / g.sw : 0;
+        if (rows > 0 && nr * ns * (g.K / BK) > ms) ms = nr * ns * (g.K / BK);
+    }
+    for (int c = nph; c < 5; ++c) tile0[c] = t;
+    *max_steps = ms;
+    return nph;
+}
+
 bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *pl)
 {
     if (g.R * g.S > 32) return false;
@@ -844,9 +908,23 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
     } else return false;
     pl->fast = true; pl->dma = true; pl->TA = d->TA; pl->TB = d->TB; pl->BK = d->BK;
     pl->vecA = pl->vecB = true;
+    pl->phase = false;
     pl->tilesA = (rowsA + d->TA - 1) / d->TA;
     pl->tilesB = (rowsB + d->TB - 1) / d->TB;
     pl->steps_total = (red + d->BK - 1) / d->BK;
+    if (pass == PASS_DGRAD && (g.sh > 1 || g.sw > 1) && g.sh <= 2 && g.sw <= 2 && g.R * g.S > 1 && force_splits <= 1) {
+        // no reduction split asked for: walk the pixels phase by phase and multiply only the taps that can hit
+        // (a 1x1 filter gains nothing: its backward-data is bound by writing dx, three quarters of it zeros)
+        int tile0[5], max_steps;
+        phase_layout(g, d->TB, d->BK, tile0, &max_steps);
+        if (max_steps > 0 && tile0[4] > 0) {
+            pl->phase = true;
+            pl->tilesB = tile0[4];
+            pl->steps_total = pl->steps_per_split = max_steps;
+            pl->splits = 1;
+            return true;
+        }
+    }
     int splits;
     if (force_splits > 0) splits = force_splits;
     else {
@@ -884,6 +962,17 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     p.flags = a.flags;
     p.x = a.x; p.w = a.w; p.dy = a.dy; p.ymask = nullptr; p.bias = a.bias; p.out = a.out; p.partial = a.partial;
     const bool wg = a.pass == PASS_WGRAD;
+    p.ph_on = 0;
+    if (a.pass == PASS_DGRAD && a.plan.phase) {
+        if (!(a.flags & KF_OUT_F32) && (p.rowsA & 7) == 0) {   // the staged bf16 epilogue carries the row map
+            int max_steps;
+            phase_layout(a.g, a.plan.TB, a.plan.BK, p.ph_tile0, &max_steps);
+            p.ph_on = 1;
+        } else {   // fp32 gradients: the same tiles in natural pixel order, all taps (masked)
+            p.tilesB = (p.rowsB + a.plan.TB - 1) / a.plan.TB;
+            p.steps_total = p.steps_per_split = (p.red + a.plan.BK - 1) / a.plan.BK;
+        }
+    }
     p.dbp = p.splits > 1 ? a.db_partial : a.db_out;
     if (!wg || p.dbp == nullptr || !plan_sums_bias_gradient(a.plan)) p.flags &= ~KF_DB;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];

@@ -37,6 +37,7 @@ struct GemmPlan {
     bool dma;             // pipelined direct-to-LDS kernel (conv_dma.hip)
     bool halo = false;    // input-patch kernel (conv_halo.hip); implies dma
     int blocks = 0;       // persistent kernels: blocks per row tile (0: one per CU)
+    bool phase = false;   // strided backward-data walks the input pixels stride phase by stride phase (conv_dma.hip)
 };
 
 struct ConvArgs {

@@ -23,6 +23,10 @@ struct KArgs {
     void *out;
     float *partial;
     float *dbp;   // KF_DB: bias-gradient sums of split s go to dbp[s * rowsA + row]
+    // strided backward-data by phase: the B rows (input pixels) are enumerated phase by phase, phase (a, b) = (h % sh,
+    // w % sw), each padded to whole tiles; B tiles ph_tile0[c] .. ph_tile0[c+1]-1 belong to phase c = a*sw + b
+    int ph_on;
+    int ph_tile0[5];
 };
 
 DEVFN u32x4 ldg16(const bf16_t *p) { return *reinterpret_cast<const u32x4 *>(p); }

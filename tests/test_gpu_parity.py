@@ -172,6 +172,52 @@ def test_strided_backward_data_pipelined(env, tag, n, h, w, c, k, r, s_, st, pd)
     U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), stride=st, pad=pd), f"{tag} dx")
 
 
+PHASE_CASES = [
+    # tag, n, h, w, c, k, r, s, stride, pad : stride 2 in one or both directions, odd and even sizes, pads that shift the phases
+    ("ph_3x3_s2_p1", 2, 15, 14, 64, 64, 3, 3, (2, 2), (1, 1)), ("ph_3x3_s2_p0", 3, 17, 17, 32, 96, 3, 3, (2, 2), (0, 0)),
+    ("ph_1x1_s2", 2, 14, 17, 128, 128, 1, 1, (2, 2), (0, 0)), ("ph_3x3_s21", 2, 13, 12, 64, 192, 3, 3, (2, 1), (1, 0)),
+    ("ph_3x3_s12", 1, 9, 20, 40, 64, 3, 3, (1, 2), (1, 1)), ("ph_7x7_s2", 1, 21, 22, 16, 64, 7, 7, (2, 2), (3, 3)),
+    ("ph_2x2_s2", 2, 8, 8, 64, 64, 2, 2, (2, 2), (0, 0)), ("ph_1x3_s2", 1, 6, 30, 64, 128, 1, 3, (2, 2), (0, 1)),
+    ("ph_tiny", 1, 1, 3, 8, 64, 1, 1, (2, 2), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("spec", PHASE_CASES, ids=[c[0] for c in PHASE_CASES])
+def test_strided_backward_data_by_phase(env, spec):
+    """Stride-2 backward-data without a reduction split walks the input pixels phase by phase ((h % sh, w % sw)) and
+    multiplies only the taps that can hit the output grid; with a split, or fp32 gradients, the masked form runs.
+    All must agree with the oracle, with and without the fused input ReLU."""
+    dp, U, orc = env
+    tag, n, h, w, c, k, r, s_, st, pd = spec
+    case = U.ConvCase(tag, n, h, w, c, k, r, s_, st, pd, bf16=True, bias=False, relu=True)
+    x = np.maximum(case.x, 0.0).astype(np.float32)
+    case.x = x
+    case.xd = U.bf16_dev(U.synth.f32_to_bf16_bits(x))
+    y = case.run_fwd()
+    torch.cuda.synchronize()
+    want = orc.conv2d_bwd_data(case.dy, case.w, x.shape, y_saved=U.to_np(y), stride=st, pad=pd)
+    for variant, splits in ((-1, 0), (200, 1), (204, 1), (207, 1), (212, 1), (226, 1), (200, 2), (207, 3)):
+        dp.dp_set_override(1, variant, splits)
+        try:
+            name = dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+            dx = case.run_dgrad(y)
+            dxm = case.run_dgrad_relu_in(y)
+            torch.cuda.synchronize()
+        finally:
+            dp.dp_set_override(1, -1, 0)
+        U.assert_bf16_close(U.to_np(dx), want, f"{tag} {variant}/{splits} {name}")
+        U.assert_bf16_close(U.to_np(dxm), orc.relu_in_backward(want, x), f"{tag} {variant}/{splits} {name} with the input ReLU")
+    # fp32 gradients take the same plan in natural pixel order
+    case32 = U.ConvCase(tag, n, h, w, c, k, r, s_, st, pd, bf16=True, bias=False, relu=True, dx_f32=True)
+    dp.dp_set_override(1, 200, 1)
+    try:
+        dx32 = case32.run_dgrad(y)
+        torch.cuda.synchronize()
+    finally:
+        dp.dp_set_override(1, -1, 0)
+    U.assert_bf16_close(U.to_np(dx32), orc.conv2d_bwd_data(case32.dy, case32.w, case32.x.shape, y_saved=U.to_np(y), stride=st, pad=pd), f"{tag} fp32 dx")
+
+
 @pytest.mark.parametrize("blocks", [0, 3, 40])
 def test_input_patch_filter_gradient(env, blocks):
     """Filter gradient with the input patch in LDS and persistent blocks (64 input channels, stride 1): both
