@@ -261,7 +261,7 @@ bool use_small_c(const ConvGeom &g, int pass) { return g_force_variant[pass].loa
 
 size_t fwd_ws_bytes(const ConvGeom &g)
 {
-    if (use_small_c(g, PASS_FWD) && small_c_direct(g)) return 0;
+    if (use_small_c(g, PASS_FWD) && (small_c_direct(g) || small_c_stem(g))) return 0;
     if (use_small_c(g, PASS_FWD)) {
         const int kpad = small_c_kpad(g);
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2) + fwd_ws_bytes(im2col_geom(g, kpad));
@@ -279,6 +279,10 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     }
     if (use_small_c(g, PASS_FWD) && small_c_direct(g)) {
         hipError_t e = small_c_fwd_direct(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
+    }
+    if (use_small_c(g, PASS_FWD) && small_c_stem(g)) {
+        hipError_t e = small_c_fwd_stem(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
     }
     if (use_small_c(g, PASS_FWD)) {
@@ -475,6 +479,11 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (desc->io_dtype == DP_F32) {
         static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
         if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
+        if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    if (pass == PASS_FWD && use_small_c(g, pass) && !small_c_direct(g) && small_c_stem(g)) {
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_fwd_stem<%d>", (g.R * 24 + 15) / 16);
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }

@@ -114,6 +114,9 @@ hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, flo
 bool small_c_direct(const ConvGeom &g);
 hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
                               hipStream_t st);
+// strided stems (7x7 stride 2 on RGB): forward straight from the input patch, no im2col matrix
+bool small_c_stem(const ConvGeom &g);
+hipError_t small_c_fwd_stem(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
 int small_c_wgrad_blocks(const ConvGeom &g);   // pixel-range blocks, each writes one fp32 partial
 size_t small_c_wgrad_partial_bytes(const ConvGeom &g);
 // ymask (saved output, may be NULL) masks dy on the fly; db (may be NULL) receives the bias gradient of the masked dy

@@ -374,6 +374,164 @@ unsigned blocks_for(long long total)
     return (unsigned)(nb < 1 ? 1 : nb);
 }
 
+// ---------------------------------------------------------------------------------------
+// Forward for strided few-channel stems (7x7 stride 2 on RGB): no im2col matrix and no im2col tile.
+// For a fixed filter row r the S*C inputs of an output pixel are CONTIGUOUS in NHWC (a "run", 21 elements
+// for 7x7x3), so the reduction is laid out as R runs padded to 24 = three 8-element groups, and the pixel
+// operand of a matrix instruction (8 consecutive reduction elements per lane) is read straight from the
+// input patch in LDS: run r, group part of output pixel (pr, pc) starts at patch row pr*sh + r, element
+// pc*sw*C + 8*part.  With sw*C even that address is 4-byte aligned, so a group is four dword reads; the
+// elements of a group past the end of the run belong to the neighbouring pixel and are masked to zero.
+// The weights (64 c_out x R*24, zero padded) stay in registers; blocks are persistent over 8x32-pixel tiles
+// and fetch the next tile's patch into registers while the current one is multiplied.
+// ---------------------------------------------------------------------------------------
+constexpr int ST_PITCH = 512;        // bytes per patch row in LDS (data + 48 bytes that the last group of a row may over-read)
+constexpr int ST_ROWS = 24;          // patch rows in LDS (rows past the real patch stay zero)
+constexpr int ST_MAXSL = 12;         // reduction slices of 16 (R * 24 <= 192)
+
+template <int NSL>
+__global__ __launch_bounds__(256, 2) void k_fwd_stem(const ConvGeom g, unsigned flags, const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
+                                                  const float *__restrict__ bias, bf16_t *__restrict__ y, int tiles, int tiles_x, int tiles_y)
+{
+    __shared__ __attribute__((aligned(16))) char patch[2][ST_ROWS * ST_PITCH];
+    __shared__ __attribute__((aligned(16))) bf16_t wlds[64 * ST_MAXSL * 16];   // [c_out][R*24 padded to the slices], zero where no weight
+    __shared__ float bias_lds[64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hsel = lane >> 5;
+    const int a0 = blockIdx.y * 64;
+    const int run = g.S * g.C;                       // elements of one filter row
+    const int prow = 7 * g.sh + g.R, pwe = (31 * g.sw + g.S) * g.C;   // real patch: rows, elements per row
+    for (int i = tid; i < 2 * ST_ROWS * ST_PITCH / 4; i += 256) reinterpret_cast<unsigned *>(&patch[0][0])[i] = 0u;
+    for (int i = tid; i < 64 * ST_MAXSL * 16 / 2; i += 256) reinterpret_cast<unsigned *>(wlds)[i] = 0u;
+    if (tid < 64) bias_lds[tid] = ((flags & KF_BIAS) && a0 + tid < g.K) ? bias[a0 + tid] : 0.f;
+    __syncthreads();
+    // weights: coalesced 2-byte loads into the padded LDS layout (reduction element 24*r + j holds w[ch][r][j]), then
+    // one 16-byte read per fragment: slice ks, channel half i; lane (channel i*32 + l%32, elements ks*16 + 8*(l/32) ..+7)
+    {
+        const int per_ch = g.R * run, total = 64 * per_ch;
+        for (int e0 = 0; e0 < total; e0 += 256 * 8) {
+            unsigned short v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * 256 + tid, ch = e / per_ch;
+                v[u] = (e < total && a0 + ch < g.K) ? w[(size_t)a0 * per_ch + e] : (unsigned short)0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int e = e0 + u * 256 + tid, ch = e / per_ch, rem = e - ch * per_ch, r = rem / run, j = rem - r * run;
+                if (e < total) wlds[ch * (ST_MAXSL * 16) + r * 24 + j] = v[u];
+            }
+        }
+    }
+    __syncthreads();
+    u32x4 wfr[NSL][2];
+#pragma unroll
+    for (int ks = 0; ks < NSL; ++ks)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            wfr[ks][i] = *reinterpret_cast<const u32x4 *>(wlds + (i * 32 + (lane & 31)) * (ST_MAXSL * 16) + ks * 16 + 8 * hsel);
+
+    // patch elements of this thread: element e = tid + 256*i -> (row, column element); fetched as 2-byte loads
+    // patch fetch: thread t takes column element t of every patch row (a row is at most 232 elements), two rows per register
+    auto fetch = [&](int tile, unsigned (&v)[ST_ROWS / 2]) {
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        const int ih0 = ty * 8 * g.sh - g.ph, ie = (tx * 32 * g.sw - g.pw) * g.C + tid;
+        const bool okc = tid < pwe && (unsigned)ie < (unsigned)(g.W * g.C);
+        const bf16_t *src = x + ((size_t)n * g.H + ih0) * g.W * g.C + ie;
+#pragma unroll
+        for (int r = 0; r < ST_ROWS; ++r) {
+            const bool ok = okc && r < prow && (unsigned)(ih0 + r) < (unsigned)g.H;
+            const unsigned val = ok ? src[(size_t)r * g.W * g.C] : 0u;
+            v[r >> 1] = (r & 1) ? v[r >> 1] | (val << 16) : val;
+        }
+    };
+    auto stash = [&](int buf, const unsigned (&v)[ST_ROWS / 2]) {
+        if (tid >= pwe) return;
+#pragma unroll
+        for (int r = 0; r < ST_ROWS; ++r)
+            if (r < prow) *reinterpret_cast<unsigned short *>(&patch[buf][r * ST_PITCH + tid * 2]) = (unsigned short)((r & 1) ? v[r >> 1] >> 16 : v[r >> 1] & 0xffffu);
+    };
+    unsigned pv[ST_ROWS / 2];
+    int tile = blockIdx.x;
+    __syncthreads();   // zero fill done
+    if (tile < tiles) { fetch(tile, pv); stash(0, pv); }
+    __syncthreads();
+
+    // per slice: which run / group this lane reads, and how many of its 8 elements are inside the run
+    int pc_off = (lane & 31) * g.sw * g.C * 2, run_v = run;
+    for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+        const bool more = tile + (int)gridDim.x < tiles;
+        if (more) fetch(tile + gridDim.x, pv);
+        const char *pb = &patch[it & 1][0];
+        asm volatile("" : "+v"(pc_off), "+v"(run_v));   // keeps the per-slice addresses and masks from being computed ahead of the tile loop
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        // the pixel fragments of slice ks + 1 are read before the matrix instructions of slice ks
+        auto read_b = [&](int ks, u32x4 (&bf)[2]) {
+            const int gidx = 2 * ks + hsel, r = gidx / 3, part = gidx - 3 * r;
+            int nval = run_v - 8 * part;
+            nval = r < g.R ? (nval < 0 ? 0 : nval > 8 ? 8 : nval) : 0;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int prr = (2 * wave + j) * g.sh + r;   // < 7*sh + R + 1 <= ST_ROWS
+                const unsigned *src = reinterpret_cast<const unsigned *>(__builtin_assume_aligned(pb + prr * ST_PITCH + pc_off + part * 16, 4));
+                unsigned d[4] = {src[0], src[1], src[2], src[3]};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) d[q] &= nval > 2 * q + 1 ? 0xffffffffu : nval > 2 * q ? 0x0000ffffu : 0u;
+                bf[j] = u32x4{d[0], d[1], d[2], d[3]};
+            }
+        };
+        u32x4 bfr[2][2];
+        read_b(0, bfr[0]);
+#pragma unroll
+        for (int ks = 0; ks < NSL; ++ks) {
+            if (ks + 1 < NSL) read_b(ks + 1, bfr[(ks + 1) & 1]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wfr[ks][i]), __builtin_bit_cast(bf16x8, bfr[ks & 1][j]), acc[i][j], 0, 0, 0);
+        }
+        // accumulator element v of lane l: channel i*32 + 8*(v/4) + 4*(l/32) + v%4, pixel l%32 of row 2*wave + j; lanes l and l+32
+        // swap halves of two channel groups so that each stores 8 consecutive channels
+        {
+            const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int pr = ty * 8 + 2 * wave + j, qc = tx * 32 + (lane & 31);
+                const bool okp = pr < g.Ho && qc < g.Wo;
+                bf16_t *orow = y + ((size_t)(n * g.Ho + pr) * g.Wo + qc) * g.K + a0;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp) {
+                        unsigned pkd[2][2];
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            const int gq = 2 * gp + e;
+                            const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + i * 32 + 8 * gq + 4 * hsel);
+                            float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y, v2 = acc[i][j][4 * gq + 2] + bv.z,
+                                  v3 = acc[i][j][4 * gq + 3] + bv.w;
+                            if (flags & KF_RELU) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
+                            pkd[e][0] = pack_bf16(v0, v1);
+                            pkd[e][1] = pack_bf16(v2, v3);
+                        }
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(pkd[0][0], pkd[1][0], false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(pkd[0][1], pkd[1][1], false, false);
+                        const int ch = i * 32 + 8 * (2 * gp + hsel);
+                        if (okp && a0 + ch < g.K) *reinterpret_cast<u32x4 *>(orow + ch) = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                    }
+            }
+        }
+        if (more) stash((it + 1) & 1, pv);   // the other buffer was last read two tiles ago, before the previous barrier
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 int small_c_kpad(const ConvGeom &g)
@@ -452,5 +610,31 @@ hipError_t small_c_pad_weights(const ConvGeom &g, int kpad, const bf16_t *w, bf1
 hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, float *dw, hipStream_t st)
 {
     hipLaunchKernelGGL(k_unpad_rows_f32, dim3(blocks_for((long long)g.K * g.R * g.S * g.C)), dim3(256), 0, st, g.K, g.R * g.S * g.C, kpad, dwpad, dw);
+    return hipGetLastError();
+}
+
+// Strided few-channel stems take the row-run kernel: filter rows of at most 24 elements whose pixel step is a whole
+// number of dwords, at most 8 rows, an 8x32 tile's patch within the LDS slot, 64-aligned c_out tiles of 8 channels.
+bool small_c_stem(const ConvGeom &g)
+{
+    if ((g.C % 8) == 0 || g.S * g.C > 24 || ((g.sw * g.C * 2) % 4) != 0 || g.R * 24 > ST_MAXSL * 16 || (g.K % 8) != 0) return false;
+    if (g.R * g.S * g.C <= 32) return false;   // the one-slice kernels above are the better fit
+    const int prow = 7 * g.sh + g.R, pwe = (31 * g.sw + g.S) * g.C;
+    return prow + 1 <= ST_ROWS && pwe * 2 + 48 <= ST_PITCH && pwe <= 256;
+}
+
+hipError_t small_c_fwd_stem(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st)
+{
+    const int tiles_x = (g.Wo + 31) / 32, tiles_y = (g.Ho + 7) / 8, ktiles = (g.K + 63) / 64;
+    const long long tiles = (long long)g.N * tiles_x * tiles_y;
+    const int nb = (int)(tiles < 512 ? tiles : 512);   // persistent beyond two blocks per CU (each block stages the weights once)
+    const int nsl = (g.R * 24 + 15) / 16;
+    dim3 grid((unsigned)nb, (unsigned)ktiles), block(256);
+#define STEM_CASE(N) case N: hipLaunchKernelGGL(k_fwd_stem<N>, grid, block, 0, st, g, flags, x, w, bias, y, (int)tiles, tiles_x, tiles_y); break;
+    switch (nsl) {
+        STEM_CASE(2) STEM_CASE(3) STEM_CASE(4) STEM_CASE(5) STEM_CASE(6) STEM_CASE(7) STEM_CASE(8) STEM_CASE(9) STEM_CASE(10) STEM_CASE(11) STEM_CASE(12)
+    default: return hipErrorInvalidValue;
+    }
+#undef STEM_CASE
     return hipGetLastError();
 }
