@@ -249,6 +249,45 @@ dp_status dp_plan_cost_tables(int32_t n_layers, int32_t n_gpu_counts, const int3
                               const double *act_bytes, const double *param_bytes, double bandwidth,
                               double delay, double *comm_out, double *sync_out);
 
+/* ---- Burst-parallel plan of a chain whose edges may be branch/join blocks (host only) -------------
+ * Paper section 4.2, paragraph "Multi-chain graph reduction".  Between main layers i-1 (the branching
+ * layer) and i (the joining layer) there may be n_branches[i] parallel branches instead of a direct
+ * edge.  For every GPU count g of the branching layer each branch is searched as a chain whose layer 0
+ * is pinned to g; for every GPU count h of the joining layer each branch's time to reach it is chosen
+ * by the chain algorithm's admission scan over the branch's last layer (transition cost join).  The
+ * longest branch is critical (first on ties).  Branches run one after another unless moved aside: a
+ * non-critical branch with layers is moved to a GPU set of its own (as many GPUs as the largest count
+ * on its plan) when time + move[g][h] <= critical time and the block's amplification
+ *   (block time + comp(i,h) + sync(i,h)) * (h + GPUs added so far + its own) / one-GPU compute of the
+ *   joining layer and all branch layers
+ * stays within amp_limit; candidates are tried in branch order.  The block's time tr[g][h] = critical +
+ * the branches not moved; it takes the place of comm[i] in the chain algorithm, and the joining layer's
+ * amplification counts the added GPUs and the block's one-GPU compute.  Blocks do not nest. */
+typedef struct {
+    int32_t n_layers;   /* Lb >= 0; 0 = a skip connection whose time is join[g][h] */
+    const double *comp; /* [Lb][G], > 0 */
+    const double *comm; /* [Lb][G][G]; comm[0][b][a] leaves the branching layer on gpu_counts[b]; NULL = zero */
+    const double *sync; /* [Lb][G]; NULL = zero */
+    const double *join; /* [G][G] join[b][a]: from the branch's last layer (the branching layer if Lb = 0) on
+                           gpu_counts[b] to the joining layer on gpu_counts[a]; NULL = zero */
+    const double *move; /* [G][G] move[g][h]: cost of taking the branch's samples to a GPU set of its own and
+                           back; entries may be INFINITY; NULL = the branch is never moved */
+} dp_plan_branch;
+
+typedef struct {
+    dp_plan_desc chain;             /* the main layers; chain.comm[i] is not read where n_branches[i] > 0 */
+    const int32_t *n_branches;      /* [L] >= 0, n_branches[0] == 0 */
+    const dp_plan_branch *branches; /* the branches of all blocks, in layer order; may be NULL if there are none */
+} dp_plan_graph_desc;
+
+/* gpus_per_layer [L]; branch_gpus: GPU count of every branch layer along the chosen plan, branches
+ * concatenated in the order of desc->branches (may be NULL); branch_parallel: one byte per branch, 1 =
+ * moved aside (may be NULL); critical_branch [L]: index of the critical branch within its block, -1 for a
+ * direct edge (may be NULL); S_out / T_out [(L+1)][G] (may be NULL).  Errors as dp_plan_chain. */
+dp_status dp_plan_graph(const dp_plan_graph_desc *desc, int32_t *gpus_per_layer, int32_t *branch_gpus,
+                        uint8_t *branch_parallel, int32_t *critical_branch, double *iteration_time,
+                        double *S_out, double *T_out);
+
 const char *dp_last_error(void); /* thread-local, static storage */
 const char *dp_version(void);
 

@@ -17,7 +17,7 @@ DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_data_relu",
            "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
            "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
-           "dp_plan_cost_tables", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
+           "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
            "dp_last_error", "dp_version"]
 
 
@@ -41,6 +41,15 @@ class dp_plan_desc(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("n_gpu_counts", C.c_int32), ("gpu_counts", C.POINTER(C.c_int32)),
                 ("comp", C.POINTER(C.c_double)), ("comm", C.POINTER(C.c_double)), ("sync", C.POINTER(C.c_double)),
                 ("amp_limit", C.c_double)]
+
+
+class dp_plan_branch(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("comp", C.POINTER(C.c_double)), ("comm", C.POINTER(C.c_double)),
+                ("sync", C.POINTER(C.c_double)), ("join", C.POINTER(C.c_double)), ("move", C.POINTER(C.c_double))]
+
+
+class dp_plan_graph_desc(C.Structure):
+    _fields_ = [("chain", dp_plan_desc), ("n_branches", C.POINTER(C.c_int32)), ("branches", C.POINTER(dp_plan_branch))]
 
 
 class DpError(RuntimeError):
@@ -77,13 +86,14 @@ def _load():
     pd = P(C.c_double)
     lib.dp_plan_chain.argtypes = [P(dp_plan_desc), P(i32), pd, pd, pd]
     lib.dp_plan_cost_tables.argtypes = [i32, i32, P(i32), pd, pd, C.c_double, C.c_double, pd, pd]
+    lib.dp_plan_graph.argtypes = [P(dp_plan_graph_desc), P(i32), P(i32), P(C.c_uint8), P(i32), pd, pd, pd]
     lib.dp_maxpool2x2_fwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp]
     lib.dp_maxpool2x2_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.dp_softmax_xent.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
     lib.dp_sgd_update.argtypes = [i64, C.c_float, C.c_float, vp, vp, vp, vp, vp]
     for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
                  "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
-                 "dp_plan_cost_tables", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update"):
+                 "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update"):
         getattr(lib, name).restype = C.c_int
     lib.dp_last_error.restype = C.c_char_p
     lib.dp_version.restype = C.c_char_p
@@ -202,6 +212,57 @@ def dp_plan_cost_tables(gpu_counts, act_bytes, param_bytes, bandwidth, delay):
     _check(lib.dp_plan_cost_tables(L, G, gc, _doubles(act_bytes, L), _doubles(param_bytes, L), float(bandwidth), float(delay), comm, sync))
     return ([[[comm[(i * G + b) * G + a] for a in range(G)] for b in range(G)] for i in range(L)],
             [[sync[i * G + a] for a in range(G)] for i in range(L)])
+
+
+def dp_plan_graph(gpu_counts, layers, amp_limit=float("inf")):
+    """Host-only.  layers[i] = {"comp": [G], "sync": [G] or None, "comm": [G][G] or None, "branches": [...]}; a layer
+    with branches is the joining layer of a block that leaves layer i-1; a branch = {"comp": [Lb][G], "comm":
+    [Lb][G][G] or None, "sync": [Lb][G] or None, "join": [G][G] or None, "move": [G][G] or None}.
+    Returns {"gpus", "time", "S", "T", "blocks": per layer None or {"critical", "parallel": [..], "gpus": [[..], ..]}}."""
+    L, G = len(layers), len(gpu_counts)
+    gc = (C.c_int32 * G)(*gpu_counts)
+    keep = []                     # the C arrays must outlive the call
+
+    def arr(rows, n):
+        a = _doubles(rows, n)
+        keep.append(a)
+        return C.cast(a, C.POINTER(C.c_double)) if a is not None else None
+
+    no_sync = all(l.get("sync") is None for l in layers)
+    sync = None if no_sync else [l.get("sync") or [0.0] * G for l in layers]
+    comm = [l.get("comm") if l.get("comm") is not None else [[0.0] * G] * G for l in layers]
+    flat = [br for l in layers for br in (l.get("branches") or [])]
+    brs = (dp_plan_branch * max(1, len(flat)))()
+    for k, br in enumerate(flat):
+        Lb = len(br["comp"])
+        brs[k] = dp_plan_branch(Lb, arr(br["comp"], Lb * G) if Lb else None, arr(br.get("comm"), Lb * G * G) if Lb else None,
+                                arr(br.get("sync"), Lb * G) if Lb else None, arr(br.get("join"), G * G), arr(br.get("move"), G * G))
+    nbr = (C.c_int32 * L)(*[len(l.get("branches") or []) for l in layers])
+    d = dp_plan_graph_desc(dp_plan_desc(L, G, gc, arr([l["comp"] for l in layers], L * G), arr(comm, L * G * G), arr(sync, L * G),
+                                        float(amp_limit)), nbr, brs)
+    out = (C.c_int32 * L)()
+    n_bl = sum(len(br["comp"]) for br in flat)
+    bg = (C.c_int32 * max(1, n_bl))()
+    par = (C.c_uint8 * max(1, len(flat)))()
+    crit = (C.c_int32 * L)()
+    t = C.c_double(0.0)
+    S = (C.c_double * ((L + 1) * G))()
+    T = (C.c_double * ((L + 1) * G))()
+    _check(lib.dp_plan_graph(C.byref(d), out, bg, par, crit, C.byref(t), S, T))
+    rows = lambda a: [[a[i * G + j] for j in range(G)] for i in range(L + 1)]
+    blocks, kb, kl = [], 0, 0
+    for l in layers:
+        bl = l.get("branches") or []
+        if not bl:
+            blocks.append(None)
+            continue
+        plans = []
+        for br in bl:
+            plans.append([bg[kl + j] for j in range(len(br["comp"]))])
+            kl += len(br["comp"])
+        blocks.append({"critical": crit[len(blocks)], "parallel": [bool(par[kb + j]) for j in range(len(bl))], "gpus": plans})
+        kb += len(bl)
+    return {"gpus": list(out), "time": t.value, "S": rows(S), "T": rows(T), "blocks": blocks}
 
 
 def dp_conv2d_kernel_info(desc, pass_):
