@@ -15,6 +15,7 @@
 // Step i:  wait(loads of step i) ; barrier ; issue loads of step i+NS-1 into the stage that
 //          step i-1 used ; matrix cores on stage i % NS.
 #include "dma_common.h"
+#include <type_traits>
 #include <cstdio>
 #include <cstdlib>
 
@@ -276,6 +277,209 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
     else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
 }
+
+// A matrix instruction pinned to its place in the instruction stream (kernels with one wave per SIMD order their
+// slots by hand: nothing else would hide a stall).
+DEVFN void mfma_pinned(f32x16 &c, const u32x4 &a, const u32x4 &b)
+{
+    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);   // nothing moves across: the instruction stays in its slot
+}
+
+// ---------------------------------------------------------------------------------------
+// Forward 3x3 / stride 1 / pad 1 with the pixel operand kept in LDS across the three taps of a filter row.
+// In flat pixel order (n, h, w) tap (r, s) of output pixel m reads input pixel m + (r-1)*W + (s-1), so the
+// 256 pixel rows of a tile for the taps s = 0, 1, 2 of one filter row are three windows, one row apart, of
+// ONE strip of 258 input pixels: the strip is copied to LDS once per (filter row, channel block) and serves
+// three reduction steps; only the weights are fetched every step.  Pairs (pixel, tap) that fall outside the
+// image would read a neighbour's pixel from the strip; those lanes read rows of zeros instead (the strip
+// buffers are 288 rows long and the rows past 258 are always filled with zeros).
+// One wave per SIMD (4 waves, 128x128 each: 256 accumulators leave no room for a second wave), so nothing
+// hides a stall and, measured, nothing overlaps the wave's own vector instructions with its matrix
+// instructions.  The loop body therefore holds matrix instructions, LDS reads and direct-to-LDS copies only:
+// every per-lane address is precomputed (48 registers of B addresses per filter row), stage and buffer
+// offsets are instruction immediates (two strips = six steps are unrolled), step offsets of the copies ride in
+// the scalar offset and a copy is switched off by a zero-length buffer resource.  Reads and copies sit in
+// slots between matrix instructions; a scheduling barrier after each keeps the compiler from regrouping them.
+// Reduction order: filter row, channel block, filter column.  Needs c_in % 128 == 0.
+// ---------------------------------------------------------------------------------------
+template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   // offset OFF0 + blk * BS as an immediate
+{
+    switch (blk) {
+    case 0: return lds_read16<OFF0>(addr);
+    case 1: return lds_read16<OFF0 + BS>(addr);
+    case 2: return lds_read16<OFF0 + 2 * BS>(addr);
+    default: return lds_read16<OFF0 + 3 * BS>(addr);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
+{
+    constexpr int TA = 256, TB = 256, BK = 64, NT = 256, FA = 4, FB = 4, ROWB = 128, BS = 32 * ROWB;
+    constexpr int A_BYTES = TA * ROWB, SROWS = 288, S_BYTES = SROWS * ROWB, IA = 8, ISB = SROWS / 8 / 4, ZROW = 272;
+    constexpr int LDS_TILES = 2 * A_BYTES + 2 * S_BYTES;
+    static_assert(LDS_TILES >= TB * (TA + 8) * 2, "the staged epilogue reuses the tiles");
+    static_assert(A_BYTES + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    unsigned *rowtab = reinterpret_cast<unsigned *>(smem + LDS_TILES);   // [TB] tap masks
+    float *bias_lds = reinterpret_cast<float *>(rowtab + TB);           // [TA]
+
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tile = logical_block(blockIdx.x, gridDim.x);
+    const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
+    const int RSC = 9 * g.C, NHW = g.N * g.H * g.W, CB = g.C / BK, nstrips = 3 * CB, nsteps = 3 * nstrips;
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(p.x, (size_t)NHW * g.C * 2);
+    __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(p.x, 0);   // every lane out of range: a switched-off copy
+    {
+        const int m = b0 + tid;
+        const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
+        rowtab[tid] = m < p.rowsB ? tap_mask(hh - 1, ww - 1, 1, 3, 3, g.H, g.W) : 0u;
+    }
+    if (p.flags & KF_BIAS) bias_lds[tid] = a0 + tid < p.rowsA ? p.bias[a0 + tid] : 0.f;
+    __syncthreads();
+
+    // copies: lane l of instruction q fills chunk position l % 8 of tile row rq = q*8 + l/8 with global chunk (l % 8) ^ swizzle(rq)
+    const unsigned wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned lds0 = lds_offset(smem), ldsS0 = lds0 + 2 * A_BYTES;
+    unsigned voffA[IA], voffS[ISB], voffS_r[ISB];
+    int pixS[ISB];
+#pragma unroll
+    for (int q = 0; q < IA; ++q) {
+        const int row = (wave * IA + q) * 8 + lane / 8, c = (lane % 8) ^ ((row >> 1) & 7);
+        voffA[q] = ((unsigned)(a0 + row) * RSC + c * 8) * 2u;
+    }
+#pragma unroll
+    for (int q = 0; q < ISB; ++q) {
+        const int row = (wave * ISB + q) * 8 + lane / 8, c = (lane % 8) ^ ((row >> 1) & 7);
+        pixS[q] = row < TB + 2 ? b0 - 1 + row : -0x40000000;   // strip row j holds input pixel b0 - 1 + j + (r-1)*W
+        voffS[q] = ((unsigned)(b0 - 1 + row) * g.C + c * 8) * 2u;
+    }
+    auto strip_row_offsets = [&](int rr) {   // per filter row: where each strip row comes from, OOR (zeros) outside the tensor
+        const int shift = (rr - 1) * g.W;
+#pragma unroll
+        for (int q = 0; q < ISB; ++q)
+            voffS_r[q] = (unsigned)(pixS[q] + shift) < (unsigned)NHW ? voffS[q] + (unsigned)(shift * g.C) * 2u : OOR;
+    };
+    // the step's offset is uniform: it rides in the scalar offset, which the range check ignores (weight rows past the last
+    // filter are out of range by their own offset)
+    auto issue_a = [&](int stage, int rr, int cc, int ss, int q, bool on) {   // weights of tap (rr, ss), channel block cc
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rw : rw_off, (lds_void)(size_t)(lds0 + stage * A_BYTES + (wave_s * IA + q) * 1024), 16, voffA[q],
+                                                 ((rr * 3 + ss) * g.C + cc * BK) * 2, 0, 0);
+    };
+    auto issue_s = [&](int buf, int cc, int q, bool on) {   // strip (filter row of voffS_r, channel block cc) into strip buffer `buf`
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rx : rx_off, (lds_void)(size_t)(ldsS0 + buf * S_BYTES + (wave_s * ISB + q) * 1024), 16, voffS_r[q],
+                                                 cc * BK * 2, 0, 0);
+    };
+
+    f32x16 acc[FA][FB];
+#pragma unroll
+    for (int i = 0; i < FA; ++i)
+#pragma unroll
+        for (int j = 0; j < FB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    const int arow = (wave & 1) * 128, brow = (wave >> 1) * 128;
+    const int rA = arow + (lane & 31), rB = brow + (lane & 31);
+    // slice ks of a row sits at chunk (2*ks + half) ^ swizzle: its address is the slice-0 address with ks << 5 xor-ed in
+    unsigned fa[4], fbs[3], fmask[FB], vsel[3][FB][4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) fa[ks] = lds0 + rA * ROWB + (((2 * ks + (lane >> 5)) ^ ((rA >> 1) & 7)) << 4);
+#pragma unroll
+    for (int ss = 0; ss < 3; ++ss) fbs[ss] = ldsS0 + (rB + ss) * ROWB + (((lane >> 5) ^ (((rB + ss) >> 1) & 7)) << 4);
+#pragma unroll
+    for (int j = 0; j < FB; ++j) fmask[j] = rowtab[rB + 32 * j];
+    // B addresses of filter row rr (strip buffer 0; fragment j is read at immediate offset j * BS): the strip row, or for a
+    // pair outside the image the zero rows, at the same position within 256 bytes (the same banks as the neighbours expect)
+    auto select_rows = [&](int rr) {
+#pragma unroll
+        for (int ss = 0; ss < 3; ++ss)
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                const unsigned zeros = ldsS0 + ZROW * ROWB - j * BS + (fbs[ss] & 0xF0u);
+                const unsigned base = (fmask[j] >> (rr * 3 + ss)) & 1u ? fbs[ss] : zeros;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) vsel[ss][j][ks] = base ^ (ks << 5);
+            }
+    };
+
+    u32x4 ra[2][4], rb[2][4];
+    // read j (a0 b0 a1 b1 ...) of slice ks of the step that uses weight stage PA, strip buffer SB and filter column ss
+    auto read8 = [&](int buf, int j, int PA, int SB, int ss, int ks) {
+        if (j & 1) rb[buf][j >> 1] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][j >> 1][ks], j >> 1) : lds_read16_at<0, BS>(vsel[ss][j >> 1][ks], j >> 1);
+        else ra[buf][j >> 1] = PA ? lds_read16_at<A_BYTES, BS>(fa[ks], j >> 1) : lds_read16_at<0, BS>(fa[ks], j >> 1);
+    };
+
+    // prologue: strip 0, weights of step 0 and the first half of step 1
+    strip_row_offsets(0);
+    int row_loaded = 0;   // filter row of voffS_r
+#pragma unroll
+    for (int q = 0; q < ISB; ++q) issue_s(0, 0, q, true);
+#pragma unroll
+    for (int q = 0; q < IA; ++q) issue_a(0, 0, 0, 0, q, true);
+#pragma unroll
+    for (int q = 0; q < IA / 2; ++q) issue_a(1, 0, 0, 1, q, true);   // the second half follows in the first slice of step 0
+    select_rows(0);
+    wait_vmcnt<IA / 2>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int j = 0; j < 8; ++j) read8(0, j, 0, 0, 0, 0);
+
+    int rr = 0, cc = 0;   // filter row and channel block of strip gg
+    // one strip = three steps; SB = gg & 1 is the strip's buffer, and with it the parity of its first step
+    auto strip_steps = [&](int gg, auto sbc) {
+        constexpr int SB = decltype(sbc)::value;
+        const bool more_strips = gg + 1 < nstrips;
+        const int ccn = cc + 1 == CB ? 0 : cc + 1, rrn = cc + 1 == CB ? rr + 1 : rr;   // strip gg + 1
+        if (rrn != row_loaded && rrn < 3) { strip_row_offsets(rrn); row_loaded = rrn; }
+#pragma unroll
+        for (int ss = 0; ss < 3; ++ss) {
+            const int i = 3 * gg + ss;
+            constexpr int dummy = 0; (void)dummy;
+            const int PA = (SB + ss) & 1;   // weight stage of step i
+#pragma unroll
+            for (int ks = 0; ks < 3; ++ks) {
+                wait_frags<0, 4, 4>(ra[ks & 1], rb[ks & 1]);
+#pragma unroll
+                for (int m = 0; m < 16; ++m) {
+                    if (m < 8) read8((ks + 1) & 1, m, PA, SB, ss, ks + 1);
+                    // second half of the weights of step i+1 (the first half went out after the last barrier), two slots
+                    // apart (the address unit takes 16 clocks per copy) and all of them BEFORE the strip copies below: the
+                    // wait at the barrier counts on the strip copies being the youngest
+                    if (ks == 0 && m < 8 && (m & 1))
+                        issue_a(PA ^ 1, ss < 2 ? rr : rrn, ss < 2 ? cc : ccn, (ss + 1) % 3, IA / 2 + (m >> 1), i + 1 < nsteps);
+                    // the strip after this one goes into the buffer the previous strip has left: three copies per slice
+                    if (ss == 0 && m >= 8 && m < 8 + ISB / 3) issue_s(SB ^ 1, ccn, ks * (ISB / 3) + m - 8, more_strips);
+                    mfma_pinned(acc[m >> 2][m & 3], ra[ks & 1][m >> 2], rb[ks & 1][m & 3]);
+                }
+            }
+            wait_frags<0, 4, 4>(ra[1], rb[1]);   // the last slice is in registers: this wave is done with the weight stage
+            if (ss == 2 && rrn != rr && rrn < 3) select_rows(rrn);   // the reads below already belong to the next filter row
+            if (ss == 0) wait_vmcnt<ISB>();      // weights of step i+1 have landed; the strip copies issued since may be in flight
+            else wait_vmcnt<0>();
+            __builtin_amdgcn_s_barrier();
+            {
+                const bool on = i + 2 < nsteps;
+#pragma unroll
+                for (int m = 0; m < 16; ++m) {
+                    if (m < 8) read8(0, m, PA ^ 1, ss < 2 ? SB : SB ^ 1, (ss + 1) % 3, 0);
+                    // first half of the weights of step i+2 into the stage just freed: same strip while ss + 2 < 3, else the next
+                    if ((m & 3) == 1) issue_a(PA, ss == 0 ? rr : rrn, ss == 0 ? cc : ccn, (ss + 2) % 3, m >> 2, on);
+                    mfma_pinned(acc[m >> 2][m & 3], ra[1][m >> 2], rb[1][m & 3]);
+                }
+            }
+        }
+        rr = rrn; cc = ccn;
+    };
+    for (int gg = 0; gg < nstrips; gg += 2) {   // c_in % 128 == 0: an even number of strips per filter row
+        strip_steps(gg, std::integral_constant<int, 0>());
+        strip_steps(gg + 1, std::integral_constant<int, 1>());
+    }
+    wait_vmcnt<0>();   // switched-off copies still write zeros: they are done before the tiles are reused
+    __syncthreads();
+    store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
+}
+constexpr int kStripLds = 2 * 256 * 128 + 2 * 288 * 128 + 256 * 4 + 256 * 4;
 
 // ---------------------------------------------------------------------------------------
 // backward-filter with the same pipeline.  Both operands are reduction-major in LDS:
@@ -729,8 +933,9 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {64, 256, 64, 1, 4, 2}, {64, 256, 32, 1, 4, 2}, {256, 256, 32, 2, 4, 4}, {256, 256, 32, 2, 4, 3},
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
-                           {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2}};
-constexpr int kNumDma = 30;
+                           {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
+                           {256, 256, 64, 2, 2, 2}};
+constexpr int kNumDma = 31, kStripVariant = 30;   // the last entry is k_fwd_strip (forward only; 4 waves)
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -799,6 +1004,7 @@ KernelFn pick_dma(int v)
     case 27: return k_fwd_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_fwd_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_fwd_dma<128, 64, 64, 2, 2, 2, 2>;
+    case 30: return k_fwd_strip;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -832,6 +1038,7 @@ size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
+    if (&d == &kDma[kStripVariant]) return kStripLds;
     size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
     const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
     if (gsum > stages) stages = gsum;
@@ -848,6 +1055,7 @@ hipError_t dma_init()
         if (e != hipSuccess) return e;
     }
     for (int v = 0; v < kNumDma; ++v) {
+        if (v == kStripVariant) continue;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma_d(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)dma_lds_bytes(kDma[v]));
         if (e != hipSuccess) return e;
@@ -891,10 +1099,13 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
         d = &kDma[force_variant - 200];
         if (g.C % d->BK != 0) return false;
+        if (force_variant - 200 == kStripVariant &&   // 3x3, stride 1, pad 1, c_in % 128, whole groups of 8 output channels, no reduction split
+            (g.C % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || g.K % 8 != 0 || force_splits > 1))
+            return false;
         pl->variant = force_variant - 200;
         rowsA = g.K; rowsB = g.N * g.Ho * g.Wo; red = g.R * g.S * g.C;
     } else if (pass == PASS_DGRAD) {
-        if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
+        if (force_variant < 200 || force_variant >= 200 + kNumDma || force_variant - 200 == kStripVariant) return false;
         d = &kDma[force_variant - 200];
         if (g.K % d->BK != 0 || g.C % 8 != 0) return false;   // any stride: taps that miss the stride grid are masked out
         pl->variant = force_variant - 200;
@@ -926,7 +1137,8 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         }
     }
     int splits;
-    if (force_splits > 0) splits = force_splits;
+    if (pass == PASS_FWD && pl->variant == kStripVariant) splits = 1;
+    else if (force_splits > 0) splits = force_splits;
     else {
         long long tiles = (long long)pl->tilesA * pl->tilesB;
         splits = tiles >= 512 ? 1 : (int)((512 + tiles - 1) / tiles);
@@ -945,7 +1157,8 @@ void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
     // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
-    if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
+    if (pass == PASS_FWD && pl.variant == kStripVariant) snprintf(name, name_bytes, "k_fwd_strip");
+    else if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
     else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
                   d.WB, d.NS, d.KG);
 }

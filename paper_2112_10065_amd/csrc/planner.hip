@@ -22,6 +22,7 @@ struct Candidate {
 
 // forward / backward-data candidates
 const Candidate kPix[] = {
+    {230, 1, 1.30f, 9.0f},   // 256x256x64, 4 waves, 3x3 stride 1 forward with the pixel strip shared by the three taps of a filter row
     {208, 1, 1.55f, 8.0f},   // 256x256x64, 8 waves, direct-to-LDS
     {200, 2, 1.08f, 5.0f},   // 128x128x64 direct-to-LDS
     {204, 3, 0.85f, 4.5f},   // 64x128x64

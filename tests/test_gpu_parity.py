@@ -386,6 +386,30 @@ def test_input_patch_stationary_weights(env, blocks):
         dp.dp_set_override(1, -1, 0)
 
 
+def test_forward_pixel_strip_kernel(env):
+    """3x3, stride 1, pad 1, c_in % 128 == 0: the forward kernel that keeps one strip of input pixels in LDS for the three
+    taps of a filter row and redirects (pixel, tap) pairs outside the image to rows of zeros.  Ragged last tiles in
+    both directions, tiles that span several images, images narrower than the filter, one and several channel
+    blocks, with and without the epilogue."""
+    dp, U, orc = env
+    dp.dp_set_override(0, 230, 1)
+    try:
+        for tag, n, h, w, c, k, epi in (("st_a", 2, 13, 12, 128, 96, True), ("st_b", 1, 37, 40, 256, 264, True), ("st_c", 3, 5, 70, 128, 8, False),
+                                        ("st_d", 5, 9, 3, 128, 64, True), ("st_e", 1, 1, 1, 128, 16, True), ("st_f", 7, 2, 2, 384, 40, False)):
+            case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=epi, relu=epi)
+            assert dp.dp_conv2d_kernel_info(case.desc, 0) == ("k_fwd_strip", 1)
+            y = case.run_fwd()
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b if epi else None, relu=epi, stride=(1, 1), pad=(1, 1)), tag)
+        # other shapes are not this kernel's: 64 input channels, no padding, stride 2, 5x5
+        for tag, c, r, st, pd in (("st_c64", 64, 3, (1, 1), (1, 1)), ("st_p0", 128, 3, (1, 1), (0, 0)), ("st_s2", 128, 3, (2, 2), (1, 1)),
+                                  ("st_5x5", 128, 5, (1, 1), (2, 2))):
+            case = U.ConvCase(tag, 1, 12, 12, c, 32, r, r, st, pd, bf16=True, bias=True, relu=True)
+            assert "k_fwd_strip" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+    finally:
+        dp.dp_set_override(0, -1, 0)
+
+
 @pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307, 308, 309, 310, 311, 312, 313, 314, 315])
 @pytest.mark.parametrize("splits", [1, 3])
 def test_pipelined_backward_filter_variants(env, variant, splits):
