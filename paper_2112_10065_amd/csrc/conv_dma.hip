@@ -287,21 +287,24 @@ DEVFN void mfma_pinned(f32x16 &c, const u32x4 &a, const u32x4 &b)
 }
 
 // ---------------------------------------------------------------------------------------
-// Forward 3x3 / stride 1 / pad 1 with the pixel operand kept in LDS across the three taps of a filter row.
-// In flat pixel order (n, h, w) tap (r, s) of output pixel m reads input pixel m + (r-1)*W + (s-1), so the
-// 256 pixel rows of a tile for the taps s = 0, 1, 2 of one filter row are three windows, one row apart, of
-// ONE strip of 258 input pixels: the strip is copied to LDS once per (filter row, channel block) and serves
-// three reduction steps; only the weights are fetched every step.  Pairs (pixel, tap) that fall outside the
-// image would read a neighbour's pixel from the strip; those lanes read rows of zeros instead (the strip
-// buffers are 288 rows long and the rows past 258 are always filled with zeros).
+// 3x3 / stride 1 / pad 1, forward and backward-data, with the pixel operand kept in LDS across the three taps
+// of a filter row.  In flat pixel order (n, h, w) tap (r, s) of output pixel m reads input pixel
+// m + (r-1)*W + (s-1), so the 256 pixel rows of a tile for the taps s = 0, 1, 2 of one filter row are three
+// windows, one row apart, of ONE strip of 258 pixels: the strip is copied to LDS once per (filter row, channel
+// block) and serves three reduction steps; only the weights are fetched every step.  Pairs (pixel, tap) that
+// fall outside the image would read a neighbour's pixel from the strip; those lanes read rows of zeros instead
+// (the strip buffers are 288 rows long and the rows past 258 are always filled with zeros).
+// Backward-data is the same walk over dy with the filter mirrored (tap (r, s) of the walk multiplies the weights
+// of tap (2-r, 2-s)); its weights are reduction-major in LDS, [64 c_out][256 c_in], and go through the LDS
+// transpose read as in k_dgrad_dma; the backward of an input ReLU rides in the staged epilogue.
 // One wave per SIMD (4 waves, 128x128 each: 256 accumulators leave no room for a second wave), so nothing
 // hides a stall and, measured, nothing overlaps the wave's own vector instructions with its matrix
 // instructions.  The loop body therefore holds matrix instructions, LDS reads and direct-to-LDS copies only:
-// every per-lane address is precomputed (48 registers of B addresses per filter row), stage and buffer
+// every per-lane address is precomputed (48 registers of pixel addresses per filter row), stage and buffer
 // offsets are instruction immediates (two strips = six steps are unrolled), step offsets of the copies ride in
 // the scalar offset and a copy is switched off by a zero-length buffer resource.  Reads and copies sit in
 // slots between matrix instructions; a scheduling barrier after each keeps the compiler from regrouping them.
-// Reduction order: filter row, channel block, filter column.  Needs c_in % 128 == 0.
+// Reduction order: filter row, channel block, filter column.  Needs reduction channels % 128 == 0.
 // ---------------------------------------------------------------------------------------
 template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   // offset OFF0 + blk * BS as an immediate
 {
@@ -313,11 +316,14 @@ template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   
     }
 }
 
-__global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
+template <bool DG>   // DG: backward-data
+__global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 {
     constexpr int TA = 256, TB = 256, BK = 64, NT = 256, FA = 4, FB = 4, ROWB = 128, BS = 32 * ROWB;
     constexpr int A_BYTES = TA * ROWB, SROWS = 288, S_BYTES = SROWS * ROWB, IA = 8, ISB = SROWS / 8 / 4, ZROW = 272;
+    constexpr int ROWA = TA * 2;   // backward-data: a weight row in LDS holds the 256 c_in of one c_out
     constexpr int LDS_TILES = 2 * A_BYTES + 2 * S_BYTES;
+    constexpr int NRD = DG ? 12 : 8;   // LDS reads per slice (a transposed weight fragment takes two)
     static_assert(LDS_TILES >= TB * (TA + 8) * 2, "the staged epilogue reuses the tiles");
     static_assert(A_BYTES + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -328,44 +334,52 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
-    const int RSC = 9 * g.C, NHW = g.N * g.H * g.W, CB = g.C / BK, nstrips = 3 * CB, nsteps = 3 * nstrips;
-    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(p.x, (size_t)NHW * g.C * 2);
-    __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(p.x, 0);   // every lane out of range: a switched-off copy
+    const int CR = DG ? g.K : g.C;   // reduction channels = channels of the pixel operand
+    const int RSC = 9 * g.C, NHW = g.N * g.H * g.W, CB = CR / BK, nstrips = 3 * CB, nsteps = 3 * nstrips;
+    const bf16_t *pix = DG ? p.dy : p.x;
+    __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(pix, (size_t)NHW * CR * 2);
+    __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(pix, 0);   // every lane out of range: a switched-off copy
     {
         const int m = b0 + tid;
         const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
         rowtab[tid] = m < p.rowsB ? tap_mask(hh - 1, ww - 1, 1, 3, 3, g.H, g.W) : 0u;
     }
-    if (p.flags & KF_BIAS) bias_lds[tid] = a0 + tid < p.rowsA ? p.bias[a0 + tid] : 0.f;
+    if (!DG && (p.flags & KF_BIAS)) bias_lds[tid] = a0 + tid < p.rowsA ? p.bias[a0 + tid] : 0.f;
     __syncthreads();
 
-    // copies: lane l of instruction q fills chunk position l % 8 of tile row rq = q*8 + l/8 with global chunk (l % 8) ^ swizzle(rq)
     const unsigned wave_s = __builtin_amdgcn_readfirstlane(wave);
     const unsigned lds0 = lds_offset(smem), ldsS0 = lds0 + 2 * A_BYTES;
     unsigned voffA[IA], voffS[ISB], voffS_r[ISB];
     int pixS[ISB];
 #pragma unroll
     for (int q = 0; q < IA; ++q) {
-        const int row = (wave * IA + q) * 8 + lane / 8, c = (lane % 8) ^ ((row >> 1) & 7);
-        voffA[q] = ((unsigned)(a0 + row) * RSC + c * 8) * 2u;
+        if constexpr (DG) {
+            // one copy fills two reduction rows t (c_out) of 512 bytes: lane l takes the 16-byte chunk (l % 32) ^ swizzle(t)
+            const int t = (wave * IA + q) * 2 + lane / 32, col = a0 + ((lane % 32) ^ ((t & 3) << 2)) * 8;
+            voffA[q] = col < g.C ? ((unsigned)t * RSC + col) * 2u : OOR;   // columns past c_in stay zero
+        } else {
+            // lane l of copy q fills chunk position l % 8 of tile row rq = q*8 + l/8 with global chunk (l % 8) ^ swizzle(rq)
+            const int row = (wave * IA + q) * 8 + lane / 8, c = (lane % 8) ^ ((row >> 1) & 7);
+            voffA[q] = ((unsigned)(a0 + row) * RSC + c * 8) * 2u;
+        }
     }
 #pragma unroll
     for (int q = 0; q < ISB; ++q) {
         const int row = (wave * ISB + q) * 8 + lane / 8, c = (lane % 8) ^ ((row >> 1) & 7);
-        pixS[q] = row < TB + 2 ? b0 - 1 + row : -0x40000000;   // strip row j holds input pixel b0 - 1 + j + (r-1)*W
-        voffS[q] = ((unsigned)(b0 - 1 + row) * g.C + c * 8) * 2u;
+        pixS[q] = row < TB + 2 ? b0 - 1 + row : -0x40000000;   // strip row j holds pixel b0 - 1 + j + (r-1)*W
+        voffS[q] = ((unsigned)(b0 - 1 + row) * CR + c * 8) * 2u;
     }
     auto strip_row_offsets = [&](int rr) {   // per filter row: where each strip row comes from, OOR (zeros) outside the tensor
         const int shift = (rr - 1) * g.W;
 #pragma unroll
         for (int q = 0; q < ISB; ++q)
-            voffS_r[q] = (unsigned)(pixS[q] + shift) < (unsigned)NHW ? voffS[q] + (unsigned)(shift * g.C) * 2u : OOR;
+            voffS_r[q] = (unsigned)(pixS[q] + shift) < (unsigned)NHW ? voffS[q] + (unsigned)(shift * CR) * 2u : OOR;
     };
-    // the step's offset is uniform: it rides in the scalar offset, which the range check ignores (weight rows past the last
-    // filter are out of range by their own offset)
-    auto issue_a = [&](int stage, int rr, int cc, int ss, int q, bool on) {   // weights of tap (rr, ss), channel block cc
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rw : rw_off, (lds_void)(size_t)(lds0 + stage * A_BYTES + (wave_s * IA + q) * 1024), 16, voffA[q],
-                                                 ((rr * 3 + ss) * g.C + cc * BK) * 2, 0, 0);
+    // the step's offset is uniform: it rides in the scalar offset, which the range check ignores (weight rows / columns past
+    // the tensor are out of range by their own offset)
+    auto issue_a = [&](int stage, int rr, int cc, int ss, int q, bool on) {   // weights of walk tap (rr, ss), channel block cc
+        const int soff = DG ? (cc * BK * RSC + ((2 - rr) * 3 + (2 - ss)) * g.C) * 2 : ((rr * 3 + ss) * g.C + cc * BK) * 2;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rw : rw_off, (lds_void)(size_t)(lds0 + stage * A_BYTES + (wave_s * IA + q) * 1024), 16, voffA[q], soff, 0, 0);
     };
     auto issue_s = [&](int buf, int cc, int q, bool on) {   // strip (filter row of voffS_r, channel block cc) into strip buffer `buf`
         __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rx : rx_off, (lds_void)(size_t)(ldsS0 + buf * S_BYTES + (wave_s * ISB + q) * 1024), 16, voffS_r[q],
@@ -381,15 +395,28 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     const int arow = (wave & 1) * 128, brow = (wave >> 1) * 128;
     const int rA = arow + (lane & 31), rB = brow + (lane & 31);
-    // slice ks of a row sits at chunk (2*ks + half) ^ swizzle: its address is the slice-0 address with ks << 5 xor-ed in
-    unsigned fa[4], fbs[3], fmask[FB], vsel[3][FB][4];
+    // forward: slice ks of a weight row sits at chunk (2*ks + half) ^ swizzle; backward-data: the transpose read of
+    // fragment i, slice ks starts at reduction row t = 16*ks + tl, 64-byte segment (col / 32) ^ swizzle(t)
+    unsigned fa[4][DG ? FA : 1], fbs[3], fmask[FB], vsel[3][FB][4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) fa[ks] = lds0 + rA * ROWB + (((2 * ks + (lane >> 5)) ^ ((rA >> 1) & 7)) << 4);
+    for (int ks = 0; ks < 4; ++ks) {
+        if constexpr (DG) {
+            const int i16 = lane & 15, t = ks * 16 + (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+#pragma unroll
+            for (int i = 0; i < FA; ++i) {
+                const int col = arow + i * 32 + cl;
+                fa[ks][i] = lds0 + t * ROWA + ((((col >> 5) ^ (t & 3)) << 6) | ((col & 31) << 1));
+            }
+        } else {
+            fa[ks][0] = lds0 + rA * ROWB + (((2 * ks + (lane >> 5)) ^ ((rA >> 1) & 7)) << 4);
+        }
+    }
+    // pixel rows: slice ks is the slice-0 address with ks << 5 xor-ed in
 #pragma unroll
     for (int ss = 0; ss < 3; ++ss) fbs[ss] = ldsS0 + (rB + ss) * ROWB + (((lane >> 5) ^ (((rB + ss) >> 1) & 7)) << 4);
 #pragma unroll
     for (int j = 0; j < FB; ++j) fmask[j] = rowtab[rB + 32 * j];
-    // B addresses of filter row rr (strip buffer 0; fragment j is read at immediate offset j * BS): the strip row, or for a
+    // pixel addresses of filter row rr (strip buffer 0; fragment j is read at immediate offset j * BS): the strip row, or for a
     // pair outside the image the zero rows, at the same position within 256 bytes (the same banks as the neighbours expect)
     auto select_rows = [&](int rr) {
 #pragma unroll
@@ -404,10 +431,39 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
     };
 
     u32x4 ra[2][4], rb[2][4];
-    // read j (a0 b0 a1 b1 ...) of slice ks of the step that uses weight stage PA, strip buffer SB and filter column ss
-    auto read8 = [&](int buf, int j, int PA, int SB, int ss, int ks) {
-        if (j & 1) rb[buf][j >> 1] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][j >> 1][ks], j >> 1) : lds_read16_at<0, BS>(vsel[ss][j >> 1][ks], j >> 1);
-        else ra[buf][j >> 1] = PA ? lds_read16_at<A_BYTES, BS>(fa[ks], j >> 1) : lds_read16_at<0, BS>(fa[ks], j >> 1);
+    u32x2 alo[2][DG ? 4 : 1], ahi[2][DG ? 4 : 1];
+    // read j of slice ks of the step that uses weight stage PA, strip buffer SB and filter column ss
+    // (forward: a0 b0 a1 b1 ...; backward-data: a0lo a0hi b0 a1lo a1hi b1 ...)
+    auto read_b = [&](int buf, int f, int SB, int ss, int ks) {
+        rb[buf][f] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][f][ks], f) : lds_read16_at<0, BS>(vsel[ss][f][ks], f);
+    };
+    auto read_slot = [&](int buf, int j, int PA, int SB, int ss, int ks) {
+        if constexpr (DG) {
+            const int f = j / 3;
+            if (j % 3 == 2) read_b(buf, f, SB, ss, ks);
+            else if (j % 3 == 0) alo[buf][f] = PA ? lds_read_tr<A_BYTES>(fa[ks][f]) : lds_read_tr<0>(fa[ks][f]);
+            else ahi[buf][f] = PA ? lds_read_tr<A_BYTES + 4 * ROWA>(fa[ks][f]) : lds_read_tr<4 * ROWA>(fa[ks][f]);   // 4 rows on: same swizzle class
+        } else {
+            if (j & 1) read_b(buf, j >> 1, SB, ss, ks);
+            else ra[buf][j >> 1] = PA ? lds_read16_at<A_BYTES, BS>(fa[ks][0], j >> 1) : lds_read16_at<0, BS>(fa[ks][0], j >> 1);
+        }
+    };
+    auto landed = [&](int buf) {   // the LDS reads so far have arrived; the fragments depend on the wait
+        if constexpr (DG) {
+            asm volatile("s_waitcnt lgkmcnt(0)");
+#pragma unroll
+            for (int f = 0; f < 4; ++f) { asm volatile("" : "+v"(alo[buf][f])); asm volatile("" : "+v"(ahi[buf][f])); asm volatile("" : "+v"(rb[buf][f])); }
+        } else {
+            wait_frags<0, 4, 4>(ra[buf], rb[buf]);
+        }
+    };
+    auto multiply = [&](int buf, int m) {
+        if constexpr (DG) {
+            const u32x4 av = {alo[buf][m >> 2].x, alo[buf][m >> 2].y, ahi[buf][m >> 2].x, ahi[buf][m >> 2].y};
+            mfma_pinned(acc[m >> 2][m & 3], av, rb[buf][m & 3]);
+        } else {
+            mfma_pinned(acc[m >> 2][m & 3], ra[buf][m >> 2], rb[buf][m & 3]);
+        }
     };
 
     // prologue: strip 0, weights of step 0 and the first half of step 1
@@ -423,7 +479,7 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
     wait_vmcnt<IA / 2>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) read8(0, j, 0, 0, 0, 0);
+    for (int j = 0; j < NRD; ++j) read_slot(0, j, 0, 0, 0, 0);
 
     int rr = 0, cc = 0;   // filter row and channel block of strip gg
     // one strip = three steps; SB = gg & 1 is the strip's buffer, and with it the parity of its first step
@@ -435,14 +491,13 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
 #pragma unroll
         for (int ss = 0; ss < 3; ++ss) {
             const int i = 3 * gg + ss;
-            constexpr int dummy = 0; (void)dummy;
             const int PA = (SB + ss) & 1;   // weight stage of step i
 #pragma unroll
             for (int ks = 0; ks < 3; ++ks) {
-                wait_frags<0, 4, 4>(ra[ks & 1], rb[ks & 1]);
+                landed(ks & 1);
 #pragma unroll
                 for (int m = 0; m < 16; ++m) {
-                    if (m < 8) read8((ks + 1) & 1, m, PA, SB, ss, ks + 1);
+                    if (m < NRD) read_slot((ks + 1) & 1, m, PA, SB, ss, ks + 1);
                     // second half of the weights of step i+1 (the first half went out after the last barrier), two slots
                     // apart (the address unit takes 16 clocks per copy) and all of them BEFORE the strip copies below: the
                     // wait at the barrier counts on the strip copies being the youngest
@@ -450,10 +505,10 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
                         issue_a(PA ^ 1, ss < 2 ? rr : rrn, ss < 2 ? cc : ccn, (ss + 1) % 3, IA / 2 + (m >> 1), i + 1 < nsteps);
                     // the strip after this one goes into the buffer the previous strip has left: three copies per slice
                     if (ss == 0 && m >= 8 && m < 8 + ISB / 3) issue_s(SB ^ 1, ccn, ks * (ISB / 3) + m - 8, more_strips);
-                    mfma_pinned(acc[m >> 2][m & 3], ra[ks & 1][m >> 2], rb[ks & 1][m & 3]);
+                    multiply(ks & 1, m);
                 }
             }
-            wait_frags<0, 4, 4>(ra[1], rb[1]);   // the last slice is in registers: this wave is done with the weight stage
+            landed(1);   // the last slice is in registers: this wave is done with the weight stage
             if (ss == 2 && rrn != rr && rrn < 3) select_rows(rrn);   // the reads below already belong to the next filter row
             if (ss == 0) wait_vmcnt<ISB>();      // weights of step i+1 have landed; the strip copies issued since may be in flight
             else wait_vmcnt<0>();
@@ -462,16 +517,16 @@ __global__ __launch_bounds__(256) void k_fwd_strip(const KArgs p)
                 const bool on = i + 2 < nsteps;
 #pragma unroll
                 for (int m = 0; m < 16; ++m) {
-                    if (m < 8) read8(0, m, PA ^ 1, ss < 2 ? SB : SB ^ 1, (ss + 1) % 3, 0);
+                    if (m < NRD) read_slot(0, m, PA ^ 1, ss < 2 ? SB : SB ^ 1, (ss + 1) % 3, 0);
                     // first half of the weights of step i+2 into the stage just freed: same strip while ss + 2 < 3, else the next
                     if ((m & 3) == 1) issue_a(PA, ss == 0 ? rr : rrn, ss == 0 ? cc : ccn, (ss + 2) % 3, m >> 2, on);
-                    mfma_pinned(acc[m >> 2][m & 3], ra[1][m >> 2], rb[1][m & 3]);
+                    multiply(1, m);
                 }
             }
         }
         rr = rrn; cc = ccn;
     };
-    for (int gg = 0; gg < nstrips; gg += 2) {   // c_in % 128 == 0: an even number of strips per filter row
+    for (int gg = 0; gg < nstrips; gg += 2) {   // reduction channels % 128 == 0: an even number of strips per filter row
         strip_steps(gg, std::integral_constant<int, 0>());
         strip_steps(gg + 1, std::integral_constant<int, 1>());
     }
@@ -935,7 +990,7 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
                            {256, 256, 64, 2, 2, 2}};
-constexpr int kNumDma = 31, kStripVariant = 30;   // the last entry is k_fwd_strip (forward only; 4 waves)
+constexpr int kNumDma = 31, kStripVariant = 30;   // the last entry is k_conv_strip (4 waves; its own LDS layout)
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -969,6 +1024,7 @@ KernelFn pick_dma_d(int v)
     case 27: return k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>;
+    case 30: return k_conv_strip<true>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1004,7 +1060,7 @@ KernelFn pick_dma(int v)
     case 27: return k_fwd_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_fwd_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_fwd_dma<128, 64, 64, 2, 2, 2, 2>;
-    case 30: return k_fwd_strip;
+    case 30: return k_conv_strip<false>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1055,7 +1111,6 @@ hipError_t dma_init()
         if (e != hipSuccess) return e;
     }
     for (int v = 0; v < kNumDma; ++v) {
-        if (v == kStripVariant) continue;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(pick_dma_d(v)), hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)dma_lds_bytes(kDma[v]));
         if (e != hipSuccess) return e;
@@ -1105,9 +1160,12 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         pl->variant = force_variant - 200;
         rowsA = g.K; rowsB = g.N * g.Ho * g.Wo; red = g.R * g.S * g.C;
     } else if (pass == PASS_DGRAD) {
-        if (force_variant < 200 || force_variant >= 200 + kNumDma || force_variant - 200 == kStripVariant) return false;
+        if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
         d = &kDma[force_variant - 200];
-        if (g.K % d->BK != 0 || g.C % 8 != 0) return false;   // any stride: taps that miss the stride grid are masked out
+        if (g.K % d->BK != 0 || g.C % 8 != 0) return false;
+        if (force_variant - 200 == kStripVariant &&   // as forward, with c_out as the reduction; bf16 gradients only (the caller checks)
+            (g.K % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || force_splits > 1))
+            return false;   // any stride: taps that miss the stride grid are masked out
         pl->variant = force_variant - 200;
         rowsA = g.C; rowsB = g.N * g.H * g.W; red = g.R * g.S * g.K;
     } else if (pass == PASS_WGRAD) {
@@ -1137,7 +1195,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         }
     }
     int splits;
-    if (pass == PASS_FWD && pl->variant == kStripVariant) splits = 1;
+    if (pass != PASS_WGRAD && pl->variant == kStripVariant) splits = 1;
     else if (force_splits > 0) splits = force_splits;
     else {
         long long tiles = (long long)pl->tilesA * pl->tilesB;
@@ -1157,7 +1215,7 @@ void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
     // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
-    if (pass == PASS_FWD && pl.variant == kStripVariant) snprintf(name, name_bytes, "k_fwd_strip");
+    if (pass != PASS_WGRAD && pl.variant == kStripVariant) snprintf(name, name_bytes, pass == PASS_FWD ? "k_conv_strip<false>" : "k_conv_strip<true>");
     else if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
     else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
                   d.WB, d.NS, d.KG);

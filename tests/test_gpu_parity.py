@@ -397,7 +397,7 @@ def test_forward_pixel_strip_kernel(env):
         for tag, n, h, w, c, k, epi in (("st_a", 2, 13, 12, 128, 96, True), ("st_b", 1, 37, 40, 256, 264, True), ("st_c", 3, 5, 70, 128, 8, False),
                                         ("st_d", 5, 9, 3, 128, 64, True), ("st_e", 1, 1, 1, 128, 16, True), ("st_f", 7, 2, 2, 384, 40, False)):
             case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=epi, relu=epi)
-            assert dp.dp_conv2d_kernel_info(case.desc, 0) == ("k_fwd_strip", 1)
+            assert dp.dp_conv2d_kernel_info(case.desc, 0) == ("k_conv_strip<false>", 1)
             y = case.run_fwd()
             torch.cuda.synchronize()
             U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b if epi else None, relu=epi, stride=(1, 1), pad=(1, 1)), tag)
@@ -405,9 +405,39 @@ def test_forward_pixel_strip_kernel(env):
         for tag, c, r, st, pd in (("st_c64", 64, 3, (1, 1), (1, 1)), ("st_p0", 128, 3, (1, 1), (0, 0)), ("st_s2", 128, 3, (2, 2), (1, 1)),
                                   ("st_5x5", 128, 5, (1, 1), (2, 2))):
             case = U.ConvCase(tag, 1, 12, 12, c, 32, r, r, st, pd, bf16=True, bias=True, relu=True)
-            assert "k_fwd_strip" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            assert "k_conv_strip" not in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
     finally:
         dp.dp_set_override(0, -1, 0)
+
+
+def test_backward_data_pixel_strip_kernel(env):
+    """The same kernel on the backward-data pass (c_out % 128 == 0): mirrored filter, weights through the LDS transpose
+    read, with and without the fused backward of the input ReLU; fp32 gradients are not this kernel's."""
+    dp, U, orc = env
+    dp.dp_set_override(1, 230, 1)
+    try:
+        for tag, n, h, w, c, k in (("sd_a", 2, 13, 12, 96, 128), ("sd_b", 1, 37, 40, 264, 256), ("sd_c", 3, 5, 70, 8, 128),
+                                   ("sd_d", 5, 9, 3, 64, 128), ("sd_e", 1, 1, 1, 16, 128), ("sd_f", 7, 2, 2, 40, 384)):
+            case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+            assert dp.dp_conv2d_kernel_info(case.desc, 1) == ("k_conv_strip<true>", 1)
+            y = case.run_fwd()
+            dx = case.run_dgrad(y)          # the incoming gradient is masked by the saved output first
+            torch.cuda.synchronize()
+            ref = orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), pad=(1, 1))
+            U.assert_bf16_close(U.to_np(dx), ref, tag)
+            dxm = case.run_dgrad_relu_in(y)      # the backward of the ReLU in front of the layer rides in the epilogue
+            torch.cuda.synchronize()
+            U.assert_bf16_close(U.to_np(dxm), orc.relu_in_backward(ref, case.x), tag + " masked")
+        case = U.ConvCase("sd_f32", 2, 13, 12, 72, 128, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=True)
+        assert "k_conv_strip" not in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+        dx = case.run_dgrad(None)
+        torch.cuda.synchronize()
+        assert dx.dtype == torch.float32
+        U.assert_bf16_close(U.to_np(dx), orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=None, pad=(1, 1)), "sd_f32")
+        case = U.ConvCase("sd_k64", 1, 12, 12, 32, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+        assert "k_conv_strip" not in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+    finally:
+        dp.dp_set_override(1, -1, 0)
 
 
 @pytest.mark.parametrize("variant", [300, 301, 302, 303, 304, 305, 306, 307, 308, 309, 310, 311, 312, 313, 314, 315])
