@@ -316,16 +316,34 @@ template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   
     }
 }
 
-template <bool DG>   // DG: backward-data
+// which fragment read j of a slice fetches: fragment index * 4 + kind (0 weights / weights low half, 1 weights high half, 2 pixels);
+// order: weights of fragment f (two transposed reads on backward-data), then pixels of fragment f while there are any
+constexpr int strip_read_kind(int j, bool dg, int fb)
+{
+    int n = 0;
+    for (int f = 0; f < 4; ++f) {
+        if (n++ == j) return f * 4;
+        if (dg && n++ == j) return f * 4 + 1;
+        if (f < fb && n++ == j) return f * 4 + 2;
+    }
+    return -1;
+}
+
+template <bool DG, int TB>   // DG: backward-data; TB: pixel rows of a tile (256, or 128 for grids that would leave most CUs idle)
 __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 {
-    constexpr int TA = 256, TB = 256, BK = 64, NT = 256, FA = 4, FB = 4, ROWB = 128, BS = 32 * ROWB;
-    constexpr int A_BYTES = TA * ROWB, SROWS = 288, S_BYTES = SROWS * ROWB, IA = 8, ISB = SROWS / 8 / 4, ZROW = 272;
+#if __HIP_DEVICE_COMPILE__   // the host pass only needs the launch stub (and silently drops it when it sees this body)
+    constexpr int TA = 256, BK = 64, NT = 256, FA = 4, FB = TB / 64, ROWB = 128, BS = 32 * ROWB;
+    constexpr int NSA = TB == 256 ? 2 : 3;   // weight stages: what fits beside the two strip buffers
+    constexpr int A_BYTES = TA * ROWB, SROWS = TB == 256 ? 288 : 192, S_BYTES = SROWS * ROWB, IA = 8, ISB = SROWS / 32, ZROW = TB + 16;
     constexpr int ROWA = TA * 2;   // backward-data: a weight row in LDS holds the 256 c_in of one c_out
-    constexpr int LDS_TILES = 2 * A_BYTES + 2 * S_BYTES;
-    constexpr int NRD = DG ? 12 : 8;   // LDS reads per slice (a transposed weight fragment takes two)
+    constexpr int LDS_TILES = NSA * A_BYTES + 2 * S_BYTES;
+    constexpr int NM = FA * FB;                     // matrix instructions (= slots) per slice
+    constexpr int NRD = (DG ? 2 * FA : FA) + FB;   // LDS reads per slice (a transposed weight fragment takes two)
+    constexpr int SPS = ISB / 3, SM0 = NM - 8 + (TB == 256 ? 0 : 6);   // strip copies per slice and their first slot
     static_assert(LDS_TILES >= TB * (TA + 8) * 2, "the staged epilogue reuses the tiles");
-    static_assert(A_BYTES + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
+    static_assert(A_BYTES + 4 * ROWA + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
+    static_assert(ISB % 3 == 0 && SM0 + SPS <= NM && ZROW + 2 <= SROWS && (NSA == 2 || NM == IA), "slot plan");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     unsigned *rowtab = reinterpret_cast<unsigned *>(smem + LDS_TILES);   // [TB] tap masks
     float *bias_lds = reinterpret_cast<float *>(rowtab + TB);           // [TA]
@@ -339,7 +357,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     const bf16_t *pix = DG ? p.dy : p.x;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(pix, (size_t)NHW * CR * 2);
     __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(pix, 0);   // every lane out of range: a switched-off copy
-    {
+    if (tid < TB) {
         const int m = b0 + tid;
         const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
         rowtab[tid] = m < p.rowsB ? tap_mask(hh - 1, ww - 1, 1, 3, 3, g.H, g.W) : 0u;
@@ -348,7 +366,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     __syncthreads();
 
     const unsigned wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const unsigned lds0 = lds_offset(smem), ldsS0 = lds0 + 2 * A_BYTES;
+    const unsigned lds0 = lds_offset(smem), ldsS0 = lds0 + NSA * A_BYTES;
     unsigned voffA[IA], voffS[ISB], voffS_r[ISB];
     int pixS[ISB];
 #pragma unroll
@@ -393,11 +411,12 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         for (int j = 0; j < FB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    const int arow = (wave & 1) * 128, brow = (wave >> 1) * 128;
+    const int arow = (wave & 1) * 128, brow = (wave >> 1) * (TB / 2);
     const int rA = arow + (lane & 31), rB = brow + (lane & 31);
     // forward: slice ks of a weight row sits at chunk (2*ks + half) ^ swizzle; backward-data: the transpose read of
-    // fragment i, slice ks starts at reduction row t = 16*ks + tl, 64-byte segment (col / 32) ^ swizzle(t)
-    unsigned fa[4][DG ? FA : 1], fbs[3], fmask[FB], vsel[3][FB][4];
+    // fragment i, slice ks starts at reduction row t = 16*ks + tl, 64-byte segment (col / 32) ^ swizzle(t).
+    // fa_hi: the same for the third weight stage, which a 16-bit immediate cannot reach from the first
+    unsigned fa[4][DG ? FA : 1], fa_hi[4][DG ? FA : 1], fbs[3], fmask[FB], vsel[3][FB][4];
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         if constexpr (DG) {
@@ -406,9 +425,11 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
             for (int i = 0; i < FA; ++i) {
                 const int col = arow + i * 32 + cl;
                 fa[ks][i] = lds0 + t * ROWA + ((((col >> 5) ^ (t & 3)) << 6) | ((col & 31) << 1));
+                fa_hi[ks][i] = fa[ks][i] + 2 * A_BYTES;
             }
         } else {
             fa[ks][0] = lds0 + rA * ROWB + (((2 * ks + (lane >> 5)) ^ ((rA >> 1) & 7)) << 4);
+            fa_hi[ks][0] = fa[ks][0] + 2 * A_BYTES;
         }
     }
     // pixel rows: slice ks is the slice-0 address with ks << 5 xor-ed in
@@ -430,56 +451,70 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
             }
     };
 
-    u32x4 ra[2][4], rb[2][4];
+    u32x4 ra[2][4], rb[2][FB];
     u32x2 alo[2][DG ? 4 : 1], ahi[2][DG ? 4 : 1];
-    // read j of slice ks of the step that uses weight stage PA, strip buffer SB and filter column ss
-    // (forward: a0 b0 a1 b1 ...; backward-data: a0lo a0hi b0 a1lo a1hi b1 ...)
-    auto read_b = [&](int buf, int f, int SB, int ss, int ks) {
-        rb[buf][f] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][f][ks], f) : lds_read16_at<0, BS>(vsel[ss][f][ks], f);
-    };
-    auto read_slot = [&](int buf, int j, int PA, int SB, int ss, int ks) {
-        if constexpr (DG) {
-            const int f = j / 3;
-            if (j % 3 == 2) read_b(buf, f, SB, ss, ks);
-            else if (j % 3 == 0) alo[buf][f] = PA ? lds_read_tr<A_BYTES>(fa[ks][f]) : lds_read_tr<0>(fa[ks][f]);
-            else ahi[buf][f] = PA ? lds_read_tr<A_BYTES + 4 * ROWA>(fa[ks][f]) : lds_read_tr<4 * ROWA>(fa[ks][f]);   // 4 rows on: same swizzle class
+    // read j of slice ks of the step that uses weight stage ST, strip buffer SB and filter column ss
+    auto read_slot = [&](int buf, int j, int ST, int SB, int ss, int ks) {
+        const int kind = strip_read_kind(j, DG, FB), f = kind >> 2;
+        if ((kind & 3) == 2) {
+            rb[buf][f] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][f][ks], f) : lds_read16_at<0, BS>(vsel[ss][f][ks], f);
+        } else if constexpr (DG) {
+            const unsigned ad = ST == 2 ? fa_hi[ks][f] : fa[ks][f];
+            if ((kind & 3) == 0) alo[buf][f] = ST == 1 ? lds_read_tr<A_BYTES>(ad) : lds_read_tr<0>(ad);
+            else ahi[buf][f] = ST == 1 ? lds_read_tr<A_BYTES + 4 * ROWA>(ad) : lds_read_tr<4 * ROWA>(ad);   // 4 rows on: same swizzle class
         } else {
-            if (j & 1) read_b(buf, j >> 1, SB, ss, ks);
-            else ra[buf][j >> 1] = PA ? lds_read16_at<A_BYTES, BS>(fa[ks][0], j >> 1) : lds_read16_at<0, BS>(fa[ks][0], j >> 1);
+            const unsigned ad = ST == 2 ? fa_hi[ks][0] : fa[ks][0];
+            ra[buf][f] = ST == 1 ? lds_read16_at<A_BYTES, BS>(ad, f) : lds_read16_at<0, BS>(ad, f);
+        }
+    };
+    // the reads of a slice sit in the first slots, one per slot (two in the first slots if there are more reads than slots)
+    auto read_slots = [&](int m, int buf, int ST, int SB, int ss, int ks) {
+#pragma unroll
+        for (int j = 0; j < NRD; ++j) {
+            const int slot = NRD <= NM ? j : (j < 2 * (NRD - NM) ? j / 2 : j - (NRD - NM));
+            if (slot == m) read_slot(buf, j, ST, SB, ss, ks);
         }
     };
     auto landed = [&](int buf) {   // the LDS reads so far have arrived; the fragments depend on the wait
-        if constexpr (DG) {
-            asm volatile("s_waitcnt lgkmcnt(0)");
+        asm volatile("s_waitcnt lgkmcnt(0)");
 #pragma unroll
-            for (int f = 0; f < 4; ++f) { asm volatile("" : "+v"(alo[buf][f])); asm volatile("" : "+v"(ahi[buf][f])); asm volatile("" : "+v"(rb[buf][f])); }
-        } else {
-            wait_frags<0, 4, 4>(ra[buf], rb[buf]);
+        for (int f = 0; f < 4; ++f) {
+            if constexpr (DG) { asm volatile("" : "+v"(alo[buf][f])); asm volatile("" : "+v"(ahi[buf][f])); }
+            else asm volatile("" : "+v"(ra[buf][f]));
         }
+#pragma unroll
+        for (int f = 0; f < FB; ++f) asm volatile("" : "+v"(rb[buf][f]));
     };
     auto multiply = [&](int buf, int m) {
         if constexpr (DG) {
-            const u32x4 av = {alo[buf][m >> 2].x, alo[buf][m >> 2].y, ahi[buf][m >> 2].x, ahi[buf][m >> 2].y};
-            mfma_pinned(acc[m >> 2][m & 3], av, rb[buf][m & 3]);
+            const u32x4 av = {alo[buf][m / FB].x, alo[buf][m / FB].y, ahi[buf][m / FB].x, ahi[buf][m / FB].y};
+            mfma_pinned(acc[m / FB][m % FB], av, rb[buf][m % FB]);
         } else {
-            mfma_pinned(acc[m >> 2][m & 3], ra[buf][m >> 2], rb[buf][m & 3]);
+            mfma_pinned(acc[m / FB][m % FB], ra[buf][m / FB], rb[buf][m % FB]);
         }
     };
 
-    // prologue: strip 0, weights of step 0 and the first half of step 1
+    // prologue: strip 0 and the weights of the first steps (two stages: step 0 and half of step 1; three: steps 0, 1, 2)
     strip_row_offsets(0);
     int row_loaded = 0;   // filter row of voffS_r
 #pragma unroll
     for (int q = 0; q < ISB; ++q) issue_s(0, 0, q, true);
 #pragma unroll
     for (int q = 0; q < IA; ++q) issue_a(0, 0, 0, 0, q, true);
+    if constexpr (NSA == 2) {
 #pragma unroll
-    for (int q = 0; q < IA / 2; ++q) issue_a(1, 0, 0, 1, q, true);   // the second half follows in the first slice of step 0
+        for (int q = 0; q < IA / 2; ++q) issue_a(1, 0, 0, 1, q, true);   // the second half follows in the first slice of step 0
+    } else {
+#pragma unroll
+        for (int q = 0; q < IA; ++q) issue_a(1, 0, 0, 1, q, true);
+#pragma unroll
+        for (int q = 0; q < IA; ++q) issue_a(2, 0, 0, 2, q, true);
+    }
     select_rows(0);
-    wait_vmcnt<IA / 2>();
+    wait_vmcnt<NSA == 2 ? IA / 2 : 2 * IA>();
     __builtin_amdgcn_s_barrier();
 #pragma unroll
-    for (int j = 0; j < NRD; ++j) read_slot(0, j, 0, 0, 0, 0);
+    for (int m = 0; m < NM; ++m) read_slots(m, 0, 0, 0, 0, 0);
 
     int rr = 0, cc = 0;   // filter row and channel block of strip gg
     // one strip = three steps; SB = gg & 1 is the strip's buffer, and with it the parity of its first step
@@ -491,37 +526,41 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 #pragma unroll
         for (int ss = 0; ss < 3; ++ss) {
             const int i = 3 * gg + ss;
-            const int PA = (SB + ss) & 1;   // weight stage of step i
+            const int ST = NSA == 2 ? (SB + ss) & 1 : ss, STN = NSA == 2 ? ST ^ 1 : (ss + 1) % 3;   // weight stages of steps i, i+1
 #pragma unroll
             for (int ks = 0; ks < 3; ++ks) {
                 landed(ks & 1);
 #pragma unroll
-                for (int m = 0; m < 16; ++m) {
-                    if (m < NRD) read_slot((ks + 1) & 1, m, PA, SB, ss, ks + 1);
-                    // second half of the weights of step i+1 (the first half went out after the last barrier), two slots
-                    // apart (the address unit takes 16 clocks per copy) and all of them BEFORE the strip copies below: the
-                    // wait at the barrier counts on the strip copies being the youngest
-                    if (ks == 0 && m < 8 && (m & 1))
-                        issue_a(PA ^ 1, ss < 2 ? rr : rrn, ss < 2 ? cc : ccn, (ss + 1) % 3, IA / 2 + (m >> 1), i + 1 < nsteps);
-                    // the strip after this one goes into the buffer the previous strip has left: three copies per slice
-                    if (ss == 0 && m >= 8 && m < 8 + ISB / 3) issue_s(SB ^ 1, ccn, ks * (ISB / 3) + m - 8, more_strips);
+                for (int m = 0; m < NM; ++m) {
+                    read_slots(m, (ks + 1) & 1, ST, SB, ss, ks + 1);
+                    // two stages: second half of the weights of step i+1 (the first half went out after the last barrier),
+                    // two slots apart (the address unit takes 16 clocks per copy) and all of them BEFORE the strip copies
+                    // below: the wait at the barrier counts on the strip copies being the youngest
+                    if (NSA == 2 && ks == 0 && m < 8 && (m & 1))
+                        issue_a(STN, ss < 2 ? rr : rrn, ss < 2 ? cc : ccn, (ss + 1) % 3, IA / 2 + (m >> 1), i + 1 < nsteps);
+                    // the strip after this one goes into the buffer the previous strip has left: SPS copies per slice
+                    if (ss == 0 && m >= SM0 && m < SM0 + SPS) issue_s(SB ^ 1, ccn, ks * SPS + m - SM0, more_strips);
                     multiply(ks & 1, m);
                 }
             }
             landed(1);   // the last slice is in registers: this wave is done with the weight stage
             if (ss == 2 && rrn != rr && rrn < 3) select_rows(rrn);   // the reads below already belong to the next filter row
-            if (ss == 0) wait_vmcnt<ISB>();      // weights of step i+1 have landed; the strip copies issued since may be in flight
-            else wait_vmcnt<0>();
+            // the weights of step i+1 have landed; younger copies may be in flight: with two stages the strip copies of this
+            // step; with three the weights of step i+2 and the strip copies issued after those of step i+1 (this step's if
+            // ss == 0, the previous step's if ss == 1)
+            if constexpr (NSA == 2) { if (ss == 0) wait_vmcnt<ISB>(); else wait_vmcnt<0>(); }
+            else { if (ss == 2) wait_vmcnt<IA>(); else wait_vmcnt<IA + ISB>(); }
             __builtin_amdgcn_s_barrier();
-            {
-                const bool on = i + 2 < nsteps;
 #pragma unroll
-                for (int m = 0; m < 16; ++m) {
-                    if (m < NRD) read_slot(0, m, PA ^ 1, ss < 2 ? SB : SB ^ 1, (ss + 1) % 3, 0);
+            for (int m = 0; m < NM; ++m) {
+                read_slots(m, 0, STN, ss < 2 ? SB : SB ^ 1, (ss + 1) % 3, 0);
+                if constexpr (NSA == 2) {
                     // first half of the weights of step i+2 into the stage just freed: same strip while ss + 2 < 3, else the next
-                    if ((m & 3) == 1) issue_a(PA, ss == 0 ? rr : rrn, ss == 0 ? cc : ccn, (ss + 2) % 3, m >> 2, on);
-                    multiply(1, m);
+                    if ((m & 3) == 1) issue_a(ST, ss == 0 ? rr : rrn, ss == 0 ? cc : ccn, (ss + 2) % 3, m >> 2, i + 2 < nsteps);
+                } else {
+                    issue_a(ST, rrn, ccn, ss, m, i + 3 < nsteps);   // weights of step i+3 (same column of the next strip)
                 }
+                multiply(1, m);
             }
         }
         rr = rrn; cc = ccn;
@@ -533,8 +572,9 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     wait_vmcnt<0>();   // switched-off copies still write zeros: they are done before the tiles are reused
     __syncthreads();
     store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
+#endif
 }
-constexpr int kStripLds = 2 * 256 * 128 + 2 * 288 * 128 + 256 * 4 + 256 * 4;
+constexpr int strip_lds_bytes(int tb) { return (tb == 256 ? 2 : 3) * 256 * 128 + 2 * (tb == 256 ? 288 : 192) * 128 + tb * 4 + 256 * 4; }
 
 // ---------------------------------------------------------------------------------------
 // backward-filter with the same pipeline.  Both operands are reduction-major in LDS:
@@ -989,8 +1029,9 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
-                           {256, 256, 64, 2, 2, 2}};
-constexpr int kNumDma = 31, kStripVariant = 30;   // the last entry is k_conv_strip (4 waves; its own LDS layout)
+                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}};
+constexpr int kNumDma = 32, kStripVariant = 30;   // the last two entries are k_conv_strip (4 waves; its own LDS layout)
+inline bool is_strip(int v) { return v >= kStripVariant; }
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -1024,7 +1065,8 @@ KernelFn pick_dma_d(int v)
     case 27: return k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>;
-    case 30: return k_conv_strip<true>;
+    case 30: return k_conv_strip<true, 256>;
+    case 31: return k_conv_strip<true, 128>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1060,7 +1102,8 @@ KernelFn pick_dma(int v)
     case 27: return k_fwd_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_fwd_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_fwd_dma<128, 64, 64, 2, 2, 2, 2>;
-    case 30: return k_conv_strip<false>;
+    case 30: return k_conv_strip<false, 256>;
+    case 31: return k_conv_strip<false, 128>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1094,7 +1137,7 @@ size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
-    if (&d == &kDma[kStripVariant]) return kStripLds;
+    if (&d >= &kDma[kStripVariant]) return strip_lds_bytes(d.TB);
     size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
     const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
     if (gsum > stages) stages = gsum;
@@ -1154,7 +1197,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
         d = &kDma[force_variant - 200];
         if (g.C % d->BK != 0) return false;
-        if (force_variant - 200 == kStripVariant &&   // 3x3, stride 1, pad 1, c_in % 128, whole groups of 8 output channels, no reduction split
+        if (is_strip(force_variant - 200) &&   // 3x3, stride 1, pad 1, c_in % 128, whole groups of 8 output channels, no reduction split
             (g.C % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || g.K % 8 != 0 || force_splits > 1))
             return false;
         pl->variant = force_variant - 200;
@@ -1163,7 +1206,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         if (force_variant < 200 || force_variant >= 200 + kNumDma) return false;
         d = &kDma[force_variant - 200];
         if (g.K % d->BK != 0 || g.C % 8 != 0) return false;
-        if (force_variant - 200 == kStripVariant &&   // as forward, with c_out as the reduction; bf16 gradients only (the caller checks)
+        if (is_strip(force_variant - 200) &&   // as forward, with c_out as the reduction; bf16 gradients only (the caller checks)
             (g.K % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || force_splits > 1))
             return false;   // any stride: taps that miss the stride grid are masked out
         pl->variant = force_variant - 200;
@@ -1195,7 +1238,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         }
     }
     int splits;
-    if (pass != PASS_WGRAD && pl->variant == kStripVariant) splits = 1;
+    if (pass != PASS_WGRAD && is_strip(pl->variant)) splits = 1;
     else if (force_splits > 0) splits = force_splits;
     else {
         long long tiles = (long long)pl->tilesA * pl->tilesB;
@@ -1215,7 +1258,7 @@ void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
     // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
-    if (pass != PASS_WGRAD && pl.variant == kStripVariant) snprintf(name, name_bytes, pass == PASS_FWD ? "k_conv_strip<false>" : "k_conv_strip<true>");
+    if (pass != PASS_WGRAD && is_strip(pl.variant)) snprintf(name, name_bytes, "k_conv_strip<%s, %d>", pass == PASS_FWD ? "false" : "true", d.TB);
     else if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
     else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
                   d.WB, d.NS, d.KG);
