@@ -353,7 +353,8 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
     const int CR = DG ? g.K : g.C;   // reduction channels = channels of the pixel operand
-    const int RSC = 9 * g.C, NHW = g.N * g.H * g.W, CB = CR / BK, nstrips = 3 * CB, nsteps = 3 * nstrips;
+    // a reduction split (blockIdx.y) takes CB of the CR / 64 channel blocks, all nine taps of them
+    const int RSC = 9 * g.C, NHW = g.N * g.H * g.W, CB = CR / BK / p.splits, cc0 = blockIdx.y * CB, nstrips = 3 * CB, nsteps = 3 * nstrips;
     const bf16_t *pix = DG ? p.dy : p.x;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(pix, (size_t)NHW * CR * 2);
     __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(pix, 0);   // every lane out of range: a switched-off copy
@@ -396,12 +397,12 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     // the step's offset is uniform: it rides in the scalar offset, which the range check ignores (weight rows / columns past
     // the tensor are out of range by their own offset)
     auto issue_a = [&](int stage, int rr, int cc, int ss, int q, bool on) {   // weights of walk tap (rr, ss), channel block cc
-        const int soff = DG ? (cc * BK * RSC + ((2 - rr) * 3 + (2 - ss)) * g.C) * 2 : ((rr * 3 + ss) * g.C + cc * BK) * 2;
+        const int soff = DG ? ((cc0 + cc) * BK * RSC + ((2 - rr) * 3 + (2 - ss)) * g.C) * 2 : ((rr * 3 + ss) * g.C + (cc0 + cc) * BK) * 2;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rw : rw_off, (lds_void)(size_t)(lds0 + stage * A_BYTES + (wave_s * IA + q) * 1024), 16, voffA[q], soff, 0, 0);
     };
     auto issue_s = [&](int buf, int cc, int q, bool on) {   // strip (filter row of voffS_r, channel block cc) into strip buffer `buf`
         __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rx : rx_off, (lds_void)(size_t)(ldsS0 + buf * S_BYTES + (wave_s * ISB + q) * 1024), 16, voffS_r[q],
-                                                 cc * BK * 2, 0, 0);
+                                                 (cc0 + cc) * BK * 2, 0, 0);
     };
 
     f32x16 acc[FA][FB];
@@ -570,6 +571,23 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         strip_steps(gg + 1, std::integral_constant<int, 1>());
     }
     wait_vmcnt<0>();   // switched-off copies still write zeros: they are done before the tiles are reused
+    if (p.splits > 1) {   // fp32 partial sums [split][pixel][channel]; the split-reduce kernel applies the epilogue
+        float *part = p.partial + (size_t)blockIdx.y * p.rowsB * p.rowsA;
+#pragma unroll
+        for (int i = 0; i < FA; ++i)
+#pragma unroll
+            for (int j = 0; j < FB; ++j) {
+                const int pixel = b0 + brow + j * 32 + (lane & 31);
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int ch = a0 + arow + i * 32 + 8 * gq + 4 * (lane >> 5);   // rowsA % 8 == 0: whole groups of four
+                    if (pixel < p.rowsB && ch < p.rowsA)
+                        *reinterpret_cast<f32x4 *>(part + (size_t)pixel * p.rowsA + ch) =
+                            f32x4{acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+                }
+            }
+        return;
+    }
     __syncthreads();
     store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
 #endif
@@ -1198,7 +1216,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         d = &kDma[force_variant - 200];
         if (g.C % d->BK != 0) return false;
         if (is_strip(force_variant - 200) &&   // 3x3, stride 1, pad 1, c_in % 128, whole groups of 8 output channels, no reduction split
-            (g.C % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || g.K % 8 != 0 || force_splits > 1))
+            (g.C % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || g.K % 8 != 0))
             return false;
         pl->variant = force_variant - 200;
         rowsA = g.K; rowsB = g.N * g.Ho * g.Wo; red = g.R * g.S * g.C;
@@ -1207,7 +1225,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         d = &kDma[force_variant - 200];
         if (g.K % d->BK != 0 || g.C % 8 != 0) return false;
         if (is_strip(force_variant - 200) &&   // as forward, with c_out as the reduction; bf16 gradients only (the caller checks)
-            (g.K % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W || force_splits > 1))
+            (g.K % 128 != 0 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1 || g.Ho != g.H || g.Wo != g.W))
             return false;   // any stride: taps that miss the stride grid are masked out
         pl->variant = force_variant - 200;
         rowsA = g.C; rowsB = g.N * g.H * g.W; red = g.R * g.S * g.K;
@@ -1238,8 +1256,12 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         }
     }
     int splits;
-    if (pass != PASS_WGRAD && is_strip(pl->variant)) splits = 1;
-    else if (force_splits > 0) splits = force_splits;
+    if (pass != PASS_WGRAD && is_strip(pl->variant)) {
+        // a split takes whole channel blocks, an even number of them (two strips are unrolled): the largest such count <= the request
+        const int cb = (pass == PASS_FWD ? g.C : g.K) / 64;
+        splits = force_splits > 0 ? force_splits : 1;
+        while (splits > 1 && cb % (2 * splits) != 0) --splits;
+    } else if (force_splits > 0) splits = force_splits;
     else {
         long long tiles = (long long)pl->tilesA * pl->tilesB;
         splits = tiles >= 512 ? 1 : (int)((512 + tiles - 1) / tiles);

@@ -149,9 +149,9 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
             // reduction step 32 only where 64 does not divide the channel count
             if (pass != PASS_WGRAD && cand.BK == 32 && ((pass == PASS_FWD ? g.C : g.K) % 64) == 0) break;
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
-            // the pixel-strip kernels cannot split the reduction: with few tiles each block streams its weights alone, which
-            // times well on a warm cache (the measured choice) and badly inside a step
-            if ((cands[ci].code == 230 || cands[ci].code == 231) && (long long)cand.tilesA * cand.tilesB < 160) break;
+            // pixel-strip kernels on a grid of few blocks: each block streams its weights alone, which times well on a warm
+            // cache (the measured choice) and badly inside a step
+            if ((cands[ci].code == 230 || cands[ci].code == 231) && (long long)cand.tilesA * cand.tilesB * cand.splits < 160) continue;
             last_splits = cand.splits;
             if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;
             if (n < 512) { all[n].t = price(g, pass, cands[ci], cand); all[n].pl = cand; all[n].code = cands[ci].code; ++n; }
