@@ -318,32 +318,35 @@ template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   
 
 // which fragment read j of a slice fetches: fragment index * 4 + kind (0 weights / weights low half, 1 weights high half, 2 pixels);
 // order: weights of fragment f (two transposed reads on backward-data), then pixels of fragment f while there are any
-constexpr int strip_read_kind(int j, bool dg, int fb)
+constexpr int strip_read_kind(int j, bool dg, int fa, int fb)
 {
     int n = 0;
     for (int f = 0; f < 4; ++f) {
-        if (n++ == j) return f * 4;
-        if (dg && n++ == j) return f * 4 + 1;
+        if (f < fa && n++ == j) return f * 4;
+        if (f < fa && dg && n++ == j) return f * 4 + 1;
         if (f < fb && n++ == j) return f * 4 + 2;
     }
     return -1;
 }
 
-template <bool DG, int TB>   // DG: backward-data; TB: pixel rows of a tile (256, or 128 for grids that would leave most CUs idle)
+// DG: backward-data; TB: pixel rows of a tile (256, or 128 for grids that would leave most CUs idle); TA: output channels of a
+// tile (256, or 128 for layers with 128 of them)
+template <bool DG, int TB, int TA>
 __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 {
 #if __HIP_DEVICE_COMPILE__   // the host pass only needs the launch stub (and silently drops it when it sees this body)
-    constexpr int TA = 256, BK = 64, NT = 256, FA = 4, FB = TB / 64, ROWB = 128, BS = 32 * ROWB;
-    constexpr int NSA = TB == 256 ? 2 : 3;   // weight stages: what fits beside the two strip buffers
-    constexpr int A_BYTES = TA * ROWB, SROWS = TB == 256 ? 288 : 192, S_BYTES = SROWS * ROWB, IA = 8, ISB = SROWS / 32, ZROW = TB + 16;
-    constexpr int ROWA = TA * 2;   // backward-data: a weight row in LDS holds the 256 c_in of one c_out
+    constexpr int BK = 64, NT = 256, FA = TA / 64, FB = TB / 64, ROWB = 128, BS = 32 * ROWB;
+    constexpr int NSA = TA == 256 && TB == 256 ? 2 : 3;   // weight stages: what fits beside the two strip buffers
+    constexpr int A_BYTES = TA * ROWB, SROWS = TB == 256 ? 288 : 192, S_BYTES = SROWS * ROWB, IA = TA / 32, ISB = SROWS / 32, ZROW = TB + 16;
+    constexpr int ROWA = TA * 2;   // backward-data: a weight row in LDS holds the TA c_in of one c_out
     constexpr int LDS_TILES = NSA * A_BYTES + 2 * S_BYTES;
     constexpr int NM = FA * FB;                     // matrix instructions (= slots) per slice
     constexpr int NRD = (DG ? 2 * FA : FA) + FB;   // LDS reads per slice (a transposed weight fragment takes two)
-    constexpr int SPS = ISB / 3, SM0 = NM - 8 + (TB == 256 ? 0 : 6);   // strip copies per slice and their first slot
+    constexpr int SPS = ISB / 3, SM0 = NM - SPS - (NM == 16 ? 5 : 0);   // strip copies per slice and their first slot
+    static_assert(TA * TB <= 256 * 256 && TA * TB >= 128 * 256, "tile shapes: 256x256, 256x128, 128x256");
     static_assert(LDS_TILES >= TB * (TA + 8) * 2, "the staged epilogue reuses the tiles");
     static_assert(A_BYTES + 4 * ROWA + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
-    static_assert(ISB % 3 == 0 && SM0 + SPS <= NM && ZROW + 2 <= SROWS && (NSA == 2 || NM == IA), "slot plan");
+    static_assert(ISB % 3 == 0 && SM0 >= 0 && SM0 + SPS <= NM && ZROW + 2 <= SROWS && (NSA == 2 || NM % IA == 0), "slot plan");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     unsigned *rowtab = reinterpret_cast<unsigned *>(smem + LDS_TILES);   // [TB] tap masks
     float *bias_lds = reinterpret_cast<float *>(rowtab + TB);           // [TA]
@@ -363,7 +366,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
         rowtab[tid] = m < p.rowsB ? tap_mask(hh - 1, ww - 1, 1, 3, 3, g.H, g.W) : 0u;
     }
-    if (!DG && (p.flags & KF_BIAS)) bias_lds[tid] = a0 + tid < p.rowsA ? p.bias[a0 + tid] : 0.f;
+    if (!DG && (p.flags & KF_BIAS) && tid < TA) bias_lds[tid] = a0 + tid < p.rowsA ? p.bias[a0 + tid] : 0.f;
     __syncthreads();
 
     const unsigned wave_s = __builtin_amdgcn_readfirstlane(wave);
@@ -373,8 +376,9 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 #pragma unroll
     for (int q = 0; q < IA; ++q) {
         if constexpr (DG) {
-            // one copy fills two reduction rows t (c_out) of 512 bytes: lane l takes the 16-byte chunk (l % 32) ^ swizzle(t)
-            const int t = (wave * IA + q) * 2 + lane / 32, col = a0 + ((lane % 32) ^ ((t & 3) << 2)) * 8;
+            // one copy fills 512 / TA reduction rows t (c_out) of 2 * TA bytes: lane l takes the 16-byte chunk (l % CPRA) ^ swizzle(t)
+            constexpr int CPRA = TA / 8;
+            const int t = (wave * IA + q) * (64 / CPRA) + lane / CPRA, col = a0 + ((lane % CPRA) ^ ((t & 3) << 2)) * 8;
             voffA[q] = col < g.C ? ((unsigned)t * RSC + col) * 2u : OOR;   // columns past c_in stay zero
         } else {
             // lane l of copy q fills chunk position l % 8 of tile row rq = q*8 + l/8 with global chunk (l % 8) ^ swizzle(rq)
@@ -412,7 +416,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         for (int j = 0; j < FB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    const int arow = (wave & 1) * 128, brow = (wave >> 1) * (TB / 2);
+    const int arow = (wave & 1) * (TA / 2), brow = (wave >> 1) * (TB / 2);
     const int rA = arow + (lane & 31), rB = brow + (lane & 31);
     // forward: slice ks of a weight row sits at chunk (2*ks + half) ^ swizzle; backward-data: the transpose read of
     // fragment i, slice ks starts at reduction row t = 16*ks + tl, 64-byte segment (col / 32) ^ swizzle(t).
@@ -456,7 +460,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     u32x2 alo[2][DG ? 4 : 1], ahi[2][DG ? 4 : 1];
     // read j of slice ks of the step that uses weight stage ST, strip buffer SB and filter column ss
     auto read_slot = [&](int buf, int j, int ST, int SB, int ss, int ks) {
-        const int kind = strip_read_kind(j, DG, FB), f = kind >> 2;
+        const int kind = strip_read_kind(j, DG, FA, FB), f = kind >> 2;
         if ((kind & 3) == 2) {
             rb[buf][f] = SB ? lds_read16_at<S_BYTES, BS>(vsel[ss][f][ks], f) : lds_read16_at<0, BS>(vsel[ss][f][ks], f);
         } else if constexpr (DG) {
@@ -479,7 +483,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     auto landed = [&](int buf) {   // the LDS reads so far have arrived; the fragments depend on the wait
         asm volatile("s_waitcnt lgkmcnt(0)");
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
+        for (int f = 0; f < FA; ++f) {
             if constexpr (DG) { asm volatile("" : "+v"(alo[buf][f])); asm volatile("" : "+v"(ahi[buf][f])); }
             else asm volatile("" : "+v"(ra[buf][f]));
         }
@@ -559,7 +563,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
                     // first half of the weights of step i+2 into the stage just freed: same strip while ss + 2 < 3, else the next
                     if ((m & 3) == 1) issue_a(ST, ss == 0 ? rr : rrn, ss == 0 ? cc : ccn, (ss + 2) % 3, m >> 2, i + 2 < nsteps);
                 } else {
-                    issue_a(ST, rrn, ccn, ss, m, i + 3 < nsteps);   // weights of step i+3 (same column of the next strip)
+                    if (m % (NM / IA) == 0) issue_a(ST, rrn, ccn, ss, m / (NM / IA), i + 3 < nsteps);   // weights of step i+3 (same column of the next strip)
                 }
                 multiply(1, m);
             }
@@ -592,7 +596,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
 #endif
 }
-constexpr int strip_lds_bytes(int tb) { return (tb == 256 ? 2 : 3) * 256 * 128 + 2 * (tb == 256 ? 288 : 192) * 128 + tb * 4 + 256 * 4; }
+constexpr int strip_lds_bytes(int ta, int tb) { return (ta == 256 && tb == 256 ? 2 : 3) * ta * 128 + 2 * (tb == 256 ? 288 : 192) * 128 + tb * 4 + ta * 4; }
 
 // ---------------------------------------------------------------------------------------
 // backward-filter with the same pipeline.  Both operands are reduction-major in LDS:
@@ -1047,8 +1051,8 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
-                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}};
-constexpr int kNumDma = 32, kStripVariant = 30;   // the last two entries are k_conv_strip (4 waves; its own LDS layout)
+                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}};
+constexpr int kNumDma = 33, kStripVariant = 30;   // the last three entries are k_conv_strip (4 waves; its own LDS layout)
 inline bool is_strip(int v) { return v >= kStripVariant; }
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
@@ -1083,8 +1087,9 @@ KernelFn pick_dma_d(int v)
     case 27: return k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>;
-    case 30: return k_conv_strip<true, 256>;
-    case 31: return k_conv_strip<true, 128>;
+    case 30: return k_conv_strip<true, 256, 256>;
+    case 31: return k_conv_strip<true, 128, 256>;
+    case 32: return k_conv_strip<true, 256, 128>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1120,8 +1125,9 @@ KernelFn pick_dma(int v)
     case 27: return k_fwd_dma<64, 64, 64, 2, 2, 2, 2>;
     case 28: return k_fwd_dma<64, 128, 64, 2, 2, 2, 2>;
     case 29: return k_fwd_dma<128, 64, 64, 2, 2, 2, 2>;
-    case 30: return k_conv_strip<false, 256>;
-    case 31: return k_conv_strip<false, 128>;
+    case 30: return k_conv_strip<false, 256, 256>;
+    case 31: return k_conv_strip<false, 128, 256>;
+    case 32: return k_conv_strip<false, 256, 128>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1155,7 +1161,7 @@ size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
-    if (&d >= &kDma[kStripVariant]) return strip_lds_bytes(d.TB);
+    if (&d >= &kDma[kStripVariant]) return strip_lds_bytes(d.TA, d.TB);
     size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
     const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
     if (gsum > stages) stages = gsum;
@@ -1280,7 +1286,7 @@ void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes
 {
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
     // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
-    if (pass != PASS_WGRAD && is_strip(pl.variant)) snprintf(name, name_bytes, "k_conv_strip<%s, %d>", pass == PASS_FWD ? "false" : "true", d.TB);
+    if (pass != PASS_WGRAD && is_strip(pl.variant)) snprintf(name, name_bytes, "k_conv_strip<%s, %d, %d>", pass == PASS_FWD ? "false" : "true", d.TB, d.TA);
     else if (pass == PASS_WGRAD) snprintf(name, name_bytes, "k_wgrad_dma<%d, %d, %d, %d, %d, %d>", d.TA, d.TB, d.BK, d.WA, d.WB, d.NS);
     else snprintf(name, name_bytes, "%s<%d, %d, %d, %d, %d, %d, %d>", pass == PASS_DGRAD ? "k_dgrad_dma" : "k_fwd_dma", d.TA, d.TB, d.BK, d.WA,
                   d.WB, d.NS, d.KG);
