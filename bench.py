@@ -31,12 +31,12 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {
-    "k_conv_strip<false, 256>": 140056303,
+    "k_conv_strip<false, 256, 256>": 131334119,
     "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 126579397,
-    "k_halo_ws<0>": 473776729,
-    "k_fwd_direct": 226671429,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 214031867,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>": 51882829,
+    "k_halo_ws<0>": 320908169,
+    "k_fwd_direct": 226669118,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 213974062,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>": 51880624,
     "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>": 131364910
 }
 
