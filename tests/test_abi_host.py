@@ -143,3 +143,33 @@ def test_fused_input_relu_argument_errors(dp):
     assert lib.dp_linear_fwd_bwd(C.byref(ld), None, A, None, A, None, None, A, None, None, None, 0, None) == dp.DP_ERR_NULL  # dx needs x
     # the flag changes which kernels a call may use, so the workspace query takes it into account without failing
     assert dp.dp_conv2d_workspace_bytes(d, 1) >= 0
+
+
+def test_pixel_strip_plan_rules(dp):
+    """Host logic of the kernel choice (no GPU call): the pixel-strip kernels are planned for the 3x3 / stride 1 / pad 1
+    layers with 128 or more reduction channels on grids of 160 or more blocks, never for fp32 input gradients, other
+    filters, strides or paddings, and a reduction split takes an even number of 64-channel blocks."""
+    def info(n, h, c, k, pass_, r=3, stride=(1, 1), pad=(1, 1), extra=0):
+        d = dp.conv_desc(n, h, h, c, k, r, r, stride, pad, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU | extra)
+        return dp.dp_conv2d_kernel_info(d, pass_)
+    assert info(32, 56, 256, 256, 0) == ("k_conv_strip<false, 256, 256>", 1)        # conv3_2: 392 tiles
+    assert info(32, 56, 256, 256, 1) == ("k_conv_strip<true, 256, 256>", 1)
+    assert info(32, 14, 512, 512, 0) == ("k_conv_strip<false, 128, 256>", 2)        # conv5_x: 98 tiles, two splits of four blocks
+    assert "k_conv_strip" not in info(32, 56, 256, 256, 1, extra=dp.DP_DX_F32)[0]   # bf16 staged epilogue only
+    assert "k_conv_strip" not in info(4, 14, 512, 512, 0)[0]                         # too few blocks
+    assert "k_conv_strip" not in info(32, 56, 64, 256, 0)[0]                         # 64 reduction channels
+    assert "k_conv_strip" not in info(32, 56, 256, 256, 0, r=1, pad=(0, 0))[0]
+    assert "k_conv_strip" not in info(32, 56, 256, 256, 0, stride=(2, 2))[0]
+    assert "k_conv_strip" not in info(32, 56, 256, 256, 2)[0]                        # not a filter-gradient kernel
+    for code, splits, want in ((230, 2, 2), (230, 3, 2), (230, 4, 2), (231, 4, 2), (232, 8, 2)):   # 256 channels: four blocks
+        dp.dp_set_override(0, code, splits)
+        try:
+            assert info(8, 28, 256, 256, 0)[1] == want
+        finally:
+            dp.dp_set_override(0, -1, 0)
+    dp.dp_set_override(1, 230, 4)
+    try:
+        assert info(8, 14, 512, 512, 1) == ("k_conv_strip<true, 256, 256>", 4)      # 512 channels: eight blocks, four splits of two
+    finally:
+        dp.dp_set_override(1, -1, 0)
+
