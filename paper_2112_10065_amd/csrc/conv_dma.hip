@@ -1236,6 +1236,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
         pl->variant = force_variant - 200;
         rowsA = g.C; rowsB = g.N * g.H * g.W; red = g.R * g.S * g.K;
     } else if (pass == PASS_WGRAD) {
+        if (force_variant == 316) return wstrip_plan(g, force_splits, pl);
         if (force_variant < 300 || force_variant >= 300 + kNumDmaW) return false;
         d = &kDmaW[force_variant - 300];
         if (g.K % 8 || g.C % 8) return false;
@@ -1284,6 +1285,7 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
 
 void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
+    if (pl.wstrip) { snprintf(name, name_bytes, "k_wgrad_strip"); return; }
     const DmaVariant &d = pass == PASS_WGRAD ? kDmaW[pl.variant] : kDma[pl.variant];
     // as the profiler prints the instantiation: the forward / backward-data kernels carry the group count
     if (pass != PASS_WGRAD && is_strip(pl.variant)) snprintf(name, name_bytes, "k_conv_strip<%s, %d, %d>", pass == PASS_FWD ? "false" : "true", d.TB, d.TA);

@@ -111,6 +111,7 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, in
 {
     pl->dma = false;
     pl->halo = false;
+    pl->wstrip = false;
     if (fv < 0 && auto_plan(g, pass, fs, pl, restr)) return;
     // a forced input-patch variant the call may not use falls through to the next family
     const bool patch_banned = pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && fv == 404));
@@ -178,13 +179,14 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
 // the pipelined backward-filter kernels (conv_dma.hip); their scratch [splits][c_out] fits the bias-gradient
 // workspace for up to 512 splits.  (Tried and dropped for the input-patch kernel: the extra matrix instructions
 // unbalance its one-wave-per-tap blocks and cost more than the separate column-sum pass.)
-bool plan_sums_bias_gradient(const GemmPlan &plan) { return plan.dma && !plan.halo && plan.splits <= 512; }
+bool plan_sums_bias_gradient(const GemmPlan &plan) { return plan.dma && !plan.halo && !plan.wstrip && plan.splits <= 512; }
 
 namespace {
 
 hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 {
     if (a.plan.halo) return halo_launch(a, st);
+    if (a.plan.wstrip) return wstrip_launch(a, st);
     if (a.plan.dma) return dma_launch(a, st);
     return a.plan.fast ? fast_launch(a, st) : mfma_launch(a, st);
 }
@@ -239,7 +241,7 @@ size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
 
 dp_status ensure_init()
 {
-    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); if (g_init_err == hipSuccess) g_init_err = dma_init(); if (g_init_err == hipSuccess) g_init_err = halo_init(); });
+    std::call_once(g_init_once, [] { g_init_err = mfma_init(); if (g_init_err == hipSuccess) g_init_err = fast_init(); if (g_init_err == hipSuccess) g_init_err = dma_init(); if (g_init_err == hipSuccess) g_init_err = halo_init(); if (g_init_err == hipSuccess) g_init_err = wstrip_init(); });
     if (g_init_err != hipSuccess) return hip_fail(g_init_err, "library initialisation (is a gfx950 device present?)");
     return DP_OK;
 }

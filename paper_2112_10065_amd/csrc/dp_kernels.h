@@ -38,6 +38,7 @@ struct GemmPlan {
     bool halo = false;    // input-patch kernel (conv_halo.hip); implies dma
     int blocks = 0;       // persistent kernels: blocks per row tile (0: one per CU)
     bool phase = false;   // strided backward-data walks the input pixels stride phase by stride phase (conv_dma.hip)
+    bool wstrip = false;  // filter gradient with the x strip shared by the taps of a filter row (conv_wstrip.hip); implies dma
 };
 
 struct ConvArgs {
@@ -55,6 +56,11 @@ struct ConvArgs {
     float *db_out = nullptr;      // KF_DB: bias gradient [rowsA]
     float *db_partial = nullptr;  // KF_DB: [splits][rowsA] scratch for split plans
 };
+
+// conv_wstrip.hip
+hipError_t wstrip_init();
+bool wstrip_plan(const ConvGeom &g, int force_splits, GemmPlan *pl);
+hipError_t wstrip_launch(const ConvArgs &a, hipStream_t st);
 
 // conv_mfma.hip
 hipError_t mfma_init();                                      // raises dynamic LDS limits

@@ -66,6 +66,7 @@ const Candidate kWg[] = {
     {307, 2, 1.60f, 5.0f},   // 256x128x32, 8 waves
     {314, 2, 1.65f, 5.0f},   // 128x256x32, 8 waves
     {312, 1, 2.90f, 7.0f},   // 256x256x64, 8 waves
+    {316, 1, 1.60f, 9.0f},   // 3x3 stride 1: 256 x (3 taps x 64 channels), x strip shared by the taps, padded pixel slots
     {410, 1, 0.13f, 6.0f},   // input patch in LDS, persistent blocks (64 input channels, stride 1); a step = 16 pixels
     {100, 3, 1.30f, 4.0f},
     {101, 3, 1.00f, 3.5f},
@@ -77,6 +78,7 @@ const int kSplits[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 20, 24, 32, 48, 64, 96, 
 bool family_plan(const ConvGeom &g, int pass, int code, int splits, GemmPlan *pl)
 {
     pl->halo = false;
+    pl->wstrip = false;
     if (code >= 400) return halo_plan(g, pass, code, splits, pl);
     if (code >= 200) return dma_plan(g, pass, code, splits, pl);
     return fast_plan(g, pass, code, splits, pl);

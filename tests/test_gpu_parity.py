@@ -478,6 +478,42 @@ def test_pipelined_backward_filter_variants(env, variant, splits):
         dp.dp_set_override(2, -1, 0)
 
 
+@pytest.mark.parametrize("splits", [1, 3])
+def test_filter_gradient_pixel_strip_kernel(env, splits):
+    """3x3, stride 1, pad 1, c_in % 64 == 0: the filter-gradient kernel that pads every image row to a power-of-two number
+    of pixel slots and shares one strip of x between the three taps of a filter row.  Row widths that fill a segment
+    exactly (14), almost (28, 56, 30) and to three quarters (12); one, two and four image rows per step; steps that
+    straddle images and run past the last row; c_out below, at and above one tile; with the saved-output mask and the
+    bias gradient (a separate pass here) and without."""
+    dp, U, orc = env
+    dp.dp_set_override(2, 316, splits)
+    try:
+        for tag, n, h, w, c, k in (("wsx_a", 2, 5, 28, 64, 256), ("wsx_b", 1, 9, 14, 128, 72), ("wsx_c", 3, 4, 56, 64, 264),
+                                   ("wsx_d", 2, 7, 12, 192, 16), ("wsx_e", 1, 1, 14, 64, 8), ("wsx_f", 5, 3, 30, 64, 40)):
+            case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+            name, got_splits = dp.dp_conv2d_kernel_info(case.desc, 2)
+            assert name == "k_wgrad_strip" and 1 <= got_splits <= splits
+            y = case.run_fwd()
+            dw, db = case.run_wgrad(y)
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=U.to_np(y), stride=(1, 1), pad=(1, 1), want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} splits {splits} dw")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} splits {splits} db")
+            dw, db = case.run_wgrad(None)
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=None, stride=(1, 1), pad=(1, 1), want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} splits {splits} dw, unmasked")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} splits {splits} db, unmasked")
+        # other shapes are not this kernel's: rows that would leave more than a quarter of their slots empty or are too long,
+        # 48 input channels, other filters and strides
+        for tag, w, c, r, st, pd in (("wsx_w40", 40, 64, 3, (1, 1), (1, 1)), ("wsx_w70", 70, 64, 3, (1, 1), (1, 1)), ("wsx_c48", 14, 48, 3, (1, 1), (1, 1)),
+                                     ("wsx_1x1", 14, 64, 1, (1, 1), (0, 0)), ("wsx_s2", 14, 64, 3, (2, 2), (1, 1))):
+            case = U.ConvCase(tag, 1, 6, w, c, 32, r, r, st, pd, bf16=True, bias=True, relu=True)
+            assert dp.dp_conv2d_kernel_info(case.desc, 2)[0] != "k_wgrad_strip"
+    finally:
+        dp.dp_set_override(2, -1, 0)
+
+
 def test_unfused_relu_gradient_flow(env):
     """dp_relu_bias_grad materialises the masked gradient once; both backward passes then take it
     with y_saved = NULL and must agree with the oracle's masked definitions."""
