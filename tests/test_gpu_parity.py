@@ -483,13 +483,14 @@ def test_filter_gradient_pixel_strip_kernel(env, splits):
     """3x3, stride 1, pad 1, c_in % 64 == 0: the filter-gradient kernel that pads every image row to a power-of-two number
     of pixel slots and shares one strip of x between the three taps of a filter row.  Row widths that fill a segment
     exactly (14), almost (28, 56, 30) and to three quarters (12); one, two and four image rows per step; steps that
-    straddle images and run past the last row; c_out below, at and above one tile; with the saved-output mask and the
-    bias gradient (a separate pass here) and without."""
+    straddle images and run past the last row; c_out below, at and above one tile; 3 to 24 tap-and-channel tiles; with
+    the saved-output mask and the bias gradient (a separate pass here) and without."""
     dp, U, orc = env
     dp.dp_set_override(2, 316, splits)
     try:
         for tag, n, h, w, c, k in (("wsx_a", 2, 5, 28, 64, 256), ("wsx_b", 1, 9, 14, 128, 72), ("wsx_c", 3, 4, 56, 64, 264),
-                                   ("wsx_d", 2, 7, 12, 192, 16), ("wsx_e", 1, 1, 14, 64, 8), ("wsx_f", 5, 3, 30, 64, 40)):
+                                   ("wsx_d", 2, 7, 12, 192, 16), ("wsx_e", 1, 1, 14, 64, 8), ("wsx_f", 5, 3, 30, 64, 40),
+                                   ("wsx_g", 2, 6, 14, 256, 40), ("wsx_h", 2, 14, 14, 512, 264), ("wsx_i", 1, 20, 28, 320, 24)):
             case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
             name, got_splits = dp.dp_conv2d_kernel_info(case.desc, 2)
             assert name == "k_wgrad_strip" and 1 <= got_splits <= splits
