@@ -31,6 +31,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {
+    "k_conv_strip<false, 224, 256>": 111270430,
     "k_conv_strip<false, 256, 256>": 127237311,
     "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 126579397,
     "k_halo_ws<0>": 320908169,

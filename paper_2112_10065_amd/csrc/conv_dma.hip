@@ -55,7 +55,7 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
     if ((p.flags & KF_MASK_IN) && !all_zero) {
         // fused backward of the input ReLU: the saved-input vectors are requested in groups of eight before
         // they are needed (the first group before the staging barrier), so that their latency overlaps
-        constexpr int ITERS = (TB * CPR + NT - 1) / NT, GRP = ITERS < 8 ? ITERS : 8;
+        constexpr int ITERS = (TB * CPR + NT - 1) / NT, GRP = ITERS < 8 ? ITERS : ITERS % 8 == 0 ? 8 : 4;
         static_assert(ITERS % GRP == 0, "copy-out iterations come in whole groups");
         u32x4 xm[GRP];
         auto fetch = [&](int g0) {
@@ -312,7 +312,10 @@ template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   
     case 0: return lds_read16<OFF0>(addr);
     case 1: return lds_read16<OFF0 + BS>(addr);
     case 2: return lds_read16<OFF0 + 2 * BS>(addr);
-    default: return lds_read16<OFF0 + 3 * BS>(addr);
+    case 3: return lds_read16<OFF0 + 3 * BS>(addr);
+    case 4: return lds_read16<OFF0 + 4 * BS>(addr);
+    case 5: return lds_read16<OFF0 + 5 * BS>(addr);
+    default: return lds_read16<OFF0 + 6 * BS>(addr);
     }
 }
 
@@ -321,7 +324,7 @@ template <int OFF0, int BS> DEVFN u32x4 lds_read16_at(unsigned addr, int blk)   
 constexpr int strip_read_kind(int j, bool dg, int fa, int fb)
 {
     int n = 0;
-    for (int f = 0; f < 4; ++f) {
+    for (int f = 0; f < 8; ++f) {
         if (f < fa && n++ == j) return f * 4;
         if (f < fa && dg && n++ == j) return f * 4 + 1;
         if (f < fb && n++ == j) return f * 4 + 2;
@@ -329,23 +332,25 @@ constexpr int strip_read_kind(int j, bool dg, int fa, int fb)
     return -1;
 }
 
-// DG: backward-data; TB: pixel rows of a tile (256, or 128 for grids that would leave most CUs idle); TA: output channels of a
-// tile (256, or 128 for layers with 128 of them)
+// DG: backward-data; TB: pixel rows of a tile (256; 128 for grids that would leave most CUs idle; 224 where 256 leaves the
+// last round of blocks mostly empty: 7 fragments do not split over a 2 x 2 wave grid, so the four waves then each take 64
+// output channels and all 224 pixel rows); TA: output channels of a tile (256, or 128 for layers with 128 of them)
 template <bool DG, int TB, int TA>
 __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
 {
 #if __HIP_DEVICE_COMPILE__   // the host pass only needs the launch stub (and silently drops it when it sees this body)
-    constexpr int BK = 64, NT = 256, FA = TA / 64, FB = TB / 64, ROWB = 128, BS = 32 * ROWB;
-    constexpr int NSA = TA == 256 && TB == 256 ? 2 : 3;   // weight stages: what fits beside the two strip buffers
-    constexpr int A_BYTES = TA * ROWB, SROWS = TB == 256 ? 288 : 192, S_BYTES = SROWS * ROWB, IA = TA / 32, ISB = SROWS / 32, ZROW = TB + 16;
+    constexpr int WA = TB % 64 ? 4 : 2, WB = 4 / WA;   // wave grid: channels x pixels
+    constexpr int BK = 64, NT = 256, FA = TA / (32 * WA), FB = TB / (32 * WB), ROWB = 128, BS = 32 * ROWB;
+    constexpr int NSA = TA == 256 && TB >= 224 ? 2 : 3;   // weight stages: what fits beside the two strip buffers
+    constexpr int A_BYTES = TA * ROWB, SROWS = TB > 128 ? 288 : 192, S_BYTES = SROWS * ROWB, IA = TA / 32, ISB = SROWS / 32, ZROW = TB + 16;
     constexpr int ROWA = TA * 2;   // backward-data: a weight row in LDS holds the TA c_in of one c_out
     constexpr int LDS_TILES = NSA * A_BYTES + 2 * S_BYTES;
     constexpr int NM = FA * FB;                     // matrix instructions (= slots) per slice
     constexpr int NRD = (DG ? 2 * FA : FA) + FB;   // LDS reads per slice (a transposed weight fragment takes two)
     constexpr int SPS = ISB / 3, SM0 = NM - SPS - (NM == 16 ? 5 : 0);   // strip copies per slice and their first slot
-    static_assert(TA * TB <= 256 * 256 && TA * TB >= 128 * 256, "tile shapes: 256x256, 256x128, 128x256");
+    static_assert(TA * TB <= 256 * 256 && TA * TB >= 128 * 256, "tile shapes: 256x256, 224x256, 256x128, 128x256");
     static_assert(LDS_TILES >= TB * (TA + 8) * 2, "the staged epilogue reuses the tiles");
-    static_assert(A_BYTES + 4 * ROWA + 3 * BS < 65536 && S_BYTES + 3 * BS < 65536, "stage offsets fit the 16-bit immediate");
+    static_assert(A_BYTES + 4 * ROWA + 3 * BS < 65536 && S_BYTES + (FB - 1) * BS < 65536 && FA <= 4 && FB <= 7, "stage offsets fit the 16-bit immediate");
     static_assert(ISB % 3 == 0 && SM0 >= 0 && SM0 + SPS <= NM && ZROW + 2 <= SROWS && (NSA == 2 || NM % IA == 0), "slot plan");
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     unsigned *rowtab = reinterpret_cast<unsigned *>(smem + LDS_TILES);   // [TB] tap masks
@@ -416,7 +421,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         for (int j = 0; j < FB; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    const int arow = (wave & 1) * (TA / 2), brow = (wave >> 1) * (TB / 2);
+    const int arow = (wave % WA) * (TA / WA), brow = (wave / WA) * (TB / WB);
     const int rA = arow + (lane & 31), rB = brow + (lane & 31);
     // forward: slice ks of a weight row sits at chunk (2*ks + half) ^ swizzle; backward-data: the transpose read of
     // fragment i, slice ks starts at reduction row t = 16*ks + tl, 64-byte segment (col / 32) ^ swizzle(t).
@@ -596,7 +601,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid);
 #endif
 }
-constexpr int strip_lds_bytes(int ta, int tb) { return (ta == 256 && tb == 256 ? 2 : 3) * ta * 128 + 2 * (tb == 256 ? 288 : 192) * 128 + tb * 4 + ta * 4; }
+constexpr int strip_lds_bytes(int ta, int tb) { return (ta == 256 && tb >= 224 ? 2 : 3) * ta * 128 + 2 * (tb > 128 ? 288 : 192) * 128 + tb * 4 + ta * 4; }
 
 // ---------------------------------------------------------------------------------------
 // backward-filter with the same pipeline.  Both operands are reduction-major in LDS:
@@ -1051,8 +1056,8 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
-                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}};
-constexpr int kNumDma = 33, kStripVariant = 30;   // the last three entries are k_conv_strip (4 waves; its own LDS layout)
+                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}, {256, 224, 64, 4, 1, 2}};
+constexpr int kNumDma = 34, kStripVariant = 30;   // the last four entries are k_conv_strip (4 waves; its own LDS layout)
 inline bool is_strip(int v) { return v >= kStripVariant; }
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
@@ -1090,6 +1095,7 @@ KernelFn pick_dma_d(int v)
     case 30: return k_conv_strip<true, 256, 256>;
     case 31: return k_conv_strip<true, 128, 256>;
     case 32: return k_conv_strip<true, 256, 128>;
+    case 33: return k_conv_strip<true, 224, 256>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1128,6 +1134,7 @@ KernelFn pick_dma(int v)
     case 30: return k_conv_strip<false, 256, 256>;
     case 31: return k_conv_strip<false, 128, 256>;
     case 32: return k_conv_strip<false, 256, 128>;
+    case 33: return k_conv_strip<false, 224, 256>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }

@@ -117,7 +117,7 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, in
     const bool patch_banned = pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && fv == 404));
     if (fv >= 400 && !patch_banned && halo_plan(g, pass, fv, fs, pl)) return;
     // the pixel-strip kernel stages bf16 only: not for fp32 input gradients
-    if (fv >= 200 && !(fv >= 230 && fv <= 232 && pass == PASS_DGRAD && (restr & 1)) && dma_plan(g, pass, fv, fs, pl)) return;
+    if (fv >= 200 && !(fv >= 230 && fv <= 233 && pass == PASS_DGRAD && (restr & 1)) && dma_plan(g, pass, fv, fs, pl)) return;
     if (fv >= 100 && fast_plan(g, pass, fv, fs, pl)) return;
     mfma_plan(g, pass, fv >= 100 ? -1 : fv, fs, pl);
 }

@@ -25,6 +25,7 @@ const Candidate kPix[] = {
     {230, 1, 1.30f, 9.0f},   // 256x256x64, 4 waves, 3x3 stride 1 with the pixel strip shared by the three taps of a filter row
     {231, 1, 0.70f, 7.0f},   // the same with 128 pixel rows per tile and three weight stages
     {232, 1, 0.70f, 7.0f},   // the same with 128 output channels per tile (layers with 128 of them)
+    {233, 1, 1.15f, 9.0f},   // the same with 224 pixel rows per tile (four waves side by side over the channels)
     {208, 1, 1.55f, 8.0f},   // 256x256x64, 8 waves, direct-to-LDS
     {200, 2, 1.08f, 5.0f},   // 128x128x64 direct-to-LDS
     {204, 3, 0.85f, 4.5f},   // 64x128x64
@@ -140,7 +141,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
     const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
     for (int ci = 0; ci < ncand; ++ci) {
         if (pass != PASS_WGRAD && cands[ci].code >= 400 && ((restr & 1) || ((restr & 2) && cands[ci].code == 404))) continue;
-        if (pass == PASS_DGRAD && cands[ci].code >= 230 && cands[ci].code <= 232 && (restr & 1)) continue;   // bf16 staged epilogue only
+        if (pass == PASS_DGRAD && cands[ci].code >= 230 && cands[ci].code <= 233 && (restr & 1)) continue;   // bf16 staged epilogue only
         int last_splits = -1;
         for (int s : kSplits) {
             if (force_splits > 0 && s != kSplits[0]) break;
@@ -154,7 +155,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
             // pixel-strip kernels on a grid of few blocks: each block streams its weights alone, which times well on a warm
             // cache (the measured choice) and badly inside a step
-            if (cands[ci].code >= 230 && cands[ci].code <= 232 && (long long)cand.tilesA * cand.tilesB * cand.splits < 160) continue;
+            if (cands[ci].code >= 230 && cands[ci].code <= 233 && (long long)cand.tilesA * cand.tilesB * cand.splits < 160) continue;
             last_splits = cand.splits;
             if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;
             if (n < 512) { all[n].t = price(g, pass, cands[ci], cand); all[n].pl = cand; all[n].code = cands[ci].code; ++n; }

@@ -152,8 +152,9 @@ def test_pixel_strip_plan_rules(dp):
     def info(n, h, c, k, pass_, r=3, stride=(1, 1), pad=(1, 1), extra=0):
         d = dp.conv_desc(n, h, h, c, k, r, r, stride, pad, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU | extra)
         return dp.dp_conv2d_kernel_info(d, pass_)
-    assert info(32, 56, 256, 256, 0) == ("k_conv_strip<false, 256, 256>", 1)        # conv3_2: 392 tiles
-    assert info(32, 56, 256, 256, 1) == ("k_conv_strip<true, 256, 256>", 1)
+    assert info(32, 56, 256, 256, 0) == ("k_conv_strip<false, 224, 256>", 1)        # conv3_2: 448 tiles of 224 pixels fill two rounds of
+    assert info(32, 56, 256, 256, 1) == ("k_conv_strip<true, 224, 256>", 1)         # 256 blocks better than 392 tiles of 256
+    assert info(32, 28, 512, 512, 0) == ("k_conv_strip<false, 224, 256>", 1)        # conv4_2: 224 blocks instead of 196
     assert info(32, 14, 512, 512, 0) == ("k_conv_strip<false, 128, 256>", 2)        # conv5_x: 98 tiles, two splits of four blocks
     assert "k_conv_strip" not in info(32, 56, 256, 256, 1, extra=dp.DP_DX_F32)[0]   # bf16 staged epilogue only
     assert "k_conv_strip" not in info(4, 14, 512, 512, 0)[0]                         # too few blocks

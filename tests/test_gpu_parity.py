@@ -387,15 +387,16 @@ def test_input_patch_stationary_weights(env, blocks):
 
 
 @pytest.mark.parametrize("splits", [1, 2])
-@pytest.mark.parametrize("tile", [(256, 256), (128, 256), (256, 128)])
+@pytest.mark.parametrize("tile", [(256, 256), (128, 256), (256, 128), (224, 256)])
 def test_forward_pixel_strip_kernel(env, tile, splits):
     """3x3, stride 1, pad 1, c_in % 128 == 0: the forward kernel that keeps one strip of input pixels in LDS for the three
     taps of a filter row and redirects (pixel, tap) pairs outside the image to rows of zeros.  Ragged last tiles in
     both directions, tiles that span several images, images narrower than the filter, one and several channel
-    blocks, with and without the epilogue; tiles of 256 x 256 (two weight stages), 128 pixel rows and 128 channels (three)."""
+    blocks, with and without the epilogue; tiles of 256 x 256 (two weight stages), 128 pixel rows and 128 channels (three), and
+    224 pixel rows (each wave 64 channels x 224 pixels)."""
     dp, U, orc = env
     rows, chans = tile
-    dp.dp_set_override(0, {(256, 256): 230, (128, 256): 231, (256, 128): 232}[tile], splits)   # a split takes an even number of 64-channel blocks
+    dp.dp_set_override(0, {(256, 256): 230, (128, 256): 231, (256, 128): 232, (224, 256): 233}[tile], splits)   # a split takes an even number of 64-channel blocks
     try:
         for tag, n, h, w, c, k, epi in (("st_a", 2, 13, 12, 128, 96, True), ("st_b", 1, 37, 40, 256, 264, True), ("st_c", 3, 5, 70, 128, 8, False),
                                         ("st_d", 5, 9, 3, 128, 64, True), ("st_e", 1, 1, 1, 128, 16, True), ("st_f", 7, 2, 2, 384, 40, False),
@@ -415,13 +416,13 @@ def test_forward_pixel_strip_kernel(env, tile, splits):
 
 
 @pytest.mark.parametrize("splits", [1, 2])
-@pytest.mark.parametrize("tile", [(256, 256), (128, 256), (256, 128)])
+@pytest.mark.parametrize("tile", [(256, 256), (128, 256), (256, 128), (224, 256)])
 def test_backward_data_pixel_strip_kernel(env, tile, splits):
     """The same kernel on the backward-data pass (c_out % 128 == 0): mirrored filter, weights through the LDS transpose
     read, with and without the fused backward of the input ReLU; fp32 gradients are not this kernel's."""
     dp, U, orc = env
     rows, chans = tile
-    dp.dp_set_override(1, {(256, 256): 230, (128, 256): 231, (256, 128): 232}[tile], splits)
+    dp.dp_set_override(1, {(256, 256): 230, (128, 256): 231, (256, 128): 232, (224, 256): 233}[tile], splits)
     try:
         for tag, n, h, w, c, k in (("sd_a", 2, 13, 12, 96, 128), ("sd_b", 1, 37, 40, 264, 256), ("sd_c", 3, 5, 70, 8, 128),
                                    ("sd_d", 5, 9, 3, 64, 128), ("sd_e", 1, 1, 1, 16, 128), ("sd_f", 7, 2, 2, 40, 384), ("sd_g", 2, 11, 9, 72, 512)):
