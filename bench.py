@@ -236,7 +236,7 @@ def cpu_baseline():
     import numpy as np
     import oracle
     from paper_2112_10065_amd import synth
-    sample = [("conv2_2", 112, 128, 128, 1), ("conv3_2", 56, 256, 256, 4), ("conv4_2", 28, 512, 512, 4), ("conv5_1", 14, 512, 512, 4)]
+    sample = [("conv2_2", 112, 128, 128, 2), ("conv3_2", 56, 256, 256, 8), ("conv4_2", 28, 512, 512, 8), ("conv5_1", 14, 512, 512, 8)]
     flops, secs = 0.0, 0.0
     for name, hw, c, k, n in sample:
         x, w, b = synth.conv_tensors(f"vgg/{name}", n, hw, hw, c, k, 3, 3)
@@ -249,7 +249,7 @@ def cpu_baseline():
         secs += time.perf_counter() - t0
         flops += 3 * 2.0 * n * hw * hw * k * 9 * c
     return {"value": flops / secs / 1e12, "unit": "TFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
-            "sample": "fp64 nested-loop oracle, fwd+dgrad+wgrad of VGG-16 conv2_2 (N=1), conv3_2 (N=4), conv4_2 (N=4), conv5_1 (N=4); "
+            "sample": "fp64 nested-loop oracle, fwd+dgrad+wgrad of VGG-16 " + ", ".join(f"{nm} (N={n})" for nm, _, _, _, n in sample) + "; "
                       f"{flops / 1e9:.1f} GFLOP nominal in {secs:.1f} s"}
 
 
