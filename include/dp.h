@@ -211,9 +211,9 @@ dp_status dp_sgd_update(int64_t count, float lr, float momentum, const float *gr
                         void *w_bf16, void *hip_stream);
 
 /* ---- Burst-parallel plan of a chain of layers (host only: no GPU call, all pointers host) -------
- * Paper section 4.2, algorithm "Search Linear": dynamic programming over
- *   S[i][g] = shortest time to complete layers 1..i with layer i on g GPUs,
- *   T[i][g] = time spent on layer i while minimising S[i][g],
+ * Paper section 4.2, algorithm "Search Linear": dynamic programming over two tables,
+ *   S[i][g] = earliest finish of layer i when it runs on g GPUs, over the predecessor choices the search admits,
+ *   T[i][g] = layer i's own share of that finish time (transition into it + its compute + its gradient sync),
  * admitting a predecessor GPU count h only while its GPU-sec amplification
  *   Amp(i-1,h) = T[i-1][h] * h / comp(i-1,1)
  * is within max(best amplification admitted so far, amp_limit) and S[i-1][h] + comm does not exceed

@@ -10,8 +10,10 @@ forward+backward time the planner consumes, Table 1 the layer kinds).
 
 Pins (tests/test_oracle_pins.py): explicit-operator brute force, adjoint
 identities, finite differences, closed forms (delta / shifted-delta kernels,
-all-ones tap counts, 1x1 conv == matmul), superposition, batch independence.
-No function here is "parity unpinned"; timings have no paper value to pin to.
+all-ones tap counts, 1x1 conv == matmul), superposition, batch independence;
+relu_in_backward by finite differences through relu(u) including entries that
+are exactly zero.  No function here is "parity unpinned"; timings have no paper
+value to pin to.
 
 Layouts: x [N,H,W,C], w [K,R,S,C], y/dy [N,Ho,Wo,K], dense, C order.
 """
@@ -81,7 +83,8 @@ def conv2d_bwd_data(dy, w, xshape, y_saved=None, stride=(1, 1), pad=(0, 0)):
 
 def relu_in_backward(dx, x_in):
     """Backward of the ReLU that produced a layer's input, applied to that layer's data gradient:
-    dx * [x_in > 0] (derivative 0 at 0, as for the output-side mask)."""
+    dx * [x_in > 0] (derivative 0 at 0, as for the output-side mask).  Pinned by
+    test_relu_in_backward_by_finite_differences."""
     return _d(dx) * (_d(x_in) > 0)
 
 

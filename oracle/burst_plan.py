@@ -1,32 +1,40 @@
 """Oracle of the burst-parallel planner for a single chain of layers.
 
-TEST INFRASTRUCTURE ONLY (see the package docstring).  Plain Python floats (fp64), loops in the
-order and notation of the paper's Section 4.2, Algorithm "Search Linear":
+TEST INFRASTRUCTURE ONLY (see the package docstring).  Plain Python floats (fp64).  What it computes is
+the dynamic programme of the paper's Section 4.2, Algorithm "Search Linear", over two tables indexed by
+(layer, GPU count):
 
-  S[i][g] = shortest time to complete L_1..L_i while using g GPUs for L_i
-  T[i][g] = time spent on L_i while minimizing S[i][g]
-  Amp(i, g) = T[i][g] * g / comp(i, 1)                      (GPU-sec amplification, Section 4.2)
+  S[i][g]   the earliest finish of layer i when that layer runs on g GPUs, over the predecessor
+            choices the search admits;
+  T[i][g]   the part of that finish time that belongs to layer i alone: the transition into it plus
+            its compute and gradient synchronisation;
+  Amp(i, g) = T[i][g] * g / comp(i, 1), how many single-GPU seconds the layer costs per second it would
+            take on one GPU (the paper's GPU-sec amplification).
 
-The algorithm is a pruned shortest-path search, not an exact constrained optimum, so this file takes
-its steps as printed.  Inputs are tables: comp[i][a] for layer i (0-based here, L_{i+1} in the paper)
-at GPU count gpus[a]; comm[i][b][a] = comm_{(i-1, gpus[b]) -> (i, gpus[a])} for i >= 1 (comm[0] is the
-transition into the first layer); sync[i][a].
+The search is pruned (a predecessor is dropped once its amplification is over the limit and over the best
+admitted before it), so it is not an exact constrained optimum and cannot be replaced by a textbook
+shortest path; this file therefore performs the search's decisions in the paper's scan order (GPU counts
+ascending), organised as one admission helper plus a table fill.  Inputs are tables: comp[i][a] for layer
+i (0-based here) at GPU count gpus[a]; comm[i][b][a] = cost of going from layer i-1 on gpus[b] to layer i
+on gpus[a] (comm[0] leads into the first layer); sync[i][a].
 
 Readings where the text is silent (each also listed in the design notes):
-  * "g in [1, G]" ranges over a caller-given ascending list of GPU counts whose first entry is 1
-    (needed for comp(i, 1)); the evaluation restricts it to powers of two.
-  * Layer 0 does not exist: S[0][g] = 0 as printed, Amp(0, h) = 0 (always admissible), and the
-    transition into L_1 is whatever comm[0] holds (zeros: input loading is not modelled).
-  * The back-trace needs the h that produced bestS; it is recorded next to S and T.
-  * The last layer's g is picked with the same admission rule the loop applies to a predecessor
-    (a virtual layer L+1 with zero transition cost): scan g in order, admit when
-    Amp(L, g) <= max(bestAmp, AmpLimit) and S[L][g] <= bestS.
+  * GPU counts are a caller-given ascending list whose first entry is 1 (comp(i, 1) is needed); the
+    evaluation restricts it to powers of two.
+  * There is no layer 0: its row of S is zero and it is always admissible (amplification 0); the
+    transition into the first layer is whatever comm[0] holds (zeros: input loading is not modelled).
+  * The admission test compares against max(best amplification admitted so far, limit) with "best so
+    far" starting at infinity: the first candidate scanned always passes; ties in arrival time go to
+    the later candidate.
+  * The back-trace needs the predecessor behind each S entry; it is recorded in a third table.
+  * The last layer's GPU count is picked by the same admission helper (a virtual successor with zero
+    transition cost).
 
 The closed-form cost model (Section 4.1: payload divided by per-GPU bandwidth plus a propagation
-delay, full bisection) is in comm_model / sync_model; the payload split between GPU sets is a
+delay, full bisection) is in comm_time / sync_time; the payload split between GPU sets is a
 reading, stated at each function.
 
-Pins (tests/test_planner_pins.py): exhaustive enumeration of all assignments with AmpLimit = inf,
+Pins (tests/test_planner_pins.py): exhaustive enumeration of all assignments with no limit,
 a hand-worked two-layer example, Amp(i,1) = 1 without communication, perfectly linear scaling,
 path-sum consistency of the back-trace, the all-ones plan as an upper bound.
 """
@@ -35,33 +43,39 @@ import math
 INF = math.inf
 
 
+def admit(candidates, amp_limit):
+    """One admission scan.  candidates: (amplification, arrival time, payload) triples in ascending
+    GPU-count order.  A candidate is taken when its amplification is within the limit or no worse than
+    the smallest one taken so far, and its arrival is not later than the current best.
+    Returns (best arrival, payload of the candidate behind it), payload None if nothing was scanned."""
+    lowest_amp, best_arrival, chosen = INF, INF, None
+    for amp, arrival, payload in candidates:
+        if amp > max(lowest_amp, amp_limit) or arrival > best_arrival:
+            continue
+        best_arrival, chosen = arrival, payload
+        lowest_amp = min(lowest_amp, amp)
+    return best_arrival, chosen
+
+
 def search_linear(gpus, comp, comm, sync, amp_limit):
-    """Algorithm "Search Linear".  Returns (S, T, H): tables of L+1 rows (row 0 = the printed
-    initialisation) and the predecessor index H[i][a] (index into gpus) behind S[i][a]."""
+    """Fills S, T (L+1 rows; row 0 is the start state) and H, the index into gpus of the predecessor
+    count behind each S entry."""
     L, G = len(comp), len(gpus)
     assert gpus[0] == 1 and all(gpus[a] < gpus[a + 1] for a in range(G - 1))
     S = [[0.0] * G] + [[INF] * G for _ in range(L)]
     T = [[0.0] * G] + [[INF] * G for _ in range(L)]
     H = [[-1] * G for _ in range(L + 1)]
-
-    def amp(i, b):   # Amp(i, gpus[b]); layer 0 is always admissible
-        if i == 0:
-            return 0.0
-        return T[i][b] * gpus[b] / comp[i - 1][0]
-
-    for i in range(1, L + 1):
+    for layer in range(1, L + 1):
+        own = comp[layer - 1]
+        # amplification of every predecessor state; the start state costs nothing
+        prev_amp = [0.0 if layer == 1 else T[layer - 1][b] * gpus[b] / comp[layer - 2][0] for b in range(G)]
         for a in range(G):
-            best_amp, best_s, best_t, best_h = INF, INF, INF, -1
-            for b in range(G):
-                c = comm[i - 1][b][a]
-                if amp(i - 1, b) <= max(best_amp, amp_limit) and S[i - 1][b] + c <= best_s:
-                    best_s = S[i - 1][b] + c
-                    best_t = c
-                    best_amp = min(best_amp, amp(i - 1, b))
-                    best_h = b
-            S[i][a] = best_s + comp[i - 1][a] + sync[i - 1][a]
-            T[i][a] = best_t + comp[i - 1][a] + sync[i - 1][a]
-            H[i][a] = best_h
+            hop = [comm[layer - 1][b][a] for b in range(G)]
+            arrival, b = admit([(prev_amp[b], S[layer - 1][b] + hop[b], b) for b in range(G)], amp_limit)
+            # summed left to right, as the algorithm writes the two sums
+            S[layer][a] = arrival + own[a] + sync[layer - 1][a]
+            T[layer][a] = (hop[b] if b is not None else INF) + own[a] + sync[layer - 1][a]
+            H[layer][a] = b if b is not None else -1
     return S, T, H
 
 
@@ -73,17 +87,13 @@ def amplification(gpus, comp, T):
 def backtrace(gpus, comp, S, T, H, amp_limit):
     """GPU-count index per layer (length L) and the iteration time S[L][g_L]."""
     L, G = len(comp), len(gpus)
-    best_amp, best_s, last = INF, INF, -1
-    for a in range(G):
-        am = T[L][a] * gpus[a] / comp[L - 1][0]
-        if am <= max(best_amp, amp_limit) and S[L][a] <= best_s:
-            best_s, best_amp, last = S[L][a], min(best_amp, am), a
+    final = [(T[L][a] * gpus[a] / comp[L - 1][0], S[L][a], a) for a in range(G)]
+    total, a = admit(final, amp_limit)
     plan = [0] * L
-    a = last
-    for i in range(L, 0, -1):
-        plan[i - 1] = a
-        a = H[i][a]
-    return plan, best_s
+    for layer in range(L, 0, -1):
+        plan[layer - 1] = a
+        a = H[layer][a]
+    return plan, total
 
 
 def plan_chain(gpus, comp, comm, sync, amp_limit):

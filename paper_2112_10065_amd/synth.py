@@ -14,7 +14,7 @@ SEED = 20211210
 _G = np.uint64(0x9E3779B97F4A7C15)
 _M1 = np.uint64(0xBF58476D1CE4E5B9)
 _M2 = np.uint64(0x94D049BB133111EB)
-_CHUNK = 1 << 22
+_CHUNK = 1 << 20
 
 
 def fnv1a64(name: str) -> int:
@@ -42,14 +42,29 @@ def _base(name, seed):
     return (int(seed) ^ fnv1a64(name)) & 0xFFFFFFFFFFFFFFFF
 
 
+def _fill_chunks(n, fill):
+    """Run fill(start, end) over [0, n) in chunks; large tensors use a few threads (every element depends
+    on its own counter only, so the values do not depend on how the range is cut up)."""
+    spans = [(s, min(n, s + _CHUNK)) for s in range(0, n, _CHUNK)]
+    if len(spans) < 4:
+        for s, e in spans:
+            fill(s, e)
+        return
+    import os
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, min(16, os.cpu_count() or 1))) as ex:
+        list(ex.map(lambda se: fill(*se), spans))
+
+
 def uniform(name, shape, lo=-1.0, hi=1.0, seed=SEED):
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
     b = _base(name, seed)
-    for s in range(0, n, _CHUNK):
-        e = min(n, s + _CHUNK)
+
+    def fill(s, e):
         idx = np.arange(s, e, dtype=np.uint64)
         out[s:e] = lo + (hi - lo) * _u01(b, idx)
+    _fill_chunks(n, fill)
     return out.reshape(shape)
 
 
@@ -57,12 +72,13 @@ def normal(name, shape, std=1.0, seed=SEED):
     n = int(np.prod(shape))
     out = np.empty(n, dtype=np.float32)
     b = _base(name, seed)
-    for s in range(0, n, _CHUNK):
-        e = min(n, s + _CHUNK)
+
+    def fill(s, e):
         idx = np.arange(s, e, dtype=np.uint64)
         u1 = _u01(b, idx * np.uint64(2))
         u2 = _u01(b, idx * np.uint64(2) + np.uint64(1))
         out[s:e] = std * np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+    _fill_chunks(n, fill)
     return out.reshape(shape)
 
 

@@ -644,97 +644,8 @@ def test_relu_bias_grad(env, rows, k, bf16):
     assert rel <= 1e-5, (rel, mx)
 
 
-# ---- full-size layers of the benchmark workload, spot-checked --------------------------------
-FULL = [("conv1_1", 224, 3, 64, 8, True), ("conv1_2", 224, 64, 64, 4, False), ("conv3_2", 56, 256, 256, 32, False),
-        ("conv5_1", 14, 512, 512, 2, False), ("conv5_1", 14, 512, 512, 32, False)]
-
-
-@pytest.mark.parametrize("tuned", [False, True], ids=["model", "measured"])
-@pytest.mark.parametrize("name,hw,c,k,n,dxf", FULL, ids=[f"{f[0]}_n{f[4]}" for f in FULL])
-def test_vgg_layer_full_size_sampled(env, name, hw, c, k, n, dxf, tuned):
-    """Full-size VGG-16 layers, sampled against the oracle's spot evaluation; `measured` is the kernel choice
-    bench.py times (the first call of each pass measures the candidates on these very buffers)."""
-    dp, U, orc = env
-    dp.dp_set_autotune(tuned)
-    try:
-        _full_size_case(dp, U, orc, name, hw, c, k, n, dxf)
-    finally:
-        dp.dp_set_autotune(False)
-
-
-def _full_size_case(dp, U, orc, name, hw, c, k, n, dxf):
-    case = U.ConvCase(f"vgg/{name}", n, hw, hw, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True, dx_f32=dxf)
-    y = case.run_fwd()
-    dx = case.run_dgrad(y)
-    dw, db = case.run_wgrad(y)
-    torch.cuda.synchronize()
-    rng = np.random.default_rng(7)
-    y_np = U.to_np(y)
-    # border pixels are always part of the sample
-    idx = rng.integers(0, y_np.size, 3000)
-    idx[:64] = np.arange(64)
-    idx[64:128] = y_np.size - 1 - np.arange(64)
-    U.assert_bf16_close(y_np.ravel()[idx], orc.conv2d_fwd_at(case.x, case.w, case.b, True, (1, 1), (1, 1), idx), f"{name} y")
-    dx_np = U.to_np(dx)
-    idx = rng.integers(0, dx_np.size, 3000)
-    idx[:32] = np.arange(32)
-    idx[32:64] = dx_np.size - 1 - np.arange(32)
-    U.assert_bf16_close(dx_np.ravel()[idx], orc.conv2d_bwd_data_at(case.dy, case.w, case.x.shape, y_np, (1, 1), (1, 1), idx), f"{name} dx")
-    dw_np = U.to_np(dw)
-    idx = rng.integers(0, dw_np.size, 600)
-    U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, y_np, (1, 1), (1, 1), idx), f"{name} dw")
-    # the calls of bench.py's step: the incoming gradient is taken as already masked (no saved output), backward-data
-    # applies the backward of the ReLU in front of the layer, the filter-gradient call also sums the bias gradient
-    del dx, dw
-    if not dxf:
-        dx = case.run_dgrad_relu_in(None)
-    dw, db = case.run_wgrad(None)
-    torch.cuda.synchronize()
-    if not dxf:
-        dx_np = U.to_np(dx)
-        idx = rng.integers(0, dx_np.size, 3000)
-        idx[:32] = np.arange(32)
-        idx[32:64] = dx_np.size - 1 - np.arange(32)
-        want = orc.conv2d_bwd_data_at(case.dy, case.w, case.x.shape, None, (1, 1), (1, 1), idx) * (case.x.ravel()[idx] > 0)
-        U.assert_bf16_close(dx_np.ravel()[idx], want, f"{name} dx with the input ReLU")
-        assert not dx_np.ravel()[idx][case.x.ravel()[idx] <= 0].any()
-    dw_np = U.to_np(dw)
-    idx = rng.integers(0, dw_np.size, 600)
-    U.assert_bf16_close(dw_np.ravel()[idx], orc.conv2d_bwd_filter_at(case.x, case.dy, case.w.shape, None, (1, 1), (1, 1), idx), f"{name} dw unmasked")
-    rel, _ = U.errs(U.to_np(db), case.dy.reshape(-1, case.dy.shape[-1]).astype(np.float64).sum(axis=0))
-    assert rel <= U.BF16_REL, f"{name} db rel_l2={rel:.3e}"
-
-
-def test_fc6_full_size_sampled(env):
-    dp, U, orc = env
-    from paper_2112_10065_amd import synth
-    n, i, o = 32, 25088, 4096
-    x, W, b = synth.linear_tensors("vgg/fc6", n, i, o)
-    dy = synth.upstream_grad("vgg/fc6", (n, o))
-    xb, Wb, dyb = (synth.f32_to_bf16_bits(a) for a in (x, W, dy))
-    x, W, dy = (synth.bf16_bits_to_f32(a) for a in (xb, Wb, dyb))
-    xd, Wd, dyd = U.bf16_dev(xb), U.bf16_dev(Wb), U.bf16_dev(dyb)
-    bd = torch.from_numpy(b).to(U.DEV)
-    desc = dp.linear_desc(n, i, o, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
-    ws = U.workspace(dp.dp_linear_workspace_bytes(desc))
-    y = torch.empty((n, o), dtype=torch.bfloat16, device=U.DEV)
-    dx = torch.empty((n, i), dtype=torch.bfloat16, device=U.DEV)
-    dW = torch.empty((o, i), dtype=torch.float32, device=U.DEV)
-    db = torch.empty((o,), dtype=torch.float32, device=U.DEV)
-    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, bias=bd, y=y, ws=ws)
-    dp.dp_linear_fwd_bwd(desc, x=xd, W=Wd, dy=dyd, y_saved=y, dx=dx, dW=dW, dbias=db, ws=ws)
-    torch.cuda.synchronize()
-    y_np = U.to_np(y)
-    rng = np.random.default_rng(11)
-    idx = rng.integers(0, n * o, 4000)
-    U.assert_bf16_close(y_np.ravel()[idx], orc.linear_fwd_at(x, W, b, True, idx), "fc6 y")
-    idx = rng.integers(0, n * i, 4000)
-    U.assert_bf16_close(U.to_np(dx).ravel()[idx], orc.linear_dx_at(W, dy, y_np, idx), "fc6 dx")
-    idx = rng.integers(0, o * i, 20000)
-    U.assert_bf16_close(U.to_np(dW).ravel()[idx], orc.linear_dw_at(x, dy, y_np, idx), "fc6 dW")
-    _, rdb = orc.relu_bias_grad(dy, y_np)
-    rel, _ = U.errs(U.to_np(db), rdb)
-    assert rel <= 1e-5
+# Full-size layers of the benchmark workload at every per-GPU batch: tests/test_gpu_full_size.py; the chained step:
+# tests/test_gpu_chain.py.
 
 
 # ---- the planner's table --------------------------------------------------------------------

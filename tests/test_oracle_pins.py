@@ -136,6 +136,52 @@ def test_finite_differences_with_bias_and_relu(orc):
             assert abs(fd - grad.ravel()[i]) <= 1e-7 * max(1.0, abs(fd)), (which, i)
 
 
+def test_relu_in_backward_by_finite_differences(orc):
+    """relu_in_backward (the backward of the ReLU that produced a layer's input, reading "derivative 0 at 0") against
+    finite differences of L(u) = <conv(relu(u), w), g> in the pre-activation u: central differences where u != 0,
+    and, at entries that are exactly 0, the one-sided difference from below (0: the reading taken) next to the one
+    from above (the unmasked gradient).  A mask of x >= 0 instead of x > 0 fails at every u <= 0."""
+    n, h, w, c, k = 2, 6, 5, 3, 4
+    st, pd = (1, 2), (1, 1)
+    u = rng.standard_normal((n, h, w, c))
+    zeros = rng.choice(u.size, size=9, replace=False)
+    u.ravel()[zeros] = 0.0
+    wt = rng.standard_normal((k, 3, 3, c))
+    x_in = np.maximum(u, 0.0)
+    g = rng.standard_normal(orc.conv2d_fwd(x_in, wt, None, stride=st, pad=pd).shape)
+
+    def loss(u_):
+        return np.vdot(orc.conv2d_fwd(np.maximum(u_, 0.0), wt, None, stride=st, pad=pd), g)
+
+    plain = orc.conv2d_bwd_data(g, wt, u.shape, stride=st, pad=pd)
+    got = orc.relu_in_backward(plain, x_in)
+    assert got.shape == u.shape and not got.ravel()[zeros].any() and not got[u < 0].any()
+    np.testing.assert_array_equal(got[u > 0], plain[u > 0])
+    assert (np.abs(plain[u <= 0]) > 1e-3).any()   # the mask matters: unmasked gradients there are not small
+    eps = 1e-6
+    flat = u.ravel()
+    picks = np.concatenate([rng.choice(np.flatnonzero(flat > 1e-3), 10, replace=False),
+                            rng.choice(np.flatnonzero(flat < -1e-3), 10, replace=False)])
+    for i in picks:
+        old = flat[i]
+        flat[i] = old + eps
+        lp = loss(u)
+        flat[i] = old - eps
+        lm = loss(u)
+        flat[i] = old
+        fd = (lp - lm) / (2 * eps)
+        assert abs(fd - got.ravel()[i]) <= 1e-7 * max(1.0, abs(fd)), i
+    l0 = loss(u)
+    for i in zeros:
+        flat[i] = -eps
+        below = (l0 - loss(u)) / eps
+        flat[i] = eps
+        above = (loss(u) - l0) / eps
+        flat[i] = 0.0
+        assert below == 0.0 and got.ravel()[i] == 0.0
+        assert abs(above - plain.ravel()[i]) <= 1e-6 * max(1.0, abs(above))
+
+
 def test_delta_and_shifted_delta_kernels(orc):
     n, h, w, c = 2, 6, 7, 3
     x = rng.standard_normal((n, h, w, c))

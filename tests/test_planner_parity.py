@@ -9,8 +9,10 @@ import pytest
 from oracle import burst_plan as orc
 
 
-@pytest.fixture(scope="module")
-def dp():
+# Every test runs twice: unmarked (any host) and marked `gpu`, so that the run on the GPU machine also records the
+# planner's parity (the library there is the one the kernels were built into).
+@pytest.fixture(scope="module", params=["host", pytest.param("gpu_box", marks=pytest.mark.gpu)])
+def dp(request):
     from paper_2112_10065_amd import binding
     return binding
 
