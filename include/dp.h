@@ -118,6 +118,21 @@ dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const vo
                                const void *y_saved_or_null, float *dw, float *dbias_or_null,
                                void *ws, size_t ws_bytes, void *hip_stream);
 
+/* dp_conv2d_bwd_filter for callers that cannot allocate or pass a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors, minus ws: split partials,
+ * the masked gradient and bias-gradient sums go to a scratch array built into the library (DP_NOALLOC_SCRATCH_BYTES
+ * of device memory per GPU, held from the library's load until the process ends).  The call allocates nothing on the
+ * device (no hipMalloc / hipFree / events) and always uses the analytic kernel choice (dp_set_autotune is ignored).
+ * A layer whose pass needs more scratch than that (dp_conv2d_workspace_bytes(desc, DP_PASS_WGRAD) with the measured
+ * choice off) is rejected with DP_ERR_WORKSPACE before any launch.  The first call on a device looks the array's
+ * address up on that device (hipGetSymbolAddress, device current) and performs the library's one-time kernel
+ * set-up: make it outside a capture.  All calls on one GPU share the one array: calls that overlap on a GPU
+ * (different streams or threads) race; serialise them.  Nothing in it has to be cleared between calls. */
+#define DP_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+dp_status dp_conv2d_bwd_filter_noalloc(const dp_conv_desc *desc, const void *x, const void *dy,
+                                       const void *y_saved_or_null, float *dw, float *dbias_or_null,
+                                       void *hip_stream);
+
 /* Dense layer, forward and/or backward in one call (paper Table 1 "Dense"; section 4.1):
  *   y = x W^T + bias (ReLU if DP_RELU)                       if y != NULL   (needs x, W)
  *   g = dy * [y_saved > 0] (or dy);  dx = g W; dW = g^T x; dbias = sum_n g

@@ -15,7 +15,7 @@ DP_BIAS, DP_RELU, DP_DETERMINISTIC, DP_DX_F32, DP_RELU_IN = 1, 2, 4, 8, 16
 DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_data_relu",
-           "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
+           "dp_conv2d_bwd_filter", "dp_conv2d_bwd_filter_noalloc", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
            "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
            "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
            "dp_last_error", "dp_version"]
@@ -74,6 +74,7 @@ def _load():
     lib.dp_conv2d_bwd_data_relu.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_conv2d_bwd_data_relu.restype = C.c_int
     lib.dp_conv2d_bwd_filter.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.dp_conv2d_bwd_filter_noalloc.argtypes = [P(dp_conv_desc), vp, vp, vp, vp, vp, vp]
     lib.dp_linear_fwd_bwd.argtypes = [P(dp_linear_desc), vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_relu_bias_grad_workspace_bytes.restype = sz
     lib.dp_relu_bias_grad_workspace_bytes.argtypes = [i64, i32]
@@ -91,7 +92,7 @@ def _load():
     lib.dp_maxpool2x2_bwd.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.dp_softmax_xent.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
     lib.dp_sgd_update.argtypes = [i64, C.c_float, C.c_float, vp, vp, vp, vp, vp]
-    for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_linear_fwd_bwd",
+    for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_conv2d_bwd_filter_noalloc", "dp_linear_fwd_bwd",
                  "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
                  "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update"):
         getattr(lib, name).restype = C.c_int
@@ -304,6 +305,14 @@ def dp_conv2d_bwd_filter(desc, x, dy, y_saved, dw, dbias=None, ws=None, stream=N
     p, b = _ws(ws)
     _check(lib.dp_conv2d_bwd_filter(C.byref(desc), _ptr(x), _ptr(dy), _ptr(y_saved), _ptr(dw), _ptr(dbias), p, b,
                                     _stream(stream)))
+
+
+DP_NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def dp_conv2d_bwd_filter_noalloc(desc, x, dy, y_saved, dw, dbias=None, stream=None):
+    _check(lib.dp_conv2d_bwd_filter_noalloc(C.byref(desc), _ptr(x), _ptr(dy), _ptr(y_saved), _ptr(dw), _ptr(dbias),
+                                            _stream(stream)))
 
 
 def dp_linear_fwd_bwd(desc, x=None, W=None, bias=None, dy=None, y_saved=None, y=None, dx=None, dW=None, dbias=None,

@@ -11,6 +11,8 @@
 #include <unordered_map>
 #include <vector>
 
+static __device__ __align__(256) unsigned char scratch[DP_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -20,6 +22,15 @@ std::atomic<int> g_autotune{0};
 thread_local bool g_analytic_only = false;   // the descriptor of the running call asks for DP_DETERMINISTIC
 std::once_flag g_init_once;
 hipError_t g_init_err = hipSuccess;
+
+// Scratch of the allocation-free entry point (dp_conv2d_bwd_filter_noalloc): split partials, masked gradient and
+// bias-gradient sums live here instead of in a caller workspace.  Every GPU the library runs on holds its own copy
+// of this array at its own address until the process ends; in host code the array's name is only a handle for
+// hipGetSymbolAddress, never a device address.
+constexpr size_t kNoAllocScratchBytes = DP_NOALLOC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, looked up on first use
 
 dp_status fail(dp_status st, const char *fmt, ...)
 {
@@ -594,6 +605,42 @@ dp_status dp_conv2d_bwd_filter(const dp_conv_desc *desc, const void *x, const vo
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-filter needs %zu workspace bytes, got %zu", need, ws_bytes);
     if ((s = ensure_init()) != DP_OK) return s;
     return run_wgrad(g, desc->io_dtype, x, dy, y_saved, dw, dbias, ws, ws_bytes, (hipStream_t)hip_stream);
+}
+
+dp_status dp_conv2d_bwd_filter_noalloc(const dp_conv_desc *desc, const void *x, const void *dy, const void *y_saved, float *dw,
+                                       float *dbias, void *hip_stream)
+{
+    ConvGeom g;
+    dp_status s;
+    if ((s = check_conv(desc, &g)) != DP_OK) return s;
+    // the analytic kernel choice only: measuring candidates would create events and drain the stream
+    g_analytic_only = true;
+    if ((s = check_ptr(x, "x")) != DP_OK || (s = check_ptr(dy, "dy")) != DP_OK || (s = check_ptr(dw, "dw")) != DP_OK) return s;
+    if ((s = check_opt(y_saved, "y_saved")) != DP_OK || (s = check_opt(dbias, "dbias")) != DP_OK) return s;
+    const size_t need = wgrad_ws_bytes(g, desc->io_dtype, dbias != nullptr);
+    if (need > kNoAllocScratchBytes)
+        return fail(DP_ERR_WORKSPACE, "backward-filter of this layer needs %zu scratch bytes, the built-in scratch holds %zu: use dp_conv2d_bwd_filter with a workspace",
+                    need, kNoAllocScratchBytes);
+    if ((s = ensure_init()) != DP_OK) return s;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(DP_ERR_UNSUPPORTED, "device index %d is beyond the %d devices the built-in scratch is tracked for", dev, kMaxDevices);
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mu);
+        if (g_scratch_ptr[dev] == nullptr) {
+            // once per device, with that device current: each GPU holds its own copy of the array
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || p == nullptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // every kernel of this pass writes its scratch before reading it (partials, masked gradient, column sums), so the
+    // previous call's contents need no clearing
+    return run_wgrad(g, desc->io_dtype, x, dy, y_saved, dw, dbias, ptr, kNoAllocScratchBytes, (hipStream_t)hip_stream);
 }
 
 dp_status dp_linear_fwd_bwd(const dp_linear_desc *desc, const void *x, const void *W, const float *bias, const void *dy,

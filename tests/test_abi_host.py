@@ -74,6 +74,23 @@ def test_workspace_errors(dp):
     assert dp.dp_relu_bias_grad_workspace_bytes(100, 64) > 0
 
 
+def test_noalloc_backward_filter_argument_errors(dp):
+    """The allocation-free form validates like dp_conv2d_bwd_filter and rejects layers beyond its built-in scratch
+    before any HIP call."""
+    lib = dp.lib
+    d = dp.conv_desc(2, 28, 28, 64, 64, 3, 3, (1, 1), (1, 1), dp.DP_BF16, 0)
+    assert lib.dp_conv2d_bwd_filter_noalloc(None, A, A, None, A, A, None) == dp.DP_ERR_NULL
+    assert lib.dp_conv2d_bwd_filter_noalloc(C.byref(d), None, A, None, A, A, None) == dp.DP_ERR_NULL
+    assert lib.dp_conv2d_bwd_filter_noalloc(C.byref(d), A, A, None, None, A, None) == dp.DP_ERR_NULL
+    assert lib.dp_conv2d_bwd_filter_noalloc(C.byref(d), A, A + 4, None, A, A, None) == dp.DP_ERR_BAD_DESC
+    big = dp.conv_desc(32, 224, 224, 64, 64, 3, 3, (1, 1), (1, 1), dp.DP_BF16, 0)
+    assert dp.dp_conv2d_workspace_bytes(big, dp.DP_PASS_WGRAD) > dp.DP_NOALLOC_SCRATCH_BYTES
+    assert lib.dp_conv2d_bwd_filter_noalloc(C.byref(big), A, A, None, A, A, None) == dp.DP_ERR_WORKSPACE
+    assert b"built-in scratch" in lib.dp_last_error()
+    hdr = open(os.path.join(ROOT, "include", "dp.h")).read()
+    assert "#define DP_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)" in hdr and dp.DP_NOALLOC_SCRATCH_BYTES == 32 << 20
+
+
 def test_linear_and_pointwise_argument_errors(dp):
     lib = dp.lib
     ld = dp.linear_desc(4, 64, 32, dp.DP_BF16, dp.DP_BIAS)
