@@ -29,16 +29,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
-# the launches of each kernel at per-GPU batch 32: profiles/vgg16_n32_hbm_traffic.md
-TRAFFIC_BYTES_PER_LAUNCH = {
-    "k_conv_strip<false, 224, 256>": 111270430,
-    "k_conv_strip<false, 256, 256>": 127237311,
-    "k_fwd_dma<256, 256, 64, 2, 4, 2, 1>": 126579397,
-    "k_halo_ws<0>": 320908169,
-    "k_fwd_direct": 226669118,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>": 213974062,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>": 51880624,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>": 131364910
+# the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
+TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
 }
 
 
@@ -49,8 +41,13 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batches", type=str, default="1,2,4,8,16,32")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--side-streams", type=int, default=2, help="streams that run the filter gradients beside the backward chain")
-    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying one HIP graph per step")
+    ap.add_argument("--side-streams", type=int, default=2, help="streams that run the filter gradients beside the backward chain (0: everything on one stream)")
+    ap.add_argument("--launch", type=str, default="auto", choices=["auto", "eager", "graph"],
+                    help="auto: per batch, one small HIP graph per sub-step if it replays faster than launching the kernels one by one")
+    ap.add_argument("--no-graph", action="store_true", help="same as --launch eager")
+    ap.add_argument("--no-table", action="store_true", help="skip the dp_profile_layer table")
+    ap.add_argument("--multiplex", action="store_true",
+                    help="single-GPU multiplexing run instead of the sweep: foreground VGG-16 step at batch 2 beside a background ResNet-50 step at batch 64")
     ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception", "wrn101_2"],
                     help="layer list; the metric and the default run are VGG-16, the others emit their own tables")
     ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
@@ -60,7 +57,10 @@ def parse():
                     help="keep the analytic kernel choice instead of timing the candidates once per layer shape before the warm-up")
     ap.add_argument("--no-glue", action="store_true", help="skip the separate timing of pooling, loss and SGD update")
     ap.add_argument("--table", type=str, default="", help="also write the per-layer time-vs-batch table (JSON) here")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.no_graph:
+        args.launch = "eager"
+    return args
 
 
 class _BindProxy:
@@ -253,6 +253,68 @@ def cpu_baseline():
                       f"{flops / 1e9:.1f} GFLOP nominal in {secs:.1f} s"}
 
 
+def median(v):
+    v = sorted(v)
+    return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
+
+
+def algorithmic_bytes(l, n, pname):
+    """Algorithmic HBM bytes of one pass (bf16 tensors, fp32 filter / bias gradients): what the pass must read and write."""
+    sp = l.spec
+    if l.is_conv:
+        xe, we, ye = n * sp.h * sp.w * sp.c, sp.k * sp.r * sp.s * sp.c, n * l.ho * l.wo * sp.k
+    else:
+        xe, we, ye = n * sp.in_f, sp.out_f * sp.in_f, n * sp.out_f
+    if pname == "fwd":
+        return 2.0 * (xe + we + ye) + 4.0 * l.k
+    if pname == "dgrad":
+        return 2.0 * (ye + we + xe) + 2.0 * xe      # + the saved input read by the fused ReLU backward
+    return 2.0 * (xe + ye) + 4.0 * we + 4.0 * l.k
+
+
+RIDGE_FLOP_PER_BYTE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+
+
+def roofline_objects(trace, layers, n):
+    """The two roofline objects of per-GPU batch n from the per-kernel trace.  A call (layer, pass) is bound by the
+    matrix cores when its flops / algorithmic bytes exceed the ridge of the two peaks, else by HBM; the calls of each
+    class are grouped by the kernel name the profiler prints.  Dominant = largest summed main-kernel duration over
+    all layers and passes of the class."""
+    groups = {"mfma": {}, "hbm": {}}
+    total_us = 0.0
+    for l in layers:
+        for pname, _, _ in l.passes():
+            rows = trace.get((l.name, n, pname))
+            if not rows:
+                continue
+            fl, by = l.flops(n), algorithmic_bytes(l, n, pname)
+            bound = "mfma" if fl / by >= RIDGE_FLOP_PER_BYTE else "hbm"
+            g = groups[bound].setdefault(rows[0]["kernel"], {"us": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0, "calls": []})
+            main = median([r["main_us"] for r in rows])
+            total_us += main
+            g["us"] += main
+            g["launches"] += 1
+            g["flops"] += fl
+            g["bytes"] += by
+            g["calls"].append(f"{l.name}.{pname}")
+    out = {}
+    for bound in ("mfma", "hbm"):
+        if not groups[bound]:
+            out[bound] = None
+            continue
+        kname, g = max(groups[bound].items(), key=lambda kv: kv[1]["us"])
+        if bound == "mfma":
+            achieved, peak, unit = g["flops"] / g["us"] / 1e6, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+        else:
+            achieved, peak, unit = g["bytes"] / g["us"] / 1e3, HBM_PEAK_GBS, "GB/s"
+        out[bound] = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                      "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(f"{kname}@{n}"),
+                      "kernel": kname, "samples_per_launch": n, "avg_launch_us": g["us"] / g["launches"], "launches_per_step": g["launches"],
+                      "flops_per_launch_avg": g["flops"] / g["launches"], "algorithmic_bytes_per_launch_avg": g["bytes"] / g["launches"],
+                      "share_of_batch_kernel_time": g["us"] / total_us, "calls": g["calls"]}
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -266,6 +328,10 @@ def main():
         sys.exit(1)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.multiplex:
+        from paper_2112_10065_amd import multiplex
+        print(json.dumps(multiplex.run(args, dp, torch, dev, Layer)))
+        return
     gen = torch.Generator(device=dev)
     gen.manual_seed(20211210)
     batches = [int(b) for b in args.batches.split(",")]
@@ -302,23 +368,29 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    n_side = max(1, args.side_streams)
+    n_side = max(0, args.side_streams)
     ws_side = [torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(n_side)]
     side_streams = [torch.cuda.Stream() for _ in range(n_side)]   # default priority
 
-    def build_step(main):
-        """Pre-marshalled launch list of one step on stream `main` (+ the side streams)."""
+    def build_batch(n, main):
+        """Pre-marshalled launch list of the sub-step of per-GPU batch n on stream `main` (+ the side streams):
+        forward through the layers, then backward from the last layer; a layer's filter gradient depends only on
+        that layer's (already masked) incoming gradient, so it runs on a side stream beside the data-gradient
+        chain, after an event that stands for "the layer behind has produced this gradient"."""
         ops = []   # (kind, payload): "call" zero-arg launch, "fork" (event, side stream), "join"
-        for n in batches:
-            for l in layers:
-                ops.append(("call", l.bound("fwd", dp, descs[(l.name, n)], ws, main)))
-            for li, l in enumerate(reversed(layers)):
-                d = descs[(l.name, n)]
+        for l in layers:
+            ops.append(("call", l.bound("fwd", dp, descs[(l.name, n)], ws, main)))
+        for li, l in enumerate(reversed(layers)):
+            d = descs[(l.name, n)]
+            if n_side > 0:
                 side, wss = side_streams[li % n_side], ws_side[li % n_side]
                 ops.append(("fork", (torch.cuda.Event(), side)))
                 ops.append(("call", l.bound("wgrad", dp, d, wss, side)))
-                if l.needs_dx:
-                    ops.append(("call", l.bound("dgrad", dp, d, ws, main)))
+            else:
+                ops.append(("call", l.bound("wgrad", dp, d, ws, main)))
+            if l.needs_dx:
+                ops.append(("call", l.bound("dgrad", dp, d, ws, main)))
+        if n_side > 0:
             ops.append(("join", None))
         return ops
 
@@ -336,20 +408,13 @@ def main():
 
     _ops_cache = {}
 
-    def step():
-        """One training-iteration-shaped pass per batch size: forward through the layers, then backward
-        from the last layer; the filter gradient of a layer depends only on that layer's masked
-        gradient, so it runs on a side stream beside the data-gradient chain (own workspace per stream)."""
+    def eager_batch(n):
         main = torch.cuda.current_stream()
-        key = main.cuda_stream
+        key = (n, main.cuda_stream)
         if key not in _ops_cache:
-            _ops_cache[key] = build_step(main)
+            _ops_cache[key] = build_batch(n, main)
         run_ops(_ops_cache[key], main)
 
-    flops_step = sum(l.step_flops(n) for l in layers for n in batches)
-    # One step is captured into a HIP graph and replayed (the paper runs whole iterations as
-    # graphs for the same reason: at small per-GPU batch the kernels are shorter than a launch).
-    # The library enqueues only kernels on the stream it is given: nothing else is recorded.
     def timed(fn, reps):
         torch.cuda.synchronize()
         t = time.perf_counter()
@@ -358,98 +423,88 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / reps
 
-    run_step, launch = step, "eager"
-    for _ in range(max(1, args.warmup)):
-        step()                           # also runs the library's one-time initialisation
-    if not args.no_graph:
-        cap = torch.cuda.Stream()
-        cap.wait_stream(torch.cuda.current_stream())
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=cap):
-            step()
-        graph.replay()
-        # warm-up doubles as the choice of launch mode: both replay the same kernels on the same data
-        reps = max(1, args.warmup)
-        if timed(graph.replay, reps) < timed(step, reps):
-            run_step, launch = graph.replay, "hip_graph"
+    # Launch mode per batch.  The paper runs whole iterations as device graphs and splits them into small graphs
+    # (section 5, "Multiplexing"); here every per-GPU batch's sub-step is one small graph, captured with its side
+    # streams, and a step replays the six of them in order.  A batch keeps the graph only if it replays faster than
+    # launching its kernels one by one (measured in the warm-up, same kernels, same data).
+    runners, launch = {}, {}
+    reps = max(2, args.warmup)
+    for n in batches:
+        eager = (lambda n=n: eager_batch(n))
+        for _ in range(max(1, args.warmup)):
+            eager()                     # also runs the library's one-time initialisation
+        runners[n], launch[n] = eager, "eager"
+        if args.launch != "eager":
+            cap = torch.cuda.Stream()
+            cap.wait_stream(torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=cap):
+                eager_batch(n)
+            graph.replay()
+            torch.cuda.synchronize()
+            if args.launch == "graph" or timed(graph.replay, reps) < timed(eager, reps):
+                runners[n], launch[n] = graph.replay, "hip_graph"
+
+    def step():
+        for n in batches:
+            runners[n]()
+
+    flops_step = sum(l.step_flops(n) for l in layers for n in batches)
+    step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run_step()
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed * 1e3 / args.steps
     value = flops_step / (elapsed / args.steps) / 1e12
 
-    # ---- instrumented steps: HIP events (on the launch stream) around every library call ----
-    stream = torch.cuda.current_stream()
-    calls = []
-    for _ in range(args.steps):
-        for n in batches:
-            # the stream is idle after the synchronize below: one untimed call first, so that the first timed
-            # call of the batch does not carry the queue's start-up latency
-            layers[0].passes()[0][1](dp, descs[(layers[0].name, n)], ws)
-            for l in layers:
-                d = descs[(l.name, n)]
-                for pname, fn, _ in l.passes():
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(stream)
-                    fn(dp, d, ws)
-                    e1.record(stream)
-                    calls.append((l, n, pname, e0, e1))
-            torch.cuda.synchronize()   # keeps the number of pending events small (the runtime stalls on very long event queues)
-    torch.cuda.synchronize()
-    per = {}
-    for l, n, pname, e0, e1 in calls:
-        per.setdefault((l.name, n, pname), []).append(e0.elapsed_time(e1) * 1e3)  # microseconds
-    # per-call statistic: the median over the steps (a rare multi-millisecond stall between two
-    # events, unrelated to the kernels, would otherwise dominate a mean of five samples)
-    def med(v):
-        v = sorted(v)
-        return v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2])
-    per = {k: [med(v)] * len(v) for k, v in per.items()}
-    table = {}
-    for (lname, n, pname), v in per.items():
-        table.setdefault(lname, {}).setdefault(str(n), {})[pname + "_us"] = sum(v) / len(v)
-
-    # per-batch throughput (fraction of the bf16 dense MFMA peak) over all 16 layers
+    # ---- per batch: wall time of that batch's sub-step alone, launched as in the step ----
     per_batch = {}
     for n in batches:
-        us = sum(sum(per[(l.name, n, p)]) / len(per[(l.name, n, p)]) for l in layers for p, _, _ in l.passes())
+        us = min(timed(runners[n], max(3, args.steps)) for _ in range(3)) * 1e6
         fl = sum(l.step_flops(n) for l in layers)
-        per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us}
+        per_batch[str(n)] = {"tflops": fl / us / 1e6, "frac_mfma_peak": fl / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, "us": us, "launch": launch[n]}
 
-    # dominant kernel: the conv kernel instantiation with the largest total time among the forward calls at
-    # the largest batch of the sweep that are a single launch (no split reduction); its figures below are
-    # over exactly those launches, each of which processes nmax samples.  (Forward only: the forward and
-    # backward-data instantiations of one tile shape take nearly the same time, and which of the two came
-    # out on top used to change from run to run.)
-    groups = {}
-    for l in layers:
-        if not l.is_conv:
-            continue
-        for n in (nmax,):
-            for pi, pname in enumerate(("fwd",)):
-                kname, splits = dp.dp_conv2d_kernel_info(descs[(l.name, n)], pi)
-                if splits != 1 or (l.name, n, pname) not in per:
-                    continue
-                v = per[(l.name, n, pname)]
-                g = groups.setdefault(kname, {"us": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
-                g["us"] += sum(v)
-                g["launches"] += len(v)
-                g["flops"] += l.flops(n) * len(v)
-                sp = l.spec   # algorithmic bytes: input activation + weights + output activation, bf16
-                g["bytes"] += 2.0 * (n * sp.h * sp.w * sp.c + sp.k * sp.r * sp.s * sp.c + n * l.ho * l.wo * sp.k) * len(v)
-    roofline = None
-    if groups:
-        kname, g = max(groups.items(), key=lambda kv: kv[1]["us"])
-        achieved = g["flops"] / g["us"] / 1e6
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": TRAFFIC_BYTES_PER_LAUNCH.get(kname), "kernel": kname, "samples_per_launch": nmax,
-                    "avg_launch_us": g["us"] / g["launches"], "launches": g["launches"],
-                    "flops_per_launch_avg": g["flops"] / g["launches"],
-                    "algorithmic_bytes_per_launch_avg": g["bytes"] / g["launches"]}
+    # ---- per kernel: the library's own trace (HIP events on the launch stream before / after the main kernel of every
+    # pass and after its last kernel); calls issued one after another on one stream ----
+    trace = {}
+    for _ in range(max(3, min(args.steps, 10))):
+        for n in batches:
+            layers[0].passes()[0][1](dp, descs[(layers[0].name, n)], ws)   # untraced: absorbs the idle queue's start-up latency
+            dp.dp_trace_begin()
+            order = []
+            for l in layers:
+                for pname, fn, _ in l.passes():
+                    fn(dp, descs[(l.name, n)], ws)
+                    order.append((l.name, n, pname))
+            rows = dp.dp_trace_end()
+            assert len(rows) == len(order), (len(rows), len(order))
+            for key, r in zip(order, rows):
+                trace.setdefault(key, []).append(r)
+    for n in batches:
+        per_batch[str(n)]["us_sum_of_calls"] = sum(median([r["total_us"] for r in trace[(l.name, n, p)]]) for l in layers for p, _, _ in l.passes())
+        per_batch[str(n)]["us_sum_of_main_kernels"] = sum(median([r["main_us"] for r in trace[(l.name, n, p)]]) for l in layers for p, _, _ in l.passes())
+    kernels = {}
+    for (lname, n, pname), rows in trace.items():
+        kernels.setdefault(lname, {}).setdefault(str(n), {})[pname] = {
+            "kernel": rows[0]["kernel"], "splits": rows[0]["splits"], "main_us": median([r["main_us"] for r in rows]),
+            "total_us": median([r["total_us"] for r in rows])}
+
+    rf_max = roofline_objects(trace, layers, nmax)
+    rf_small = roofline_objects(trace, layers, 2) if 2 in batches and nmax != 2 else {"mfma": None, "hbm": None}
+
+    # ---- the planner's table comp(i, g): dp_profile_layer per layer over the batches (paper section 4.1) ----
+    table = {}
+    if not args.no_table:
+        for l in layers:
+            d = descs[(l.name, batches[0])]
+            rows = dp.dp_profile_layer(conv=d, batches=batches, warmup=2, iters=10) if l.is_conv else \
+                dp.dp_profile_layer(linear=d, batches=batches, warmup=2, iters=10)
+            table[l.name] = {str(r["batch"]): {"fwd_us": r["fwd_us"], "dgrad_us": r["dgrad_us"] if l.needs_dx else 0.0, "wgrad_us": r["wgrad_us"],
+                                               "flops_per_pass": r["flops_per_pass"]} for r in rows}
 
     out = {
         "metric": "conv+FC fwd/bwd TFLOP/s and % bf16 MFMA peak vs per-GPU batch 1-32 (VGG-16)",
@@ -464,17 +519,24 @@ def main():
                                + ("layers " + args.layers + ", " if args.layers else "")
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
-        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch, "kernel_choice": "model" if args.no_autotune else "measured",
+        "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch if len(set(launch.values())) > 1 else next(iter(launch.values())),
+        "kernel_choice": "model" if args.no_autotune else "measured",
         "per_batch": per_batch,
-        "roofline": roofline,
+        "roofline": rf_max["mfma"] or rf_max["hbm"],
+        "roofline_hbm": rf_max["hbm"],
+        "roofline_batch2": rf_small["mfma"],
+        "roofline_hbm_batch2": rf_small["hbm"],
     }
+    if table:
+        out["layer_table_us"] = {ln: {b: [round(v["fwd_us"], 2), round(v["dgrad_us"], 2), round(v["wgrad_us"], 2)] for b, v in t.items()} for ln, t in table.items()}
+        out["layer_table_source"] = "dp_profile_layer (fwd, dgrad, wgrad microseconds per layer and per-GPU batch; comp(i,g) of the planner = their sum at batch 32/g)"
     if args.workload == "vgg16" and not args.layers and not args.no_glue:
         out["glue"] = glue_times(dp, torch, dev, batches)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     if args.table:
         with open(args.table, "w") as f:
-            json.dump(table, f, indent=1)
+            json.dump({"source": "dp_profile_layer", "layers": table, "kernels": kernels}, f, indent=1)
     print(json.dumps(out))
 
 

@@ -171,6 +171,10 @@ typedef struct {
  * pattern, runs `warmup` untimed and `iters` timed back-to-back launches of each pass
  * between HIP events on `hip_stream`, and synchronises: the only blocking call here.
  * For a dense layer fwd_us is the y pass, dgrad_us the dx pass, wgrad_us the dW+dbias pass.
+ * The backward passes mask the incoming gradient with the saved output when the flags have DP_RELU; with
+ * DP_RELU_IN as well they run as in a step where each ReLU is differentiated by the layer behind it
+ * (y_saved = NULL, dx *= [x > 0]).  One untimed call per pass precedes the warm-up, so the measured kernel
+ * choice (dp_set_autotune) never times its candidates inside the timed window, whatever `warmup` is.
  * rows_out: host array of n_batches rows. */
 dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linear,
                            const int32_t *batches, int32_t n_batches, int32_t warmup,
@@ -196,6 +200,23 @@ dp_status dp_set_override(int pass, int tile_variant, int splits);
  * place while the stream is being captured (the model's choice is used), with a forced override,
  * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */
 dp_status dp_set_autotune(int enabled);
+
+/* Per-kernel timing of the calling thread's compute calls, for benchmarks (the measured side of a roofline).
+ * Between dp_trace_begin and dp_trace_end every conv / dense pass records three HIP events on the stream it is
+ * given: before its first kernel, after its main kernel (the implicit-GEMM kernel; a split-reduce or column-sum
+ * kernel may follow) and after its last kernel.  dp_trace_end waits for the events (it blocks until the traced
+ * work is done), writes one row per pass in call order (at most max_rows; a dense call yields one row per
+ * half it ran) and frees the events.  kernel: the main kernel as the profiler prints it; main_us: first event to
+ * second; total_us: first to third.  Tracing creates events: not for use under stream capture.  Passes that
+ * the measured kernel choice (dp_set_autotune) uses for its measurement are timed from the end of that measurement. */
+typedef struct {
+    char kernel[96];
+    int32_t pass;   /* DP_PASS_* */
+    int32_t splits; /* reduction splits of the plan that ran (> 1: a reduce kernel follows the main kernel) */
+    float main_us, total_us;
+} dp_trace_row;
+dp_status dp_trace_begin(void);
+dp_status dp_trace_end(dp_trace_row *rows, int32_t max_rows, int32_t *n_rows);
 
 /* ---- Glue layers of a whole training step (paper Table 1 counts VGG-16's pooling layers among its 21
  * layers; the paper gives no arithmetic for them).  Pointwise, HBM-bound, asynchronous on hip_stream, no

@@ -16,7 +16,7 @@ DP_PASS_FWD, DP_PASS_DGRAD, DP_PASS_WGRAD = 0, 1, 2
 
 EXPORTS = ["dp_conv2d_workspace_bytes", "dp_linear_workspace_bytes", "dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_data_relu",
            "dp_conv2d_bwd_filter", "dp_conv2d_bwd_filter_noalloc", "dp_linear_fwd_bwd", "dp_relu_bias_grad_workspace_bytes", "dp_relu_bias_grad",
-           "dp_profile_layer", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
+           "dp_profile_layer", "dp_trace_begin", "dp_trace_end", "dp_conv2d_kernel_info", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
            "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update",
            "dp_last_error", "dp_version"]
 
@@ -35,6 +35,11 @@ class dp_profile_row(C.Structure):
     _fields_ = [("batch", C.c_int32), ("fwd_us", C.c_float), ("dgrad_us", C.c_float), ("wgrad_us", C.c_float),
                 ("flops_per_pass", C.c_double), ("min_bytes_fwd", C.c_double), ("min_bytes_dgrad", C.c_double),
                 ("min_bytes_wgrad", C.c_double)]
+
+
+class dp_trace_row(C.Structure):
+    _fields_ = [("kernel", C.c_char * 96), ("pass_", C.c_int32), ("splits", C.c_int32), ("main_us", C.c_float),
+                ("total_us", C.c_float)]
 
 
 class dp_plan_desc(C.Structure):
@@ -80,6 +85,8 @@ def _load():
     lib.dp_relu_bias_grad_workspace_bytes.argtypes = [i64, i32]
     lib.dp_relu_bias_grad.argtypes = [i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.dp_profile_layer.argtypes = [P(dp_conv_desc), P(dp_linear_desc), P(i32), i32, i32, i32, P(dp_profile_row), vp]
+    lib.dp_trace_begin.argtypes = []
+    lib.dp_trace_end.argtypes = [P(dp_trace_row), i32, P(i32)]
     lib.dp_set_override.argtypes = [C.c_int, C.c_int, C.c_int]
     lib.dp_set_autotune.argtypes = [C.c_int]
     lib.dp_conv2d_kernel_info.argtypes = [P(dp_conv_desc), C.c_int, C.c_char_p, sz, P(i32)]
@@ -93,7 +100,7 @@ def _load():
     lib.dp_softmax_xent.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
     lib.dp_sgd_update.argtypes = [i64, C.c_float, C.c_float, vp, vp, vp, vp, vp]
     for name in ("dp_conv2d_fwd", "dp_conv2d_bwd_data", "dp_conv2d_bwd_filter", "dp_conv2d_bwd_filter_noalloc", "dp_linear_fwd_bwd",
-                 "dp_relu_bias_grad", "dp_profile_layer", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
+                 "dp_relu_bias_grad", "dp_profile_layer", "dp_trace_begin", "dp_trace_end", "dp_set_override", "dp_set_autotune", "dp_plan_chain",
                  "dp_plan_cost_tables", "dp_plan_graph", "dp_maxpool2x2_fwd", "dp_maxpool2x2_bwd", "dp_softmax_xent", "dp_sgd_update"):
         getattr(lib, name).restype = C.c_int
     lib.dp_last_error.restype = C.c_char_p
@@ -336,6 +343,19 @@ def dp_profile_layer(conv=None, linear=None, batches=(1,), warmup=3, iters=10, s
                                 C.byref(linear) if linear is not None else None, arr, n, warmup, iters, rows,
                                 _stream(stream)))
     return [dict((f, getattr(r, f)) for f, _ in dp_profile_row._fields_) for r in rows]
+
+
+def dp_trace_begin():
+    _check(lib.dp_trace_begin())
+
+
+def dp_trace_end(max_rows=8192):
+    """Rows of the trace started by dp_trace_begin, in call order: dicts with kernel, pass, splits, main_us, total_us."""
+    rows = (dp_trace_row * max_rows)()
+    n = C.c_int32(0)
+    _check(lib.dp_trace_end(rows, max_rows, C.byref(n)))
+    return [{"kernel": rows[i].kernel.decode(), "pass": rows[i].pass_, "splits": rows[i].splits,
+             "main_us": rows[i].main_us, "total_us": rows[i].total_us} for i in range(n.value)]
 
 
 def bind(fn_name, *args):

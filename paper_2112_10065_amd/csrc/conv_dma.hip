@@ -1056,9 +1056,14 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
-                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}, {256, 224, 64, 4, 1, 2}};
-constexpr int kNumDma = 34, kStripVariant = 30;   // the last four entries are k_conv_strip (4 waves; its own LDS layout)
-inline bool is_strip(int v) { return v >= kStripVariant; }
+                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}, {256, 224, 64, 4, 1, 2},
+                           // deep pipelines for the small grids of batch 1-4: one block per CU cannot hide the L2 latency with
+                           // one step in flight, so these keep 3-7 steps (72-120 KB) on their way
+                           {64, 128, 64, 2, 2, 5}, {128, 64, 64, 2, 2, 5}, {64, 64, 64, 2, 2, 8}, {64, 64, 64, 2, 2, 4},
+                           {128, 128, 64, 2, 2, 4}, {128, 128, 64, 2, 2, 3}, {64, 128, 64, 2, 2, 3}, {128, 64, 64, 2, 2, 3},
+                           {64, 128, 128, 2, 2, 3}, {128, 64, 128, 2, 2, 3}};
+constexpr int kNumDma = 44, kStripVariant = 30, kStripEnd = 34;   // entries 30..33 are k_conv_strip (4 waves; its own LDS layout)
+inline bool is_strip(int v) { return v >= kStripVariant && v < kStripEnd; }
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
 {
@@ -1096,6 +1101,16 @@ KernelFn pick_dma_d(int v)
     case 31: return k_conv_strip<true, 128, 256>;
     case 32: return k_conv_strip<true, 256, 128>;
     case 33: return k_conv_strip<true, 224, 256>;
+    case 34: return k_dgrad_dma<64, 128, 64, 2, 2, 5>;
+    case 35: return k_dgrad_dma<128, 64, 64, 2, 2, 5>;
+    case 36: return k_dgrad_dma<64, 64, 64, 2, 2, 8>;
+    case 37: return k_dgrad_dma<64, 64, 64, 2, 2, 4>;
+    case 38: return k_dgrad_dma<128, 128, 64, 2, 2, 4>;
+    case 39: return k_dgrad_dma<128, 128, 64, 2, 2, 3>;
+    case 40: return k_dgrad_dma<64, 128, 64, 2, 2, 3>;
+    case 41: return k_dgrad_dma<128, 64, 64, 2, 2, 3>;
+    case 42: return k_dgrad_dma<64, 128, 128, 2, 2, 3>;
+    case 43: return k_dgrad_dma<128, 64, 128, 2, 2, 3>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1135,6 +1150,16 @@ KernelFn pick_dma(int v)
     case 31: return k_conv_strip<false, 128, 256>;
     case 32: return k_conv_strip<false, 256, 128>;
     case 33: return k_conv_strip<false, 224, 256>;
+    case 34: return k_fwd_dma<64, 128, 64, 2, 2, 5>;
+    case 35: return k_fwd_dma<128, 64, 64, 2, 2, 5>;
+    case 36: return k_fwd_dma<64, 64, 64, 2, 2, 8>;
+    case 37: return k_fwd_dma<64, 64, 64, 2, 2, 4>;
+    case 38: return k_fwd_dma<128, 128, 64, 2, 2, 4>;
+    case 39: return k_fwd_dma<128, 128, 64, 2, 2, 3>;
+    case 40: return k_fwd_dma<64, 128, 64, 2, 2, 3>;
+    case 41: return k_fwd_dma<128, 64, 64, 2, 2, 3>;
+    case 42: return k_fwd_dma<64, 128, 128, 2, 2, 3>;
+    case 43: return k_fwd_dma<128, 64, 128, 2, 2, 3>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1168,7 +1193,7 @@ size_t dma_w_lds_bytes(const DmaVariant &d) { return (size_t)d.NS * (d.TA + d.TB
 
 size_t dma_lds_bytes(const DmaVariant &d)
 {
-    if (&d >= &kDma[kStripVariant]) return strip_lds_bytes(d.TA, d.TB);
+    if (&d >= &kDma[kStripVariant] && &d < &kDma[kStripEnd]) return strip_lds_bytes(d.TA, d.TB);
     size_t stages = (size_t)d.KG * d.NS * (d.TA + d.TB) * d.BK * 2, epi = (size_t)d.TB * (d.TA + 8) * 2;
     const size_t gsum = (size_t)(d.KG - 1) * d.TA * d.TB * 4;   // extra groups' accumulators
     if (gsum > stages) stages = gsum;
@@ -1330,6 +1355,7 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB * d.KG, 1, 1);
     if (wg) grid = dim3((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1);
     hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
+    dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
     return launch_split_reduce(a, p.rowsA, p.rowsB, st, (p.flags & KF_DB) != 0);

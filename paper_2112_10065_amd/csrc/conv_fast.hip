@@ -555,6 +555,7 @@ hipError_t fast_launch(const ConvArgs &a, hipStream_t st)
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * fv.WA * fv.WB, 1, 1);
     hipLaunchKernelGGL(pick_fast(a.pass, a.plan.variant, a.plan.BK), grid, block,
                        fast_lds_bytes(a.pass, fv.TA, fv.TB, a.plan.BK), st, p);
+    dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
     return launch_split_reduce(a, p.rowsA, p.rowsB, st);

@@ -786,6 +786,7 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         const int tiles_x = (g.Wo + tw - 1) / tw, tiles_y = (g.Ho + th - 1) / th;
         hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * g.R * g.S), 2 * WH_BUF, st, p, tws,
                            tiles_x, tiles_y, g.N * tiles_x * tiles_y);
+        dp_trace_main_kernel_done(st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         return launch_split_reduce(a, p.rowsA, p.rowsB, st);
@@ -807,10 +808,12 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         if (blocks > p.tilesB) blocks = p.tilesB;
         hipLaunchKernelGGL(fwd ? k_halo_ws<PASS_FWD> : k_halo_ws<PASS_DGRAD>, dim3((unsigned)blocks, (unsigned)p.tilesA), dim3(256), WS_LDS, st, p,
                            tws, tiles_x, tiles_y, p.tilesB);
+        dp_trace_main_kernel_done(st);
         return hipGetLastError();
     }
     const HaloVariant &h = kHalo[a.plan.variant];
     dim3 grid((unsigned)(p.tilesA * p.tilesB), 1, 1), block(64 * h.WA * h.WB, 1, 1);
     hipLaunchKernelGGL(pick_halo(a.pass, a.plan.variant), grid, block, halo_lds_bytes(h), st, p, tws, tiles_x, tiles_y);
+    dp_trace_main_kernel_done(st);
     return hipGetLastError();
 }

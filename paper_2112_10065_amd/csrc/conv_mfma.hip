@@ -734,6 +734,7 @@ hipError_t mfma_launch(const ConvArgs &a, hipStream_t st)
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * tv.WA * tv.WB, 1, 1);
     size_t shmem = lds_bytes(tv.TA, tv.TB, a.plan.BK);
     hipLaunchKernelGGL(fn, grid, block, shmem, st, p);
+    dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.splits > 1) e = launch_split_reduce(a, p.rowsA, p.rowsB, st);

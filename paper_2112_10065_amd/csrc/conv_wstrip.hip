@@ -269,6 +269,7 @@ hipError_t wstrip_launch(const ConvArgs &a, hipStream_t st)
     p.ph_tile0[0] = seg_slots(a.g.W);
     dim3 grid((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1), block(256, 1, 1);
     hipLaunchKernelGGL(k_wgrad_strip, grid, block, kWsLds, st, p);
+    dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || p.splits <= 1) return e;
     return launch_split_reduce(a, p.rowsA, p.rowsB, st, false);

@@ -32,6 +32,18 @@ constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mu;
 void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each device, looked up on first use
 
+// ---- dp_trace_begin / dp_trace_end: HIP events around the kernels of the calling thread's passes ----
+struct TraceRec {
+    hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;   // before the pass, after its main kernel, after its last kernel
+    bool main_marked = false;
+    char name[96] = "";
+    int pass = 0, splits = 1;
+};
+thread_local bool g_trace_on = false;
+thread_local std::vector<TraceRec> g_trace;
+thread_local int g_trace_cur = -1;        // index of the record of the pass being issued, -1 outside a traced pass
+thread_local int g_trace_suppress = 0;    // > 0 while the measured kernel choice times its candidates
+
 dp_status fail(dp_status st, const char *fmt, ...)
 {
     va_list ap;
@@ -52,7 +64,58 @@ void dp_set_error(const char *fmt, ...)
     va_end(ap);
 }
 
+void dp_trace_main_kernel_done(hipStream_t st)
+{
+    if (g_trace_cur < 0 || g_trace_suppress > 0) return;
+    TraceRec &r = g_trace[g_trace_cur];
+    if (r.main_marked) return;
+    r.main_marked = hipEventRecord(r.e1, st) == hipSuccess;
+}
+
 namespace {
+
+// One traced pass: events before and after it on the pass's stream; nested passes (a layer that runs as an im2col
+// followed by a 1x1 layer) belong to the outer record.
+struct TraceScope {
+    int idx = -1;
+    hipStream_t st;
+    TraceScope(int pass, hipStream_t stream) : st(stream)
+    {
+        if (!g_trace_on || g_trace_cur >= 0) return;
+        TraceRec r;
+        if (hipEventCreate(&r.e0) != hipSuccess) return;
+        if (hipEventCreate(&r.e1) != hipSuccess) { (void)hipEventDestroy(r.e0); return; }
+        if (hipEventCreate(&r.e2) != hipSuccess) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); return; }
+        r.pass = pass;
+        g_trace.push_back(r);
+        idx = g_trace_cur = (int)g_trace.size() - 1;
+        (void)hipEventRecord(r.e0, st);
+    }
+    TraceScope(const TraceScope &) = delete;
+    void name(const char *kernel, int splits)
+    {
+        if (idx < 0) return;
+        snprintf(g_trace[idx].name, sizeof(g_trace[idx].name), "%s", kernel);
+        g_trace[idx].splits = splits;
+    }
+    void restart()   // after the measured choice has run its candidates inside this pass: time only what follows
+    {
+        if (idx >= 0) (void)hipEventRecord(g_trace[idx].e0, st);
+    }
+    ~TraceScope()
+    {
+        if (idx < 0) return;
+        (void)hipEventRecord(g_trace[idx].e2, st);
+        g_trace_cur = -1;
+    }
+};
+void plan_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
+{
+    if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes);
+    else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes);
+    else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes);
+    else mfma_kernel_name(pass, pl, name, name_bytes);
+}
 
 dp_status hip_fail(hipError_t e, const char *what)
 {
@@ -255,10 +318,20 @@ void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st)
     pe.cands.clear();
 }
 
-hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st)
+hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &ts)
 {
-    if (!pe.tuned) tune_entry(a, pe, st);
+    if (!pe.tuned) {
+        ++g_trace_suppress;
+        tune_entry(a, pe, st);
+        --g_trace_suppress;
+        ts.restart();
+    }
     a.plan = pe.plan;
+    if (ts.idx >= 0) {
+        char nm[96];
+        plan_kernel_name(a.pass, a.plan, nm, sizeof(nm));
+        ts.name(nm, a.plan.splits);
+    }
     return launch_plan(a, st);
 }
 
@@ -303,15 +376,19 @@ size_t fwd_ws_bytes(const ConvGeom &g)
 dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, const void *w, const float *bias, void *y,
                   void *ws, size_t ws_bytes, hipStream_t st)
 {
+    TraceScope ts(PASS_FWD, st);
     if (dtype == DP_F32) {
+        ts.name("k_f32_fwd", 1);
         hipError_t e = f32_conv_fwd(g, kflags(flags, true), (const float *)x, (const float *)w, bias, (float *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
     }
     if (use_small_c(g, PASS_FWD) && small_c_direct(g)) {
+        ts.name("k_fwd_direct", 1);
         hipError_t e = small_c_fwd_direct(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
     }
     if (use_small_c(g, PASS_FWD) && small_c_stem(g)) {
+        ts.name("k_fwd_stem", 1);
         hipError_t e = small_c_fwd_stem(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
     }
@@ -333,7 +410,7 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     size_t need = pe.part_cap;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.x = (const bf16_t *)x; a.w = (const bf16_t *)w; a.bias = bias; a.out = y; a.partial = (float *)ws;
-    hipError_t e = launch_entry(a, pe, st);
+    hipError_t e = launch_entry(a, pe, st, ts);
     return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
 }
 
@@ -350,7 +427,9 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
                     void *dx, void *ws, size_t ws_bytes, hipStream_t st)
 {
     if (!(flags & DP_RELU_IN)) xin = nullptr;
+    TraceScope ts(PASS_DGRAD, st);
     if (dtype == DP_F32) {
+        ts.name("k_f32_dgrad", 1);
         hipError_t e = f32_conv_dgrad(g, (const float *)dy, (const float *)ym, (const float *)w, (const float *)xin, (float *)dx, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 backward-data launch");
     }
@@ -369,7 +448,7 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
         if (e != hipSuccess) return hip_fail(e, "ReLU-gradient launch");
         a.dy = (const bf16_t *)gbuf; a.ymask = nullptr;
     }
-    hipError_t e = launch_entry(a, pe, st);
+    hipError_t e = launch_entry(a, pe, st, ts);
     return e == hipSuccess ? DP_OK : hip_fail(e, "backward-data launch");
 }
 
@@ -401,7 +480,9 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
     size_t need = wgrad_ws_bytes(g, dtype, db != nullptr);
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-filter needs %zu workspace bytes, got %zu", need, ws_bytes);
     const long long rows = (long long)g.N * g.Ho * g.Wo;
+    TraceScope ts(PASS_WGRAD, st);
     if (dtype == DP_F32) {
+        ts.name("k_f32_wgrad", 1);
         if (dw != nullptr) {
             hipError_t e = f32_conv_wgrad(g, (const float *)x, (const float *)dy, (const float *)ym, dw, st);
             if (e != hipSuccess) return hip_fail(e, "fp32 backward-filter launch");
@@ -418,6 +499,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         bool db_done = false;
         if (dw != nullptr) {
             // the kernel masks dy with the saved output while loading it and sums the bias gradient on the way
+            ts.name("k_wgrad_direct", small_c_wgrad_blocks(g));
             hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)ym, (float *)ws, dw, db, st);
             if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
             db_done = true;
@@ -466,7 +548,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         // known only after the launch, because the first call of a shape may measure several candidates
         const bool want_fused = db != nullptr && !db_done && ym == nullptr;
         if (want_fused) { a.flags |= KF_DB; a.db_out = db; a.db_partial = rws; }
-        hipError_t e = launch_entry(a, pe, st);
+        hipError_t e = launch_entry(a, pe, st, ts);
         if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
         if (want_fused && plan_sums_bias_gradient(a.plan)) db_done = true;
     }
@@ -492,6 +574,45 @@ dp_status dp_set_override(int pass, int tile_variant, int splits)
     g_force_variant[pass].store(tile_variant);
     g_force_splits[pass].store(splits);
     return DP_OK;
+}
+
+dp_status dp_trace_begin(void)
+{
+    if (g_trace_on) return fail(DP_ERR_UNSUPPORTED, "a trace is already being recorded on this thread");
+    g_trace.clear();
+    g_trace_cur = -1;
+    g_trace_on = true;
+    return DP_OK;
+}
+
+dp_status dp_trace_end(dp_trace_row *rows, int32_t max_rows, int32_t *n_rows)
+{
+    if (!g_trace_on) return fail(DP_ERR_UNSUPPORTED, "no trace is being recorded on this thread");
+    g_trace_on = false;
+    g_trace_cur = -1;
+    dp_status result = DP_OK;
+    if (n_rows == nullptr || (rows == nullptr && max_rows > 0) || max_rows < 0) result = fail(DP_ERR_NULL, "rows / n_rows missing");
+    int out = 0;
+    for (TraceRec &r : g_trace) {
+        if (result == DP_OK && out < max_rows) {
+            float main_ms = 0.f, total_ms = 0.f;
+            hipError_t e = hipEventSynchronize(r.e2);
+            if (e == hipSuccess) e = hipEventElapsedTime(&total_ms, r.e0, r.e2);
+            if (e == hipSuccess && r.main_marked) e = hipEventElapsedTime(&main_ms, r.e0, r.e1);
+            if (e != hipSuccess) result = hip_fail(e, "reading the trace events");
+            else {
+                dp_trace_row &o = rows[out++];
+                snprintf(o.kernel, sizeof(o.kernel), "%s", r.name);
+                o.pass = r.pass; o.splits = r.splits;
+                o.total_us = total_ms * 1000.f;
+                o.main_us = r.main_marked ? main_ms * 1000.f : o.total_us;
+            }
+        }
+        (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); (void)hipEventDestroy(r.e2);
+    }
+    g_trace.clear();
+    if (n_rows != nullptr) *n_rows = out;
+    return result;
 }
 
 dp_status dp_set_autotune(int enabled)
@@ -524,7 +645,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
     const GemmPlan pl = plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0).plan;
-    if (name != nullptr && name_bytes > 0) { if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes); else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes); else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes); else mfma_kernel_name(pass, pl, name, name_bytes); }
+    if (name != nullptr && name_bytes > 0) plan_kernel_name(pass, pl, name, name_bytes);
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
 }
@@ -741,10 +862,14 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
             // 0x3c3c is a small positive bf16 and 0x3c3c3c3c a small positive fp32: finite inputs, no mask holes
             if (b.fill && (e = hipMemsetAsync(*b.p, 0x3c, b.bytes, st)) != hipSuccess) { result = hip_fail(e, "hipMemsetAsync"); break; }
         }
-        const void *ym = (flags & DP_RELU) ? y : nullptr;
+        // DP_RELU_IN describes a step in which every ReLU is differentiated by the layer behind it: the incoming gradient is
+        // then already masked and the backward passes take no saved output
+        const void *ym = ((flags & DP_RELU) && !(flags & DP_RELU_IN)) ? y : nullptr;
         float us[3] = {0, 0, 0};
         for (int pass = 0; pass < 3 && result == DP_OK; ++pass) {
-            for (int it = 0; it < warmup + iters && result == DP_OK; ++it) {
+            // it = -1: one call outside the timed window in any case; with the measured kernel choice on it is the
+            // call that times the candidates of a new shape (and drains the stream), which must not count as layer time
+            for (int it = -1; it < warmup + iters && result == DP_OK; ++it) {
                 if (it == warmup && (e = hipEventRecord(ev0, st)) != hipSuccess) { result = hip_fail(e, "hipEventRecord"); break; }
                 if (pass == 0) result = run_fwd(g, dtype, flags, x, w, (const float *)bias, y, ws, wsb, st);
                 else if (pass == 1) result = run_dgrad(g, dtype, flags, dy, ym, w, x, dx, ws, wsb, st);

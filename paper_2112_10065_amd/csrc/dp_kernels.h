@@ -57,6 +57,10 @@ struct ConvArgs {
     float *db_partial = nullptr;  // KF_DB: [splits][rowsA] scratch for split plans
 };
 
+// dp_api.hip: timing hook of dp_trace_begin / dp_trace_end.  The launch function of every kernel family calls this right
+// after it has enqueued the main kernel of a pass (before any split-reduce or column-sum kernel that follows).
+void dp_trace_main_kernel_done(hipStream_t st);
+
 // conv_wstrip.hip
 hipError_t wstrip_init();
 bool wstrip_plan(const ConvGeom &g, int force_splits, GemmPlan *pl);

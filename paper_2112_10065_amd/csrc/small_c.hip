@@ -588,6 +588,7 @@ hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t
     const int spb = (int)((steps + nb - 1) / nb);
     float *dbp = db != nullptr ? partial + (size_t)nb * ktiles * 64 * 32 : nullptr;
     hipLaunchKernelGGL(k_wgrad_direct, dim3((unsigned)nb, (unsigned)ktiles), dim3(256), 0, st, g, x, dy, ymask, partial, dbp, spb);
+    dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_wgrad_direct_sum, dim3((unsigned)(g.K + (db != nullptr ? ktiles : 0))), dim3(1024), 0, st, g.K, g.R * g.S * g.C, nb,

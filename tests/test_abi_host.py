@@ -119,6 +119,15 @@ def test_profile_and_override_argument_errors(dp):
     assert lib.dp_set_override(5, 0, 0) == dp.DP_ERR_UNSUPPORTED
     assert lib.dp_set_override(0, -1, 0) == dp.DP_OK
     assert lib.dp_set_autotune(1) == dp.DP_OK and lib.dp_set_autotune(0) == dp.DP_OK
+    # the trace hook: end without begin, begin twice, missing output arguments; an empty trace has no rows
+    n = C.c_int32(7)
+    trows = (dp.dp_trace_row * 2)()
+    assert lib.dp_trace_end(trows, 2, C.byref(n)) == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_trace_begin() == dp.DP_OK and lib.dp_trace_begin() == dp.DP_ERR_UNSUPPORTED
+    assert lib.dp_trace_end(trows, 2, None) == dp.DP_ERR_NULL
+    assert lib.dp_trace_begin() == dp.DP_OK
+    assert lib.dp_trace_end(trows, 2, C.byref(n)) == dp.DP_OK and n.value == 0
+    assert C.sizeof(dp.dp_trace_row) == 96 + 16
 
 
 def test_no_gpu_fails_loudly(dp):

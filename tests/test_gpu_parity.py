@@ -663,6 +663,78 @@ def test_profile_layer_rows(env):
     assert rows[1]["flops_per_pass"] == 2.0 * 32 * 4096 * 1000 and rows[0]["wgrad_us"] > 0
 
 
+def test_trace_rows_and_profile_table_agree(env):
+    """dp_trace_begin / dp_trace_end: one row per pass in call order, naming the kernel dp_conv2d_kernel_info names; and
+    the planner's table (dp_profile_layer: back-to-back launches between two events) agrees with those per-call event
+    timings within a band of 0.5x .. 1.6x on a layer whose kernels take tens of microseconds (the trace's events sit
+    between dependent launches, so its figures run a few microseconds higher)."""
+    dp, U, orc = env
+    flags = dp.DP_BIAS | dp.DP_RELU | dp.DP_RELU_IN
+    n, hw, c, k = 8, 28, 512, 512
+    case = U.ConvCase("trace", n, hw, hw, c, k, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=True)
+    d = dp.conv_desc(n, hw, hw, c, k, 3, 3, (1, 1), (1, 1), dp.DP_BF16, flags)
+    ws = U.workspace(max(dp.dp_conv2d_workspace_bytes(d, p) for p in range(3)))
+    y = torch.empty((n, hw, hw, k), dtype=torch.bfloat16, device=U.DEV)
+    dx = torch.empty((n, hw, hw, c), dtype=torch.bfloat16, device=U.DEV)
+    dw = torch.empty((k, 3, 3, c), dtype=torch.float32, device=U.DEV)
+    db = torch.empty((k,), dtype=torch.float32, device=U.DEV)
+
+    def three_passes():
+        dp.dp_conv2d_fwd(d, case.xd, case.wd, case.bd, y, ws)
+        dp.dp_conv2d_bwd_data_relu(d, case.dyd, None, case.wd, case.xd, dx, ws)
+        dp.dp_conv2d_bwd_filter(d, case.xd, case.dyd, None, dw, db, ws)
+
+    three_passes()
+    torch.cuda.synchronize()
+    runs = []
+    for _ in range(7):
+        dp.dp_trace_begin()
+        three_passes()
+        rows = dp.dp_trace_end()
+        assert [r["pass"] for r in rows] == [0, 1, 2]
+        for p, r in enumerate(rows):
+            name, splits = dp.dp_conv2d_kernel_info(d, p)
+            assert r["kernel"] == name and r["splits"] == splits
+            assert 0.0 < r["main_us"] <= r["total_us"] * 1.001
+        runs.append(rows)
+    with pytest.raises(dp.DpError):
+        dp.dp_trace_end()          # nothing is being recorded any more
+    # results are not disturbed by the events
+    torch.cuda.synchronize()
+    U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b, relu=True, pad=(1, 1)), "traced forward")
+    traced = [sorted(r[p]["total_us"] for r in runs)[len(runs) // 2] for p in range(3)]
+    prof = dp.dp_profile_layer(conv=d, batches=(n,), warmup=0, iters=20)[0]
+    for p, key in enumerate(("fwd_us", "dgrad_us", "wgrad_us")):
+        ratio = prof[key] / traced[p]
+        assert 0.5 <= ratio <= 1.6, (key, prof[key], traced[p])
+    # a dense call yields one row per half it ran
+    ld = dp.linear_desc(4, 512, 256, dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)
+    x, W, b = U.synth.linear_tensors("trace/fc", 4, 512, 256)
+    xd, Wd = (U.bf16_dev(U.synth.f32_to_bf16_bits(a)) for a in (x, W))
+    dyd = U.bf16_dev(U.synth.f32_to_bf16_bits(U.synth.upstream_grad("trace/fc", (4, 256))))
+    yl = torch.empty((4, 256), dtype=torch.bfloat16, device=U.DEV)
+    dxl = torch.empty((4, 512), dtype=torch.bfloat16, device=U.DEV)
+    dWl = torch.empty((256, 512), dtype=torch.float32, device=U.DEV)
+    wsl = U.workspace(dp.dp_linear_workspace_bytes(ld))
+    dp.dp_trace_begin()
+    dp.dp_linear_fwd_bwd(ld, x=xd, W=Wd, bias=torch.from_numpy(b).to(U.DEV), y=yl, ws=wsl)
+    dp.dp_linear_fwd_bwd(ld, x=xd, W=Wd, dy=dyd, dx=dxl, dW=dWl, ws=wsl)
+    assert [r["pass"] for r in dp.dp_trace_end()] == [0, 1, 2]
+
+
+def test_profile_layer_with_measured_choice_and_no_warmup(env):
+    """With the measured kernel choice on and warmup = 0 the candidates of a new shape are timed in the untimed call that
+    precedes the window: the reported time is a layer time (well under a millisecond here), not the tuning time."""
+    dp, U, orc = env
+    dp.dp_set_autotune(True)
+    try:
+        d = dp.conv_desc(1, 20, 20, 192, 320, 3, 3, (1, 1), (1, 1), dp.DP_BF16, dp.DP_BIAS | dp.DP_RELU)   # a shape no other test uses
+        r = dp.dp_profile_layer(conv=d, batches=(3,), warmup=0, iters=3)[0]
+        assert 0 < r["fwd_us"] < 300 and 0 < r["dgrad_us"] < 300 and 0 < r["wgrad_us"] < 300, r
+    finally:
+        dp.dp_set_autotune(False)
+
+
 # ---- ResNet-50 and Inception-v3-style layer lists (configurations 3 and 4), full size, spot-checked --------
 def _sampled_layer_check(dp, U, orc, l, n, tag):
     st, pd = (l.sh, l.sw), (l.ph, l.pw)
