@@ -46,6 +46,10 @@ def parse():
                     help="auto: per batch, one small HIP graph per sub-step if it replays faster than launching the kernels one by one")
     ap.add_argument("--no-graph", action="store_true", help="same as --launch eager")
     ap.add_argument("--no-table", action="store_true", help="skip the dp_profile_layer table")
+    ap.add_argument("--fg-batch", type=int, default=2, help="--multiplex: per-GPU batch of the foreground VGG-16 step")
+    ap.add_argument("--bg-batch", type=int, default=64, help="--multiplex: batch of the background ResNet-50 step")
+    ap.add_argument("--pace", type=int, default=2, help="--multiplex: most un-finished launches the background queue may hold")
+    ap.add_argument("--graph-piece", type=int, default=8, help="--multiplex: library calls per small foreground graph")
     ap.add_argument("--multiplex", action="store_true",
                     help="single-GPU multiplexing run instead of the sweep: foreground VGG-16 step at batch 2 beside a background ResNet-50 step at batch 64")
     ap.add_argument("--workload", type=str, default="vgg16", choices=["vgg16", "resnet50", "inception", "wrn101_2"],

@@ -195,7 +195,8 @@ dp_status dp_set_override(int pass, int tile_variant, int splits);
  * library's own kernels): enabled != 0 makes the first launch of a pass on a new layer shape time
  * the analytic model's best tile/split candidates on the caller's own buffers and stream (each
  * candidate writes the same result; the stream is drained, so that one call blocks the host) and
- * keeps the fastest for later calls of the calling thread.  Workspace queries made while it is on
+ * keeps the fastest for later calls of every thread (a shape is measured once per process; a thread that asks for
+ * a shape while another is measuring it waits for that choice).  Workspace queries made while it is on
  * return the largest need of any candidate, so query after switching it on.  No measurement takes
  * place while the stream is being captured (the model's choice is used), with a forced override,
  * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */

@@ -1056,13 +1056,8 @@ const DmaVariant kDma[] = {{128, 128, 64, 2, 2, 2}, {128, 128, 32, 2, 2, 2}, {12
                            {128, 32, 64, 4, 1, 6}, {256, 32, 64, 4, 1, 4}, {128, 32, 64, 4, 1, 4}, {256, 64, 32, 4, 1, 6}, {64, 32, 64, 2, 1, 8},
                            {64, 64, 128, 2, 2, 3}, {64, 128, 128, 2, 2, 2}, {128, 128, 128, 2, 2, 2}, {128, 64, 128, 2, 2, 2}, {64, 64, 128, 2, 2, 4},
                            {64, 64, 64, 2, 2, 2, 4}, {64, 64, 64, 2, 2, 2, 2}, {64, 128, 64, 2, 2, 2, 2}, {128, 64, 64, 2, 2, 2, 2},
-                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}, {256, 224, 64, 4, 1, 2},
-                           // deep pipelines for the small grids of batch 1-4: one block per CU cannot hide the L2 latency with
-                           // one step in flight, so these keep 3-7 steps (72-120 KB) on their way
-                           {64, 128, 64, 2, 2, 5}, {128, 64, 64, 2, 2, 5}, {64, 64, 64, 2, 2, 8}, {64, 64, 64, 2, 2, 4},
-                           {128, 128, 64, 2, 2, 4}, {128, 128, 64, 2, 2, 3}, {64, 128, 64, 2, 2, 3}, {128, 64, 64, 2, 2, 3},
-                           {64, 128, 128, 2, 2, 3}, {128, 64, 128, 2, 2, 3}};
-constexpr int kNumDma = 44, kStripVariant = 30, kStripEnd = 34;   // entries 30..33 are k_conv_strip (4 waves; its own LDS layout)
+                           {256, 256, 64, 2, 2, 2}, {256, 128, 64, 2, 2, 3}, {128, 256, 64, 2, 2, 3}, {256, 224, 64, 4, 1, 2}};
+constexpr int kNumDma = 34, kStripVariant = 30, kStripEnd = 34;   // entries 30..33 are k_conv_strip (4 waves; its own LDS layout)
 inline bool is_strip(int v) { return v >= kStripVariant && v < kStripEnd; }
 typedef void (*KernelFn)(const KArgs);
 KernelFn pick_dma_d(int v)
@@ -1101,16 +1096,6 @@ KernelFn pick_dma_d(int v)
     case 31: return k_conv_strip<true, 128, 256>;
     case 32: return k_conv_strip<true, 256, 128>;
     case 33: return k_conv_strip<true, 224, 256>;
-    case 34: return k_dgrad_dma<64, 128, 64, 2, 2, 5>;
-    case 35: return k_dgrad_dma<128, 64, 64, 2, 2, 5>;
-    case 36: return k_dgrad_dma<64, 64, 64, 2, 2, 8>;
-    case 37: return k_dgrad_dma<64, 64, 64, 2, 2, 4>;
-    case 38: return k_dgrad_dma<128, 128, 64, 2, 2, 4>;
-    case 39: return k_dgrad_dma<128, 128, 64, 2, 2, 3>;
-    case 40: return k_dgrad_dma<64, 128, 64, 2, 2, 3>;
-    case 41: return k_dgrad_dma<128, 64, 64, 2, 2, 3>;
-    case 42: return k_dgrad_dma<64, 128, 128, 2, 2, 3>;
-    case 43: return k_dgrad_dma<128, 64, 128, 2, 2, 3>;
     default: return k_dgrad_dma<64, 64, 64, 2, 2, 3>;
     }
 }
@@ -1150,16 +1135,6 @@ KernelFn pick_dma(int v)
     case 31: return k_conv_strip<false, 128, 256>;
     case 32: return k_conv_strip<false, 256, 128>;
     case 33: return k_conv_strip<false, 224, 256>;
-    case 34: return k_fwd_dma<64, 128, 64, 2, 2, 5>;
-    case 35: return k_fwd_dma<128, 64, 64, 2, 2, 5>;
-    case 36: return k_fwd_dma<64, 64, 64, 2, 2, 8>;
-    case 37: return k_fwd_dma<64, 64, 64, 2, 2, 4>;
-    case 38: return k_fwd_dma<128, 128, 64, 2, 2, 4>;
-    case 39: return k_fwd_dma<128, 128, 64, 2, 2, 3>;
-    case 40: return k_fwd_dma<64, 128, 64, 2, 2, 3>;
-    case 41: return k_fwd_dma<128, 64, 64, 2, 2, 3>;
-    case 42: return k_fwd_dma<64, 128, 128, 2, 2, 3>;
-    case 43: return k_fwd_dma<128, 64, 128, 2, 2, 3>;
     default: return k_fwd_dma<64, 64, 64, 2, 2, 3>;
     }
 }

@@ -526,21 +526,39 @@ __global__ __launch_bounds__(256) void k_reduce_pixel_major(const KArgs p)
     }
 }
 
-// Blocks nb1 .. gridDim.x-1 of the two backward-filter reductions sum a second, small array in split order
-// (the fused bias gradient: partial2 [splits][total2] -> out2 [total2]), one column per thread.
-DEVFN void reduce_second(int blk, const float *partial2, float *out2, int total2, int splits)
+// Blocks nb1 .. gridDim.x-1 of the two backward-filter reductions sum a second, small array in a fixed order (the
+// bias gradient: partial2 [rows][total2] -> out2 [total2]; up to 512 rows).  A block takes 32 columns: 8 threads per
+// column each add every 8th row with four independent sums in flight, the 8 part sums meet in LDS in order.
+DEVFN void reduce_second(int blk, const float *partial2, float *out2, int total2, int rows)
 {
-    const int col = blk * 256 + threadIdx.x;
-    if (col >= total2) return;
-    float v = partial2[col];
-    for (int sp = 1; sp < splits; ++sp) v += partial2[(size_t)sp * total2 + col];
-    out2[col] = v;
+    __shared__ float sm2[8][32];
+    const int cl = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int col = blk * 32 + cl;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (col < total2) {
+        int b = part;
+        for (; b + 24 < rows; b += 32) {
+            s0 += partial2[(size_t)b * total2 + col];
+            s1 += partial2[(size_t)(b + 8) * total2 + col];
+            s2 += partial2[(size_t)(b + 16) * total2 + col];
+            s3 += partial2[(size_t)(b + 24) * total2 + col];
+        }
+        for (; b < rows; b += 8) s0 += partial2[(size_t)b * total2 + col];
+    }
+    sm2[part][cl] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (part == 0 && col < total2) {
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += sm2[i][cl];
+        out2[col] = s;
+    }
 }
 
 __global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float *out, size_t total, int splits, int nb1,
-                                                      const float *partial2, float *out2, int total2)
+                                                      const float *partial2, float *out2, int total2, int rows2)
 {
-    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, splits); return; }
+    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, rows2); return; }
     const size_t gstride = (size_t)nb1 * blockDim.x;
     if ((total & 3) == 0) {
         for (size_t e = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4; e < total; e += gstride * 4) {
@@ -568,9 +586,9 @@ __global__ __launch_bounds__(256) void k_reduce_flat(const float *partial, float
 // Many splits over a small output (long reductions into a small filter): 8 threads share one group
 // of four outputs, each sums every 8th partial, the 8 part sums are combined through LDS in order.
 __global__ __launch_bounds__(256) void k_reduce_flat_wide(const float *partial, float *out, size_t total, int splits, int nb1,
-                                                           const float *partial2, float *out2, int total2)
+                                                           const float *partial2, float *out2, int total2, int rows2)
 {
-    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, splits); return; }
+    if ((int)blockIdx.x >= nb1) { reduce_second(blockIdx.x - nb1, partial2, out2, total2, rows2); return; }
     __shared__ f32x4 sm[8][32];
     const int g = threadIdx.x & 31, part = threadIdx.x >> 5;
     const size_t e = ((size_t)blockIdx.x * 32 + g) * 4;
@@ -752,15 +770,18 @@ hipError_t launch_split_reduce(const ConvArgs &a, int rowsA, int rowsB, hipStrea
     if (nb > 4096) nb = 4096;
     if (nb < 1) nb = 1;
     if (a.pass == PASS_WGRAD) {
-        const bool db = with_db && a.db_partial != nullptr && a.db_out != nullptr;
-        const unsigned nb2 = db ? (unsigned)((rowsA + 255) / 256) : 0u;
+        // the second array: bias-gradient sums of the main kernel's splits (with_db), or the row-block sums a pointwise
+        // pass left there before the main kernel (db_rows)
+        const bool db = (with_db || a.db_rows > 0) && a.db_partial != nullptr && a.db_out != nullptr;
+        const unsigned nb2 = db ? (unsigned)((rowsA + 31) / 32) : 0u;
+        const int rows2 = a.db_rows > 0 ? a.db_rows : p.splits;
         if ((total & 3) == 0 && p.splits >= 16 && work <= 65536) {
             const unsigned nbw = (unsigned)((work + 31) / 32);
             hipLaunchKernelGGL(k_reduce_flat_wide, dim3(nbw + nb2), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits,
-                               (int)nbw, a.db_partial, a.db_out, rowsA);
+                               (int)nbw, a.db_partial, a.db_out, rowsA, rows2);
         } else
             hipLaunchKernelGGL(k_reduce_flat, dim3(nb + nb2), dim3(256), 0, st, p.partial, reinterpret_cast<float *>(p.out), total, p.splits, (int)nb,
-                               a.db_partial, a.db_out, rowsA);
+                               a.db_partial, a.db_out, rowsA, rows2);
     } else
         hipLaunchKernelGGL(k_reduce_pixel_major, dim3(nb), dim3(256), 0, st, p);
     return hipGetLastError();

@@ -7,6 +7,8 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <functional>
+#include <memory>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -35,6 +37,8 @@ void *g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each 
 // ---- dp_trace_begin / dp_trace_end: HIP events around the kernels of the calling thread's passes ----
 struct TraceRec {
     hipEvent_t e0 = nullptr, e1 = nullptr, e2 = nullptr;   // before the pass, after its main kernel, after its last kernel
+    hipEvent_t em = nullptr;                               // right before the main kernel (a pointwise kernel may precede it)
+    bool main_begun = false;
     bool main_marked = false;
     char name[96] = "";
     int pass = 0, splits = 1;
@@ -86,6 +90,7 @@ struct TraceScope {
         if (hipEventCreate(&r.e0) != hipSuccess) return;
         if (hipEventCreate(&r.e1) != hipSuccess) { (void)hipEventDestroy(r.e0); return; }
         if (hipEventCreate(&r.e2) != hipSuccess) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); return; }
+        if (hipEventCreate(&r.em) != hipSuccess) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); (void)hipEventDestroy(r.e2); return; }
         r.pass = pass;
         g_trace.push_back(r);
         idx = g_trace_cur = (int)g_trace.size() - 1;
@@ -101,6 +106,10 @@ struct TraceScope {
     void restart()   // after the measured choice has run its candidates inside this pass: time only what follows
     {
         if (idx >= 0) (void)hipEventRecord(g_trace[idx].e0, st);
+    }
+    void main_begins()   // the next launch is the pass's main kernel
+    {
+        if (idx >= 0 && !g_trace[idx].main_begun) g_trace[idx].main_begun = hipEventRecord(g_trace[idx].em, st) == hipSuccess;
     }
     ~TraceScope()
     {
@@ -197,8 +206,9 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, in
 }
 
 // Planning prices a few hundred candidates; a training loop asks for the same few layers again and
-// again, so each thread remembers its plans.  With the measured choice switched on an entry also
-// keeps the model's best candidates until the first launch has timed them.
+// again, so the library remembers its plans (one cache for the process: a plan measured by one thread serves
+// every thread, e.g. a foreground and a background launcher).  With the measured choice switched on an entry
+// also keeps the model's best candidates until the first launch has timed them.
 struct PlanKey {
     int v[17];
     bool operator==(const PlanKey &o) const { return std::memcmp(v, o.v, sizeof(v)) == 0; }
@@ -212,24 +222,35 @@ struct PlanKeyHash {
     }
 };
 struct PlanEntry {
+    std::mutex mu;                 // guards plan / tuned / cands once the entry is in the cache
     GemmPlan plan;                 // the plan in use (the model's until measured)
-    size_t part_cap = 0;           // bytes reserved for split partials: the largest any candidate needs
+    size_t part_cap = 0;           // bytes reserved for split partials: the largest any candidate needs (never changes)
     bool tuned = true;             // false: candidates wait for their timing run
     std::vector<GemmPlan> cands;
 };
+typedef std::shared_ptr<PlanEntry> PlanRef;   // an entry stays alive while a call uses it, even if the cache is emptied
 constexpr int kTuneCandidates = 12;
+std::mutex g_plan_mu;                         // guards the cache itself
+
+GemmPlan current_plan(PlanEntry &pe)
+{
+    std::lock_guard<std::mutex> lock(pe.mu);
+    return pe.plan;
+}
 
 // restr: see dgrad_restr
-PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
+PlanRef plan_entry(const ConvGeom &g, int pass, int restr = 0)
 {
-    thread_local std::unordered_map<PlanKey, PlanEntry, PlanKeyHash> cache;
+    static std::unordered_map<PlanKey, PlanRef, PlanKeyHash> cache;
     const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
     const int at = g_analytic_only ? 0 : g_autotune.load();
     PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (restr << 1)}};
+    std::lock_guard<std::mutex> lock(g_plan_mu);
     auto it = cache.find(key);
     if (it != cache.end()) return it->second;
     if (cache.size() > 4096) cache.clear();
-    PlanEntry e;
+    PlanRef ep = std::make_shared<PlanEntry>();
+    PlanEntry &e = *ep;
     plan_uncached(g, pass, fv, fs, &e.plan, restr);
     e.part_cap = mfma_partial_bytes(g, pass, e.plan);
     if (at != 0 && fv < 0 && e.plan.fast) {
@@ -244,7 +265,8 @@ PlanEntry &plan_entry(const ConvGeom &g, int pass, int restr = 0)
             }
         }
     }
-    return cache.emplace(key, std::move(e)).first->second;
+    cache.emplace(key, ep);
+    return ep;
 }
 
 
@@ -267,7 +289,11 @@ hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 
 // Measured choice: run every candidate on the caller's buffers (each writes the same result), keep
 // the fastest.  Blocks the host until the stream has drained; skipped while the stream is captured.
-void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st)
+// what a pass does before its main kernel once the plan is known (e.g. the pointwise column sums a filter-gradient plan
+// without a fused bias gradient needs); run for every candidate, so the measurement prices whole passes
+typedef std::function<hipError_t(ConvArgs &)> PrepFn;
+
+void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st, const PrepFn &prep)
 {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
@@ -276,14 +302,15 @@ void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st)
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return; }
     // one measurement: a warm-up launch (which also checks the launch), then 4 launches between two events, or 24 if those
     // took under 0.4 ms (the event pair itself costs a few microseconds); < 0 when a launch failed
+    auto run_once = [&]() -> bool { return (!prep || prep(a) == hipSuccess) && launch_plan(a, st) == hipSuccess; };
     auto measure = [&](const GemmPlan &c) -> float {
         a.plan = c;
-        if (launch_plan(a, st) != hipSuccess) { (void)hipGetLastError(); return -1.f; }
+        if (!run_once()) { (void)hipGetLastError(); return -1.f; }
         float per_launch = 0.f;
         bool ok = true;
         for (int reps = 4; ok; reps = 24) {
             ok = hipEventRecord(e0, st) == hipSuccess;
-            for (int r = 0; r < reps && ok; ++r) ok = launch_plan(a, st) == hipSuccess;
+            for (int r = 0; r < reps && ok; ++r) ok = run_once();
             ok = ok && hipEventRecord(e1, st) == hipSuccess && hipEventSynchronize(e1) == hipSuccess;
             float ms = 0.f;
             ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
@@ -318,20 +345,28 @@ void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st)
     pe.cands.clear();
 }
 
-hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &ts)
+hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &ts, const PrepFn &prep = PrepFn())
 {
-    if (!pe.tuned) {
-        ++g_trace_suppress;
-        tune_entry(a, pe, st);
-        --g_trace_suppress;
-        ts.restart();
+    {
+        std::lock_guard<std::mutex> lock(pe.mu);   // one thread measures a shape; the others wait for its choice
+        if (!pe.tuned) {
+            ++g_trace_suppress;
+            tune_entry(a, pe, st, prep);
+            --g_trace_suppress;
+            ts.restart();
+        }
+        a.plan = pe.plan;
     }
-    a.plan = pe.plan;
     if (ts.idx >= 0) {
         char nm[96];
         plan_kernel_name(a.pass, a.plan, nm, sizeof(nm));
         ts.name(nm, a.plan.splits);
     }
+    if (prep) {
+        hipError_t e = prep(a);
+        if (e != hipSuccess) return e;
+    }
+    ts.main_begins();
     return launch_plan(a, st);
 }
 
@@ -369,7 +404,7 @@ size_t fwd_ws_bytes(const ConvGeom &g)
         const int kpad = small_c_kpad(g);
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 2) + fwd_ws_bytes(im2col_geom(g, kpad));
     }
-    return plan_entry(g, PASS_FWD).part_cap;
+    return plan_entry(g, PASS_FWD)->part_cap;
 }
 
 // ---- the three passes on a validated geometry --------------------------------------
@@ -405,8 +440,9 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_FWD; a.flags = kflags(flags, true);
-    PlanEntry &pe = plan_entry(g, PASS_FWD);
-    a.plan = pe.plan;
+    const PlanRef pep = plan_entry(g, PASS_FWD);
+    PlanEntry &pe = *pep;
+    a.plan = current_plan(pe);
     size_t need = pe.part_cap;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "forward needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.x = (const bf16_t *)x; a.w = (const bf16_t *)w; a.bias = bias; a.out = y; a.partial = (float *)ws;
@@ -416,9 +452,9 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
 
 size_t dgrad_ws_bytes(const ConvGeom &g, int restr)
 {
-    const PlanEntry &pe = plan_entry(g, PASS_DGRAD, restr);
-    size_t need = round256(pe.part_cap);
-    if (pe.plan.fast) need += round256(ybytes(g));   // room for the masked gradient
+    const PlanRef pep = plan_entry(g, PASS_DGRAD, restr);
+    size_t need = round256(pep->part_cap);
+    if (current_plan(*pep).fast) need += round256(ybytes(g));   // room for the masked gradient
     return need;
 }
 
@@ -436,8 +472,9 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
     ConvArgs a{};
     a.g = g; a.pass = PASS_DGRAD; a.flags = ((flags & DP_DX_F32) ? KF_OUT_F32 : 0u) | (xin != nullptr ? KF_MASK_IN : 0u);
     a.x = (const bf16_t *)xin;
-    PlanEntry &pe = plan_entry(g, PASS_DGRAD, dgrad_restr(flags));
-    a.plan = pe.plan;
+    const PlanRef pep = plan_entry(g, PASS_DGRAD, dgrad_restr(flags));
+    PlanEntry &pe = *pep;
+    a.plan = current_plan(pe);
     size_t need = dgrad_ws_bytes(g, dgrad_restr(flags));
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return fail(DP_ERR_WORKSPACE, "backward-data needs %zu workspace bytes, got %zu", need, ws_bytes);
     a.dy = (const bf16_t *)dy; a.ymask = (const bf16_t *)ym; a.w = (const bf16_t *)w; a.out = dx; a.partial = (float *)ws;
@@ -465,9 +502,9 @@ size_t wgrad_ws_bytes(const ConvGeom &g, int dtype, bool with_db)
         return xcol_bytes(g, kpad) + round256((size_t)g.K * kpad * 4) + wgrad_ws_bytes(im2col_geom(g, kpad), dtype, with_db);
     }
     if (dtype == DP_BF16) {
-        const PlanEntry &pe = plan_entry(g, PASS_WGRAD);
-        need = round256(pe.part_cap);
-        if (pe.plan.fast) need += round256(ybytes(g));
+        const PlanRef pep = plan_entry(g, PASS_WGRAD);
+        need = round256(pep->part_cap);
+        if (current_plan(*pep).fast) need += round256(ybytes(g));
     }
     if (with_db) need += rbg_workspace_bytes((long long)g.N * g.Ho * g.Wo, g.K);
     return need;
@@ -527,8 +564,9 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
     }
     ConvArgs a{};
     a.g = g; a.pass = PASS_WGRAD; a.flags = 0;
-    PlanEntry &pe = plan_entry(g, PASS_WGRAD);
-    a.plan = pe.plan;
+    const PlanRef pep = plan_entry(g, PASS_WGRAD);
+    PlanEntry &pe = *pep;
+    a.plan = current_plan(pe);
     const size_t part = round256(pe.part_cap);
     const size_t gb = a.plan.fast ? round256(ybytes(g)) : 0;
     void *gbuf = (char *)ws + part;
@@ -543,14 +581,26 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         db_done = true;
     }
     if (dw != nullptr) {
-        // unmasked gradient and a bias gradient wanted: the pipelined kernels sum it on the
-        // matrix cores beside dW (no second pass over dy); whether the plan that finally ran is one of them is
-        // known only after the launch, because the first call of a shape may measure several candidates
-        const bool want_fused = db != nullptr && !db_done && ym == nullptr;
-        if (want_fused) { a.flags |= KF_DB; a.db_out = db; a.db_partial = rws; }
-        hipError_t e = launch_entry(a, pe, st, ts);
+        // Unmasked gradient and a bias gradient wanted.  The pipelined kernels sum it on the matrix cores beside dW (no
+        // second pass over dy).  The other plans get the column sums of row blocks from the pointwise kernel, launched
+        // BEFORE the main kernel, and the few rows that are left to add ride in the main kernel's split-reduce (or
+        // take the small final kernel when the plan has no split).  Which of these applies depends on the plan, which on
+        // a shape's first call is known only after the candidates have been measured: hence a callback.
+        const bool want_db = db != nullptr && !db_done && ym == nullptr;
+        PrepFn prep;
+        if (want_db)
+            prep = [&](ConvArgs &c) -> hipError_t {
+                c.flags &= ~KF_DB; c.db_out = nullptr; c.db_partial = nullptr; c.db_rows = 0;
+                if (plan_sums_bias_gradient(c.plan)) { c.flags |= KF_DB; c.db_out = db; c.db_partial = rws; return hipSuccess; }
+                int rb = 1;
+                hipError_t pe_ = rbg_launch_partial(rows, g.K, true, dy, nullptr, nullptr, db, rws, st, &rb);
+                if (pe_ != hipSuccess || rb == 1) return pe_;
+                if (c.plan.splits > 1) { c.db_out = db; c.db_partial = rws; c.db_rows = rb; return hipSuccess; }
+                return rbg_launch_final(g.K, rb, rws, db, st);
+            };
+        hipError_t e = launch_entry(a, pe, st, ts, prep);
         if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
-        if (want_fused && plan_sums_bias_gradient(a.plan)) db_done = true;
+        if (want_db) db_done = true;
     }
     if (db != nullptr && !db_done) {
         hipError_t e = rbg_launch(rows, g.K, true, dy, ym, nullptr, db, rws, st);
@@ -598,7 +648,7 @@ dp_status dp_trace_end(dp_trace_row *rows, int32_t max_rows, int32_t *n_rows)
             float main_ms = 0.f, total_ms = 0.f;
             hipError_t e = hipEventSynchronize(r.e2);
             if (e == hipSuccess) e = hipEventElapsedTime(&total_ms, r.e0, r.e2);
-            if (e == hipSuccess && r.main_marked) e = hipEventElapsedTime(&main_ms, r.e0, r.e1);
+            if (e == hipSuccess && r.main_marked) e = hipEventElapsedTime(&main_ms, r.main_begun ? r.em : r.e0, r.e1);
             if (e != hipSuccess) result = hip_fail(e, "reading the trace events");
             else {
                 dp_trace_row &o = rows[out++];
@@ -608,7 +658,7 @@ dp_status dp_trace_end(dp_trace_row *rows, int32_t max_rows, int32_t *n_rows)
                 o.main_us = r.main_marked ? main_ms * 1000.f : o.total_us;
             }
         }
-        (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); (void)hipEventDestroy(r.e2);
+        (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); (void)hipEventDestroy(r.e2); (void)hipEventDestroy(r.em);
     }
     g_trace.clear();
     if (n_rows != nullptr) *n_rows = out;
@@ -644,7 +694,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
-    const GemmPlan pl = plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0).plan;
+    const GemmPlan pl = current_plan(*plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0));
     if (name != nullptr && name_bytes > 0) plan_kernel_name(pass, pl, name, name_bytes);
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;

@@ -55,6 +55,8 @@ struct ConvArgs {
     float *partial;       // [splits][rowsB][rowsA] (fwd/dgrad) or [splits][rowsA][rowsB] (wgrad)
     float *db_out = nullptr;      // KF_DB: bias gradient [rowsA]
     float *db_partial = nullptr;  // KF_DB: [splits][rowsA] scratch for split plans
+    int db_rows = 0;              // > 0: db_partial holds this many rows of column sums from an earlier pointwise pass; the
+                                  // split-reduce kernel adds them up into db_out (the main kernel does not touch them)
 };
 
 // dp_api.hip: timing hook of dp_trace_begin / dp_trace_end.  The launch function of every kernel family calls this right
@@ -108,6 +110,12 @@ hipError_t f32_conv_wgrad(const ConvGeom &g, const float *x, const float *dy, co
 size_t rbg_workspace_bytes(long long rows, int k);
 hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask,
                       void *g_out, float *dbias, float *ws, hipStream_t st);
+// the first kernel only: column sums of `*row_blocks` row ranges in ws [row_blocks][k]; with one row block the sums
+// go straight to dbias and nothing is left to add
+hipError_t rbg_launch_partial(long long rows, int k, bool bf16, const void *dy, const void *ymask,
+                              void *g_out, float *dbias, float *ws, hipStream_t st, int *row_blocks);
+// sums ws [row_blocks][k] into dbias in row-block order
+hipError_t rbg_launch_final(int k, int row_blocks, const float *ws, float *dbias, hipStream_t st);
 
 // planner.hip : picks the cheapest fast-path variant and split for a pass (host-side cost model)
 bool auto_plan(const ConvGeom &g, int pass, int force_splits, GemmPlan *plan, int restr = 0);

@@ -165,8 +165,8 @@ size_t rbg_workspace_bytes(long long rows, int k)
     return (size_t)MAX_ROW_BLOCKS * (size_t)k * sizeof(float);
 }
 
-hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask, void *g_out, float *dbias,
-                      float *ws, hipStream_t st)
+hipError_t rbg_launch_partial(long long rows, int k, bool bf16, const void *dy, const void *ymask, void *g_out, float *dbias,
+                              float *ws, hipStream_t st, int *row_blocks)
 {
     float *wsp = dbias != nullptr ? ws : nullptr;   // replaced by dbias itself when a single row block is used
     int rb;
@@ -195,8 +195,21 @@ hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const vo
             hipLaunchKernelGGL(k_rbg_cols<float>, dim3(col_blocks, rb), dim3(64), 0, st, rows, k, (const float *)dy,
                                (const float *)ymask, (float *)g_out, wsp);
     }
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || dbias == nullptr || rb == 1) return e;
-    hipLaunchKernelGGL(k_rbg_final, dim3((k + 31) / 32), dim3(256), 0, st, k, rb, ws, dbias);
+    *row_blocks = rb;
     return hipGetLastError();
+}
+
+hipError_t rbg_launch_final(int k, int row_blocks, const float *ws, float *dbias, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_rbg_final, dim3((k + 31) / 32), dim3(256), 0, st, k, row_blocks, ws, dbias);
+    return hipGetLastError();
+}
+
+hipError_t rbg_launch(long long rows, int k, bool bf16, const void *dy, const void *ymask, void *g_out, float *dbias,
+                      float *ws, hipStream_t st)
+{
+    int rb = 1;
+    hipError_t e = rbg_launch_partial(rows, k, bf16, dy, ymask, g_out, dbias, ws, st, &rb);
+    if (e != hipSuccess || dbias == nullptr || rb == 1) return e;
+    return rbg_launch_final(k, rb, ws, dbias, st);
 }
