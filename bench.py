@@ -31,6 +31,37 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 311634736,
+    "k_conv_strip<false, 224, 256>@32": 111335767,
+    "k_halo_ws<0>@32": 421860215,
+    "k_conv_strip<true, 256, 128>@32": 201416151,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 180383835,
+    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 172961098,
+    "k_conv_strip<true, 224, 256>@32": 168064195,
+    "k_wgrad_halo@32": 509465204,
+    "k_fwd_direct@32": 226660288,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 96724405,
+    "k_conv_strip<false, 256, 128>@32": 221285469,
+    "k_wgrad_direct@32": 226868094,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 38755159,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 18886342,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 12542748,
+    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>@32": 10967799,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 51829432,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 50505018,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 107728180,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 35506282,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 38790550,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 70375875,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 36737528,
+    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 75234303,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 18341999,
+    "k_halo_ws<0>@2": 30397056,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 34356853,
+    "k_fwd_direct@2": 14386047,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 14135801,
+    "k_wgrad_direct@2": 18083190,
+    "k_conv_gemm<1, 128, 32, 32, 4, 1, true, true>@2": 8522518,
 }
 
 
@@ -57,6 +88,9 @@ def parse():
     ap.add_argument("--layers", type=str, default="", help="comma-separated layer names: run only these (profiling aid)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="profiling aid: also run an elementwise fp32 copy kernel that reads and writes this many MiB")
+    ap.add_argument("--autotune", type=str, default="cold", choices=["warm", "cold"],
+                    help="measured kernel choice: time the candidates back to back (warm) or with the caches flushed before every timed launch (cold: "
+                         "the state a layer meets inside a step)")
     ap.add_argument("--no-autotune", action="store_true",
                     help="keep the analytic kernel choice instead of timing the candidates once per layer shape before the warm-up")
     ap.add_argument("--no-glue", action="store_true", help="skip the separate timing of pooling, loss and SGD update")
@@ -348,7 +382,7 @@ def main():
     layers += [Layer(torch, dp, l, nmax, gen, dev, False) for l in linears if keep is None or l.name in keep]
     # Measured kernel choice: the first call per (layer, batch, pass) times the planner's candidates.
     # It is switched on before the workspace query (the query then covers every candidate).
-    dp.dp_set_autotune(not args.no_autotune)
+    dp.dp_set_autotune(0 if args.no_autotune else 2 if args.autotune == "cold" else 1)
     ws_bytes = max(l.ws_bytes(dp, n) for l in layers for n in batches)
     ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device=dev)
     descs = {(l.name, n): l.desc(dp, n) for l in layers for n in batches}
@@ -524,7 +558,7 @@ def main():
                                + "per-GPU batches " + args.batches + " (strong-scaling shards of global batch 32)",
                    "batches": batches, "flops_per_step": flops_step},
         "frac_mfma_peak": value / MFMA_BF16_PEAK_TFLOPS, "launch": launch if len(set(launch.values())) > 1 else next(iter(launch.values())),
-        "kernel_choice": "model" if args.no_autotune else "measured",
+        "kernel_choice": "model" if args.no_autotune else "measured (" + args.autotune + ")",
         "per_batch": per_batch,
         "roofline": rf_max["mfma"] or rf_max["hbm"],
         "roofline_hbm": rf_max["hbm"],

@@ -199,7 +199,11 @@ dp_status dp_set_override(int pass, int tile_variant, int splits);
  * a shape while another is measuring it waits for that choice).  Workspace queries made while it is on
  * return the largest need of any candidate, so query after switching it on.  No measurement takes
  * place while the stream is being captured (the model's choice is used), with a forced override,
- * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide. */
+ * or for fp32.  0 (the default) restores the purely analytic choice.  Process-wide.
+ * enabled == 2 measures COLD: before every timed launch a kernel reads a 384 MiB buffer (allocated by the library on
+ * first use and kept until the process ends), so the candidate finds its operands in HBM rather than in the L2 / memory-side
+ * caches -- the state a layer meets inside a training step, where the traffic of the other layers has gone through the
+ * caches since its operands were last touched.  Any other non-zero value measures warm (back-to-back launches). */
 dp_status dp_set_autotune(int enabled);
 
 /* Per-kernel timing of the calling thread's compute calls, for benchmarks (the measured side of a roofline).

@@ -159,7 +159,8 @@ def dp_set_override(pass_, tile_variant=-1, splits=0):
 
 
 def dp_set_autotune(enabled):
-    _check(lib.dp_set_autotune(1 if enabled else 0))
+    """0 / False: analytic choice; 1 / True: measured warm; 2: measured with the caches flushed before each timed launch."""
+    _check(lib.dp_set_autotune(int(enabled)))
 
 
 def dp_maxpool2x2_fwd(n, h, w, c, io_dtype, x, y, stream=None):

@@ -1,6 +1,6 @@
 """Burst-parallel plan of the VGG-16 chain from a measured time-versus-batch table.
 
-    python bench.py --table table.json                       # measures comp(i, g): layer time at per-GPU batch B/g
+    python bench.py --table table.json                       # dp_profile_layer's comp(i, g): layer time at per-GPU batch B/g
     python -m paper_2112_10065_amd.burst_plan table.json --amp-limit 2
 
 Feeds the table to the library's dp_plan_chain (paper section 4.2, algorithm "Search Linear") together
@@ -40,6 +40,7 @@ def main():
     args = ap.parse_args()
     with open(args.table) as f:
         table = json.load(f)
+    table = table.get("layers", table)   # bench.py --table: {"source": "dp_profile_layer", "layers": {...}, "kernels": {...}}
     names, gpus, comp, act, par = chain_inputs(table, args.global_batch)
     comm, sync = dp.dp_plan_cost_tables(gpus, act, par, args.bandwidth, args.delay)
     plan = dp.dp_plan_chain(gpus, comp, comm, sync, args.amp_limit)

@@ -3,9 +3,11 @@
 #include "../../include/dp.h"
 #include "dp_kernels.h"
 
+#include <algorithm>
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <memory>
@@ -14,6 +16,18 @@
 #include <vector>
 
 static __device__ __align__(256) unsigned char scratch[DP_NOALLOC_SCRATCH_BYTES];
+
+// Reads a buffer larger than the caches (8 x 4 MB of L2 and the 256 MB memory-side cache), so that the launch timed after it
+// finds its operands in HBM, as it does inside a training step where other layers' traffic has gone through the caches.
+__global__ __launch_bounds__(256) void k_cache_flush(const uint4 *p, size_t n16)
+{
+    uint4 acc = {0, 0, 0, 0};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) {
+        const uint4 v = p[i];
+        acc.x |= v.x; acc.y |= v.y; acc.z |= v.z; acc.w |= v.w;
+    }
+    asm volatile("" ::"v"(acc.x), "v"(acc.y), "v"(acc.z), "v"(acc.w));   // keeps the loads; nothing is stored
+}
 
 namespace {
 
@@ -229,7 +243,7 @@ struct PlanEntry {
     std::vector<GemmPlan> cands;
 };
 typedef std::shared_ptr<PlanEntry> PlanRef;   // an entry stays alive while a call uses it, even if the cache is emptied
-constexpr int kTuneCandidates = 12;
+constexpr int kTuneCandidates = 16;
 std::mutex g_plan_mu;                         // guards the cache itself
 
 GemmPlan current_plan(PlanEntry &pe)
@@ -244,7 +258,7 @@ PlanRef plan_entry(const ConvGeom &g, int pass, int restr = 0)
     static std::unordered_map<PlanKey, PlanRef, PlanKeyHash> cache;
     const int fv = g_force_variant[pass].load(), fs = g_force_splits[pass].load();
     const int at = g_analytic_only ? 0 : g_autotune.load();
-    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (restr << 1)}};
+    PlanKey key = {{g.N, g.H, g.W, g.C, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, g.Ho, g.Wo, pass, fv, fs, at | (restr << 2)}};
     std::lock_guard<std::mutex> lock(g_plan_mu);
     auto it = cache.find(key);
     if (it != cache.end()) return it->second;
@@ -255,7 +269,8 @@ PlanRef plan_entry(const ConvGeom &g, int pass, int restr = 0)
     e.part_cap = mfma_partial_bytes(g, pass, e.plan);
     if (at != 0 && fv < 0 && e.plan.fast) {
         GemmPlan list[kTuneCandidates];
-        const int n = auto_plan_list(g, pass, fs, list, kTuneCandidates, restr);
+        // a cold measurement judges for itself what the model's warm-cache prices cannot: more candidates, a wider price band
+        const int n = auto_plan_list(g, pass, fs, list, at == 2 ? kTuneCandidates : 12, restr | (at == 2 ? 4 : 0));
         if (n > 1) {
             e.cands.assign(list, list + n);
             e.tuned = false;
@@ -293,7 +308,23 @@ hipError_t launch_plan(const ConvArgs &a, hipStream_t st)
 // without a fused bias gradient needs); run for every candidate, so the measurement prices whole passes
 typedef std::function<hipError_t(ConvArgs &)> PrepFn;
 
-void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st, const PrepFn &prep)
+// the buffer k_cache_flush reads (cold measurement only): allocated on first use, kept until the process ends
+constexpr size_t kFlushBytes = (size_t)384 << 20;
+std::mutex g_flush_mu;
+void *g_flush_buf = nullptr;
+void *flush_buffer()
+{
+    std::lock_guard<std::mutex> lock(g_flush_mu);
+    if (g_flush_buf == nullptr) {
+        void *p = nullptr;
+        if (hipMalloc(&p, kFlushBytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        if (hipMemset(p, 0, kFlushBytes) != hipSuccess) { (void)hipGetLastError(); (void)hipFree(p); return nullptr; }
+        g_flush_buf = p;
+    }
+    return g_flush_buf;
+}
+
+void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st, const PrepFn &prep, int mode)
 {
     hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { (void)hipGetLastError(); return; }
@@ -320,17 +351,36 @@ void tune_entry(ConvArgs a, PlanEntry &pe, hipStream_t st, const PrepFn &prep)
         if (!ok) { (void)hipGetLastError(); return -1.f; }
         return per_launch;
     };
+    // cold measurement: the caches are flushed before every timed launch, one event pair per launch, median of five
+    void *flush = mode == 2 ? flush_buffer() : nullptr;
+    auto measure_cold = [&](const GemmPlan &c) -> float {
+        a.plan = c;
+        if (!run_once()) { (void)hipGetLastError(); return -1.f; }
+        float times[5];
+        for (int r = 0; r < 5; ++r) {
+            hipLaunchKernelGGL(k_cache_flush, dim3(2048), dim3(256), 0, st, (const uint4 *)flush, kFlushBytes / 16);
+            bool ok = hipGetLastError() == hipSuccess && hipEventRecord(e0, st) == hipSuccess && run_once() && hipEventRecord(e1, st) == hipSuccess &&
+                      hipEventSynchronize(e1) == hipSuccess;
+            float ms = 0.f;
+            ok = ok && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (!ok) { (void)hipGetLastError(); return -1.f; }
+            times[r] = ms;
+        }
+        std::sort(times, times + 5);
+        return times[2];
+    };
+    auto measure_any = [&](const GemmPlan &c) -> float { return flush != nullptr ? measure_cold(c) : measure(c); };
     std::vector<float> t(pe.cands.size(), -1.f);
     float best = 1e30f;
     for (size_t i = 0; i < pe.cands.size(); ++i) {
-        t[i] = measure(pe.cands[i]);
+        t[i] = measure_any(pe.cands[i]);
         if (t[i] >= 0.f && t[i] < best) best = t[i];
     }
     // a single measurement of a short kernel is off by several percent now and then: everything within 8 % of the
     // fastest is measured once more and keeps the smaller of its two times
     for (size_t i = 0; i < pe.cands.size(); ++i)
         if (t[i] >= 0.f && t[i] <= 1.08f * best) {
-            const float again = measure(pe.cands[i]);
+            const float again = measure_any(pe.cands[i]);
             if (again >= 0.f && again < t[i]) t[i] = again;
         }
     best = 1e30f;
@@ -351,7 +401,7 @@ hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &
         std::lock_guard<std::mutex> lock(pe.mu);   // one thread measures a shape; the others wait for its choice
         if (!pe.tuned) {
             ++g_trace_suppress;
-            tune_entry(a, pe, st, prep);
+            tune_entry(a, pe, st, prep, g_autotune.load());
             --g_trace_suppress;
             ts.restart();
         }
@@ -667,7 +717,7 @@ dp_status dp_trace_end(dp_trace_row *rows, int32_t max_rows, int32_t *n_rows)
 
 dp_status dp_set_autotune(int enabled)
 {
-    g_autotune.store(enabled != 0 ? 1 : 0);
+    g_autotune.store(enabled == 2 ? 2 : enabled != 0 ? 1 : 0);
     return DP_OK;
 }
 

@@ -155,7 +155,8 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
             if (cand.splits == last_splits) continue;   // the request was clamped to the same plan
             // pixel-strip kernels on a grid of few blocks: each block streams its weights alone, which times well on a warm
             // cache (the measured choice) and badly inside a step
-            if (cands[ci].code >= 230 && cands[ci].code <= 233 && (long long)cand.tilesA * cand.tilesB * cand.splits < 160) continue;
+            // (restr bit 2: the caller measures with cold caches and can judge these grids itself)
+            if (!(restr & 4) && cands[ci].code >= 230 && cands[ci].code <= 233 && (long long)cand.tilesA * cand.tilesB * cand.splits < 160) continue;
             last_splits = cand.splits;
             if (force_splits <= 0 && cand.splits > 1 && cand.steps_per_split < 4) break;
             if (n < 512) { all[n].t = price(g, pass, cands[ci], cand); all[n].pl = cand; all[n].code = cands[ci].code; ++n; }
@@ -174,7 +175,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
         if (best < 0) break;
         if (all[best].t > 0.0) {
             if (t_first < 0.0) t_first = all[best].t;
-            else if (all[best].t > 1.6 * t_first) break;
+            else if (all[best].t > ((restr & 4) ? 2.0 : 1.6) * t_first) break;
         }
         int u = 0;
         while (u < nused && used_code[u] != all[best].code) ++u;

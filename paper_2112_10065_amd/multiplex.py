@@ -61,7 +61,7 @@ def run(args, dp, torch, dev, Layer):
     from . import workloads as W
     gen = torch.Generator(device=dev)
     gen.manual_seed(20211210)
-    dp.dp_set_autotune(not args.no_autotune)
+    dp.dp_set_autotune(0 if args.no_autotune else 2 if args.autotune == "cold" else 1)
     fg_stream, bg_stream = torch.cuda.Stream(), torch.cuda.Stream()   # both at the default priority
     fg = _Job(torch, dp, Layer, W.vgg16_convs(), W.vgg16_linears(), args.fg_batch, gen, dev, fg_stream)
     bg = _Job(torch, dp, Layer, W.resnet50_convs(), [], args.bg_batch, gen, dev, bg_stream)
