@@ -551,14 +551,15 @@ def test_bitwise_deterministic(env):
     assert torch.equal(dw1, dw2) and torch.equal(db1, db2)
 
 
-def test_measured_kernel_choice(env):
-    """With the measured choice on, the first call of each pass times the candidates on the caller's
-    buffers: results must match the oracle on that call and on the next (cached plan), the workspace
-    the query asks for must suffice, and the choice must stay the same afterwards."""
+@pytest.mark.parametrize("mode", [1, 2], ids=["warm", "cold"])
+def test_measured_kernel_choice(env, mode):
+    """With the measured choice on (back-to-back launches, or the caches flushed before every timed launch), the first call
+    of each pass times the candidates on the caller's buffers: results must match the oracle on that call and on the next
+    (cached plan), the workspace the query asks for must suffice, and the choice must stay the same afterwards."""
     dp, U, orc = env
-    dp.dp_set_autotune(True)
+    dp.dp_set_autotune(mode)
     try:
-        for tag, n, h, w, c, k, pd in (("tune_a", 2, 28, 28, 64, 128, (1, 1)), ("tune_b", 1, 14, 14, 128, 192, (1, 1))):
+        for tag, n, h, w, c, k, pd in ((f"tune_a{mode}", 2, 28 + mode, 28, 64, 128, (1, 1)), (f"tune_b{mode}", 1, 14, 14 + mode, 128, 192, (1, 1))):
             case = U.ConvCase(tag, n, h, w, c, k, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
             for rep in range(2):
                 y = case.run_fwd()
