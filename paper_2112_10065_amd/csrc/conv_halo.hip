@@ -332,7 +332,11 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
 
     // transpose-read lane roles: reduction row tl (+4 for the second read), operand columns cl .. cl+3
     const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
-    const int tr = wave / S, ts = wave - tr * S;        // this wave's tap
+    // A block launched with one wave more than taps sums the bias gradient in that wave: it multiplies the dy^T fragments with
+    // an all-ones operand (column 0 of the product = sum over the tile's pixels) and reads no x.  The waves sit 3-3-2-2 on the
+    // four SIMDs instead of 3-2-2-2, and this wave issues half the matrix instructions of a tap wave: the block is no slower.
+    const bool dbw = wave == R * S;
+    const int tr = dbw ? 0 : wave / S, ts = dbw ? 0 : wave - tr * S;        // this wave's tap
     const int tapoff = tr * PW + ts;
     unsigned a_lane[2];   // dy: row tl of slice 0, column half i; later slices add 16 rows = 2048 bytes
 #pragma unroll
@@ -360,6 +364,7 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
                 alo[buf][i] = lds_read_tr<0>(base + a_lane[i] + sl * 2048);
                 ahi[buf][i] = lds_read_tr<4 * 128>(base + a_lane[i] + sl * 2048);
             }
+            if (dbw) return;   // wave-uniform
 #pragma unroll
             for (int jf = 0; jf < 2; ++jf) {
                 const int col = jf * 32 + cl;
@@ -369,8 +374,22 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
             }
         };
         auto multiply = [&](int buf, bool newer_in_flight) {
-            if (newer_in_flight) asm volatile("s_waitcnt lgkmcnt(8)");
-            else asm volatile("s_waitcnt lgkmcnt(0)");
+            // reads of the next slice issued after this slice's: 8 for a tap wave, 4 for the bias-gradient wave
+            if (!newer_in_flight) asm volatile("s_waitcnt lgkmcnt(0)");
+            else if (dbw) asm volatile("s_waitcnt lgkmcnt(4)");
+            else asm volatile("s_waitcnt lgkmcnt(8)");
+            if (dbw) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    asm volatile("" : "+v"(alo[buf][i])); asm volatile("" : "+v"(ahi[buf][i]));
+                }
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const u32x4 av = {alo[buf][i].x, alo[buf][i].y, ahi[buf][i].x, ahi[buf][i].y};
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), ones_bf16(), acc[i][0], 0, 0, 0);
+                }
+                return;
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 asm volatile("" : "+v"(alo[buf][i])); asm volatile("" : "+v"(ahi[buf][i]));
@@ -392,6 +411,12 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
             if (sl + 2 < HALO_TB / 16) read_slice(sl + 2, 0);
             multiply(1, sl + 2 < HALO_TB / 16);
         }
+    }
+    if (dbw) {   // column 0 of the ones-product: this block's bias-gradient sums, one row of [blocks][c_out]
+        if (p.dbp != nullptr)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) store_db_fragment(acc[i][0], p.dbp + (size_t)blockIdx.x * p.rowsA, a0 + i * 32, p.rowsA, lane);
+        return;
     }
     // partial[block][c_out][tap][c_in]; accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32
     float *out = p.partial + (size_t)blockIdx.x * p.rowsA * p.rowsB;
@@ -716,6 +741,7 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         if (blocks > tiles) blocks = (int)tiles;
         if (blocks < 2) return false;   // the split-reduce kernel writes the result
         pl->variant = 10;
+        pl->db_wave = g.R * g.S <= 15;   // 16 waves per block at most
         pl->fast = true; pl->dma = true; pl->halo = true;
         pl->TA = 64; pl->TB = 64 * g.R * g.S; pl->BK = 16; pl->vecA = pl->vecB = true;
         pl->tilesA = ktiles; pl->tilesB = 1;
@@ -781,15 +807,18 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         p.tilesA = a.plan.tilesA; p.tilesB = 1; p.steps_total = a.plan.steps_total; p.steps_per_split = a.plan.steps_per_split;
         p.splits = a.plan.splits; p.flags = a.flags;
         p.x = a.x; p.w = nullptr; p.dy = a.dy; p.ymask = nullptr; p.bias = nullptr; p.out = a.out; p.partial = a.partial;
-        p.dbp = nullptr; p.flags &= ~KF_DB;   // this kernel does not sum the bias gradient (its tap waves are evenly loaded as they are)
+        // the bias gradient, when asked for, is summed by one extra wave per block; its [blocks][c_out] rows are added up by the split-reduce
+        const bool db = (a.flags & KF_DB) && a.plan.db_wave && a.db_partial != nullptr && a.db_out != nullptr;
+        p.dbp = db ? a.db_partial : nullptr;
+        if (!db) p.flags &= ~KF_DB;
         const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
         const int tiles_x = (g.Wo + tw - 1) / tw, tiles_y = (g.Ho + th - 1) / th;
-        hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * g.R * g.S), 2 * WH_BUF, st, p, tws,
+        hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * (g.R * g.S + (db ? 1 : 0))), 2 * WH_BUF, st, p, tws,
                            tiles_x, tiles_y, g.N * tiles_x * tiles_y);
         dp_trace_main_kernel_done(st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        return launch_split_reduce(a, p.rowsA, p.rowsB, st);
+        return launch_split_reduce(a, p.rowsA, p.rowsB, st, db);
     }
     const bool fwd = a.pass == PASS_FWD;
     p.rowsA = fwd ? a.g.K : a.g.C;

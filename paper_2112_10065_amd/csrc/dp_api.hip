@@ -287,10 +287,14 @@ PlanRef plan_entry(const ConvGeom &g, int pass, int restr = 0)
 
 }  // namespace
 
-// the pipelined backward-filter kernels (conv_dma.hip); their scratch [splits][c_out] fits the bias-gradient
-// workspace for up to 512 splits.  (Tried and dropped for the input-patch kernel: the extra matrix instructions
-// unbalance its one-wave-per-tap blocks and cost more than the separate column-sum pass.)
-bool plan_sums_bias_gradient(const GemmPlan &plan) { return plan.dma && !plan.halo && !plan.wstrip && plan.splits <= 512; }
+// the pipelined backward-filter kernels (conv_dma.hip) and the input-patch one (conv_halo.hip); their scratch
+// [splits][c_out] fits the bias-gradient workspace for up to 512 splits.  (In the input-patch kernel letting tap waves do
+// the extra matrix instructions unbalanced its one-wave-per-tap blocks; a wave of its own does not.)
+bool plan_sums_bias_gradient(const GemmPlan &plan)
+{
+    if (plan.halo) return plan.db_wave && plan.splits <= 512;   // input-patch kernel: one extra wave per block
+    return plan.dma && !plan.wstrip && plan.splits <= 512;
+}
 
 namespace {
 

@@ -39,6 +39,7 @@ struct GemmPlan {
     int blocks = 0;       // persistent kernels: blocks per row tile (0: one per CU)
     bool phase = false;   // strided backward-data walks the input pixels stride phase by stride phase (conv_dma.hip)
     bool wstrip = false;  // filter gradient with the x strip shared by the taps of a filter row (conv_wstrip.hip); implies dma
+    bool db_wave = false; // input-patch filter gradient: one more wave per block can sum the bias gradient (at most 15 taps)
 };
 
 struct ConvArgs {
