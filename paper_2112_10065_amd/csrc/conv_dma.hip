@@ -117,7 +117,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
     float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // [TA]
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, grp = (tid >> 6) / NW, wave = (tid >> 6) % NW;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), grp = wv / NW, wave = wv % NW;   // wave-uniform: scalar registers
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
     const int bbeg = blockIdx.y * p.steps_per_split, bend = min(bbeg + p.steps_per_split, p.steps_total);
@@ -163,13 +163,12 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
     int tap = kk / g.C, c0 = kk - tap * g.C;
     int tr = tap / g.S, ts = tap - tr * g.S;
     int issued = 0;
-    auto issue = [&](int stage) {   // loads of the next not-yet-issued step into `stage`
+    auto issue = [&](unsigned sb) {   // loads of the next not-yet-issued step into the stage at byte offset sb
         const bool on = KG == 1 || issued < live;
         ++issued;
         const unsigned ua = (unsigned)(tap * g.C + c0) * 2u;
         const unsigned ub = (unsigned)((tr * g.W + ts) * g.C + c0) * 2u;
         const unsigned bit = on ? 1u << (tap & 31) : 0u;
-        const unsigned sb = stage * STAGE;
 #pragma unroll
         for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
 #pragma unroll
@@ -205,7 +204,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
     // step i+1 are fetched while the matrix cores still work on step i.
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        if (s < nsteps) issue(s);
+        if (s < nsteps) issue(s * STAGE);
     u32x4 fr_a[2][FA], fr_b[2][FB];
     auto wait_landed = [&](int step) {   // loads of `step` have landed; younger steps may be in flight
         const int younger = min(step + NS - 1, nsteps - 1) - step;
@@ -219,8 +218,9 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
         __builtin_amdgcn_s_barrier();
         read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0], fb[0]);
     }
+    unsigned sb = 0;   // byte offset of step i's stage: a running scalar, one addition per fragment address
     for (int i = 0; i < nsteps; ++i) {
-        const unsigned sb = (i % NS) * STAGE;
+        const unsigned sn = sb + STAGE == NS * STAGE ? 0u : sb + STAGE;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (ks < KS - 1) {
@@ -235,8 +235,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
                     else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
                     else wait_vmcnt<0>();
                     __builtin_amdgcn_s_barrier();
-                    if (i + NS < nsteps) issue(i % NS);
-                    const unsigned sn = ((i + 1) % NS) * STAGE;
+                    if (i + NS < nsteps) issue(sb);
                     read_frags<FA, FB, 32 * ROWB>(fr_a[0], fr_b[0], fa[0] + sn, fb[0] + sn);
                 }
             }
@@ -247,6 +246,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
                     acc[ii][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fr_a[ks & 1][ii]),
                                                                          __builtin_bit_cast(bf16x8, fr_b[ks & 1][jj]), acc[ii][jj], 0, 0, 0);
         }
+        sb = sn;
     }
     __syncthreads();   // every wave is done reading the stages before they are reused for staging
     if constexpr (KG > 1) {
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     float *bias_lds = reinterpret_cast<float *>(rowtab + TB);           // [TA]
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, b0 = (tile / p.tilesA) * TB;
     const int CR = DG ? g.K : g.C;   // reduction channels = channels of the pixel operand
@@ -631,7 +631,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     const unsigned tab_base = smem_base + NS * STAGE;            // [2][TABN] x {base, mask}
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: scalar registers
     // grid = (splits, tiles): consecutive workgroup ids go round-robin to the 8 XCDs, so with the
     // split as the fast index (and a split count that is a multiple of 8) every block that reads a
     // given pixel range of x and dy runs on the same XCD and shares that XCD's L2
@@ -675,9 +675,8 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
         const unsigned addr = tab_base + ((chunk & 1) * TABN + tid) * 8;
         asm volatile("ds_write_b64 %0, %1" ::"v"(addr), "v"(e) : "memory");
     };
-    auto issue = [&](int stage, int ls) {   // ls: step index relative to kbeg
+    auto issue = [&](unsigned sb, int ls) {   // sb: byte offset of the stage to fill; ls: step index relative to kbeg
         const unsigned ua = (unsigned)(kbeg + ls) * BK * g.K * 2u;
-        const unsigned sb = stage * STAGE;
         const unsigned tb = (unsigned)(ls % (2 * SPC)) * BK * 8;
         u32x2 e[IB];
 #pragma unroll
@@ -738,8 +737,9 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     __syncthreads();
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
-        if (s < nsteps) issue(s, s);
-    for (int i = 0; i < nsteps; ++i) {
+        if (s < nsteps) issue(s * STAGE, s);
+    unsigned sb = 0, sfill = (NS - 1) * STAGE;   // stage of step i and the stage step i-1 used (filled next): running scalars
+    for (int i = 0; i < nsteps; sfill = sb, sb = sb + STAGE == NS * STAGE ? 0u : sb + STAGE, ++i) {
         const int younger = min(nsteps - 1 - i, NS - 2);
         if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
         else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
@@ -750,8 +750,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
         // used them was issued NS-1 steps ago, before a barrier): its half of the table takes chunk c+1,
         // whose first reader is the issue NS-1 steps before that chunk starts, after at least one barrier
         if (i % SPC == 0 && (i / SPC + 1) * SPC < nsteps + NS) fill_table(i / SPC + 1);
-        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS, i + NS - 1);
-        const unsigned sb = (i % NS) * STAGE;
+        if (i + NS - 1 < nsteps) issue(sfill, i + NS - 1);
         // fragments are double-buffered in registers: the transpose reads of slice ks+1 are issued
         // before the matrix instructions of slice ks
         u32x2 alo[2][FA], ahi[2][FA], blo[2][FB], bhi[2][FB];
@@ -832,7 +831,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     float *bias_lds = reinterpret_cast<float *>(rowtab + 2 * TB);         // unused (no bias in this pass)
 
     const ConvGeom &g = p.g;
-    const int tid = threadIdx.x, lane = tid & 63, grp = (tid >> 6) / NW, wave = (tid >> 6) % NW;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), grp = wv / NW, wave = wv % NW;   // wave-uniform: scalar registers
     const int tile = logical_block(blockIdx.x, gridDim.x);
     const int a0 = (tile % p.tilesA) * TA, tb = tile / p.tilesA, b0 = tb * TB;
     // Stride phases (p.ph_on): a tile holds input pixels of one phase (h % sh, w % sw) = (pa, pb) only.  Of the R*S taps
@@ -921,14 +920,17 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     int c0 = kk - li0 * g.K;
     int tr = tap_r0 + (tap_ns > 0 ? li0 / tap_ns : 0) * step_r, ts = tap_s0 + (tap_ns > 0 ? li0 % tap_ns : 0) * step_s;
     int tap = tr * g.S + ts;
+    // output-pixel offset of the tap, in dy rows: recomputed only when the tap changes (the divisions stay out of the
+    // steady-state step; stride 1 needs none)
+    auto tap_rows = [&]() { return (g.sh == 1 ? tr : tr / g.sh) * g.Wo + (g.sw == 1 ? ts : ts / g.sw); };
+    int trow = tap_rows();
     int issued = 0;
-    auto issue = [&](int stage) {
+    auto issue = [&](unsigned sb) {   // sb: byte offset of the stage to fill
         const bool on = KG == 1 || issued < live;
         ++issued;
         const unsigned ua = ((unsigned)c0 * RSC + (unsigned)tap * g.C) * 2u;
-        const unsigned ub = (unsigned)(c0 - ((tr / g.sh) * g.Wo + ts / g.sw) * g.K) * 2u;
+        const unsigned ub = (unsigned)(c0 - trow * g.K) * 2u;
         const unsigned bit = on ? 1u << (tap & 31) : 0u;
-        const unsigned sb = stage * STAGE;
 #pragma unroll
         for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
 #pragma unroll
@@ -939,6 +941,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
             ts += step_s;
             if (ts >= g.S) { ts = tap_s0; tr += step_r; }
             tap = tr * g.S + ts;
+            trow = tap_rows();
         }
     };
 
@@ -970,15 +973,15 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
     constexpr int LPS = IA + IB;
 #pragma unroll
     for (int s = 0; s < NS - 1; ++s)
-        if (s < nsteps) issue(s);
-    for (int i = 0; i < nsteps; ++i) {
+        if (s < nsteps) issue(s * STAGE);
+    unsigned sb = 0, sfill = (NS - 1) * STAGE;   // stage of step i and the stage step i-1 used (filled next): running scalars
+    for (int i = 0; i < nsteps; sfill = sb, sb = sb + STAGE == NS * STAGE ? 0u : sb + STAGE, ++i) {
         const int younger = min(nsteps - 1 - i, NS - 2);
         if (NS >= 3 && younger == NS - 2) wait_vmcnt<(NS - 2) * LPS>();
         else if (NS >= 4 && younger == NS - 3) wait_vmcnt<(NS >= 4 ? NS - 3 : 0) * LPS>();
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
-        if (i + NS - 1 < nsteps) issue((i + NS - 1) % NS);
-        const unsigned sb = (i % NS) * STAGE;
+        if (i + NS - 1 < nsteps) issue(sfill);
         // fragments are double-buffered in registers: the reads of slice ks+1 are issued before the
         // matrix instructions of slice ks
         u32x2 alo[2][FA], ahi[2][FA];
