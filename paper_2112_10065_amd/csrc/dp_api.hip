@@ -472,7 +472,7 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
     }
     if (use_small_c(g, PASS_FWD) && small_c_direct(g)) {
-        ts.name("k_fwd_direct", 1);
+        ts.name(small_c_fwd_kernel(g), 1);
         hipError_t e = small_c_fwd_direct(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
     }
@@ -590,7 +590,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         bool db_done = false;
         if (dw != nullptr) {
             // the kernel masks dy with the saved output while loading it and sums the bias gradient on the way
-            ts.name("k_wgrad_direct", small_c_wgrad_blocks(g));
+            ts.name(small_c_wgrad_kernel(g, ym != nullptr), small_c_wgrad_blocks(g, ym != nullptr));
             hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)ym, (float *)ws, dw, db, st);
             if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
             db_done = true;
@@ -743,8 +743,9 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass) && small_c_direct(g)) {
-        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", pass == PASS_FWD ? "k_fwd_direct" : "k_wgrad_direct");
-        if (splits != nullptr) *splits = pass == PASS_FWD ? 1 : small_c_wgrad_blocks(g);
+        // the filter gradient is named for a call without a saved output (the masked form runs k_wgrad_direct on every shape)
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", pass == PASS_FWD ? small_c_fwd_kernel(g) : small_c_wgrad_kernel(g, false));
+        if (splits != nullptr) *splits = pass == PASS_FWD ? 1 : small_c_wgrad_blocks(g, false);
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));

@@ -136,7 +136,9 @@ hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x
 // strided stems (7x7 stride 2 on RGB): forward straight from the input patch, no im2col matrix
 bool small_c_stem(const ConvGeom &g);
 hipError_t small_c_fwd_stem(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
-int small_c_wgrad_blocks(const ConvGeom &g);   // pixel-range blocks, each writes one fp32 partial
+int small_c_wgrad_blocks(const ConvGeom &g, bool masked);   // pixel-range blocks, each writes one fp32 partial (masked: a saved output is applied to dy)
+const char *small_c_wgrad_kernel(const ConvGeom &g, bool masked);   // name of the kernel that runs
+const char *small_c_fwd_kernel(const ConvGeom &g);
 size_t small_c_wgrad_partial_bytes(const ConvGeom &g);
 // ymask (saved output, may be NULL) masks dy on the fly; db (may be NULL) receives the bias gradient of the masked dy
 hipError_t small_c_wgrad_direct(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, const bf16_t *ymask, float *partial, float *dw,

@@ -40,6 +40,23 @@ def check_case(dp, U, orc, case, what):
     chk(U.to_np(db), ref_db, f"{what} db")
 
 
+def test_rgb_stem_kernels_are_chosen_and_filter_gradient_without_bias_gradient(env):
+    """The RGB 3x3 stem with rows of whole 32-pixel segments runs the segment kernels (names as the profiler shows them); the filter gradient
+    alone (no bias gradient asked for) equals the oracle's."""
+    dp, U, orc = env
+    case = U.ConvCase("rgb_seg", 2, 6, 64, 3, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=False, dx_f32=True)
+    assert dp.dp_conv2d_kernel_info(case.desc, 0)[0] == "k_fwd_rgb3"
+    assert dp.dp_conv2d_kernel_info(case.desc, 2)[0] == "k_wgrad_rgb3"
+    other = U.ConvCase("rgb_noseg", 2, 6, 40, 3, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=False, dx_f32=True)
+    assert dp.dp_conv2d_kernel_info(other.desc, 0)[0] == "k_fwd_direct"
+    assert dp.dp_conv2d_kernel_info(other.desc, 2)[0] == "k_wgrad_direct"
+    dw, db = case.run_wgrad(None, want_db=False)
+    torch.cuda.synchronize()
+    assert db is None
+    ref_dw, _ = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=None, stride=(1, 1), pad=(1, 1), want_db=True)
+    U.assert_bf16_close(U.to_np(dw), ref_dw, "stem filter gradient without bias gradient")
+
+
 # ---- configuration 1: single 3x3 layer in fp32 ------------------------------------------
 @pytest.mark.parametrize("bias", [False, True])
 def test_config1_fp32(env, bias):
@@ -64,6 +81,11 @@ BF16_CASES = [
     ("stem_7x7_s2", 2, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3), False, False, True),
     ("rgb_3x3_s2_k32", 3, 23, 21, 3, 32, 3, 3, (2, 2), (0, 0), False, True, True),
     ("rgb_3x3_k136", 1, 37, 19, 3, 136, 3, 3, (1, 1), (1, 1), True, True, True),
+    # rows of whole 32-pixel segments: the RGB stem kernels (unmasked filter gradient, forward); with ReLU the saved output masks dy
+    ("rgb_3x3_w32", 2, 5, 32, 3, 64, 3, 3, (1, 1), (1, 1), True, False, True),
+    ("rgb_3x3_w64_relu_k128", 3, 7, 64, 3, 128, 3, 3, (1, 1), (1, 1), True, True, True),
+    ("rgb_3x3_w96_k128", 1, 9, 96, 3, 128, 3, 3, (1, 1), (1, 1), False, False, True),
+    ("rgb_3x3_one_row", 2, 1, 32, 3, 64, 3, 3, (1, 1), (1, 1), True, False, True),
     ("gray_5x5", 2, 18, 18, 1, 16, 5, 5, (1, 1), (2, 2), True, False, True),
     ("res_1x1", 2, 14, 14, 256, 64, 1, 1, (1, 1), (0, 0), False, False, False),
     ("res_1x1_s2", 2, 14, 14, 128, 256, 1, 1, (2, 2), (0, 0), False, False, False),
