@@ -169,8 +169,13 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
         const unsigned ua = (unsigned)(tap * g.C + c0) * 2u;
         const unsigned ub = (unsigned)((tr * g.W + ts) * g.C + c0) * 2u;
         const unsigned bit = on ? 1u << (tap & 31) : 0u;
+        if (p.flags & KF_NT_A) {
 #pragma unroll
-        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+            for (int q = 0; q < IA; ++q) dma16_nt(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+        } else {
+#pragma unroll
+            for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+        }
 #pragma unroll
         for (int q = 0; q < IB; ++q) dma16(rx, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
         c0 += BK;
@@ -931,8 +936,13 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
         const unsigned ua = ((unsigned)c0 * RSC + (unsigned)tap * g.C) * 2u;
         const unsigned ub = (unsigned)(c0 - trow * g.K) * 2u;
         const unsigned bit = on ? 1u << (tap & 31) : 0u;
+        if (p.flags & KF_NT_A) {
 #pragma unroll
-        for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+            for (int q = 0; q < IA; ++q) dma16_nt(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+        } else {
+#pragma unroll
+            for (int q = 0; q < IA; ++q) dma16(rw, ldsA_w + sb + q * 1024, on ? voffA[q] + ua : OOR);
+        }
 #pragma unroll
         for (int q = 0; q < IB; ++q) dma16(rdy, ldsB_w + sb + q * 1024, (maskB[q] & bit) ? voffB[q] + ub : OOR);
         c0 += BK;
@@ -1327,6 +1337,10 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
             p.steps_total = p.steps_per_split = (p.red + a.plan.BK - 1) / a.plan.BK;
         }
     }
+    // operands touched exactly once are streamed past the caches: the weights of a pass with a single pixel tile (dense layers at
+    // small batch), and a large filter gradient stored straight to its destination
+    if (!wg && p.tilesB == 1 && (size_t)p.rowsA * p.red * 2 >= ((size_t)8 << 20)) p.flags |= KF_NT_A;
+    if (wg && p.splits == 1 && (size_t)p.rowsA * p.rowsB * 4 >= ((size_t)32 << 20)) p.flags |= KF_NT_OUT;
     p.dbp = p.splits > 1 ? a.db_partial : a.db_out;
     if (!wg || p.dbp == nullptr || !plan_sums_bias_gradient(a.plan)) p.flags &= ~KF_DB;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];

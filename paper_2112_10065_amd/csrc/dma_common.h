@@ -18,6 +18,12 @@ DEVFN void dma16(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff)
 {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, 0, 0, 0);
 }
+// the same copy with the non-temporal hint: for operands that are read exactly once (allocating them in the caches
+// would push out dirty lines that then have to be written back in the middle of the stream)
+DEVFN void dma16_nt(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, 0, 0, 2);
+}
 DEVFN unsigned lds_offset(const void *p) { return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p; }
 
 template <int N> DEVFN void wait_vmcnt()

@@ -471,6 +471,12 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
         hipError_t e = f32_conv_fwd(g, kflags(flags, true), (const float *)x, (const float *)w, bias, (float *)y, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
     }
+    if (g_force_variant[PASS_FWD].load() < 0 && dense_fwd_stream_shape(g)) {
+        ts.name("k_dense_fwd", 1);
+        hipError_t e = dense_fwd_stream(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
+        dp_trace_main_kernel_done(st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
+    }
     if (use_small_c(g, PASS_FWD) && small_c_direct(g)) {
         ts.name(small_c_fwd_kernel(g), 1);
         hipError_t e = small_c_fwd_direct(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
@@ -734,6 +740,11 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (desc->io_dtype == DP_F32) {
         static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
         if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
+        if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    if (pass == PASS_FWD && g_force_variant[PASS_FWD].load() < 0 && dense_fwd_stream_shape(g)) {
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_dense_fwd");
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }

@@ -12,6 +12,8 @@ enum : unsigned {
     KF_OUT_F32 = 4u,  // final output stored as fp32 instead of bf16
     KF_DB = 16u,      // backward-filter: also sum the bias gradient (kernels that cannot leave db_done unset)
     KF_MASK_IN = 8u,  // backward-data: dx *= [x > 0], x = the layer's saved input (output of the preceding ReLU)
+    KF_NT_A = 32u,    // forward / backward-data: every weight is read by one block only (a single pixel tile): non-temporal loads, the stream leaves the caches alone
+    KF_NT_OUT = 64u,  // backward-filter: a large gradient written once: non-temporal stores
 };
 
 enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
@@ -130,6 +132,9 @@ hipError_t small_c_im2col(const ConvGeom &g, int kpad, const bf16_t *x, bf16_t *
 hipError_t small_c_pad_weights(const ConvGeom &g, int kpad, const bf16_t *w, bf16_t *wpad, hipStream_t st);
 hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, float *dw, hipStream_t st);
 // direct kernels without the im2col matrix (R*S*C <= 32, c_out % 8 == 0)
+// dense_fwd.hip: 1x1 layers over at most 32 pixel rows (dense layers at small batch), one launch that streams the weights
+bool dense_fwd_stream_shape(const ConvGeom &g);
+hipError_t dense_fwd_stream(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
 bool small_c_direct(const ConvGeom &g);
 hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
                               hipStream_t st);

@@ -169,7 +169,9 @@ DEVFN void store_row_major(const KArgs &p, const f32x16 (&acc)[FA][FB], int arow
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int row = arow0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-                if (row < p.rowsA) base[(size_t)row * p.rowsB + col] = acc[i][j][v];
+                if (row >= p.rowsA) continue;
+                if (p.flags & KF_NT_OUT) __builtin_nontemporal_store(acc[i][j][v], base + (size_t)row * p.rowsB + col);
+                else base[(size_t)row * p.rowsB + col] = acc[i][j][v];
             }
         }
 }

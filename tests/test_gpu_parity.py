@@ -607,8 +607,19 @@ def test_measured_kernel_choice(env, mode):
         dp.dp_set_autotune(False)
 
 
+def test_dense_forward_kernel_names(env):
+    """Which forward kernel a dense layer gets (names as the profiler shows them)."""
+    dp, U, orc = env
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(16, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] == "k_dense_fwd"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(17, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(4, 1, 1, 448, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
+
+
 # ---- dense layers ----------------------------------------------------------------------------
+# up to 16 samples with at least 512 input features (a multiple of 64) take the streaming forward kernel: whole and ragged
+# 16-row groups of outputs, an output count that is not a multiple of 4, features that do not divide evenly over the eight waves
 @pytest.mark.parametrize("n,i,o,bf16", [(5, 200, 136, True), (32, 1024, 512, True), (1, 4096, 1000, True),
+                                        (16, 512, 48, True), (7, 1600, 42, True), (2, 576, 200, True), (17, 512, 64, True),
                                         (3, 50, 20, False)])
 def test_linear_parity(env, n, i, o, bf16):
     dp, U, orc = env
