@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdp_mi355x.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["dp_api.hip", "conv_mfma.hip", "conv_fast.hip", "conv_dma.hip", "conv_halo.hip", "planner.hip", "small_c.hip", "conv_fp32.hip", "pointwise.hip", "burst_plan.hip", "glue.hip", "conv_wstrip.hip", "dense_fwd.hip"]
+SOURCES = ["dp_api.hip", "conv_mfma.hip", "conv_fast.hip", "conv_dma.hip", "conv_halo.hip", "planner.hip", "small_c.hip", "conv_fp32.hip", "pointwise.hip", "burst_plan.hip", "glue.hip", "conv_wstrip.hip", "dense_stream.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -529,6 +529,13 @@ dp_status run_dgrad(const ConvGeom &g, int dtype, unsigned flags, const void *dy
         hipError_t e = f32_conv_dgrad(g, (const float *)dy, (const float *)ym, (const float *)w, (const float *)xin, (float *)dx, st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 backward-data launch");
     }
+    if (g_force_variant[PASS_DGRAD].load() < 0 && ym == nullptr && dense_dgrad_stream_shape(g)) {
+        ts.name("k_dense_dgrad", 1);
+        hipError_t e = dense_dgrad_stream(g, ((flags & DP_DX_F32) ? KF_OUT_F32 : 0u) | (xin != nullptr ? KF_MASK_IN : 0u), (const bf16_t *)dy,
+                                          (const bf16_t *)w, (const bf16_t *)xin, dx, st);
+        dp_trace_main_kernel_done(st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "backward-data launch");
+    }
     ConvArgs a{};
     a.g = g; a.pass = PASS_DGRAD; a.flags = ((flags & DP_DX_F32) ? KF_OUT_F32 : 0u) | (xin != nullptr ? KF_MASK_IN : 0u);
     a.x = (const bf16_t *)xin;
@@ -740,6 +747,12 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (desc->io_dtype == DP_F32) {
         static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
         if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
+        if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    if (pass == PASS_DGRAD && g_force_variant[PASS_DGRAD].load() < 0 && dense_dgrad_stream_shape(g)) {
+        // named for a call without a saved output (with one, dy is masked first and the tiled kernels run)
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_dense_dgrad");
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }

@@ -132,9 +132,11 @@ hipError_t small_c_im2col(const ConvGeom &g, int kpad, const bf16_t *x, bf16_t *
 hipError_t small_c_pad_weights(const ConvGeom &g, int kpad, const bf16_t *w, bf16_t *wpad, hipStream_t st);
 hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, float *dw, hipStream_t st);
 // direct kernels without the im2col matrix (R*S*C <= 32, c_out % 8 == 0)
-// dense_fwd.hip: 1x1 layers over at most 32 pixel rows (dense layers at small batch), one launch that streams the weights
+// dense_stream.hip: 1x1 layers over a few pixel rows (dense layers at small batch), one launch per pass that streams the weights
 bool dense_fwd_stream_shape(const ConvGeom &g);
 hipError_t dense_fwd_stream(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
+bool dense_dgrad_stream_shape(const ConvGeom &g);
+hipError_t dense_dgrad_stream(const ConvGeom &g, unsigned flags, const bf16_t *dy, const bf16_t *w, const bf16_t *xin, void *dx, hipStream_t st);
 bool small_c_direct(const ConvGeom &g);
 hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y,
                               hipStream_t st);

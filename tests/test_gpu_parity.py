@@ -613,6 +613,11 @@ def test_dense_forward_kernel_names(env):
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(16, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] == "k_dense_fwd"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(17, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(4, 1, 1, 448, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
+    # backward-data: the streaming kernel takes the shapes whose output count is not a multiple of 64 (the cases (1, 4096, 1000) and
+    # (5, 200, 136) of test_linear_parity run it, the second with a ragged last block of input features)
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(5, 1, 1, 200, 136, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] != "k_dense_dgrad"
 
 
 # ---- dense layers ----------------------------------------------------------------------------
