@@ -14,6 +14,7 @@
 //     together with the weight loads of the same step so that the in-order load counter never waits for a young load.
 // Bias and ReLU are applied after the waves' sums are added.
 #include "dma_common.h"
+#include <type_traits>
 
 namespace {
 
@@ -276,6 +277,93 @@ __global__ __launch_bounds__(64 * DF_WAVES) void k_dense_dgrad(int N, int C, int
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Filter gradient of the same layers: dW[o][i] = sum_n dy[n][o] * x[n][i] with N <= 32 is an outer product that writes
+// K*C fp32 once and reads next to nothing, so it is a store stream.  A wave owns one 64 x 64 tile of dW: it copies its
+// dy tile [32 samples][64 outputs] and its x tile [32 samples][64 inputs] into its own LDS (direct-to-LDS loads, rows of
+// samples the batch does not have fetch zeros), reads both through the LDS transpose read (samples are the reduction),
+// multiplies (one 16-sample slice, two beyond 16 samples) and stores its sums, non-temporally when the gradient is large.
+// No barrier, no row tables, no partial sums.  The bias gradient (dy fragments times ones) is added by the waves of the
+// first input tile.
+// ---------------------------------------------------------------------------------------
+template <bool NT>
+__global__ __launch_bounds__(64 * DF_WAVES) void k_dense_wgrad(int N, int C, int K, const bf16_t *x, const bf16_t *dy, float *dw, float *db)
+{
+    __shared__ __attribute__((aligned(1024))) char lds[DF_WAVES * 8192];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int o0 = blockIdx.x * 64, i0 = (blockIdx.y * DF_WAVES + wave) * 64;
+    if (i0 >= C) return;   // no barrier follows
+    __amdgpu_buffer_rsrc_t rdy = make_rsrc(dy, (size_t)N * K * 2);
+    __amdgpu_buffer_rsrc_t rx = make_rsrc(x, (size_t)N * C * 2);
+    const unsigned base = lds_offset(lds) + wave * 8192;
+    // lane l of load j fills 16-byte position l%8 of tile row (sample) 8*j + l/8 with global chunk (l%8) ^ 4*swz(row)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int t = 8 * j + (lane >> 3), c = (lane & 7) ^ (seg_swz<64>(t) << 2);
+        const bool row = t < N;
+        dma16(rdy, base + j * 1024, row && o0 + c * 8 < K ? ((unsigned)t * K + o0 + c * 8) * 2u : OOR);
+        dma16(rx, base + 4096 + j * 1024, row && i0 + c * 8 < C ? ((unsigned)t * C + i0 + c * 8) * 2u : OOR);
+    }
+    const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+    unsigned fa[2];   // fragment f of either tile: sample rows tl (+4), columns 32*f + cl .. +3
+#pragma unroll
+    for (int f = 0; f < 2; ++f) fa[f] = base + tl * 128 + (((f ^ seg_swz<64>(tl)) << 6) | (cl << 1));
+    f32x16 acc[2][2], accdb[2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accdb[a][v] = 0.f;
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+    }
+    const bool do_db = db != nullptr && i0 == 0;
+    wait_vmcnt<0>();
+    auto slice = [&](auto ks_tag) {
+        constexpr int KS = decltype(ks_tag)::value;
+        u32x2 alo[2], ahi[2], blo[2], bhi[2];
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            alo[f] = lds_read_tr_off<KS * 2048>(fa[f]);
+            ahi[f] = lds_read_tr_off<KS * 2048 + 512>(fa[f]);
+            blo[f] = lds_read_tr_off<4096 + KS * 2048>(fa[f]);
+            bhi[f] = lds_read_tr_off<4096 + KS * 2048 + 512>(fa[f]);
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        asm volatile("" : "+v"(alo[0]), "+v"(ahi[0]), "+v"(alo[1]), "+v"(ahi[1]), "+v"(blo[0]), "+v"(bhi[0]), "+v"(blo[1]), "+v"(bhi[1]));
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            const bf16x8 av = __builtin_bit_cast(bf16x8, u32x4{alo[a].x, alo[a].y, ahi[a].x, ahi[a].y});
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, __builtin_bit_cast(bf16x8, u32x4{blo[b].x, blo[b].y, bhi[b].x, bhi[b].y}), acc[a][b], 0, 0, 0);
+            if (do_db) accdb[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, ones_bf16(), accdb[a], 0, 0, 0);
+        }
+    };
+    slice(std::integral_constant<int, 0>{});
+    if (N > 16) slice(std::integral_constant<int, 1>{});
+    // element v of lane l: output row 8*(v/4) + 4*(l/32) + v%4 of its fragment, input column l%32
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int o = o0 + 32 * a + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (o >= K) continue;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int i = i0 + 32 * b + (lane & 31);
+                if (i >= C) continue;
+                if (NT) __builtin_nontemporal_store(acc[a][b][v], dw + (size_t)o * C + i);
+                else dw[(size_t)o * C + i] = acc[a][b][v];
+            }
+        }
+    if (do_db) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a) store_db_fragment(accdb[a], db, o0 + 32 * a, K, lane);
+    }
+}
+
 }  // namespace
 
 // shapes the streaming dense forward takes: a 1x1 layer over at most 16 pixel rows (beyond that the activation operand, which
@@ -311,5 +399,24 @@ hipError_t dense_dgrad_stream(const ConvGeom &g, unsigned flags, const bf16_t *d
 {
     const int rows = g.N * g.H * g.W, blocks = (g.C + 63) / 64;
     hipLaunchKernelGGL(k_dense_dgrad, dim3((unsigned)blocks), dim3(64 * DF_WAVES), 0, st, rows, g.C, g.K, flags, dy, w, xin, dx);
+    return hipGetLastError();
+}
+
+// shapes the streaming dense filter gradient takes: a 1x1 layer over at most 32 pixel rows, features in whole 8-element chunks,
+// a gradient of 4 to 128 MB (measured: 4096 x 4096 28 -> 21 us and 4096 x 1000 19 -> 14 us against the pipelined tile kernel,
+// which in turn writes the 411 MB of the 25088 x 4096 layer 15 us faster with its 128 x 128 tiles)
+bool dense_wgrad_stream_shape(const ConvGeom &g)
+{
+    const long long rows = (long long)g.N * g.Ho * g.Wo, elems = (long long)g.K * g.C;
+    return g.R == 1 && g.S == 1 && g.sh == 1 && g.sw == 1 && g.ph == 0 && g.pw == 0 && rows <= 32 && g.C % 8 == 0 && g.K % 8 == 0 &&
+           elems >= (1 << 20) && elems <= (32 << 20);
+}
+
+hipError_t dense_wgrad_stream(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *dw, float *db, hipStream_t st)
+{
+    const int rows = g.N * g.Ho * g.Wo;
+    const dim3 grid((unsigned)((g.K + 63) / 64), (unsigned)((g.C + 64 * DF_WAVES - 1) / (64 * DF_WAVES)));
+    if ((size_t)g.K * g.C * 4 >= ((size_t)32 << 20)) hipLaunchKernelGGL(k_dense_wgrad<true>, grid, dim3(64 * DF_WAVES), 0, st, rows, g.C, g.K, x, dy, dw, db);
+    else hipLaunchKernelGGL(k_dense_wgrad<false>, grid, dim3(64 * DF_WAVES), 0, st, rows, g.C, g.K, x, dy, dw, db);
     return hipGetLastError();
 }

@@ -597,6 +597,12 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         }
         return DP_OK;
     }
+    if (g_force_variant[PASS_WGRAD].load() < 0 && ym == nullptr && dw != nullptr && dense_wgrad_stream_shape(g)) {
+        ts.name("k_dense_wgrad", 1);
+        hipError_t e = dense_wgrad_stream(g, (const bf16_t *)x, (const bf16_t *)dy, dw, db, st);
+        dp_trace_main_kernel_done(st);
+        return e == hipSuccess ? DP_OK : hip_fail(e, "backward-filter launch");
+    }
     if (use_small_c(g, PASS_WGRAD) && small_c_direct(g)) {
         const size_t part = round256(small_c_wgrad_partial_bytes(g));
         float *rws = (float *)((char *)ws + part);   // bias-gradient scratch of the db-only case
@@ -747,6 +753,12 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (desc->io_dtype == DP_F32) {
         static const char *names[3] = {"k_f32_fwd", "k_f32_dgrad", "k_f32_wgrad"};
         if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", names[pass]);
+        if (splits != nullptr) *splits = 1;
+        return DP_OK;
+    }
+    if (pass == PASS_WGRAD && g_force_variant[PASS_WGRAD].load() < 0 && dense_wgrad_stream_shape(g)) {
+        // named for a call without a saved output
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_dense_wgrad");
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }

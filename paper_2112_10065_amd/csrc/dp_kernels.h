@@ -135,6 +135,8 @@ hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, flo
 // dense_stream.hip: 1x1 layers over a few pixel rows (dense layers at small batch), one launch per pass that streams the weights
 bool dense_fwd_stream_shape(const ConvGeom &g);
 hipError_t dense_fwd_stream(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
+bool dense_wgrad_stream_shape(const ConvGeom &g);
+hipError_t dense_wgrad_stream(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *dw, float *db, hipStream_t st);
 bool dense_dgrad_stream_shape(const ConvGeom &g);
 hipError_t dense_dgrad_stream(const ConvGeom &g, unsigned flags, const bf16_t *dy, const bf16_t *w, const bf16_t *xin, void *dx, hipStream_t st);
 bool small_c_direct(const ConvGeom &g);

@@ -618,6 +618,9 @@ def test_dense_forward_kernel_names(env):
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(5, 1, 1, 200, 136, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] != "k_dense_dgrad"
+    # filter gradient: gradients of 4 to 128 MB
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0] == "k_dense_wgrad"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(1, 1, 1, 25088, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0] != "k_dense_wgrad"
 
 
 # ---- dense layers ----------------------------------------------------------------------------
@@ -625,6 +628,7 @@ def test_dense_forward_kernel_names(env):
 # 16-row groups of outputs, an output count that is not a multiple of 4, features that do not divide evenly over the eight waves
 @pytest.mark.parametrize("n,i,o,bf16", [(5, 200, 136, True), (32, 1024, 512, True), (1, 4096, 1000, True),
                                         (16, 512, 48, True), (7, 1600, 42, True), (2, 576, 200, True), (17, 512, 64, True),
+                                        (9, 1032, 1016, True), (20, 2048, 520, True),   # streaming filter gradient, ragged tiles both ways
                                         (3, 50, 20, False)])
 def test_linear_parity(env, n, i, o, bf16):
     dp, U, orc = env
