@@ -183,6 +183,9 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
 /* Names the main kernel this pass of the layer would launch, as the profiler prints it
  * (e.g. "k_conv_gemm<0, 128, 128, 32, 2, 2, true, true>"), and its number of reduction
  * splits (> 1 means a second, small reduction kernel follows).  Host-only, no launch.
+ * The backward passes are named for a call that passes no saved output (y_saved = NULL, the gradient
+ * arrives already masked) and, for the filter gradient, asks for the bias gradient too; a few shapes run
+ * another kernel when dy still has to be masked.
  * name: host buffer of name_bytes; either output pointer may be NULL. */
 dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, size_t name_bytes,
                                 int32_t *splits);

@@ -420,3 +420,6 @@ hipError_t dense_wgrad_stream(const ConvGeom &g, const bf16_t *x, const bf16_t *
     else hipLaunchKernelGGL(k_dense_wgrad<false>, grid, dim3(64 * DF_WAVES), 0, st, rows, g.C, g.K, x, dy, dw, db);
     return hipGetLastError();
 }
+
+const char *dense_fwd_stream_name(const ConvGeom &g) { return g.N * g.Ho * g.Wo <= 16 ? "k_dense_fwd<1>" : "k_dense_fwd<2>"; }
+const char *dense_wgrad_stream_name(const ConvGeom &g) { return (size_t)g.K * g.C * 4 >= ((size_t)32 << 20) ? "k_dense_wgrad<true>" : "k_dense_wgrad<false>"; }

@@ -472,7 +472,7 @@ dp_status run_fwd(const ConvGeom &g, int dtype, unsigned flags, const void *x, c
         return e == hipSuccess ? DP_OK : hip_fail(e, "fp32 forward launch");
     }
     if (g_force_variant[PASS_FWD].load() < 0 && dense_fwd_stream_shape(g)) {
-        ts.name("k_dense_fwd", 1);
+        ts.name(dense_fwd_stream_name(g), 1);
         hipError_t e = dense_fwd_stream(g, kflags(flags, true), (const bf16_t *)x, (const bf16_t *)w, bias, (bf16_t *)y, st);
         dp_trace_main_kernel_done(st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "forward launch");
@@ -598,7 +598,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         return DP_OK;
     }
     if (g_force_variant[PASS_WGRAD].load() < 0 && ym == nullptr && dw != nullptr && dense_wgrad_stream_shape(g)) {
-        ts.name("k_dense_wgrad", 1);
+        ts.name(dense_wgrad_stream_name(g), 1);
         hipError_t e = dense_wgrad_stream(g, (const bf16_t *)x, (const bf16_t *)dy, dw, db, st);
         dp_trace_main_kernel_done(st);
         return e == hipSuccess ? DP_OK : hip_fail(e, "backward-filter launch");
@@ -609,7 +609,7 @@ dp_status run_wgrad(const ConvGeom &g, int dtype, const void *x, const void *dy,
         bool db_done = false;
         if (dw != nullptr) {
             // the kernel masks dy with the saved output while loading it and sums the bias gradient on the way
-            ts.name(small_c_wgrad_kernel(g, ym != nullptr), small_c_wgrad_blocks(g, ym != nullptr));
+            ts.name(small_c_wgrad_kernel(g, ym != nullptr, db != nullptr), small_c_wgrad_blocks(g, ym != nullptr));
             hipError_t e = small_c_wgrad_direct(g, (const bf16_t *)x, (const bf16_t *)dy, (const bf16_t *)ym, (float *)ws, dw, db, st);
             if (e != hipSuccess) return hip_fail(e, "backward-filter launch");
             db_done = true;
@@ -758,7 +758,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     }
     if (pass == PASS_WGRAD && g_force_variant[PASS_WGRAD].load() < 0 && dense_wgrad_stream_shape(g)) {
         // named for a call without a saved output
-        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_dense_wgrad");
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", dense_wgrad_stream_name(g));
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }
@@ -769,7 +769,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass == PASS_FWD && g_force_variant[PASS_FWD].load() < 0 && dense_fwd_stream_shape(g)) {
-        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "k_dense_fwd");
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", dense_fwd_stream_name(g));
         if (splits != nullptr) *splits = 1;
         return DP_OK;
     }
@@ -779,8 +779,9 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
         return DP_OK;
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass) && small_c_direct(g)) {
-        // the filter gradient is named for a call without a saved output (the masked form runs k_wgrad_direct on every shape)
-        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", pass == PASS_FWD ? small_c_fwd_kernel(g) : small_c_wgrad_kernel(g, false));
+        // the filter gradient is named for a call without a saved output (the masked form runs k_wgrad_direct on every shape) that
+        // asks for the bias gradient as well
+        if (name != nullptr && name_bytes > 0) snprintf(name, name_bytes, "%s", pass == PASS_FWD ? small_c_fwd_kernel(g) : small_c_wgrad_kernel(g, false, true));
         if (splits != nullptr) *splits = pass == PASS_FWD ? 1 : small_c_wgrad_blocks(g, false);
         return DP_OK;
     }

@@ -136,6 +136,8 @@ hipError_t small_c_unpad_dw(const ConvGeom &g, int kpad, const float *dwpad, flo
 bool dense_fwd_stream_shape(const ConvGeom &g);
 hipError_t dense_fwd_stream(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
 bool dense_wgrad_stream_shape(const ConvGeom &g);
+const char *dense_fwd_stream_name(const ConvGeom &g);     // kernel names as a profiler prints them
+const char *dense_wgrad_stream_name(const ConvGeom &g);
 hipError_t dense_wgrad_stream(const ConvGeom &g, const bf16_t *x, const bf16_t *dy, float *dw, float *db, hipStream_t st);
 bool dense_dgrad_stream_shape(const ConvGeom &g);
 hipError_t dense_dgrad_stream(const ConvGeom &g, unsigned flags, const bf16_t *dy, const bf16_t *w, const bf16_t *xin, void *dx, hipStream_t st);
@@ -146,7 +148,7 @@ hipError_t small_c_fwd_direct(const ConvGeom &g, unsigned flags, const bf16_t *x
 bool small_c_stem(const ConvGeom &g);
 hipError_t small_c_fwd_stem(const ConvGeom &g, unsigned flags, const bf16_t *x, const bf16_t *w, const float *bias, bf16_t *y, hipStream_t st);
 int small_c_wgrad_blocks(const ConvGeom &g, bool masked);   // pixel-range blocks, each writes one fp32 partial (masked: a saved output is applied to dy)
-const char *small_c_wgrad_kernel(const ConvGeom &g, bool masked);   // name of the kernel that runs
+const char *small_c_wgrad_kernel(const ConvGeom &g, bool masked, bool with_db);   // name of the kernel that runs, as a profiler prints it
 const char *small_c_fwd_kernel(const ConvGeom &g);
 size_t small_c_wgrad_partial_bytes(const ConvGeom &g);
 // ymask (saved output, may be NULL) masks dy on the fly; db (may be NULL) receives the bias gradient of the masked dy

@@ -905,7 +905,10 @@ static void wgrad_rgb3_split(const ConvGeom &g, int *segs, int *per_wave, int *b
     *segs = (int)total; *per_wave = (int)spw; *blocks = (int)(((total + spw - 1) / spw + 3) / 4);
 }
 const char *small_c_fwd_kernel(const ConvGeom &g) { return rgb3_shape(g) ? "k_fwd_rgb3" : "k_fwd_direct"; }
-const char *small_c_wgrad_kernel(const ConvGeom &g, bool masked) { return !masked && rgb3_shape(g) ? "k_wgrad_rgb3" : "k_wgrad_direct"; }
+const char *small_c_wgrad_kernel(const ConvGeom &g, bool masked, bool with_db)
+{
+    return masked || !rgb3_shape(g) ? "k_wgrad_direct" : with_db ? "k_wgrad_rgb3<true>" : "k_wgrad_rgb3<false>";
+}
 int small_c_wgrad_blocks(const ConvGeom &g, bool masked)
 {
     if (!masked && rgb3_shape(g)) {

@@ -46,7 +46,7 @@ def test_rgb_stem_kernels_are_chosen_and_filter_gradient_without_bias_gradient(e
     dp, U, orc = env
     case = U.ConvCase("rgb_seg", 2, 6, 64, 3, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=False, dx_f32=True)
     assert dp.dp_conv2d_kernel_info(case.desc, 0)[0] == "k_fwd_rgb3"
-    assert dp.dp_conv2d_kernel_info(case.desc, 2)[0] == "k_wgrad_rgb3"
+    assert dp.dp_conv2d_kernel_info(case.desc, 2)[0] == "k_wgrad_rgb3<true>"
     other = U.ConvCase("rgb_noseg", 2, 6, 40, 3, 64, 3, 3, (1, 1), (1, 1), bf16=True, bias=True, relu=False, dx_f32=True)
     assert dp.dp_conv2d_kernel_info(other.desc, 0)[0] == "k_fwd_direct"
     assert dp.dp_conv2d_kernel_info(other.desc, 2)[0] == "k_wgrad_direct"
@@ -610,17 +610,17 @@ def test_measured_kernel_choice(env, mode):
 def test_dense_forward_kernel_names(env):
     """Which forward kernel a dense layer gets (names as the profiler shows them)."""
     dp, U, orc = env
-    assert dp.dp_conv2d_kernel_info(dp.conv_desc(16, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] == "k_dense_fwd"
-    assert dp.dp_conv2d_kernel_info(dp.conv_desc(17, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
-    assert dp.dp_conv2d_kernel_info(dp.conv_desc(4, 1, 1, 448, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(16, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] == "k_dense_fwd<1>"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(17, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd<1>"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(4, 1, 1, 448, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, dp.DP_BIAS), 0)[0] != "k_dense_fwd<1>"
     # backward-data: the streaming kernel takes the shapes whose output count is not a multiple of 64 (the cases (1, 4096, 1000) and
     # (5, 200, 136) of test_linear_parity run it, the second with a ragged last block of input features)
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(5, 1, 1, 200, 136, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] == "k_dense_dgrad"
     assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 1)[0] != "k_dense_dgrad"
     # filter gradient: gradients of 4 to 128 MB
-    assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0] == "k_dense_wgrad"
-    assert dp.dp_conv2d_kernel_info(dp.conv_desc(1, 1, 1, 25088, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0] != "k_dense_wgrad"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(32, 1, 1, 4096, 1000, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0] == "k_dense_wgrad<false>"
+    assert dp.dp_conv2d_kernel_info(dp.conv_desc(1, 1, 1, 25088, 4096, 1, 1, (1, 1), (0, 0), dp.DP_BF16, 0), 2)[0][:13] != "k_dense_wgrad"
 
 
 # ---- dense layers ----------------------------------------------------------------------------
