@@ -41,7 +41,7 @@ TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-G
     "k_wgrad_halo@32": 356322073,
     "k_conv_strip<false, 224, 256>@32": 121464930,
     "k_conv_strip<true, 224, 256>@32": 172665460,
-    "k_halo_ws<0>@32": 320303005,
+    "k_halo_ws<0, false>@32": 320303005,
     "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 190249525,
     "k_conv_strip<true, 256, 128>@32": 161582658,
     "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 140099449,
@@ -88,7 +88,7 @@ TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-G
     "k_dense_wgrad<true>@2": 67496608,
     "k_halo<1, 64, 1, 4, 2>@2": 39676365,
     "k_dgrad_dma<64, 128, 128, 2, 2, 2, 1>@2": 19445550,
-    "k_halo_ws<0>@2": 24315960,
+    "k_halo_ws<0, false>@2": 24315960,
     "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 23563069,
     "k_dgrad_dma<64, 64, 128, 2, 2, 4, 1>@2": 17969413,
     "k_halo<0, 64, 1, 4, 4>@2": 21984151,

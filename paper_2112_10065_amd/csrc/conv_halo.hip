@@ -449,7 +449,7 @@ constexpr int WS_CPW = HALO_PP / 8 / 4;   // patch copies per wave
 static_assert(WS_CPW * 4 * 8 == HALO_PP, "patch copies divide evenly over the four waves");
 static_assert(WS_PATCH + 9 * 8192 <= 3 * WS_PATCH, "the weights are staged behind the first patch buffer");
 
-template <int PASS>
+template <int PASS, bool MASK = false>   // MASK (backward-data): fused backward of the ReLU in front of the layer
 __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -551,10 +551,15 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
     // A wave that issues a memory instruction into a full queue stalls, matrix instructions included, so the
     // copies of the patch two tiles ahead and the stores of the previous tile's output (held packed in
     // registers meanwhile) are spread over the 36 slices of the running tile instead of issued in a burst.
-    u32x4 ost[8];           // previous tile: [pixel fragment j][channel half i][group pair gp], 8 channels of one pixel each
+    u32x4 ost[MASK ? 1 : 8];           // previous tile: [pixel fragment j][channel half i][group pair gp], 8 channels of one pixel each
     bf16_t *optr[2] = {out, out};   // this lane's output row of fragment j (previous tile), at channel a0
     bool ook[2] = {false, false};
     bool have_prev = false;
+    // backward of the ReLU in front of the layer (KF_MASK_IN): the eight saved-input vectors that match this lane's eight output vectors of
+    // the running tile are requested before its first matrix instruction and used in its epilogue, behind the wait that every tile ends with
+    // (the masked form has no registers left to hold the previous tile's output as well: it stores each tile in its own epilogue)
+    constexpr bool mask_in = MASK;
+    u32x4 mk[MASK ? 8 : 1];
     auto store_one = [&](int k) {
         const int j = k >> 2, i = (k >> 1) & 1, gp = k & 1;
         const int ch = i * 32 + 8 * (2 * gp + (int)hsel);
@@ -579,6 +584,25 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
             dma16(rin, nbuf + q * 1024, ok ? (unsigned)(((nnb + ih) * IW + iw) * 64 + c * 8) * 2u : OOR);
         };
         const unsigned base = smem_base + (it % 3) * WS_PATCH;
+        if (mask_in) {
+            const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int pix = wave * 64 + j * 32 + (lane & 31);
+                const int pr = ty * TH + (pix >> tws), qc = tx * TW + (pix & (TW - 1));
+                const bool ok = pr < OH && qc < OW;
+                // a lane without an output pixel reads the first pixel instead: the load is issued by every lane, so the wait below counts right
+                const bf16_t *xrow = p.x + (ok ? ((size_t)(n * OH + pr) * OW + qc) * p.rowsA + a0 : (size_t)0);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int gp = 0; gp < 2; ++gp) {
+                        const int ch = i * 32 + 8 * (2 * gp + (int)hsel);
+                        const bf16_t *src = xrow + (ok && a0 + ch < p.rowsA ? ch : 0);
+                        asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(mk[j * 4 + i * 2 + gp]) : "v"(src) : "memory");
+                    }
+            }
+        }
         asm volatile("" : "+v"(pp0[0]), "+v"(pp0[1]));   // keeps the 72 read addresses from being computed ahead of the loop
         f32x16 acc[2][2];
 #pragma unroll
@@ -620,7 +644,7 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
             if (sl % 3 == 1 && sl / 3 < WS_CPW) {
                 if (more2) copy_one(sl / 3);
             }
-            if (sl % 4 == 2 && sl / 4 < 8) {
+            if (!MASK && sl % 4 == 2 && sl / 4 < 8) {
                 if (have_prev) store_one(sl / 4);
             }
         }
@@ -629,6 +653,13 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
         if (more1) {
             if (more2) wait_vmcnt<WS_CPW>();
             else wait_vmcnt<0>();
+        } else if (mask_in) {
+            wait_vmcnt<0>();
+        }
+        // the saved-input vectors were requested before everything this tile issued, so they have landed as well
+        if (mask_in) {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) asm volatile("" : "+v"(mk[k]));
         }
         // accumulator element v of lane l is channel i*32 + 8*(v/4) + 4*(l/32) + v%4 of pixel l%32 of fragment j; the lanes
         // l and l+32 swap halves of two channel groups, after which each holds 8 consecutive channels of one group
@@ -657,10 +688,17 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
                         }
                         const auto s0 = __builtin_amdgcn_permlane32_swap(pkd[0][0], pkd[1][0], false, false);
                         const auto s1 = __builtin_amdgcn_permlane32_swap(pkd[0][1], pkd[1][1], false, false);
-                        ost[j * 4 + i * 2 + gp] = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                        const u32x4 packed = u32x4{s0[0], s1[0], s0[1], s1[1]};
+                        if constexpr (MASK) {
+                            ost[0] = apply_mask(packed, mk[j * 4 + i * 2 + gp]);
+                            const int ch = i * 32 + 8 * (2 * gp + (int)hsel);
+                            if (ook[j] && a0 + ch < p.rowsA) asm volatile("global_store_dwordx4 %0, %1, off" ::"v"(optr[j] + ch), "v"(ost[0]) : "memory");
+                        } else {
+                            ost[j * 4 + i * 2 + gp] = packed;
+                        }
                     }
             }
-            have_prev = true;
+            have_prev = !MASK;
         }
         __builtin_amdgcn_s_barrier();   // all shares of the next patch have landed; this tile's buffer is free (no fence: copies and stores stay in flight)
     }
@@ -717,6 +755,8 @@ hipError_t halo_init()
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_halo_ws<PASS_FWD>), hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_halo_ws<PASS_DGRAD>), hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_halo_ws<PASS_DGRAD, true>), hipFuncAttributeMaxDynamicSharedMemorySize, WS_LDS);
         if (e != hipSuccess) return e;
     }
     for (int pass = 0; pass < 2; ++pass)
@@ -789,10 +829,10 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
     return true;
 }
 
-void halo_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
+void halo_kernel_name(int pass, const GemmPlan &pl, bool masked, char *name, size_t name_bytes)
 {
     if (pass == PASS_WGRAD) { snprintf(name, name_bytes, "k_wgrad_halo"); return; }
-    if (pl.variant == 4) { snprintf(name, name_bytes, "k_halo_ws<%d>", pass); return; }
+    if (pl.variant == 4) { snprintf(name, name_bytes, "k_halo_ws<%d, %s>", pass, pass == PASS_DGRAD && masked ? "true" : "false"); return; }
     const HaloVariant &h = kHalo[pl.variant];
     snprintf(name, name_bytes, "k_halo<%d, %d, %d, %d, %d>", pass, h.TA, h.WA, h.WB, h.NS);
 }
@@ -835,7 +875,12 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         int blocks = a.plan.blocks > 0 ? a.plan.blocks : 256 / p.tilesA;   // default: one persistent block per CU
         if (blocks < 1) blocks = 1;
         if (blocks > p.tilesB) blocks = p.tilesB;
-        hipLaunchKernelGGL(fwd ? k_halo_ws<PASS_FWD> : k_halo_ws<PASS_DGRAD>, dim3((unsigned)blocks, (unsigned)p.tilesA), dim3(256), WS_LDS, st, p,
+        void (*kern)(const KArgs, int, int, int, int) = k_halo_ws<PASS_FWD>;
+        if (!fwd) {
+            if (p.flags & KF_MASK_IN) kern = k_halo_ws<PASS_DGRAD, true>;
+            else kern = k_halo_ws<PASS_DGRAD>;
+        }
+        hipLaunchKernelGGL(kern, dim3((unsigned)blocks, (unsigned)p.tilesA), dim3(256), WS_LDS, st, p,
                            tws, tiles_x, tiles_y, p.tilesB);
         dp_trace_main_kernel_done(st);
         return hipGetLastError();

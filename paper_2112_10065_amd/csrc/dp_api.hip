@@ -132,9 +132,9 @@ struct TraceScope {
         g_trace_cur = -1;
     }
 };
-void plan_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
+void plan_kernel_name(int pass, const GemmPlan &pl, bool masked, char *name, size_t name_bytes)
 {
-    if (pl.halo) halo_kernel_name(pass, pl, name, name_bytes);
+    if (pl.halo) halo_kernel_name(pass, pl, masked, name, name_bytes);
     else if (pl.dma) dma_kernel_name(pass, pl, name, name_bytes);
     else if (pl.fast) fast_kernel_name(pass, pl, name, name_bytes);
     else mfma_kernel_name(pass, pl, name, name_bytes);
@@ -211,7 +211,7 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, in
     pl->wstrip = false;
     if (fv < 0 && auto_plan(g, pass, fs, pl, restr)) return;
     // a forced input-patch variant the call may not use falls through to the next family
-    const bool patch_banned = pass != PASS_WGRAD && ((restr & 1) || ((restr & 2) && fv == 404));
+    const bool patch_banned = pass != PASS_WGRAD && (restr & 1);
     if (fv >= 400 && !patch_banned && halo_plan(g, pass, fv, fs, pl)) return;
     // the pixel-strip kernel stages bf16 only: not for fp32 input gradients
     if (fv >= 200 && !(fv >= 230 && fv <= 233 && pass == PASS_DGRAD && (restr & 1)) && dma_plan(g, pass, fv, fs, pl)) return;
@@ -413,7 +413,7 @@ hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &
     }
     if (ts.idx >= 0) {
         char nm[96];
-        plan_kernel_name(a.pass, a.plan, nm, sizeof(nm));
+        plan_kernel_name(a.pass, a.plan, (a.flags & KF_MASK_IN) != 0, nm, sizeof(nm));
         ts.name(nm, a.plan.splits);
     }
     if (prep) {
@@ -787,7 +787,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     }
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
     const GemmPlan pl = current_plan(*plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0));
-    if (name != nullptr && name_bytes > 0) plan_kernel_name(pass, pl, name, name_bytes);
+    if (name != nullptr && name_bytes > 0) plan_kernel_name(pass, pl, pass == PASS_DGRAD && (desc->flags & DP_RELU_IN) != 0, name, name_bytes);
     if (splits != nullptr) *splits = pl.splits;
     return DP_OK;
 }

@@ -99,7 +99,7 @@ void dma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_byt
 hipError_t halo_init();
 bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
 hipError_t halo_launch(const ConvArgs &a, hipStream_t st);
-void halo_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_bytes);
+void halo_kernel_name(int pass, const GemmPlan &plan, bool masked, char *name, size_t name_bytes);   // masked: backward-data with the fused input-ReLU mask
 
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)
 hipError_t f32_conv_fwd(const ConvGeom &g, unsigned flags, const float *x, const float *w,

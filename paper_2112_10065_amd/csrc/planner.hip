@@ -140,7 +140,7 @@ int auto_plan_list(const ConvGeom &g, int pass, int force_splits, GemmPlan *out,
     const Candidate *cands = pass == PASS_WGRAD ? kWg : kPix;
     const int ncand = pass == PASS_WGRAD ? (int)(sizeof(kWg) / sizeof(kWg[0])) : (int)(sizeof(kPix) / sizeof(kPix[0]));
     for (int ci = 0; ci < ncand; ++ci) {
-        if (pass != PASS_WGRAD && cands[ci].code >= 400 && ((restr & 1) || ((restr & 2) && cands[ci].code == 404))) continue;
+        if (pass != PASS_WGRAD && cands[ci].code >= 400 && (restr & 1)) continue;   // the input-patch kernels store bf16 only
         if (pass == PASS_DGRAD && cands[ci].code >= 230 && cands[ci].code <= 233 && (restr & 1)) continue;   // bf16 staged epilogue only
         int last_splits = -1;
         for (int s : kSplits) {

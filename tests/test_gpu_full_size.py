@@ -179,7 +179,7 @@ FORCED = [
     ("conv4_2", 16, 2, 316, 5, "k_wgrad_strip"), ("conv5_1", 32, 2, 316, 5, "k_wgrad_strip"), ("conv3_1", 32, 2, 316, 16, "k_wgrad_strip"),
     # input patch resident in LDS (64 reduction channels per tap): conv1_2 forward / backward-data / filter gradient, conv2_1
     ("conv1_2", 32, 0, 403, 0, "k_halo<0, 64, 1, 4, 4>"), ("conv1_2", 2, 0, 400, 0, "k_halo<0, 64, 1, 4, 2>"),
-    ("conv1_2", 16, 0, 404, 0, "k_halo_ws<0>"), ("conv1_2", 32, 1, 403, 0, "k_halo<1, 64, 1, 4, 4>"),
+    ("conv1_2", 16, 0, 404, 0, "k_halo_ws<0, false>"), ("conv1_2", 32, 1, 403, 0, "k_halo<1, 64, 1, 4, 4>"),
     ("conv2_1", 32, 0, 403, 0, "k_halo<0, 64, 1, 4, 4>"), ("conv2_1", 2, 0, 401, 0, "k_halo<0, 128, 2, 2, 2>"),
     ("conv1_2", 32, 2, 410, 0, "k_wgrad_halo"), ("conv2_1", 32, 2, 410, 0, "k_wgrad_halo"), ("conv1_2", 2, 2, 410, 0, "k_wgrad_halo"),
     # pipelined tiles of the large batches and their filter-gradient forms with many splits

@@ -381,14 +381,14 @@ def test_input_patch_stationary_weights(env, blocks):
         for tag, n, h, w, k, pd in (("ws_a", 2, 13, 12, 96, (1, 1)), ("ws_b", 1, 37, 40, 64, (1, 1)), ("ws_c", 3, 20, 70, 200, (0, 0)),
                                     ("ws_d", 2, 16, 16, 8, (2, 2))):
             case = U.ConvCase(tag, n, h, w, 64, k, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
-            assert "k_halo_ws<0>" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
+            assert "k_halo_ws<0, false>" in dp.dp_conv2d_kernel_info(case.desc, 0)[0]
             y = case.run_fwd()
             torch.cuda.synchronize()
             U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd), f"{tag} blocks {blocks}")
         for tag, n, h, w, c, pd in (("wsd_a", 2, 13, 12, 96, (1, 1)), ("wsd_b", 1, 37, 40, 64, (1, 1)), ("wsd_c", 3, 20, 70, 200, (0, 0)),
                                     ("wsd_d", 2, 16, 16, 8, (2, 2))):
             case = U.ConvCase(tag, n, h, w, c, 64, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
-            assert "k_halo_ws<1>" in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
+            assert "k_halo_ws<1, " in dp.dp_conv2d_kernel_info(case.desc, 1)[0]
             y = case.run_fwd()
             dx = case.run_dgrad(y)
             torch.cuda.synchronize()
