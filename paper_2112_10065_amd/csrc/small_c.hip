@@ -372,6 +372,10 @@ DEVFN void dma16s(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff, un
 {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, soff, 0, 0);
 }
+DEVFN void dma16s_nt(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff, unsigned soff)   // non-temporal: data that is read once
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, soff, 0, 2);
+}
 template <int OFF> DEVFN unsigned lds_read_u16(unsigned addr)
 {
     unsigned v;
@@ -417,7 +421,7 @@ __global__ __launch_bounds__(256) void k_wgrad_rgb3(ConvGeom g, const bf16_t *x,
         const unsigned m = (unsigned)(row * g.W + qs * 32);   // first pixel of the segment, flat
         const unsigned soff = m * (unsigned)g.K * 2u;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dma16s(rdy, base + st + q * 1024, voffA[q], soff);
+        for (int q = 0; q < 4; ++q) dma16s_nt(rdy, base + st + q * 1024, voffA[q], soff);
         const unsigned cond = 0x10u | (h == 0 ? 1u : 0u) | (h == g.H - 1 ? 2u : 0u) | (qs == 0 ? 4u : 0u) | (qs == spr - 1 ? 8u : 0u);
         dma16s(rx, base + st + RG_DY, (xflags & cond) ? OOR : (unsigned)(xlane + (int)(m * 6u)), 0);
         ++seg;
