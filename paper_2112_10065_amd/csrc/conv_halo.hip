@@ -612,14 +612,21 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
         u32x4 fb[WS_DEPTH + 1][2];   // [buffer][pixel fragment]
+        // chunk (2*ks + hsel) ^ swz = ((hsel ^ swz) ^ 2*ks): the address of slice ks is the address of slice 0 with bits 5-6 flipped by ks,
+        // so a tap costs one address computation per pixel fragment and three exclusive-ors
+        unsigned b0[2] = {0, 0};
         auto read_b = [&](int sl) {
             const int st = sl >> 2, ks = sl & 3;
-            const int off = (st / 3) * PW + (st % 3);
+            if (ks == 0) {
+                const int off = (st / 3) * PW + (st % 3);
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int pp = pp0[j] + off;
-                fb[sl % (WS_DEPTH + 1)][j] = lds_read16<0>(base + pp * 128 + (((2 * ks + hsel) ^ ((pp >> 1) & 7)) << 4));
+                for (int j = 0; j < 2; ++j) {
+                    const int pp = pp0[j] + off;
+                    b0[j] = base + pp * 128 + (((int)hsel ^ ((pp >> 1) & 7)) << 4);
+                }
             }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[sl % (WS_DEPTH + 1)][j] = lds_read16<0>(b0[j] ^ (unsigned)(ks << 5));
         };
 #pragma unroll
         for (int sl = 0; sl < WS_DEPTH; ++sl) read_b(sl);
