@@ -672,6 +672,17 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
         // l and l+32 swap halves of two channel groups, after which each holds 8 consecutive channels of one group
         {
             const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+            // the eight bias vectors of this lane's channels, read together (one wait instead of eight round trips to LDS)
+            f32x4 bvv[2][4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+                    bvv[i][gq] = PASS == PASS_FWD ? *reinterpret_cast<const f32x4 *>(bias_lds + i * 32 + 8 * gq + 4 * hsel) : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) asm volatile("" : "+v"(bvv[i][gq]));   // all eight are in registers before the first is used
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 const int pix = wave * 64 + j * 32 + (lane & 31);
@@ -686,7 +697,7 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
 #pragma unroll
                         for (int e = 0; e < 2; ++e) {
                             const int gq = 2 * gp + e;
-                            const f32x4 bv = *reinterpret_cast<const f32x4 *>(bias_lds + i * 32 + 8 * gq + 4 * hsel);
+                            const f32x4 bv = bvv[i][gq];
                             float v0 = acc[i][j][4 * gq] + bv.x, v1 = acc[i][j][4 * gq + 1] + bv.y, v2 = acc[i][j][4 * gq + 2] + bv.z,
                                   v3 = acc[i][j][4 * gq + 3] + bv.w;
                             if (PASS == PASS_FWD && (p.flags & KF_RELU)) { v0 = fmaxf(v0, 0.f); v1 = fmaxf(v1, 0.f); v2 = fmaxf(v2, 0.f); v3 = fmaxf(v3, 0.f); }
