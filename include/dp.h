@@ -182,7 +182,8 @@ dp_status dp_profile_layer(const dp_conv_desc *conv, const dp_linear_desc *linea
 
 /* Names the main kernel this pass of the layer would launch, as the profiler prints it
  * (e.g. "k_conv_gemm<0, 128, 128, 32, 2, 2, true, true>"), and its number of reduction
- * splits (> 1 means a second, small reduction kernel follows).  Host-only, no launch.
+ * splits (> 1 means a second, small reduction kernel follows; < -1: that many splits, summed inside the main kernel
+ * by the last block to finish each output tile, so no second kernel follows).  Host-only, no launch.
  * The backward passes are named for a call that passes no saved output (y_saved = NULL, the gradient
  * arrives already masked) and, for the filter gradient, asks for the bias gradient too; a few shapes run
  * another kernel when dy still has to be masked.
@@ -191,7 +192,12 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
                                 int32_t *splits);
 
 /* Tuning hook: force the tile variant (>= 0) and/or the number of reduction splits (> 0)
- * used by the given pass; -1 / 0 restore the built-in choice.  Process-wide. */
+ * used by the given pass; -1 / 0 restore the built-in choice.  Process-wide.
+ * tile_variant 1000 + v (forward, backward-data): variant v, and if v is a pipelined kernel with a reduction split,
+ * the splits are summed inside that kernel (dp_conv2d_kernel_info then reports -splits).  The built-in choice never
+ * takes this form: on one GPU it measured no faster than the reduction kernel it saves.  Such launches share a ring
+ * of 65536 tile counters, handed out in launch order (at most 1024 per launch): a launch must have finished before
+ * 64 later ones of this form are enqueued on other streams. */
 dp_status dp_set_override(int pass, int tile_variant, int splits);
 
 /* Measured kernel choice (the paper's layer profiler, Section 3 "profiling", applied to the
@@ -220,7 +226,7 @@ dp_status dp_set_autotune(int enabled);
 typedef struct {
     char kernel[96];
     int32_t pass;   /* DP_PASS_* */
-    int32_t splits; /* reduction splits of the plan that ran (> 1: a reduce kernel follows the main kernel) */
+    int32_t splits; /* reduction splits of the plan that ran (> 1: a reduce kernel follows the main kernel; < -1: summed inside it) */
     float main_us, total_us;
 } dp_trace_row;
 dp_status dp_trace_begin(void);

@@ -18,6 +18,8 @@
 #include <type_traits>
 #include <cstdio>
 #include <cstdlib>
+#include <atomic>
+#include <mutex>
 
 namespace {
 
@@ -89,6 +91,56 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
         const int gp = out_row(pix), gc = a0 + cc * 8;
         if (gp >= 0 && gc < p.rowsA)
             *reinterpret_cast<u32x4 *>(out + (size_t)gp * p.rowsA + gc) = *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8);
+    }
+}
+
+// Reduction split without a second kernel.  Every block of a tile stores its fp32 partial as usual, makes it visible
+// device-wide (__threadfence) and takes a ticket from the tile's counter; the block that draws the last ticket adds the
+// partials of all splits IN SPLIT ORDER (so the result does not depend on which block came last), applies the epilogue and
+// stores the tile.  The counters live in a static device array, zero when no launch is using them: the last block of a
+// tile resets its counter, and concurrent launches (the data-gradient chain and the filter gradients on another stream)
+// get disjoint ranges from a host-side ring.
+constexpr int kTicketRing = 1 << 16;
+__device__ unsigned g_tickets[kTicketRing];
+
+template <int TA, int TB, int NT>
+DEVFN void fused_split_reduce(const KArgs &p, int tile, int a0, int b0, int tid)
+{
+    __shared__ unsigned s_last;
+    // the partial sums were stored at device scope (written through); once the stores have completed they are visible to every block
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) s_last = atomicAdd(p.tickets + tile, 1u) == (unsigned)(p.splits - 1) ? 1u : 0u;
+    __syncthreads();
+    if (s_last == 0) return;
+    if (tid == 0) atomicExch(p.tickets + tile, 0u);   // the next launch that is handed this counter finds it at zero
+    const unsigned total = (unsigned)p.rowsB * (unsigned)p.rowsA;   // the host keeps splits * total * 4 below 2^31
+    const __amdgpu_buffer_rsrc_t part = make_rsrc(p.partial, (size_t)p.splits * total * 4);
+    constexpr int CPR = TA / 4;
+    constexpr int kDeviceScope = 16;   // cache-policy bit sc1: the load is served coherently at device scope
+    auto ld = [&](unsigned e, int sp) {
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(part, e * 4u, (unsigned)sp * total * 4u, kDeviceScope));
+    };
+    for (int id = tid; id < TB * CPR; id += NT) {
+        const int pix = b0 + id / CPR, ch = a0 + (id % CPR) * 4;
+        if (pix >= p.rowsB || ch >= p.rowsA) continue;
+        const unsigned e = (unsigned)pix * (unsigned)p.rowsA + (unsigned)ch;
+        // split order, as the separate reduction kernel adds them; four loads in flight
+        f32x4 sum = ld(e, 0);
+        int sp = 1;
+        for (; sp + 4 <= p.splits; sp += 4) {
+            const f32x4 l0 = ld(e, sp), l1 = ld(e, sp + 1), l2 = ld(e, sp + 2), l3 = ld(e, sp + 3);
+            sum += l0; sum += l1; sum += l2; sum += l3;
+        }
+        for (; sp < p.splits; ++sp) sum += ld(e, sp);
+        float v[4] = {sum.x, sum.y, sum.z, sum.w};
+        for (int i = 0; i < 4; ++i) {
+            if (p.flags & KF_BIAS) v[i] += p.bias[ch + i];
+            if (p.flags & KF_RELU) v[i] = v[i] > 0.f ? v[i] : 0.f;
+            if (p.flags & KF_MASK_IN) v[i] = mask1f(v[i], p.x[e + i]);
+        }
+        if (p.flags & KF_OUT_F32) *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(p.out) + e) = f32x4{v[0], v[1], v[2], v[3]};
+        else *reinterpret_cast<u32x2 *>(reinterpret_cast<bf16_t *>(p.out) + e) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
     }
 }
 
@@ -281,6 +333,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_fwd_dma(const KArgs p)
         store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0);
     else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+    if (p.splits > 1 && (p.flags & KF_FUSED_REDUCE)) fused_split_reduce<TA, TB, NT>(p, tile, a0, b0, tid);
 }
 
 // A matrix instruction pinned to its place in the instruction stream (kernels with one wave per SIMD order their
@@ -1059,6 +1112,7 @@ __global__ __launch_bounds__(64 * WA * WB * KG) void k_dgrad_dma(const KArgs p)
         store_staged<FA, FB, TA, TB, NT>(p, acc, reinterpret_cast<bf16_t *>(smem), bias_lds, a0, b0, arow, brow, tid, grp == 0, rowpix, steps_tile == 0);
     else if (grp == 0)
         store_pixel_major<FA, FB>(p, acc, a0 + arow, b0 + brow, lane, blockIdx.y);
+    if (p.splits > 1 && (p.flags & KF_FUSED_REDUCE)) fused_split_reduce<TA, TB, NT>(p, tile, a0, b0, tid);
 }
 
 struct DmaVariant { int TA, TB, BK, WA, WB, NS, KG = 1; };
@@ -1303,6 +1357,19 @@ bool dma_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, 
     return true;
 }
 
+bool dma_plan_is_strip(const GemmPlan &plan) { return plan.dma && !plan.halo && !plan.wstrip && is_strip(plan.variant); }
+
+// Whether this forward / backward-data plan sums its reduction splits inside the main kernel: asked for by the plan, tiles in
+// natural pixel order, and few enough tiles that a range of the counter ring is not handed out again for at least 64 later launches.
+// The fused reduction stores and loads whole groups of four channels and addresses the partial sums through one buffer descriptor.
+bool dma_fused_reduce_fits(int rowsA, int rowsB, int splits) { return (rowsA & 3) == 0 && (size_t)rowsA * rowsB * splits * 4 < ((size_t)1 << 31); }
+
+bool dma_plan_fuses_reduce(const GemmPlan &plan)
+{
+    return plan.fused_reduce && plan.dma && !plan.halo && !plan.wstrip && plan.splits > 1 && !is_strip(plan.variant) && !plan.phase &&
+           plan.tilesA * plan.tilesB <= kTicketRing / 64;
+}
+
 void dma_kernel_name(int pass, const GemmPlan &pl, char *name, size_t name_bytes)
 {
     if (pl.wstrip) { snprintf(name, name_bytes, "k_wgrad_strip"); return; }
@@ -1344,11 +1411,39 @@ hipError_t dma_launch(const ConvArgs &a, hipStream_t st)
     p.dbp = p.splits > 1 ? a.db_partial : a.db_out;
     if (!wg || p.dbp == nullptr || !plan_sums_bias_gradient(a.plan)) p.flags &= ~KF_DB;
     const DmaVariant &d = wg ? kDmaW[a.plan.variant] : kDma[a.plan.variant];
+    p.tickets = nullptr;
+    const bool fused = !wg && dma_plan_fuses_reduce(a.plan) && dma_fused_reduce_fits(p.rowsA, p.rowsB, p.splits);
+    if (fused) {
+        // counters of this launch: a range of the ring that no launch in flight is using (ranges are handed out in order; a range is
+        // reused only after kTicketRing counters have been handed out since, i.e. thousands of launches later)
+        constexpr int kMaxDev = 16;
+        static unsigned *ring_base[kMaxDev] = {};   // each device holds its own copy of the array
+        static unsigned ring_pos[kMaxDev] = {};
+        static std::mutex ring_mu;
+        const unsigned tiles = (unsigned)(p.tilesA * p.tilesB);
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= kMaxDev) return hipErrorInvalidDevice;
+        unsigned start;
+        {
+            std::lock_guard<std::mutex> lock(ring_mu);
+            if (ring_base[dev] == nullptr) {
+                e = hipGetSymbolAddress((void **)&ring_base[dev], HIP_SYMBOL(g_tickets));
+                if (e != hipSuccess) return e;
+            }
+            if (ring_pos[dev] + tiles > (unsigned)kTicketRing) ring_pos[dev] = 0;
+            start = ring_pos[dev];
+            ring_pos[dev] += tiles;
+        }
+        p.tickets = ring_base[dev] + start;
+        p.flags |= KF_FUSED_REDUCE;
+    }
     dim3 grid((unsigned)(p.tilesA * p.tilesB), (unsigned)p.splits, 1), block(64 * d.WA * d.WB * d.KG, 1, 1);
     if (wg) grid = dim3((unsigned)p.splits, (unsigned)(p.tilesA * p.tilesB), 1);
     hipLaunchKernelGGL(wg ? pick_dma_w(a.plan.variant) : a.pass == PASS_DGRAD ? pick_dma_d(a.plan.variant) : pick_dma(a.plan.variant), grid, block, wg ? dma_w_lds_bytes(d) : dma_lds_bytes(d), st, p);
     dp_trace_main_kernel_done(st);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || p.splits <= 1) return e;
+    if (e != hipSuccess || p.splits <= 1 || fused) return e;
     return launch_split_reduce(a, p.rowsA, p.rowsB, st, (p.flags & KF_DB) != 0);
 }

@@ -209,6 +209,16 @@ void plan_uncached(const ConvGeom &g, int pass, int fv, int fs, GemmPlan *pl, in
     pl->dma = false;
     pl->halo = false;
     pl->wstrip = false;
+    pl->fused_reduce = false;
+    // 1000 + v: variant v with the split reduction fused into the main kernel (pipelined forward / backward-data).  Only a forced
+    // variant asks for it: in a chain of calls it measured no faster than the second kernel it saves (-0.2 .. +3.5 us per call),
+    // because partial sums cross compute dies through memory (write-through stores, a device-scope counter, device-scope loads)
+    if (fv >= 1000) {
+        plan_uncached(g, pass, fv - 1000, fs, pl, restr);
+        const int rowsA = pass == PASS_FWD ? g.K : g.C, rowsB = pass == PASS_FWD ? g.N * g.Ho * g.Wo : g.N * g.H * g.W;
+        pl->fused_reduce = pass != PASS_WGRAD && pl->dma && !pl->halo && pl->splits > 1 && dma_fused_reduce_fits(rowsA, rowsB, pl->splits);
+        return;
+    }
     if (fv < 0 && auto_plan(g, pass, fs, pl, restr)) return;
     // a forced input-patch variant the call may not use falls through to the next family
     const bool patch_banned = pass != PASS_WGRAD && (restr & 1);
@@ -414,7 +424,7 @@ hipError_t launch_entry(ConvArgs &a, PlanEntry &pe, hipStream_t st, TraceScope &
     if (ts.idx >= 0) {
         char nm[96];
         plan_kernel_name(a.pass, a.plan, (a.flags & KF_MASK_IN) != 0, nm, sizeof(nm));
-        ts.name(nm, a.plan.splits);
+        ts.name(nm, a.pass != PASS_WGRAD && dma_plan_fuses_reduce(a.plan) ? -a.plan.splits : a.plan.splits);
     }
     if (prep) {
         hipError_t e = prep(a);
@@ -788,7 +798,7 @@ dp_status dp_conv2d_kernel_info(const dp_conv_desc *desc, int pass, char *name, 
     if (pass != PASS_DGRAD && use_small_c(g, pass)) g = im2col_geom(g, small_c_kpad(g));
     const GemmPlan pl = current_plan(*plan_entry(g, pass, pass == PASS_DGRAD ? dgrad_restr(desc->flags) : 0));
     if (name != nullptr && name_bytes > 0) plan_kernel_name(pass, pl, pass == PASS_DGRAD && (desc->flags & DP_RELU_IN) != 0, name, name_bytes);
-    if (splits != nullptr) *splits = pl.splits;
+    if (splits != nullptr) *splits = pass != PASS_WGRAD && dma_plan_fuses_reduce(pl) ? -pl.splits : pl.splits;
     return DP_OK;
 }
 

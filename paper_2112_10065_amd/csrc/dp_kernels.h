@@ -14,6 +14,7 @@ enum : unsigned {
     KF_MASK_IN = 8u,  // backward-data: dx *= [x > 0], x = the layer's saved input (output of the preceding ReLU)
     KF_NT_A = 32u,    // forward / backward-data: every weight is read by one block only (a single pixel tile): non-temporal loads, the stream leaves the caches alone
     KF_NT_OUT = 64u,  // backward-filter: a large gradient written once: non-temporal stores
+    KF_FUSED_REDUCE = 256u,  // forward / backward-data with a reduction split: the block that finishes a tile last adds the splits' partial sums itself
 };
 
 enum { PASS_FWD = 0, PASS_DGRAD = 1, PASS_WGRAD = 2 };
@@ -42,6 +43,7 @@ struct GemmPlan {
     bool phase = false;   // strided backward-data walks the input pixels stride phase by stride phase (conv_dma.hip)
     bool wstrip = false;  // filter gradient with the x strip shared by the taps of a filter row (conv_wstrip.hip); implies dma
     bool db_wave = false; // input-patch filter gradient: one more wave per block can sum the bias gradient (at most 15 taps)
+    bool fused_reduce = false;   // pipelined forward / backward-data with splits > 1: no second kernel, the last block of a tile reduces (conv_dma.hip)
 };
 
 struct ConvArgs {
@@ -99,6 +101,9 @@ void dma_kernel_name(int pass, const GemmPlan &plan, char *name, size_t name_byt
 hipError_t halo_init();
 bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *plan);
 hipError_t halo_launch(const ConvArgs &a, hipStream_t st);
+bool dma_plan_is_strip(const GemmPlan &plan);   // the pixel-strip forward / backward-data kernels (no fused split reduction)
+bool dma_fused_reduce_fits(int rowsA, int rowsB, int splits);
+bool dma_plan_fuses_reduce(const GemmPlan &plan);   // the splits are summed by the main kernel: no reduction kernel follows
 void halo_kernel_name(int pass, const GemmPlan &plan, bool masked, char *name, size_t name_bytes);   // masked: backward-data with the fused input-ReLU mask
 
 // conv_fp32.hip : plain fp32 FMA kernels (reference-precision path)

@@ -23,6 +23,7 @@ struct KArgs {
     void *out;
     float *partial;
     float *dbp;   // KF_DB: bias-gradient sums of split s go to dbp[s * rowsA + row]
+    unsigned *tickets;   // KF_FUSED_REDUCE: one arrival counter per tile, zero before and after the launch
     // strided backward-data by phase: the B rows (input pixels) are enumerated phase by phase, phase (a, b) = (h % sh,
     // w % sw), each padded to whole tiles; B tiles ph_tile0[c] .. ph_tile0[c+1]-1 belong to phase c = a*sw + b
     int ph_on;
@@ -107,6 +108,10 @@ DEVFN void mma_step(const bf16_t *As, const bf16_t *Bs, int arow, int brow, int 
 
 // Accumulator element v of lane l belongs to D row 8*(v/4) + 4*(l>>5) + v%4, column l&31.
 
+// A 16-byte store written through to memory at device scope: blocks on other compute dies (each die has an L2 of its
+// own) read it with device-scope loads, and neither side has to write back or invalidate a whole cache.
+DEVFN void store_f32x4_device_scope(float *dst, f32x4 v) { asm volatile("global_store_dwordx4 %0, %1, off sc1" : : "v"(dst), "v"(v) : "memory"); }
+
 // Epilogue for fwd / dgrad: out[j][i] (pixel-major, channel contiguous).
 template <int FA, int FB>
 DEVFN void store_pixel_major(const KArgs &p, const f32x16 (&acc)[FA][FB], int arow0, int brow0, int lane, int split)
@@ -127,7 +132,8 @@ DEVFN void store_pixel_major(const KArgs &p, const f32x16 (&acc)[FA][FB], int ar
                 const size_t o = (size_t)pix * p.rowsA + ch;
                 if (to_partial) {
                     float *dst = p.partial + (size_t)split * p.rowsB * p.rowsA + o;
-                    if (vec4) *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+                    if (p.flags & KF_FUSED_REDUCE) store_f32x4_device_scope(dst, f32x4{v[0], v[1], v[2], v[3]});   // rowsA % 4 == 0
+                    else if (vec4) *reinterpret_cast<f32x4 *>(dst) = f32x4{v[0], v[1], v[2], v[3]};
                     else
                         for (int e = 0; e < 4; ++e) if (ch + e < p.rowsA) dst[e] = v[e];
                     continue;

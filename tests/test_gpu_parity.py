@@ -179,6 +179,46 @@ def test_pipelined_forward_variants(env, variant, splits):
         dp.dp_set_override(1, -1, 0)
 
 
+@pytest.mark.parametrize("variant", [200, 203, 207, 210, 214, 219, 221, 226, 227, 229])
+@pytest.mark.parametrize("splits", [2, 5])
+def test_split_reduction_fused_into_the_pipelined_kernels(env, variant, splits):
+    """Forced variant 1000 + v: the last block that finishes a tile sums the splits' partial tiles itself (in split
+    order, so the result equals the two-kernel path bit for bit) and applies bias / ReLU / the input-ReLU mask.
+    Two calls in a row per case: the tile counters return to zero after a call."""
+    dp, U, orc = env
+    for tag, n, h, w, c, k, r, s_, pd, f32 in (("fr_a", 2, 13, 12, 128, 192, 3, 3, (1, 1), False), ("fr_b", 1, 9, 9, 256, 200, 1, 1, (0, 0), True),
+                                               ("fr_c", 3, 10, 17, 128, 264, 1, 7, (0, 3), False), ("fr_d", 1, 14, 14, 512, 512, 3, 3, (1, 1), True)):
+        if 221 <= variant <= 225 and c % 128 != 0:
+            continue   # these variants reduce 128 channels per step
+        case = U.ConvCase(tag, n, h, w, c, k, r, s_, (1, 1), pd, bf16=True, bias=True, relu=True, dx_f32=f32)
+        out, plain = {}, {}
+        for fused in (0, 1000):
+            dp.dp_set_override(0, variant + fused, splits)
+            dp.dp_set_override(1, variant + fused, splits)
+            try:
+                for p in (0, 1):   # a negative split count reports that no reduction kernel follows
+                    nm, sp = dp.dp_conv2d_kernel_info(case.desc, p)
+                    if not fused:
+                        plain[p] = sp   # the planner may lower the forced split count to one that divides the reduction steps
+                    assert "_dma" in nm or p == 1, nm
+                    assert sp == (-plain[p] if fused and "_dma" in nm and plain[p] > 1 else plain[p]), (nm, sp, plain[p])
+                ys = [case.run_fwd() for _ in range(2)]
+                dxs = [case.run_dgrad(ys[0]) for _ in range(2)]
+                dxm = case.run_dgrad_relu_in(ys[0])
+                torch.cuda.synchronize()
+            finally:
+                dp.dp_set_override(0, -1, 0)
+                dp.dp_set_override(1, -1, 0)
+            assert torch.equal(ys[0], ys[1]) and torch.equal(dxs[0], dxs[1]), f"{tag} {variant} second call differs"
+            out[fused] = (ys[0], dxs[0], dxm)
+        for a, b, what in zip(out[0], out[1000], ("y", "dx", "dx masked")):
+            assert torch.equal(a, b), f"{tag} variant {variant} splits {splits}: fused {what} differs from the two-kernel path"
+        y, dx, dxm = out[1000]
+        U.assert_bf16_close(U.to_np(y), orc.conv2d_fwd(case.x, case.w, case.b, relu=True, stride=(1, 1), pad=pd), f"{tag} fused y")
+        ref = orc.conv2d_bwd_data(case.dy, case.w, case.x.shape, y_saved=U.to_np(y), pad=pd)
+        U.assert_bf16_close(U.to_np(dx), ref, f"{tag} fused dx")
+
+
 @pytest.mark.parametrize("tag,n,h,w,c,k,r,s_,st,pd", [
     ("sd_3x3_s2", 2, 15, 15, 64, 64, 3, 3, (2, 2), (1, 1)), ("sd_1x1_s2", 1, 14, 17, 128, 128, 1, 1, (2, 2), (0, 0)),
     ("sd_3x3_s21", 2, 13, 12, 64, 192, 3, 3, (2, 1), (1, 0)), ("sd_5x5_s3", 1, 20, 20, 256, 128, 5, 5, (3, 3), (2, 2))])
