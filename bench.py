@@ -31,74 +31,74 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 289626365,
-    "k_reduce_flat@32": 58348007,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 289954311,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 220552528,
-    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@32": 237232766,
-    "k_reduce_pixel_major@32": 28535037,
-    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 203416331,
-    "k_wgrad_halo@32": 356322073,
-    "k_conv_strip<false, 224, 256>@32": 121464930,
-    "k_conv_strip<true, 224, 256>@32": 172665460,
-    "k_halo_ws<0, false>@32": 320303005,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 190249525,
-    "k_conv_strip<true, 256, 128>@32": 161582658,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 140099449,
-    "k_conv_strip<false, 256, 128>@32": 149103838,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 114872711,
-    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@32": 112078232,
-    "k_halo<1, 64, 1, 4, 2>@32": 619286555,
-    "k_halo<1, 64, 1, 4, 4>@32": 619504139,
-    "k_dgrad_dma<128, 128, 64, 2, 2, 2, 1>@32": 195901527,
-    "k_conv_strip<true, 128, 256>@32": 142692543,
-    "k_reduce_flat_wide@32": 49395331,
-    "k_conv_fast<1, 128, 128, 64, 2, 2>@32": 285179828,
-    "k_conv_fast<0, 64, 64, 64, 2, 2>@32": 82629118,
-    "k_fwd_rgb3@32": 230236655,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@32": 99618234,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 85034073,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@32": 63499926,
-    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@32": 142651242,
-    "k_wgrad_rgb3<true>@32": 238235741,
-    "k_dense_wgrad<true>@32": 69702737,
-    "k_dense_wgrad<false>@32": 18709959,
-    "k_dense_dgrad@32": 9297704,
-    "k_wgrad_direct_sum@32": 4291677,
-    "k_wgrad_dma<64, 256, 32, 1, 4, 2>@2": 183175865,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 85949643,
-    "k_reduce_flat@2": 28625118,
-    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 40392554,
-    "k_reduce_flat_wide@2": 22528283,
-    "k_reduce_pixel_major@2": 9932329,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 58676634,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@2": 38264590,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 46317496,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 45921769,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@2": 55935093,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 29562768,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@2": 32120620,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@2": 27842193,
-    "k_wgrad_halo@2": 49657811,
-    "k_dense_fwd<1>@2": 82874972,
-    "k_conv_fast<1, 128, 64, 64, 2, 2>@2": 95191771,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 34003456,
-    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@2": 27785558,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 24253019,
-    "k_dense_wgrad<true>@2": 67496608,
-    "k_halo<1, 64, 1, 4, 2>@2": 39676365,
-    "k_dgrad_dma<64, 128, 128, 2, 2, 2, 1>@2": 19445550,
-    "k_halo_ws<0, false>@2": 24315960,
-    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 23563069,
-    "k_dgrad_dma<64, 64, 128, 2, 2, 4, 1>@2": 17969413,
-    "k_halo<0, 64, 1, 4, 4>@2": 21984151,
-    "k_fwd_dma<64, 128, 128, 2, 2, 2, 1>@2": 14826761,
-    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@2": 19756098,
-    "k_halo<0, 64, 1, 4, 3>@2": 16135252,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 292166726,
+    "k_reduce_flat@32": 59177597,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 311512317,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@32": 349159431,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 245755089,
+    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 175914295,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@32": 236775251,
+    "k_reduce_pixel_major@32": 27067309,
+    "k_wgrad_halo@32": 356320132,
+    "k_conv_strip<false, 224, 256>@32": 121523161,
+    "k_conv_strip<true, 224, 256>@32": 172522189,
+    "k_halo_ws<0, false>@32": 320329866,
+    "k_halo_ws<1, true>@32": 678097602,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 186712219,
+    "k_conv_strip<true, 256, 128>@32": 161931569,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@32": 123062843,
+    "k_conv_strip<false, 256, 128>@32": 144831730,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 86909480,
+    "k_dgrad_dma<128, 128, 64, 2, 2, 2, 1>@32": 209538077,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>@32": 147559862,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@32": 104632812,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 121950489,
+    "k_conv_strip<true, 128, 256>@32": 131765893,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 147700113,
+    "k_reduce_flat_wide@32": 49399695,
+    "k_conv_fast<1, 128, 128, 64, 2, 2>@32": 267919079,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 123202706,
+    "k_fwd_rgb3@32": 230265277,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@32": 96432035,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 142648740,
+    "k_wgrad_rgb3<true>@32": 220896620,
+    "k_fwd_dma<128, 64, 128, 2, 2, 2, 1>@32": 131473680,
+    "k_dense_wgrad<true>@32": 69695529,
+    "k_dense_wgrad<false>@32": 18709958,
+    "k_dense_dgrad@32": 9297701,
+    "k_wgrad_direct_sum@32": 4291675,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 118579870,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 83104274,
+    "k_reduce_flat@2": 27657927,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 39858096,
+    "k_reduce_flat_wide@2": 21516291,
+    "k_reduce_pixel_major@2": 10429436,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 70597911,
+    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 38257156,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 41862906,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@2": 39336378,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 47885394,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 44863280,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@2": 49187726,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 26715171,
+    "k_wgrad_halo@2": 48704436,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 34709053,
+    "k_conv_fast<0, 64, 64, 64, 2, 2>@2": 28063315,
+    "k_dense_fwd<1>@2": 82874960,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 27926419,
+    "k_dense_wgrad<true>@2": 67475016,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 2>@2": 21713497,
+    "k_halo_ws<0, false>@2": 21626928,
+    "k_conv_fast<0, 64, 128, 64, 2, 2>@2": 14139832,
+    "k_halo<1, 64, 1, 4, 2>@2": 39676357,
+    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 24406529,
+    "k_halo_ws<1, true>@2": 43203345,
+    "k_halo<0, 64, 1, 4, 3>@2": 23053543,
     "k_dense_wgrad<false>@2": 16628633,
-    "k_fwd_rgb3@2": 14118188,
-    "k_wgrad_rgb3<true>@2": 15733113,
-    "k_dense_dgrad@2": 8326932,
+    "k_fwd_rgb3@2": 14118215,
+    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@2": 17866713,
+    "k_wgrad_rgb3<true>@2": 15733104,
+    "k_dense_dgrad@2": 8326931,
     "k_wgrad_direct_sum@2": 1706703,
 }
 
