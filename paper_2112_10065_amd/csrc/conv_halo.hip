@@ -10,6 +10,7 @@
 // chunk position c ^ ((pp >> 1) & 7) (two 128-byte rows span the 64 banks), which makes the fragment reads of 32 consecutive pixels conflict-free.
 // A direct-to-LDS instruction fills 8 consecutive patch pixels.
 #include "dma_common.h"
+#include <utility>
 #include <cstdio>
 
 namespace {
@@ -432,6 +433,275 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
 }
 
 // ---------------------------------------------------------------------------------------
+// The 3x3 form of the kernel above with all nine taps in ONE wave.  With a wave per tap every wave reads
+// the same dy fragments and one x fragment per matrix instruction: 1 KB of LDS reads per matrix
+// instruction, which is the LDS port's whole bandwidth at the matrix cores' full rate, and ten waves sit
+// 3-3-2-2 on the SIMDs.  Here a block has four waves, one per SIMD: wave (pg, ch) takes every second
+// 16-pixel slice of the tile (pixel group pg) and c_in half ch for all 64 output channels and all nine
+// taps (18 accumulator tiles, 288 registers): per slice it reads the two dy fragments once and one x
+// fragment per tap, 11 fragments for 18 matrix instructions (0.61 KB each), and the four SIMDs carry
+// the same load.  The (slice, tap) pairs form one stream of items; the transpose reads of item i+4 are
+// issued before the matrix instructions of item i (ring of six x fragments, two dy fragment pairs; at
+// most 14 reads in flight, the counter holds 15).  The two pixel groups' sums meet in LDS once, at the
+// end of the kernel.  The bias gradient (dy x ones) rides in the ch = 0 waves, two more matrix
+// instructions per slice.  Tile walk, LDS layout, copies and the per-block partial are the kernel's above.
+// ---------------------------------------------------------------------------------------
+// The matrix instruction with its accumulator pinned to the accumulation registers (AG) or to the vector registers: 18 + 2
+// accumulator tiles are 320 registers, more than the 256 accumulation registers, and the compiler, left to itself, keeps them all
+// there and copies tiles back and forth around every instruction (six copies per matrix instruction).  The caller spaces reads of
+// a result from the instruction that wrote it (the compiler does not see an instruction it would have to wait for).
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression in the body
+template <typename F, int... I> DEVFN void for_constant_impl(F &&f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, typename F> DEVFN void for_constant(F &&f) { for_constant_impl(f, std::make_integer_sequence<int, N>{}); }
+
+template <int OFF, bool AG> DEVFN void lds_write_f32(unsigned addr, float v)   // AG: the value sits in an accumulation register
+{
+    if constexpr (AG) asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(addr), "a"(v), "n"(OFF) : "memory");
+    else asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(addr), "v"(v), "n"(OFF) : "memory");
+}
+template <int OFF> DEVFN float lds_read_f32(unsigned addr)
+{
+    float v;
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+
+template <bool AG> DEVFN void mfma_pinned(f32x16 &c, const u32x4 a, const u32x4 b)
+{
+    // s_nop 1: a vector instruction the compiler placed just before (a copy or a rematerialised constant that feeds an operand) needs
+    // two wait states before a matrix instruction reads its result; the compiler adds them only for instructions it knows
+    if constexpr (AG) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+
+template <bool DB>
+__global__ __launch_bounds__(256) void k_wgrad_halo9(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const ConvGeom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int pg = wave >> 1, ch = wave & 1;
+    const int TW = 1 << tws, TH = HALO_TB >> tws, PW = TW + 2, PP = (TH + 2) * PW;
+    const int a0 = blockIdx.y * 64;
+    const unsigned smem_base = lds_offset(smem);
+    __amdgpu_buffer_rsrc_t rdy = make_rsrc(p.dy, (size_t)g.N * g.Ho * g.Wo * g.K * 2);
+    __amdgpu_buffer_rsrc_t rx = make_rsrc(p.x, (size_t)g.N * g.H * g.W * g.C * 2);
+    // Copies of a tile (8 LDS rows each): 44 of the patch, 32 of the dy slice; wave w issues patch copies w, w+4, ... and dy copies
+    // w, w+4, ...  One wave per SIMD has nobody to hide the address arithmetic behind, so everything that does not depend on the
+    // tile is computed once: the byte offset of the lane's 16 bytes relative to the tile's first patch / dy pixel and the pixel's
+    // row and column in the patch / tile (packed; 0xffff rows mark lanes that never copy).  Per tile and copy that leaves two range
+    // checks and an addition, and the copies of the next tile are dealt out over the items of this one.
+    constexpr int NCP = HALO_PP / 8 / 4, NCD = HALO_TB / 8 / 4;
+    static_assert(NCP * 32 == HALO_PP && NCD * 32 == HALO_TB, "the copies divide evenly over the four waves");
+    unsigned xrel[NCP], xrc[NCP], drel[NCD], drc[NCD];
+#pragma unroll
+    for (int c = 0; c < NCP; ++c) {
+        const int pp = (wave + 4 * c) * 8 + (lane >> 3), chunk = (lane & 7) ^ (seg_swz<64>(pp) << 2);
+        const int pr = pp / PW, pc = pp - pr * PW;
+        xrel[c] = (unsigned)((pr * g.W + pc) * 64 + chunk * 8) * 2u;
+        xrc[c] = pp < PP ? (unsigned)(pr << 16 | pc) : 0xffff0000u;
+    }
+#pragma unroll
+    for (int c = 0; c < NCD; ++c) {
+        const int j = (wave + 4 * c) * 8 + (lane >> 3), chunk = (lane & 7) ^ (seg_swz<64>(j) << 2);
+        const int jr = j >> tws, jc = j & (TW - 1);
+        drel[c] = (unsigned)((jr * g.Wo + jc) * g.K + a0 + chunk * 8) * 2u;
+        drc[c] = a0 + chunk * 8 + 8 <= g.K ? (unsigned)(jr << 16 | jc) : 0xffff0000u;
+    }
+    // tile-dependent part, wave-uniform: first patch / dy pixel of the tile as byte offsets (the patch origin may lie outside the
+    // image: the sum wraps, and wraps back for every pixel that passes the range checks), and the tile's position
+    int nt_p0 = 0, nt_q0 = 0;
+    unsigned nt_xbase = 0, nt_dbase = 0, nt_lds = 0;
+    auto set_tile = [&](int tile, int buf) {
+        const int n = tile / (tiles_x * tiles_y), trem = tile - n * (tiles_x * tiles_y), ty = trem / tiles_x, tx = trem - ty * tiles_x;
+        nt_p0 = ty * TH; nt_q0 = tx * TW;
+        nt_xbase = (unsigned)(((n * g.H + nt_p0 - g.ph) * g.W + nt_q0 - g.pw) * 64) * 2u;
+        nt_dbase = (unsigned)(((n * g.Ho + nt_p0) * g.Wo + nt_q0) * g.K) * 2u;
+        nt_lds = smem_base + buf * WH_BUF;
+    };
+    auto issue_copy = [&](int c) {   // c: 0 .. NCP-1 patch copies, then NCD dy copies (compile-time)
+        if (c < NCP) {
+            const int ih = nt_p0 - g.ph + (int)(xrc[c] >> 16), iw = nt_q0 - g.pw + (int)(xrc[c] & 0xffffu);
+            const bool ok = (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
+            dma16(rx, nt_lds + (wave + 4 * c) * 1024, ok ? nt_xbase + xrel[c] : OOR);
+        } else {
+            const int d = c - NCP;
+            const bool ok = nt_p0 + (int)(drc[d] >> 16) < g.Ho && nt_q0 + (int)(drc[d] & 0xffffu) < g.Wo;
+            dma16(rdy, nt_lds + HALO_PP * 128 + (wave + 4 * d) * 1024, ok ? nt_dbase + drel[d] : OOR);
+        }
+    };
+
+    f32x16 acc[9][2];   // [tap][c_out half]
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[t][i][v] = 0.f;
+    f32x16 accdb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) accdb[i][v] = 0.f;
+    const bool do_db = DB && ch == 0;   // wave-uniform
+    const u32x4 ones = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};   // bf16 1.0 in every element
+
+    // transpose-read lane roles: reduction row tl (+4 for the second read), operand columns cl .. cl+3
+    const int i16 = lane & 15, tl = (lane >> 5) * 8 + (i16 >> 2), cl = ((lane >> 4) & 1) * 16 + (i16 & 3) * 4;
+    unsigned a_lane[2];   // dy: row tl of slice 0, column half i; later slices add 16 rows = 2048 bytes
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int col = i * 32 + cl;
+        a_lane[i] = HALO_PP * 128 + tl * 128 + ((((col >> 5) ^ seg_swz<64>(tl)) << 6) | ((col & 31) << 1));
+    }
+    const unsigned x_lane = (unsigned)(ch << 6) | (unsigned)(cl << 1);   // segment ch, columns cl .. cl+3 (the segment bit is swizzled per row)
+    int toff[9];   // patch pixels between tap (0,0) and tap t: wave-uniform
+#pragma unroll
+    for (int t = 0; t < 9; ++t) toff[t] = (t / 3) * PW + (t % 3);
+
+    u32x2 xlo[6], xhi[6], dlo[2][2], dhi[2][2];
+    // q: index of this wave's slice (slice pg + 2q of the tile); reads of one item: the x fragment of tap t of that slice
+    auto read_dy = [&](unsigned base, int q, int buf) {
+        const unsigned off = base + (unsigned)(pg + 2 * q) * 2048u;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            dlo[buf][i] = lds_read_tr<0>(off + a_lane[i]);
+            dhi[buf][i] = lds_read_tr<4 * 128>(off + a_lane[i]);
+        }
+    };
+    int tlv = tl;   // the lane's reduction row, made opaque once per slice: the fragment addresses are a few vector instructions per item,
+                    // and computed per item they cost no registers, whereas the compiler would hoist all 72 of a tile (and spill)
+    auto read_x = [&](unsigned base, int q, int t, int slot) {
+        const int j = (pg + 2 * q) * 16 + tlv;
+        const unsigned pp = (unsigned)((j >> tws) * PW + (j & (TW - 1)) + toff[t]);
+        const unsigned addr = base + (pp << 7) + (x_lane ^ ((pp & 2u) << 5));
+        xlo[slot] = lds_read_tr<0>(addr);
+        xhi[slot] = lds_read_tr<4 * 128>(addr);
+    };
+
+    int tile = blockIdx.x;
+    if (tile < tiles) {
+        set_tile(tile, 0);
+#pragma unroll
+        for (int c = 0; c < NCP + NCD; ++c) issue_copy(c);
+    }
+    for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();   // tile `it` has landed everywhere; the other buffer is no longer read
+        const bool more = tile + (int)gridDim.x < tiles;   // wave-uniform
+        if (more) set_tile(tile + gridDim.x, (it + 1) & 1);
+        const unsigned base = smem_base + (it & 1) * WH_BUF;
+        read_dy(base, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) read_x(base, 0, t, t);
+        for_constant<72>([&](auto ic) {   // every index below is a compile-time constant: registers, not indexed arrays
+            constexpr int i = decltype(ic)::value;
+            // reads of item i+4; past the tile's end the stream re-reads the last slice (never multiplied)
+            constexpr int j = i + 4, jq = j < 72 ? j / 9 : 7, jt = j % 9;
+            if constexpr (jt == 0) {
+                asm volatile("" : "+v"(tlv));
+                read_dy(base, jq, (j / 9) & 1);
+            }
+            read_x(base, jq, jt, j % 6);
+            // reads issued after item i's own: items i+1 .. i+4, two each, four more where a slice begins
+            constexpr int ti = i % 9;
+            if constexpr (ti >= 5) asm volatile("s_waitcnt lgkmcnt(12)");
+            else asm volatile("s_waitcnt lgkmcnt(8)");
+            constexpr int s6 = i % 6, db = (i / 9) & 1;
+            asm volatile("" : "+v"(xlo[s6])); asm volatile("" : "+v"(xhi[s6]));
+#pragma unroll
+            for (int k = 0; k < 2; ++k) { asm volatile("" : "+v"(dlo[db][k])); asm volatile("" : "+v"(dhi[db][k])); }
+            const u32x4 bv = {xlo[s6].x, xlo[s6].y, xhi[s6].x, xhi[s6].y};
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const u32x4 av = {dlo[db][k].x, dlo[db][k].y, dhi[db][k].x, dhi[db][k].y};
+                if constexpr (ti < 8) mfma_pinned<true>(acc[ti][k], av, bv);    // taps 0-7: the 256 accumulation registers
+                else mfma_pinned<false>(acc[ti][k], av, bv);                    // tap 8 and the bias gradient: vector registers
+            }
+            if constexpr (ti == 0) {
+                if (do_db) {
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {
+                        const u32x4 av = {dlo[db][k].x, dlo[db][k].y, dhi[db][k].x, dhi[db][k].y};
+                        mfma_pinned<false>(accdb[k], av, ones);
+                    }
+                }
+            }
+            // one copy of the next tile after each of the first 19 items: memory latency under load is a good part of a tile's time
+            // (issued after every second item: 170 us instead of 162 for conv1_2 at batch 32; two per item: no faster)
+            if constexpr (i < NCP + NCD) { if (more) issue_copy(i); }
+        });
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // the stream's reads past the end have returned
+    }
+    // the last matrix instructions have written their results before anything reads them (16 passes of 4 clocks)
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+
+    // Epilogue, one round per half of the 64 output channels (nine accumulator tiles and one bias-gradient tile per wave): pixel
+    // group 1 puts its tiles into an exchange area (lane-major: no bank conflicts), pixel group 0 adds its own and writes the sums in
+    // the partial's layout [32 c_out][9 taps x 64 c_in] into the result area, and all four waves copy that out, 16 bytes per lane and
+    // whole rows at a time.  The sums never go back into the accumulators (with all 320 of them live, adding in place made the
+    // compiler spill accumulators; LDS float atomics instead of the exchange measured 30 us slower per block; storing from registers,
+    // 4 bytes per lane with an address pair per store, spilled too).  The two areas (80 KB + 72 KB) are the 152 KB the tile buffers
+    // held; they swap ends between the rounds.  Accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+    constexpr int kXchBytes = 2 * 10 * 16 * 64 * 4, kResBytes = 32 * 576 * 4;
+    static_assert(kXchBytes + kResBytes <= 2 * WH_BUF, "exchange and result areas fit in the two tile buffers");
+    // The LDS traffic of the exchange is inline assembly: volatile statements keep their order, so at most one tile's values are in
+    // flight and the register allocator has nothing to spill.
+    for_constant<2>([&](auto ic) {
+        constexpr int i = decltype(ic)::value;
+        const unsigned xaddr = smem_base + (i == 0 ? kResBytes : 0) + ch * (10 * 16 * 256) + lane * 4;   // this lane's column of the exchange area
+        float *res = reinterpret_cast<float *>(smem + (i == 0 ? 0 : kXchBytes));
+        const unsigned raddr = smem_base + (i == 0 ? 0 : kXchBytes) + (unsigned)((4 * (lane >> 5)) * 576 + ch * 32 + (lane & 31)) * 4u;
+        __syncthreads();   // round 0: every wave is past its last tile; round 1: the first half has been copied out
+        if (pg == 1) {
+            for_constant<10>([&](auto fc) {
+                constexpr int f = decltype(fc)::value;
+                const f32x16 &src = f < 9 ? acc[f < 9 ? f : 0][i] : accdb[i];
+                for_constant<16>([&](auto vc) {
+                    constexpr int v = decltype(vc)::value;
+                    lds_write_f32<(f * 16 + v) * 256, (f < 8)>(xaddr, src[v]);   // taps 0-7 straight from the accumulation registers
+                });
+            });
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
+        if (pg == 0) {
+            for_constant<10>([&](auto fc) {
+                constexpr int f = decltype(fc)::value;
+                if (f == 9 && !(do_db && p.dbp != nullptr)) return;
+                const f32x16 &mine = f < 9 ? acc[f < 9 ? f : 0][i] : accdb[i];
+                f32x16 sum;
+                for_constant<2>([&](auto hc) {   // eight values at a time (the counter of LDS operations in flight holds 15)
+                    constexpr int h = decltype(hc)::value;
+                    float tv[8];
+                    for_constant<8>([&](auto vc) {
+                        constexpr int w = decltype(vc)::value;
+                        tv[w] = lds_read_f32<(f * 16 + h * 8 + w) * 256>(xaddr);
+                    });
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    for_constant<8>([&](auto vc) {
+                        constexpr int w = decltype(vc)::value, v = h * 8 + w;
+                        asm volatile("" : "+v"(tv[w]));
+                        float mv = mine[v];
+                        if (f < 8) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(mv) : "a"(mine[v]));   // in order: read early, these get spilled
+                        sum[v] = mv + tv[w];
+                        if (f < 9) lds_write_f32<((8 * (v >> 2) + (v & 3)) * 576 + (f < 9 ? f : 0) * 64) * 4, false>(raddr, sum[v]);
+                    });
+                });
+                if (f == 9) store_db_fragment(sum, p.dbp + (size_t)blockIdx.x * p.rowsA, a0 + i * 32, p.rowsA, lane);
+            });
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __syncthreads();
+        // partial[block][c_out][tap][c_in]: rows a0 + 32 i .. + 31 of it, 144 chunks of 16 bytes per row
+        float *out = p.partial + ((size_t)blockIdx.x * p.rowsA + a0 + 32 * i) * 576;
+        const int rows = min(32, p.rowsA - a0 - 32 * i);
+        for (int c = tid; c < rows * 144; c += 256)
+            *reinterpret_cast<f32x4 *>(out + (size_t)c * 4) = *reinterpret_cast<const f32x4 *>(res + c * 4);
+    });
+}
+
+// ---------------------------------------------------------------------------------------
 // 3x3 (nine-tap) forward / backward-data with 64 reduction channels per tap, weights stationary in
 // REGISTERS.  A block has four waves, one per SIMD, so each may use the whole register file: a wave
 // keeps the fragments of all 64 output channels for all nine taps (72 fragments, 288 registers) and
@@ -767,6 +1037,10 @@ hipError_t halo_init()
 {
     {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_wgrad_halo), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WH_BUF);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_wgrad_halo9<true>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WH_BUF);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_wgrad_halo9<false>), hipFuncAttributeMaxDynamicSharedMemorySize, 2 * WH_BUF);
         if (e != hipSuccess) return e;
     }
     {
@@ -789,8 +1063,9 @@ hipError_t halo_init()
 // variant override 400 + v; forward needs c_in == 64, backward-data c_out == 64; stride 1; no reduction split
 bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits, GemmPlan *pl)
 {
-    if (pass == PASS_WGRAD) {   // 410: input-patch filter gradient; force_splits = number of persistent blocks
-        if (force_variant != 410 || g.sh != 1 || g.sw != 1 || g.C != 64 || (g.K % 8) != 0 || g.R * g.S > 16) return false;
+    if (pass == PASS_WGRAD) {   // 410: input-patch filter gradient, a wave per tap; 411: 3x3, all taps per wave; force_splits = number of persistent blocks
+        if ((force_variant != 410 && force_variant != 411) || g.sh != 1 || g.sw != 1 || g.C != 64 || (g.K % 8) != 0 || g.R * g.S > 16) return false;
+        if (force_variant == 411 && (g.R != 3 || g.S != 3)) return false;
         const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
         if ((th + g.R - 1) * (tw + g.S - 1) > HALO_PP) return false;
         const long long tiles = (long long)g.N * ((g.Ho + th - 1) / th) * ((g.Wo + tw - 1) / tw);
@@ -798,8 +1073,8 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
         int blocks = force_splits > 1 ? force_splits : 256 / ktiles;   // default: one persistent block per CU
         if (blocks > tiles) blocks = (int)tiles;
         if (blocks < 2) return false;   // the split-reduce kernel writes the result
-        pl->variant = 10;
-        pl->db_wave = g.R * g.S <= 15;   // 16 waves per block at most
+        pl->variant = force_variant - 400;
+        pl->db_wave = force_variant == 411 || g.R * g.S <= 15;   // 16 waves per block at most; the nine-tap kernel sums it in its own waves
         pl->fast = true; pl->dma = true; pl->halo = true;
         pl->TA = 64; pl->TB = 64 * g.R * g.S; pl->BK = 16; pl->vecA = pl->vecB = true;
         pl->tilesA = ktiles; pl->tilesB = 1;
@@ -849,7 +1124,7 @@ bool halo_plan(const ConvGeom &g, int pass, int force_variant, int force_splits,
 
 void halo_kernel_name(int pass, const GemmPlan &pl, bool masked, char *name, size_t name_bytes)
 {
-    if (pass == PASS_WGRAD) { snprintf(name, name_bytes, "k_wgrad_halo"); return; }
+    if (pass == PASS_WGRAD) { snprintf(name, name_bytes, pl.variant == 11 ? "k_wgrad_halo9<true>" : "k_wgrad_halo"); return; }
     if (pl.variant == 4) { snprintf(name, name_bytes, "k_halo_ws<%d, %s>", pass, pass == PASS_DGRAD && masked ? "true" : "false"); return; }
     const HaloVariant &h = kHalo[pl.variant];
     snprintf(name, name_bytes, "k_halo<%d, %d, %d, %d, %d>", pass, h.TA, h.WA, h.WB, h.NS);
@@ -871,8 +1146,14 @@ hipError_t halo_launch(const ConvArgs &a, hipStream_t st)
         if (!db) p.flags &= ~KF_DB;
         const int tws = halo_tws(g.Ho, g.Wo), tw = 1 << tws, th = HALO_TB >> tws;
         const int tiles_x = (g.Wo + tw - 1) / tw, tiles_y = (g.Ho + th - 1) / th;
-        hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * (g.R * g.S + (db ? 1 : 0))), 2 * WH_BUF, st, p, tws,
-                           tiles_x, tiles_y, g.N * tiles_x * tiles_y);
+        if (a.plan.variant == 11) {
+            void (*kern)(const KArgs, int, int, int, int) = k_wgrad_halo9<false>;
+            if (db) kern = k_wgrad_halo9<true>;
+            hipLaunchKernelGGL(kern, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(256), 2 * WH_BUF, st, p, tws, tiles_x, tiles_y,
+                               g.N * tiles_x * tiles_y);
+        } else
+            hipLaunchKernelGGL(k_wgrad_halo, dim3((unsigned)a.plan.splits, (unsigned)a.plan.tilesA), dim3(64 * (g.R * g.S + (db ? 1 : 0))), 2 * WH_BUF, st, p, tws,
+                               tiles_x, tiles_y, g.N * tiles_x * tiles_y);
         dp_trace_main_kernel_done(st);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

@@ -69,6 +69,7 @@ const Candidate kWg[] = {
     {312, 1, 2.90f, 7.0f},   // 256x256x64, 8 waves
     {316, 1, 1.60f, 9.0f},   // 3x3 stride 1: 256 x (3 taps x 64 channels), x strip shared by the taps, padded pixel slots
     {410, 1, 0.13f, 6.0f},   // input patch in LDS, persistent blocks (64 input channels, stride 1); a step = 16 pixels
+    {411, 1, 0.10f, 6.0f},   // the same for 3x3 filters with all nine taps in one wave (four waves per block)
     {100, 3, 1.30f, 4.0f},
     {101, 3, 1.00f, 3.5f},
     {102, 3, 1.00f, 3.5f},

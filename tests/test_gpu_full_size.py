@@ -182,6 +182,7 @@ FORCED = [
     ("conv1_2", 16, 0, 404, 0, "k_halo_ws<0, false>"), ("conv1_2", 32, 1, 403, 0, "k_halo<1, 64, 1, 4, 4>"),
     ("conv2_1", 32, 0, 403, 0, "k_halo<0, 64, 1, 4, 4>"), ("conv2_1", 2, 0, 401, 0, "k_halo<0, 128, 2, 2, 2>"),
     ("conv1_2", 32, 2, 410, 0, "k_wgrad_halo"), ("conv2_1", 32, 2, 410, 0, "k_wgrad_halo"), ("conv1_2", 2, 2, 410, 0, "k_wgrad_halo"),
+    ("conv1_2", 32, 2, 411, 0, "k_wgrad_halo9<true>"), ("conv2_1", 16, 2, 411, 0, "k_wgrad_halo9<true>"), ("conv1_2", 1, 2, 411, 0, "k_wgrad_halo9<true>"),
     # pipelined tiles of the large batches and their filter-gradient forms with many splits
     ("conv2_2", 32, 0, 200, 1, "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>"), ("conv4_2", 32, 1, 208, 1, "k_dgrad_dma<256, 256, 64, 2, 4, 2, 1>"),
     ("conv2_2", 32, 2, 300, 16, "k_wgrad_dma<128, 128, 32, 2, 2, 2>"), ("conv4_2", 32, 2, 312, 8, "k_wgrad_dma<256, 256, 64, 2, 4, 2>"),

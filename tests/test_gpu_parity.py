@@ -281,6 +281,41 @@ def test_strided_backward_data_by_phase(env, spec):
 
 
 @pytest.mark.parametrize("blocks", [0, 3, 40])
+def test_input_patch_filter_gradient_all_taps_per_wave(env, blocks):
+    """The 3x3 form of the input-patch filter gradient with all nine taps in one wave (four waves: two pixel groups x two halves of
+    c_in; sums of the pixel groups meet in LDS at the end): both tile shapes, ragged edges, c_out below / above one 64-row tile,
+    padding 0 and 1, one block with many tiles and more blocks than tiles, with and without the fused bias gradient."""
+    dp, U, orc = env
+    dp.dp_set_override(2, 411, blocks)
+    try:
+        for tag, n, h, w, k, pd in (("tapsw_a", 2, 13, 12, 96, (1, 1)), ("tapsw_b", 1, 37, 40, 64, (1, 1)), ("tapsw_c", 3, 20, 70, 40, (0, 0)),
+                                    ("tapsw_d", 2, 33, 31, 136, (1, 1)), ("tapsw_e", 5, 16, 16, 64, (1, 1))):
+            case = U.ConvCase(tag, n, h, w, 64, k, 3, 3, (1, 1), pd, bf16=True, bias=True, relu=True)
+            assert dp.dp_conv2d_kernel_info(case.desc, 2)[0] == "k_wgrad_halo9<true>"
+            y = case.run_fwd()
+            dw, db = case.run_wgrad(y)   # saved output given: dy is masked first, the bias gradient comes from that pass
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=U.to_np(y), pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} blocks {blocks} dw")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} blocks {blocks} db")
+            dw, db = case.run_wgrad(None)   # no saved output: the c_in-half-0 waves also sum the bias gradient
+            db.fill_(7.0)
+            dw, db = case.run_wgrad(None)
+            torch.cuda.synchronize()
+            rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=None, pad=pd, want_db=True)
+            U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} blocks {blocks} dw, unmasked")
+            U.assert_bf16_close(U.to_np(db), rdb, f"{tag} blocks {blocks} db, fused")
+            dw2, _ = case.run_wgrad(None, want_db=False)
+            torch.cuda.synchronize()
+            assert torch.equal(dw, dw2), f"{tag}: filter gradient differs when the bias gradient is not asked for"
+        # other filter shapes stay with the wave-per-tap kernel
+        case = U.ConvCase("tapsw_1x7", 2, 9, 33, 64, 64, 1, 7, (1, 1), (0, 3), bf16=True, bias=True, relu=True)
+        assert "halo9" not in dp.dp_conv2d_kernel_info(case.desc, 2)[0]
+    finally:
+        dp.dp_set_override(2, -1, 0)
+
+
+@pytest.mark.parametrize("blocks", [0, 3, 40])
 def test_input_patch_filter_gradient(env, blocks):
     """Filter gradient with the input patch in LDS and persistent blocks (64 input channels, stride 1): both
     tile shapes, ragged edges, c_out below / above one 64-row tile, 1xS filters, more blocks than tiles."""
