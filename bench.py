@@ -31,75 +31,74 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 292166726,
-    "k_reduce_flat@32": 59177597,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 311512317,
-    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@32": 349159431,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 245755089,
-    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 175914295,
-    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@32": 236775251,
-    "k_reduce_pixel_major@32": 27067309,
-    "k_wgrad_halo@32": 356320132,
-    "k_conv_strip<false, 224, 256>@32": 121523161,
-    "k_conv_strip<true, 224, 256>@32": 172522189,
-    "k_halo_ws<0, false>@32": 320329866,
-    "k_halo_ws<1, true>@32": 678097602,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 186712219,
-    "k_conv_strip<true, 256, 128>@32": 161931569,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@32": 123062843,
-    "k_conv_strip<false, 256, 128>@32": 144831730,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 86909480,
-    "k_dgrad_dma<128, 128, 64, 2, 2, 2, 1>@32": 209538077,
-    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>@32": 147559862,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@32": 104632812,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 121950489,
-    "k_conv_strip<true, 128, 256>@32": 131765893,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 147700113,
-    "k_reduce_flat_wide@32": 49399695,
-    "k_conv_fast<1, 128, 128, 64, 2, 2>@32": 267919079,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 123202706,
-    "k_fwd_rgb3@32": 230265277,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@32": 96432035,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 142648740,
-    "k_wgrad_rgb3<true>@32": 220896620,
-    "k_fwd_dma<128, 64, 128, 2, 2, 2, 1>@32": 131473680,
-    "k_dense_wgrad<true>@32": 69695529,
-    "k_dense_wgrad<false>@32": 18709958,
-    "k_dense_dgrad@32": 9297701,
-    "k_wgrad_direct_sum@32": 4291675,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 118579870,
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 83104274,
-    "k_reduce_flat@2": 27657927,
-    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 39858096,
-    "k_reduce_flat_wide@2": 21516291,
-    "k_reduce_pixel_major@2": 10429436,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 70597911,
-    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 38257156,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 41862906,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@2": 39336378,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 47885394,
-    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 44863280,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@2": 49187726,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 26715171,
-    "k_wgrad_halo@2": 48704436,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 34709053,
-    "k_conv_fast<0, 64, 64, 64, 2, 2>@2": 28063315,
-    "k_dense_fwd<1>@2": 82874960,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 27926419,
-    "k_dense_wgrad<true>@2": 67475016,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 2>@2": 21713497,
-    "k_halo_ws<0, false>@2": 21626928,
-    "k_conv_fast<0, 64, 128, 64, 2, 2>@2": 14139832,
-    "k_halo<1, 64, 1, 4, 2>@2": 39676357,
-    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 24406529,
-    "k_halo_ws<1, true>@2": 43203345,
-    "k_halo<0, 64, 1, 4, 3>@2": 23053543,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 248685602,
+    "k_reduce_flat@32": 59521100,
+    "k_wgrad_dma<128, 256, 32, 2, 4, 2>@32": 488590806,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 242766325,
+    "k_reduce_pixel_major@32": 27857407,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 213778387,
+    "k_conv_strip<true, 256, 128>@32": 173990421,
+    "k_wgrad_halo9<true>@32": 356662339,
+    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 180321094,
+    "k_conv_strip<false, 224, 256>@32": 121442698,
+    "k_conv_strip<true, 224, 256>@32": 172631078,
+    "k_halo_ws<1, true>@32": 678076610,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 147506171,
+    "k_halo_ws<0, false>@32": 340976910,
+    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@32": 104595821,
+    "k_conv_strip<false, 256, 128>@32": 154167227,
+    "k_halo<0, 64, 1, 4, 2>@32": 263318993,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 102356218,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 92110314,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>@32": 133852775,
+    "k_reduce_flat_wide@32": 47259871,
+    "k_fwd_rgb3@32": 230141677,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 107207980,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 166695128,
+    "k_wgrad_rgb3<true>@32": 220900189,
+    "k_dense_wgrad<true>@32": 69708961,
+    "k_dense_wgrad<false>@32": 18710087,
+    "k_dense_dgrad@32": 9297574,
+    "k_wgrad_direct_sum@32": 4291676,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 130657871,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 89952631,
+    "k_reduce_flat@2": 28719699,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 72291653,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 46221579,
+    "k_reduce_pixel_major@2": 10154578,
+    "k_reduce_flat_wide@2": 22400411,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@2": 36184738,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 49673985,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 43205641,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 41614309,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@2": 50937540,
+    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@2": 118984531,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 49372903,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@2": 54868570,
+    "k_conv_fast<0, 64, 64, 64, 2, 2>@2": 33440671,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@2": 31854260,
+    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@2": 29093550,
+    "k_wgrad_halo@2": 42814832,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 26123177,
+    "k_dense_fwd<1>@2": 82874978,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 33402539,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>@2": 25302643,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 26493326,
+    "k_dense_wgrad<true>@2": 67475992,
+    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 23125765,
+    "k_halo<0, 64, 1, 4, 4>@2": 20319548,
+    "k_fwd_dma<128, 64, 128, 2, 2, 2, 1>@2": 19715610,
+    "k_fwd_dma<64, 256, 64, 1, 4, 2, 1>@2": 17539411,
+    "k_halo<1, 64, 1, 4, 4>@2": 39682441,
+    "k_halo_ws<1, true>@2": 43202048,
+    "k_halo<0, 64, 1, 4, 3>@2": 23050460,
+    "k_dgrad_dma<64, 64, 128, 2, 2, 4, 1>@2": 19933554,
+    "k_dgrad_dma<64, 128, 128, 2, 2, 2, 1>@2": 18320015,
     "k_dense_wgrad<false>@2": 16628633,
-    "k_fwd_rgb3@2": 14118215,
-    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@2": 17866713,
-    "k_wgrad_rgb3<true>@2": 15733104,
-    "k_dense_dgrad@2": 8326931,
-    "k_wgrad_direct_sum@2": 1706703,
+    "k_fwd_rgb3@2": 14118189,
+    "k_wgrad_rgb3<true>@2": 15733108,
+    "k_dense_dgrad@2": 8326934,
+    "k_wgrad_direct_sum@2": 1706704,
 }
 
 
