@@ -276,6 +276,20 @@ __global__ __launch_bounds__(64 * WA * WB) void k_halo(const KArgs p, int tws, i
     }
 }
 
+// Tiles of a persistent block.  Consecutive block ids go round-robin to the 8 XCDs, each with an L2 of its own: XCD x (blocks x,
+// x + 8, ...) walks one contiguous eighth of the tile list, its blocks side by side, so that tiles that share halo pixels (left /
+// right neighbours, and the row of tiles above / below) run on one XCD at about the same time and the second reader of a halo pixel
+// finds it in that L2.  (Dealing the tiles out block by block over the whole chip, every halo pixel was fetched from memory again: L2
+// hit rate 0.09 on conv1_2, and the copies of a CU are bound by its ~64 outstanding misses.)
+struct TileWalk { int first, end, stride; };
+DEVFN TileWalk tile_walk(int tiles)
+{
+    const int nb = gridDim.x;
+    if ((nb & 7) != 0) return {(int)blockIdx.x, tiles, nb};
+    const int x = blockIdx.x & 7;
+    return {(int)((long long)tiles * x / 8) + (int)(blockIdx.x >> 3), (int)((long long)tiles * (x + 1) / 8), nb >> 3};
+}
+
 // ---------------------------------------------------------------------------------------
 // Backward-filter with the input patch in LDS (stride 1, 64 input channels, up to 16 taps).
 // The tiled kernel copies, for every 64 pixels of reduction, the x rows of each tap again; here a
@@ -346,12 +360,13 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
         a_lane[i] = HALO_PP * 128 + tl * 128 + ((((col >> 5) ^ seg_swz<64>(tl)) << 6) | ((col & 31) << 1));
     }
 
-    int tile = blockIdx.x;
-    if (tile < tiles) issue_tile(tile, 0);
-    for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+    const TileWalk tw = tile_walk(tiles);
+    int tile = tw.first;
+    if (tile < tw.end) issue_tile(tile, 0);
+    for (int it = 0; tile < tw.end; tile += tw.stride, ++it) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();   // tile `it` has landed everywhere; the other buffer is no longer read
-        if (tile + (int)gridDim.x < tiles) issue_tile(tile + gridDim.x, (it + 1) & 1);
+        if (tile + tw.stride < tw.end) issue_tile(tile + tw.stride, (it + 1) & 1);
         const unsigned base = smem_base + (it & 1) * WH_BUF;
         // fragments are double-buffered in registers: the transpose reads of slice sl+1 are issued before the
         // matrix instructions of slice sl
@@ -579,17 +594,18 @@ __global__ __launch_bounds__(256) void k_wgrad_halo9(const KArgs p, int tws, int
         xhi[slot] = lds_read_tr<4 * 128>(addr);
     };
 
-    int tile = blockIdx.x;
-    if (tile < tiles) {
+    const TileWalk tw = tile_walk(tiles);
+    int tile = tw.first;
+    if (tile < tw.end) {
         set_tile(tile, 0);
 #pragma unroll
         for (int c = 0; c < NCP + NCD; ++c) issue_copy(c);
     }
-    for (int it = 0; tile < tiles; tile += gridDim.x, ++it) {
+    for (int it = 0; tile < tw.end; tile += tw.stride, ++it) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();   // tile `it` has landed everywhere; the other buffer is no longer read
-        const bool more = tile + (int)gridDim.x < tiles;   // wave-uniform
-        if (more) set_tile(tile + gridDim.x, (it + 1) & 1);
+        const bool more = tile + tw.stride < tw.end;   // wave-uniform
+        if (more) set_tile(tile + tw.stride, (it + 1) & 1);
         const unsigned base = smem_base + (it & 1) * WH_BUF;
         read_dy(base, 0, 0);
 #pragma unroll
@@ -720,7 +736,7 @@ static_assert(WS_CPW * 4 * 8 == HALO_PP, "patch copies divide evenly over the fo
 static_assert(WS_PATCH + 9 * 8192 <= 3 * WS_PATCH, "the weights are staged behind the first patch buffer");
 
 template <int PASS, bool MASK = false>   // MASK (backward-data): fused backward of the ReLU in front of the layer
-__global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles)
+__global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int tiles_x, int tiles_y, int tiles_all)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const ConvGeom &g = p.g;
@@ -757,8 +773,9 @@ __global__ __launch_bounds__(256) void k_halo_ws(const KArgs p, int tws, int til
             dma16(rin, smem_base + buf * WS_PATCH + (wave * WS_CPW + q) * 1024, ok ? (unsigned)(((nbase + ih) * IW + iw) * 64 + c * 8) * 2u : OOR);
         }
     };
-    int tile = blockIdx.x;
-    const int stride = gridDim.x;
+    const TileWalk tw = tile_walk(tiles_all);
+    int tile = tw.first;
+    const int stride = tw.stride, tiles = tw.end;   // this block's tiles: tile, tile + stride, ... below `tiles`
     if (tile < tiles) issue_patch(tile, 0);
 
     // ---- weights: through LDS (behind the first patch buffer) into registers ------------------------
