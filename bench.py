@@ -31,71 +31,74 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 248685602,
-    "k_reduce_flat@32": 59521100,
-    "k_wgrad_dma<128, 256, 32, 2, 4, 2>@32": 488590806,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 242766325,
-    "k_reduce_pixel_major@32": 27857407,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 213778387,
-    "k_conv_strip<true, 256, 128>@32": 173990421,
-    "k_wgrad_halo9<true>@32": 356662339,
-    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 180321094,
-    "k_conv_strip<false, 224, 256>@32": 121442698,
-    "k_conv_strip<true, 224, 256>@32": 172631078,
-    "k_halo_ws<1, true>@32": 678076610,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 147506171,
-    "k_halo_ws<0, false>@32": 340976910,
-    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@32": 104595821,
-    "k_conv_strip<false, 256, 128>@32": 154167227,
-    "k_halo<0, 64, 1, 4, 2>@32": 263318993,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 102356218,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 92110314,
-    "k_conv_fast<1, 64, 64, 64, 2, 2>@32": 133852775,
-    "k_reduce_flat_wide@32": 47259871,
-    "k_fwd_rgb3@32": 230141677,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 107207980,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 166695128,
-    "k_wgrad_rgb3<true>@32": 220900189,
-    "k_dense_wgrad<true>@32": 69708961,
-    "k_dense_wgrad<false>@32": 18710087,
-    "k_dense_dgrad@32": 9297574,
-    "k_wgrad_direct_sum@32": 4291676,
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 130657871,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@2": 89952631,
-    "k_reduce_flat@2": 28719699,
-    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 72291653,
-    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 46221579,
-    "k_reduce_pixel_major@2": 10154578,
-    "k_reduce_flat_wide@2": 22400411,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@2": 36184738,
-    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 49673985,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 43205641,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 41614309,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@2": 50937540,
-    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@2": 118984531,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 49372903,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@2": 54868570,
-    "k_conv_fast<0, 64, 64, 64, 2, 2>@2": 33440671,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@2": 31854260,
-    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@2": 29093550,
-    "k_wgrad_halo@2": 42814832,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 26123177,
-    "k_dense_fwd<1>@2": 82874978,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 33402539,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 2>@2": 25302643,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 26493326,
-    "k_dense_wgrad<true>@2": 67475992,
-    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 23125765,
-    "k_halo<0, 64, 1, 4, 4>@2": 20319548,
-    "k_fwd_dma<128, 64, 128, 2, 2, 2, 1>@2": 19715610,
-    "k_fwd_dma<64, 256, 64, 1, 4, 2, 1>@2": 17539411,
-    "k_halo<1, 64, 1, 4, 4>@2": 39682441,
-    "k_halo_ws<1, true>@2": 43202048,
-    "k_halo<0, 64, 1, 4, 3>@2": 23050460,
-    "k_dgrad_dma<64, 64, 128, 2, 2, 4, 1>@2": 19933554,
-    "k_dgrad_dma<64, 128, 128, 2, 2, 2, 1>@2": 18320015,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 265402824,
+    "k_reduce_flat@32": 58776710,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@32": 294156044,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 224136234,
+    "k_reduce_pixel_major@32": 28563446,
+    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 245940431,
+    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 186490440,
+    "k_wgrad_halo9<true>@32": 320878130,
+    "k_conv_strip<false, 224, 256>@32": 128748821,
+    "k_conv_strip<true, 256, 128>@32": 174162826,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 172513179,
+    "k_halo_ws<0, false>@32": 283801381,
+    "k_conv_strip<true, 224, 256>@32": 178334419,
+    "k_halo_ws<1, true>@32": 618029229,
+    "k_conv_strip<true, 256, 256>@32": 184126366,
+    "k_conv_strip<false, 256, 128>@32": 151688836,
+    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@32": 114666109,
+    "k_conv_strip<false, 256, 256>@32": 116036174,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@32": 115262536,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 120679883,
+    "k_reduce_flat_wide@32": 47298445,
+    "k_conv_strip<true, 128, 256>@32": 141022595,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 117392536,
+    "k_conv_fast<0, 64, 64, 64, 2, 2>@32": 97529057,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 103996972,
+    "k_conv_fast<1, 128, 128, 64, 2, 2>@32": 282727189,
+    "k_fwd_rgb3@32": 230263431,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 168082764,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@32": 98548067,
+    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@32": 142661371,
+    "k_wgrad_rgb3<true>@32": 220902179,
+    "k_dense_wgrad<true>@32": 69700975,
+    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@32": 29809617,
+    "k_dense_wgrad<false>@32": 18710093,
+    "k_dense_dgrad@32": 9297568,
+    "k_wgrad_direct_sum@32": 4291673,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 128155432,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 75064189,
+    "k_reduce_flat@2": 27480114,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 39239806,
+    "k_wgrad_dma<64, 256, 32, 1, 4, 2>@2": 88719928,
+    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 52240425,
+    "k_reduce_pixel_major@2": 9973388,
+    "k_reduce_flat_wide@2": 21433185,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 64663961,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 44689411,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 48294891,
+    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 48776710,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 28721555,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@2": 32395085,
+    "k_wgrad_halo@2": 42276772,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@2": 26708475,
+    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@2": 53824970,
+    "k_dense_fwd<1>@2": 82874981,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 34659983,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 24639753,
+    "k_dense_wgrad<true>@2": 67476080,
+    "k_halo<1, 64, 1, 4, 2>@2": 39676480,
+    "k_halo_ws<1, true>@2": 39764417,
+    "k_halo<0, 64, 1, 4, 4>@2": 21112833,
+    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 24342415,
+    "k_conv_fast<0, 64, 128, 64, 2, 2>@2": 15420540,
+    "k_halo_ws<0, false>@2": 21204641,
+    "k_halo<0, 64, 1, 4, 2>@2": 18272051,
+    "k_fwd_dma<64, 64, 128, 2, 2, 4, 1>@2": 20321665,
+    "k_dgrad_dma<64, 64, 128, 2, 2, 3, 1>@2": 17050600,
     "k_dense_wgrad<false>@2": 16628633,
-    "k_fwd_rgb3@2": 14118189,
+    "k_fwd_rgb3@2": 14118216,
     "k_wgrad_rgb3<true>@2": 15733108,
     "k_dense_dgrad@2": 8326934,
     "k_wgrad_direct_sum@2": 1706704,
