@@ -55,9 +55,33 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
     constexpr int CPR = TA / 8;
     bf16_t *out = reinterpret_cast<bf16_t *>(p.out);
     if ((p.flags & KF_MASK_IN) && !all_zero) {
-        // fused backward of the input ReLU: the saved-input vectors are requested in groups of eight before
-        // they are needed (the first group before the staging barrier), so that their latency overlaps
-        constexpr int ITERS = (TB * CPR + NT - 1) / NT, GRP = ITERS < 8 ? ITERS : ITERS % 8 == 0 ? 8 : 4;
+        // fused backward of the input ReLU.  All saved-input vectors of the thread are requested before the staging barrier
+        // and consumed in order, so that the tile pays the memory latency once.  Loads and stores go through buffer
+        // resources: an element outside the tensor gets an out-of-range offset and the hardware drops it, which keeps the
+        // copy-out free of branches (one branch per element made the compiler hold the later loads back behind the
+        // earlier stores).  Tensors of 4 GiB and more do not fit a resource and take the grouped form below.
+        constexpr int ITERS = (TB * CPR + NT - 1) / NT;
+        const size_t bytes = (size_t)p.rowsB * p.rowsA * 2;
+        if (ITERS <= 32 && bytes < 0xffffffffull) {
+            const __amdgpu_buffer_rsrc_t rin = make_rsrc(p.x, bytes), rout = make_rsrc(out, bytes);
+            auto offset = [&](int u) {
+                const int id = tid + u * NT, pix = id / CPR, cc = id % CPR;
+                const int gp = id < TB * CPR ? out_row(pix) : -1, gc = a0 + cc * 8;
+                return (gp >= 0 && gc < p.rowsA) ? ((unsigned)gp * (unsigned)p.rowsA + gc) * 2u : OOR;
+            };
+            u32x4 xm[ITERS < 32 ? ITERS : 32];
+#pragma unroll
+            for (int u = 0; u < ITERS; ++u) xm[u] = __builtin_amdgcn_raw_buffer_load_b128(rin, offset(u), 0, 0);
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < ITERS; ++u) {
+                const int id = tid + u * NT, pix = id / CPR, cc = id % CPR;
+                const u32x4 v = id < TB * CPR ? *reinterpret_cast<const u32x4 *>(stage + pix * LSO + cc * 8) : u32x4{0, 0, 0, 0};
+                __builtin_amdgcn_raw_buffer_store_b128(apply_mask(v, xm[u]), rout, offset(u), 0, 0);
+            }
+            return;
+        }
+        constexpr int GRP = ITERS < 8 ? ITERS : ITERS % 8 == 0 ? 8 : 4;
         static_assert(ITERS % GRP == 0, "copy-out iterations come in whole groups");
         u32x4 xm[GRP];
         auto fetch = [&](int g0) {
@@ -94,8 +118,8 @@ DEVFN void store_staged(const KArgs &p, const f32x16 (&acc)[FA][FB], bf16_t *sta
     }
 }
 
-// Reduction split without a second kernel.  Every block of a tile stores its fp32 partial as usual, makes it visible
-// device-wide (__threadfence) and takes a ticket from the tile's counter; the block that draws the last ticket adds the
+// Reduction split without a second kernel.  Every block of a tile stores its fp32 partial with device-scope (written
+// through) stores, waits for them and takes a ticket from the tile's counter; the block that draws the last ticket adds the
 // partials of all splits IN SPLIT ORDER (so the result does not depend on which block came last), applies the epilogue and
 // stores the tile.  The counters live in a static device array, zero when no launch is using them: the last block of a
 // tile resets its counter, and concurrent launches (the data-gradient chain and the filter gradients on another stream)
@@ -424,6 +448,13 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
     const bf16_t *pix = DG ? p.dy : p.x;
     __amdgpu_buffer_rsrc_t rw = make_rsrc(p.w, (size_t)g.K * RSC * 2), rx = make_rsrc(pix, (size_t)NHW * CR * 2);
     __amdgpu_buffer_rsrc_t rw_off = make_rsrc(p.w, 0), rx_off = make_rsrc(pix, 0);   // every lane out of range: a switched-off copy
+    // Fused input-ReLU mask: the epilogue reads the tile of the saved input, which no block has touched before, while the
+    // matrix cores have nothing left to do.  The strip copies of the last strip have no strip to fetch; they fetch 16 bytes
+    // of every 64 bytes of that tile instead (into the idle strip buffer, never read), so that the lines are in this
+    // die's L2 when the epilogue asks for them.
+    const size_t mask_bytes = (size_t)p.rowsB * p.rowsA * 2;
+    const bool mask_ahead = DG && (p.flags & KF_MASK_IN) && p.splits == 1 && mask_bytes < 0xffffffffull;
+    __amdgpu_buffer_rsrc_t rx_last = mask_ahead ? make_rsrc(p.x, mask_bytes) : rx_off;
     if (tid < TB) {
         const int m = b0 + tid;
         const int n = m / (g.H * g.W), rem = m - n * (g.H * g.W), hh = rem / g.W, ww = rem - hh * g.W;
@@ -468,8 +499,20 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rw : rw_off, (lds_void)(size_t)(lds0 + stage * A_BYTES + (wave_s * IA + q) * 1024), 16, voffA[q], soff, 0, 0);
     };
     auto issue_s = [&](int buf, int cc, int q, bool on) {   // strip (filter row of voffS_r, channel block cc) into strip buffer `buf`
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rx : rx_off, (lds_void)(size_t)(ldsS0 + buf * S_BYTES + (wave_s * ISB + q) * 1024), 16, voffS_r[q],
-                                                 (cc0 + cc) * BK * 2, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(on ? rx : rx_last, (lds_void)(size_t)(ldsS0 + buf * S_BYTES + (wave_s * ISB + q) * 1024), 16, voffS_r[q],
+                                                 on ? (cc0 + cc) * BK * 2 : 0, 0, 0);
+    };
+    // voffS_r for the last strip's copies (`last`): one 64-byte piece of the saved-input tile per lane; a select, not a
+    // branch, so that the offsets stay in registers
+    auto mask_tile_offsets = [&](bool last) {
+        constexpr int PPR = TA / 32;   // pieces per pixel row of the tile
+        static_assert(TB * PPR <= ISB * 256, "the last strip's copies cover the tile");
+#pragma unroll
+        for (int q = 0; q < ISB; ++q) {
+            const int piece = (wave * ISB + q) * 64 + lane, row = piece / PPR, col = a0 + (piece % PPR) * 32;
+            const unsigned off = (row < TB && b0 + row < p.rowsB && col < p.rowsA) ? ((unsigned)(b0 + row) * (unsigned)p.rowsA + col) * 2u : OOR;
+            voffS_r[q] = last ? off : voffS_r[q];
+        }
     };
 
     f32x16 acc[FA][FB];
@@ -591,6 +634,7 @@ __global__ __launch_bounds__(256) void k_conv_strip(const KArgs p)
         const bool more_strips = gg + 1 < nstrips;
         const int ccn = cc + 1 == CB ? 0 : cc + 1, rrn = cc + 1 == CB ? rr + 1 : rr;   // strip gg + 1
         if (rrn != row_loaded && rrn < 3) { strip_row_offsets(rrn); row_loaded = rrn; }
+        mask_tile_offsets(!more_strips && mask_ahead);   // voffS_r has no strip left to describe
 #pragma unroll
         for (int ss = 0; ss < 3; ++ss) {
             const int i = 3 * gg + ss;
