@@ -801,16 +801,27 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
     const int arow = (wave % WA) * FA * 32, brow = (wave / WA) * FB * 32;
-    // fused bias gradient: the blocks of the first tap tile also multiply their dy^T fragments with ones; the WB
-    // waves that share a row range take turns over its FA fragments (fragment ii belongs to wave column ii % WB)
-    constexpr int DBF = (FA + WB - 1) / WB;
-    const bool do_db = (p.flags & KF_DB) != 0 && b0 == 0;
+    // fused bias gradient: the column sums of the dy^T fragments, by a 16x16x32 matrix instruction against a 0/1 selector
+    // (half the time of the 32x32x16 form against ones, a quarter of its accumulators).  All blocks of a (c_out tile, split)
+    // hold the same dy; the tile's TA/32 fragments are dealt over these tilesB blocks and, within a block, over the WB waves
+    // that share the fragment's rows, so that no wave carries more than its share: fragment f belongs to block f % tilesB,
+    // wave column (f / tilesB) % WB.  One writer per row of the [split][c_out] partial.
     const int wb_ = wave / WA;
-    f32x16 accdb[DBF];
+    unsigned db_mask = 0;   // bit ii: this wave sums its fragment ii
+    if (p.flags & KF_DB) {
+        const int tb = tile / p.tilesA;
 #pragma unroll
-    for (int i = 0; i < DBF; ++i)
+        for (int ii = 0; ii < FA; ++ii) {
+            const int f = (wave % WA) * FA + ii;
+            if (f % p.tilesB == tb && (f / p.tilesB) % WB == wb_) db_mask |= 1u << ii;
+        }
+    }
+    db_mask = __builtin_amdgcn_readfirstlane(db_mask);
+    const bool do_db = db_mask != 0;
+    const bf16x8 db_sel = colsum_selector(lane);
+    f32x4 accdb[FA];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) accdb[i][v] = 0.f;
+    for (int i = 0; i < FA; ++i) accdb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // transpose-read addresses: lane l of a 16-lane block points at reduction row ks*16 + 8*(l>>5) + (l&15)/4
     // (and 4 rows further for the second half), operand rows row0 + 16*((l>>4)&1) + 4*(l&3) .. +3
@@ -895,9 +906,9 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
             if (do_db) {
 #pragma unroll
                 for (int ii = 0; ii < FA; ++ii)
-                    if (ii % WB == wb_) {
+                    if ((db_mask >> ii) & 1u) {
                         const u32x4 av = {alo[cur][ii].x, alo[cur][ii].y, ahi[cur][ii].x, ahi[cur][ii].y};
-                        accdb[ii / WB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), ones_bf16(), accdb[ii / WB], 0, 0, 0);
+                        accdb[ii] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), db_sel, accdb[ii], 0, 0, 0);
                     }
             }
         }
@@ -906,7 +917,7 @@ __global__ __launch_bounds__(64 * WA * WB) void k_wgrad_dma(const KArgs p)
     if (do_db) {
 #pragma unroll
         for (int ii = 0; ii < FA; ++ii)
-            if (ii % WB == wb_) store_db_fragment(accdb[ii / WB], p.dbp + (size_t)split * p.rowsA, a0 + arow + ii * 32, p.rowsA, lane);
+            if ((db_mask >> ii) & 1u) store_colsum_fragment(accdb[ii], p.dbp + (size_t)split * p.rowsA, a0 + arow + ii * 32, p.rowsA, lane);
     }
 }
 

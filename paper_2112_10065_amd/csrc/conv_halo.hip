@@ -461,14 +461,9 @@ __global__ __launch_bounds__(1024) void k_wgrad_halo(const KArgs p, int tws, int
 // end of the kernel.  The bias gradient (dy x ones) rides in the ch = 0 waves, two more matrix
 // instructions per slice.  Tile walk, LDS layout, copies and the per-block partial are the kernel's above.
 // ---------------------------------------------------------------------------------------
-// The matrix instruction with its accumulator pinned to the accumulation registers (AG) or to the vector registers: 18 + 2
-// accumulator tiles are 320 registers, more than the 256 accumulation registers, and the compiler, left to itself, keeps them all
-// there and copies tiles back and forth around every instruction (six copies per matrix instruction).  The caller spaces reads of
-// a result from the instruction that wrote it (the compiler does not see an instruction it would have to wait for).
-// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression in the body
-template <typename F, int... I> DEVFN void for_constant_impl(F &&f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
-template <int N, typename F> DEVFN void for_constant(F &&f) { for_constant_impl(f, std::make_integer_sequence<int, N>{}); }
-
+// The matrix instructions are pinned (mfma_in_regs) to the accumulation registers or to the vector registers: 18 + 2 accumulator
+// tiles are 320 registers, more than the 256 accumulation registers, and the compiler, left to itself, keeps them all there and
+// copies tiles back and forth around every instruction (six copies per matrix instruction).
 template <int OFF, bool AG> DEVFN void lds_write_f32(unsigned addr, float v)   // AG: the value sits in an accumulation register
 {
     if constexpr (AG) asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(addr), "a"(v), "n"(OFF) : "memory");
@@ -479,14 +474,6 @@ template <int OFF> DEVFN float lds_read_f32(unsigned addr)
     float v;
     asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
     return v;
-}
-
-template <bool AG> DEVFN void mfma_pinned(f32x16 &c, const u32x4 a, const u32x4 b)
-{
-    // s_nop 1: a vector instruction the compiler placed just before (a copy or a rematerialised constant that feeds an operand) needs
-    // two wait states before a matrix instruction reads its result; the compiler adds them only for instructions it knows
-    if constexpr (AG) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-    else asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
 
 template <bool DB>
@@ -631,15 +618,15 @@ __global__ __launch_bounds__(256) void k_wgrad_halo9(const KArgs p, int tws, int
 #pragma unroll
             for (int k = 0; k < 2; ++k) {
                 const u32x4 av = {dlo[db][k].x, dlo[db][k].y, dhi[db][k].x, dhi[db][k].y};
-                if constexpr (ti < 8) mfma_pinned<true>(acc[ti][k], av, bv);    // taps 0-7: the 256 accumulation registers
-                else mfma_pinned<false>(acc[ti][k], av, bv);                    // tap 8 and the bias gradient: vector registers
+                if constexpr (ti < 8) mfma_in_regs<true>(acc[ti][k], av, bv);    // taps 0-7: the 256 accumulation registers
+                else mfma_in_regs<false>(acc[ti][k], av, bv);                    // tap 8 and the bias gradient: vector registers
             }
             if constexpr (ti == 0) {
                 if (do_db) {
 #pragma unroll
                     for (int k = 0; k < 2; ++k) {
                         const u32x4 av = {dlo[db][k].x, dlo[db][k].y, dhi[db][k].x, dhi[db][k].y};
-                        mfma_pinned<false>(accdb[k], av, ones);
+                        mfma_in_regs<false>(accdb[k], av, ones);
                     }
                 }
             }

@@ -3,6 +3,8 @@
 // would otherwise wait for every outstanding copy before any LDS read it can see).
 #pragma once
 #include "tile_common.h"
+#include <utility>
+#include <type_traits>
 
 namespace {
 
@@ -25,6 +27,23 @@ DEVFN void dma16_nt(__amdgpu_buffer_rsrc_t r, unsigned lds_base, unsigned voff)
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_void)(size_t)lds_base, 16, voff, 0, 0, 2);
 }
 DEVFN unsigned lds_offset(const void *p) { return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p; }
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>): a loop whose index is a constant expression in the body
+template <typename F, int... I> DEVFN void for_constant_impl(F &&f, std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>{}), ...); }
+template <int N, typename F> DEVFN void for_constant(F &&f) { for_constant_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// The matrix instruction as inline assembly, its accumulator pinned to the accumulation registers (AG) or to the vector
+// registers: a kernel whose accumulators fill the accumulation registers exactly must not leave the choice to the compiler,
+// which otherwise keeps some tiles elsewhere and copies them around every instruction.  The statement is volatile: it stays
+// in its place among the other volatile statements (LDS reads, waits).  s_nop 1: a vector instruction the compiler placed
+// just before (a copy or a rematerialised constant that feeds an operand) needs two wait states before a matrix instruction
+// reads its result, and the compiler adds them only for instructions it knows.  For the same reason the caller spaces the
+// first read of a result from the instruction that wrote it.
+template <bool AG> DEVFN void mfma_in_regs(f32x16 &c, const u32x4 a, const u32x4 b)
+{
+    if constexpr (AG) asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+    else asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
 
 template <int N> DEVFN void wait_vmcnt()
 {

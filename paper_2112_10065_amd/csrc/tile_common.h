@@ -57,6 +57,27 @@ DEVFN void store_db_fragment(const f32x16 &acc, float *dst, int row0, int rows, 
         if (row < rows) dst[row] = acc[v];
     }
 }
+// The same sums at half the cost: a 32 x 16 fragment as it sits in a lane's registers (row l%32, reduction elements
+// 8*(l/32) .. +7) IS a valid first operand of the 16x16x32 instruction, which reads lane l as row l%16, reduction group l/16:
+// groups 0 and 2 then hold rows 0-15 of the fragment, groups 1 and 3 rows 16-31.  Against a second operand whose column 0
+// is one in groups 0 and 2 and whose column 1 is one in groups 1 and 3 (zero elsewhere), column 0 of the result holds the sums
+// of rows 0-15 and column 1 those of rows 16-31.  Four accumulator registers, four passes.
+DEVFN bf16x8 colsum_selector(int lane)
+{
+    const int n = lane & 15, grp = lane >> 4;
+    const unsigned one = ((n == 0 && (grp & 1) == 0) || (n == 1 && (grp & 1) == 1)) ? 0x3f803f80u : 0u;
+    return __builtin_bit_cast(bf16x8, u32x4{one, one, one, one});
+}
+// result register v of lane l is row 4*(l/16) + v, column l%16: the lanes of columns 0 and 1 store
+DEVFN void store_colsum_fragment(const f32x4 &acc, float *dst, int row0, int rows, int lane)
+{
+    if ((lane & 15) > 1) return;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int row = row0 + 16 * (lane & 15) + 4 * (lane >> 4) + v;
+        if (row < rows) dst[row] = acc[v];
+    }
+}
 DEVFN float mask1f(float v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : 0.f; }
 DEVFN bf16_t mask1(bf16_t v, bf16_t y) { return ((unsigned)(y - 1u) & 0xffffu) < 0x7f80u ? v : (bf16_t)0; }
 
