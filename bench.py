@@ -31,77 +31,71 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy kernel), averaged over
 # the launches of each kernel at one per-GPU batch: profiles/vgg16_hbm_traffic.md
 TRAFFIC_BYTES_PER_LAUNCH = {   # key: "<kernel as the profiler prints it>@<per-GPU batch>"
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 265402824,
-    "k_reduce_flat@32": 58776710,
-    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@32": 294156044,
-    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 224136234,
-    "k_reduce_pixel_major@32": 28563446,
-    "k_wgrad_dma<64, 128, 32, 2, 2, 2>@32": 245940431,
-    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 186490440,
-    "k_wgrad_halo9<true>@32": 320878130,
-    "k_conv_strip<false, 224, 256>@32": 128748821,
-    "k_conv_strip<true, 256, 128>@32": 174162826,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 172513179,
-    "k_halo_ws<0, false>@32": 283801381,
-    "k_conv_strip<true, 224, 256>@32": 178334419,
-    "k_halo_ws<1, true>@32": 618029229,
-    "k_conv_strip<true, 256, 256>@32": 184126366,
-    "k_conv_strip<false, 256, 128>@32": 151688836,
-    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@32": 114666109,
-    "k_conv_strip<false, 256, 256>@32": 116036174,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@32": 115262536,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 120679883,
-    "k_reduce_flat_wide@32": 47298445,
-    "k_conv_strip<true, 128, 256>@32": 141022595,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@32": 117392536,
-    "k_conv_fast<0, 64, 64, 64, 2, 2>@32": 97529057,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 103996972,
-    "k_conv_fast<1, 128, 128, 64, 2, 2>@32": 282727189,
-    "k_fwd_rgb3@32": 230263431,
-    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@32": 168082764,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@32": 98548067,
-    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@32": 142661371,
-    "k_wgrad_rgb3<true>@32": 220902179,
-    "k_dense_wgrad<true>@32": 69700975,
-    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@32": 29809617,
-    "k_dense_wgrad<false>@32": 18710093,
-    "k_dense_dgrad@32": 9297568,
-    "k_wgrad_direct_sum@32": 4291673,
-    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 128155432,
-    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 75064189,
-    "k_reduce_flat@2": 27480114,
-    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 39239806,
-    "k_wgrad_dma<64, 256, 32, 1, 4, 2>@2": 88719928,
-    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 52240425,
-    "k_reduce_pixel_major@2": 9973388,
-    "k_reduce_flat_wide@2": 21433185,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 64663961,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 44689411,
-    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 48294891,
-    "k_conv_fast<1, 64, 64, 64, 2, 2>@2": 48776710,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 28721555,
-    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@2": 32395085,
-    "k_wgrad_halo@2": 42276772,
-    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@2": 26708475,
-    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@2": 53824970,
-    "k_dense_fwd<1>@2": 82874981,
-    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 34659983,
-    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 24639753,
-    "k_dense_wgrad<true>@2": 67476080,
-    "k_halo<1, 64, 1, 4, 2>@2": 39676480,
-    "k_halo_ws<1, true>@2": 39764417,
-    "k_halo<0, 64, 1, 4, 4>@2": 21112833,
-    "k_conv_fast<1, 64, 128, 64, 2, 2>@2": 24342415,
-    "k_conv_fast<0, 64, 128, 64, 2, 2>@2": 15420540,
-    "k_halo_ws<0, false>@2": 21204641,
-    "k_halo<0, 64, 1, 4, 2>@2": 18272051,
-    "k_fwd_dma<64, 64, 128, 2, 2, 4, 1>@2": 20321665,
-    "k_dgrad_dma<64, 64, 128, 2, 2, 3, 1>@2": 17050600,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@32": 275078599,
+    "k_reduce_flat@32": 60161969,
+    "k_wgrad_dma<256, 256, 64, 2, 4, 2>@32": 177667828,
+    "k_wgrad_dma<128, 128, 64, 2, 2, 2>@32": 259377408,
+    "k_reduce_pixel_major@32": 27174872,
+    "k_conv_strip<true, 224, 256>@32": 171644633,
+    "k_conv_strip<false, 224, 256>@32": 121469231,
+    "k_wgrad_halo9<true>@32": 320878204,
+    "k_conv_strip<true, 256, 128>@32": 185911535,
+    "k_halo_ws<0, false>@32": 283800783,
+    "k_dgrad_dma<64, 128, 64, 2, 2, 2, 1>@32": 164571708,
+    "k_halo_ws<1, true>@32": 618192570,
+    "k_fwd_dma<128, 128, 64, 2, 2, 2, 1>@32": 146734142,
+    "k_fwd_dma<64, 128, 64, 2, 2, 2, 1>@32": 95860080,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@32": 157534286,
+    "k_conv_strip<false, 256, 128>@32": 147696706,
+    "k_conv_strip<true, 128, 256>@32": 132799145,
+    "k_reduce_flat_wide@32": 48001240,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@32": 99755382,
+    "k_wgrad_dma<64, 256, 32, 1, 4, 2>@32": 424924068,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@32": 114982045,
+    "k_fwd_rgb3@32": 230225985,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@32": 74369407,
+    "k_wgrad_rgb3<true>@32": 220898337,
+    "k_dense_wgrad<true>@32": 69690728,
+    "k_dense_wgrad<false>@32": 18710094,
+    "k_dense_dgrad@32": 9297571,
+    "k_wgrad_direct_sum@32": 4291674,
+    "k_wgrad_dma<128, 128, 32, 2, 2, 2>@2": 131164048,
+    "k_wgrad_dma<128, 64, 32, 2, 2, 2>@2": 80393531,
+    "k_reduce_flat@2": 27498692,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 2>@2": 54995695,
+    "k_wgrad_dma<64, 128, 64, 2, 2, 2>@2": 39431809,
+    "k_reduce_pixel_major@2": 9790902,
+    "k_reduce_flat_wide@2": 22073797,
+    "k_wgrad_dma<64, 64, 32, 2, 2, 2>@2": 35385434,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 2, 4>@2": 42727728,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 1>@2": 53431899,
+    "k_dgrad_dma<64, 64, 64, 2, 2, 3, 1>@2": 45686533,
+    "k_dgrad_dma<128, 64, 64, 2, 2, 2, 2>@2": 56822772,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 2>@2": 31871907,
+    "k_conv_fast<0, 64, 64, 64, 2, 2>@2": 28739201,
+    "k_dense_fwd<1>@2": 82874842,
+    "k_fwd_dma<64, 64, 64, 2, 2, 2, 4>@2": 33982470,
+    "k_conv_fast<1, 128, 64, 64, 2, 2>@2": 68977417,
+    "k_fwd_dma<128, 64, 64, 2, 2, 2, 1>@2": 30056766,
+    "k_dgrad_dma<128, 64, 128, 2, 2, 2, 1>@2": 79696568,
+    "k_wgrad_halo@2": 45397162,
+    "k_fwd_dma<64, 64, 64, 2, 2, 3, 1>@2": 25019716,
+    "k_wgrad_halo9<true>@2": 34065730,
+    "k_dense_wgrad<true>@2": 67487480,
+    "k_conv_fast<0, 128, 64, 64, 2, 2>@2": 19960021,
+    "k_halo<0, 64, 1, 4, 3>@2": 17366213,
+    "k_halo<1, 64, 1, 4, 4>@2": 39682413,
+    "k_dgrad_dma<64, 64, 128, 2, 2, 3, 1>@2": 17234433,
+    "k_halo_ws<1, true>@2": 39764571,
+    "k_fwd_dma<64, 128, 128, 2, 2, 2, 1>@2": 14300926,
+    "k_fwd_dma<64, 64, 128, 2, 2, 3, 1>@2": 20039705,
+    "k_halo<0, 64, 1, 4, 2>@2": 20847855,
+    "k_dgrad_dma<64, 128, 128, 2, 2, 2, 1>@2": 18350732,
     "k_dense_wgrad<false>@2": 16628633,
-    "k_fwd_rgb3@2": 14118216,
-    "k_wgrad_rgb3<true>@2": 15733108,
-    "k_dense_dgrad@2": 8326934,
-    "k_wgrad_direct_sum@2": 1706704,
+    "k_fwd_rgb3@2": 14118188,
+    "k_wgrad_rgb3<true>@2": 15733105,
+    "k_dense_dgrad@2": 8326932,
+    "k_wgrad_direct_sum@2": 1706703,
 }
 
 
