@@ -564,7 +564,7 @@ def test_pipelined_backward_filter_variants(env, variant, splits):
             rdw, rdb = orc.conv2d_bwd_filter(case.x, case.dy, case.w.shape, y_saved=y_np, stride=st, pad=pd, want_db=True)
             U.assert_bf16_close(U.to_np(dw), rdw, f"{tag} variant {variant} splits {splits} dw")
             U.assert_bf16_close(U.to_np(db), rdb, f"{tag} variant {variant} splits {splits} db")
-            # no saved output: the kernel itself sums the bias gradient (ones operand on the matrix cores)
+            # no saved output: the kernel itself sums the bias gradient (column sums on the matrix cores)
             dw, db = case.run_wgrad(None)
             db.fill_(7.0)
             dw, db = case.run_wgrad(None)
